@@ -1,0 +1,138 @@
+/*
+ * adapm.h - C ABI of the AdaPM optimizer step for AMD MI355X (gfx950).
+ *
+ * The library applies, to every parameter block of a model, one step of the
+ * paper's update (Alg. 1 "Low Rank Update with Correction"): full momentum
+ * (eq. 5), no momentum (Sec. 4.1 regime 1) or bias-corrected low-rank momentum
+ * (eq. 2-4, tracked by the gradient-descent solver of Alg. 2 / App. B), a
+ * per-element or blockwise second moment (Alg. 1 "v_t"; blockwise mean as in the
+ * Adam-mini combination of Sec. 5.1.3), and the clipped update with decoupled
+ * weight decay (Alg. 1 last line).
+ *
+ * Conventions
+ *  - Every pointer named *_dev is DEVICE memory owned by the caller; every other
+ *    pointer is HOST memory.  The library owns only the context object (a host
+ *    plan plus small device-side tables, released by adapm_destroy).
+ *  - A block is one parameter tensor, row-major rows x cols, rows = output units;
+ *    1-D tensors use cols = 1.  Block base pointers must be 16-byte aligned.
+ *  - adapm_step is asynchronous on the given HIP stream, allocates nothing, and
+ *    updates params and state in place; grads are read-only.
+ *  - Functions return ADAPM_OK (0) or a negative status; nothing aborts or throws.
+ *    adapm_last_error() gives a thread-local message for the last failure.
+ *  - bf16 tensors are IEEE-like bfloat16 bit patterns; stores round to nearest even.
+ */
+#ifndef ADAPM_H
+#define ADAPM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ADAPM_OK = 0,
+  ADAPM_EINVAL = -1,   /* bad argument / table entry */
+  ADAPM_ENOMEM = -2,   /* host or device allocation of the context failed */
+  ADAPM_EHIP = -3,     /* a HIP runtime call failed */
+  ADAPM_ESTATE = -4    /* call order / step number inconsistent */
+} adapm_status_t;
+
+typedef enum { ADAPM_F32 = 0, ADAPM_BF16 = 1 } adapm_dtype_t;
+
+/* Momentum regime of a block (Sec. 4.1): none / full (eq. 5) / low-rank (Alg. 1). */
+typedef enum { ADAPM_MOM_NONE = 0, ADAPM_MOM_FULL = 1, ADAPM_MOM_LOWRANK = 2 } adapm_mom_t;
+
+/* Granularity of the second moment: per element (Alg. 1), one value per group of
+ * v_group_rows consecutive rows, or one value for the whole block (Sec. 5.1.3). */
+typedef enum { ADAPM_V_ELEMENT = 0, ADAPM_V_ROWGROUP = 1, ADAPM_V_WHOLE = 2 } adapm_vmode_t;
+
+/* Arithmetic of the low-rank contractions (G R^T, L^T G, Gram matrices, L R):
+ *  F64     - operands exact, fp64 accumulation on the vector ALUs;
+ *  BF16X2  - bf16 MFMA with fp32 accumulation, every fp32 factor operand carried
+ *            as a (hi, lo) pair of bf16 values (relative operand error 2^-17);
+ *            requires bf16 gradients;
+ *  AUTO    - per block: F64 when the block's parameters are fp32, else BF16X2. */
+typedef enum { ADAPM_CONTRACT_AUTO = 0, ADAPM_CONTRACT_F64 = 1, ADAPM_CONTRACT_BF16X2 = 2 } adapm_contract_t;
+
+typedef struct {
+  int64_t rows, cols;
+  int32_t param_dtype, grad_dtype; /* adapm_dtype_t */
+  int32_t mom_mode;                /* adapm_mom_t */
+  int32_t rank;                    /* LOWRANK only: 1 <= rank <= min(rows, cols); cols >= 2 */
+  int32_t v_mode;                  /* adapm_vmode_t */
+  int32_t v_group_rows;            /* ROWGROUP: rows % v_group_rows == 0 */
+  float lr_scale;                  /* 1.0; the paper uses 0.75 for no-momentum blocks (Sec. 5.1) */
+  float weight_decay;              /* lambda of Alg. 1 for this block */
+} adapm_block_t;
+
+typedef struct {
+  float beta1, beta2, eps;    /* 0.9, 0.95, 1e-8 (Sec. 5.1) */
+  float clip;                 /* element-wise clamp of Alg. 1's last line; 1.0; +inf disables */
+  int32_t adam_debias;        /* 0 = Alg. 1 as printed; 1 = divide by (1-beta^t) (Adam comparison only) */
+  int32_t refresh_iters_K;    /* iterations of Alg. 2; 5 (App. B) */
+  int32_t refresh_period_T;   /* 1 = Alg. 2 every step (Alg. 1 verbatim).  T > 1: Alg. 2 on steps with
+                                 (step-1) % T == 0, followed by a product-preserving orthonormalisation
+                                 of R; on other steps L is the least-squares fit with R held. */
+  int32_t bias_correction;    /* 1 = eq. 4; 0 = ablation of Sec. 5.1.2 (use L_t R_t as the momentum) */
+  int32_t contraction;        /* adapm_contract_t */
+  uint64_t seed;              /* seeded start R_0 of the low-rank factors; 0 = literal all-zero start */
+} adapm_hparams_t;
+
+typedef struct adapm_ctx adapm_ctx;
+
+/* Validate the table and hyper-parameters, fix the state / workspace layout and build
+ * the launch plan on the current HIP device.  table[0..nblocks) and hp are read during
+ * the call only.  On failure *out is NULL. */
+adapm_status_t adapm_init(adapm_ctx** out, const adapm_block_t* table, int64_t nblocks,
+                          const adapm_hparams_t* hp);
+
+/* Size of the caller-allocated optimizer state: per block, in table order,
+ * [L (rows x rank) | R (rank x cols)] or [m (rows x cols)] or nothing, then v;
+ * fp32, each sub-buffer 256-byte aligned (Alg. 1 line 1).  0 if ctx is NULL. */
+size_t adapm_state_bytes(const adapm_ctx* ctx);
+
+/* Size of the caller-allocated scratch buffer used inside adapm_step (previous
+ * factors, thin products, Gram matrices, partial sums).  Contents need not survive
+ * between calls. */
+size_t adapm_workspace_bytes(const adapm_ctx* ctx);
+
+/* Byte offsets into the state buffer of block `block`'s sub-buffers; an absent
+ * sub-buffer reports (size_t)-1.  Any of L, R, m, v may be NULL. */
+adapm_status_t adapm_state_offsets(const adapm_ctx* ctx, int64_t block, size_t* L, size_t* R,
+                                   size_t* m, size_t* v);
+
+/* Zero the state and write the seeded R_0 (Alg. 1 line 1 with L_0 R_0 = 0).
+ * Asynchronous on `stream` (a hipStream_t, or NULL for the default stream). */
+adapm_status_t adapm_state_init(adapm_ctx* ctx, void* state_dev, void* stream);
+
+/* One optimizer step (Alg. 1) over all blocks.
+ *  params_dev / grads_dev: HOST arrays of nblocks DEVICE pointers (table order);
+ *  state_dev: adapm_state_bytes() bytes; workspace_dev: adapm_workspace_bytes() bytes
+ *  (may be NULL if that size is 0); step: 1-based iteration count t; lr: eta_t.
+ * Checks step >= 1, non-null and 16-byte aligned pointers; everything else was
+ * validated at init. */
+adapm_status_t adapm_step(adapm_ctx* ctx, void* const* params_dev, const void* const* grads_dev,
+                          void* state_dev, void* workspace_dev, int64_t step, float lr, void* stream);
+
+/* Number of kernel launches the last adapm_step enqueued (0 before the first). */
+int64_t adapm_last_launch_count(const adapm_ctx* ctx);
+
+/* Compulsory HBM bytes of one step over the table: every input read once and every
+ * output written once in its storage type.  refresh_step != 0 counts a step that runs
+ * Alg. 2; 0 counts a step with R held (T > 1 only). */
+double adapm_algorithmic_bytes(const adapm_ctx* ctx, int32_t refresh_step);
+
+/* Multiply-add work of the low-rank contractions of one step, in flop (2 per multiply-add),
+ * counted once per mathematical product (operand splitting not counted). */
+double adapm_algorithmic_flops(const adapm_ctx* ctx, int32_t refresh_step);
+
+const char* adapm_last_error(void);
+
+void adapm_destroy(adapm_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAPM_H */

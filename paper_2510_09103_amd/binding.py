@@ -1,0 +1,144 @@
+"""ctypes binding of include/adapm.h: argument marshalling only.
+
+Every step of the optimizer runs inside libadapm.so (hand-written HIP for gfx950).
+There is no Python or CPU fallback: if the library has not been built, importing
+this module raises.  PyTorch is used by callers for device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libadapm.so")
+
+ADAPM_OK, ADAPM_EINVAL, ADAPM_ENOMEM, ADAPM_EHIP, ADAPM_ESTATE = 0, -1, -2, -3, -4
+ADAPM_F32, ADAPM_BF16 = 0, 1
+ADAPM_MOM_NONE, ADAPM_MOM_FULL, ADAPM_MOM_LOWRANK = 0, 1, 2
+ADAPM_V_ELEMENT, ADAPM_V_ROWGROUP, ADAPM_V_WHOLE = 0, 1, 2
+ADAPM_CONTRACT_AUTO, ADAPM_CONTRACT_F64, ADAPM_CONTRACT_BF16X2 = 0, 1, 2
+
+
+class adapm_block_t(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64),
+                ("param_dtype", C.c_int32), ("grad_dtype", C.c_int32),
+                ("mom_mode", C.c_int32), ("rank", C.c_int32),
+                ("v_mode", C.c_int32), ("v_group_rows", C.c_int32),
+                ("lr_scale", C.c_float), ("weight_decay", C.c_float)]
+
+
+class adapm_hparams_t(C.Structure):
+    _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("clip", C.c_float),
+                ("adam_debias", C.c_int32), ("refresh_iters_K", C.c_int32),
+                ("refresh_period_T", C.c_int32), ("bias_correction", C.c_int32),
+                ("contraction", C.c_int32), ("seed", C.c_uint64)]
+
+
+EXPORTS = ["adapm_init", "adapm_state_bytes", "adapm_workspace_bytes", "adapm_state_offsets",
+           "adapm_state_init", "adapm_step", "adapm_last_launch_count", "adapm_algorithmic_bytes",
+           "adapm_algorithmic_flops", "adapm_last_error", "adapm_destroy"]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            "There is no fallback path.")
+    lib = C.CDLL(LIB_PATH)
+    P = C.c_void_p
+    lib.adapm_init.restype = C.c_int
+    lib.adapm_init.argtypes = [C.POINTER(P), C.POINTER(adapm_block_t), C.c_int64, C.POINTER(adapm_hparams_t)]
+    lib.adapm_state_bytes.restype = C.c_size_t
+    lib.adapm_state_bytes.argtypes = [P]
+    lib.adapm_workspace_bytes.restype = C.c_size_t
+    lib.adapm_workspace_bytes.argtypes = [P]
+    lib.adapm_state_offsets.restype = C.c_int
+    lib.adapm_state_offsets.argtypes = [P, C.c_int64] + [C.POINTER(C.c_size_t)] * 4
+    lib.adapm_state_init.restype = C.c_int
+    lib.adapm_state_init.argtypes = [P, P, P]
+    lib.adapm_step.restype = C.c_int
+    lib.adapm_step.argtypes = [P, C.POINTER(P), C.POINTER(P), P, P, C.c_int64, C.c_float, P]
+    lib.adapm_last_launch_count.restype = C.c_int64
+    lib.adapm_last_launch_count.argtypes = [P]
+    lib.adapm_algorithmic_bytes.restype = C.c_double
+    lib.adapm_algorithmic_bytes.argtypes = [P, C.c_int32]
+    lib.adapm_algorithmic_flops.restype = C.c_double
+    lib.adapm_algorithmic_flops.argtypes = [P, C.c_int32]
+    lib.adapm_last_error.restype = C.c_char_p
+    lib.adapm_last_error.argtypes = []
+    lib.adapm_destroy.restype = None
+    lib.adapm_destroy.argtypes = [P]
+    return lib
+
+
+lib = _load()
+
+
+class AdapmError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"adapm status {status}: {adapm_last_error()}")
+
+
+def adapm_last_error() -> str:
+    return lib.adapm_last_error().decode()
+
+
+def _check(st: int):
+    if st != ADAPM_OK:
+        raise AdapmError(st)
+
+
+def adapm_init(table: Sequence[adapm_block_t], hp: adapm_hparams_t) -> C.c_void_p:
+    arr = (adapm_block_t * max(len(table), 1))(*table)
+    ctx = C.c_void_p()
+    _check(lib.adapm_init(C.byref(ctx), arr, len(table), C.byref(hp)))
+    return ctx
+
+
+def adapm_state_bytes(ctx) -> int:
+    return lib.adapm_state_bytes(ctx)
+
+
+def adapm_workspace_bytes(ctx) -> int:
+    return lib.adapm_workspace_bytes(ctx)
+
+
+def adapm_state_offsets(ctx, block: int):
+    """(L, R, m, v) byte offsets; None for an absent sub-buffer."""
+    o = [C.c_size_t() for _ in range(4)]
+    _check(lib.adapm_state_offsets(ctx, block, *[C.byref(x) for x in o]))
+    absent = C.c_size_t(-1).value
+    return tuple(None if x.value == absent else x.value for x in o)
+
+
+def adapm_state_init(ctx, state_ptr: int, stream: int = 0):
+    _check(lib.adapm_state_init(ctx, C.c_void_p(state_ptr), C.c_void_p(stream)))
+
+
+def adapm_step(ctx, params_ptrs, grads_ptrs, state_ptr: int, workspace_ptr: int, step: int, lr: float,
+               stream: int = 0):
+    """params_ptrs / grads_ptrs: ctypes arrays of c_void_p (see ptr_array)."""
+    _check(lib.adapm_step(ctx, params_ptrs, grads_ptrs, C.c_void_p(state_ptr), C.c_void_p(workspace_ptr),
+                          step, lr, C.c_void_p(stream)))
+
+
+def adapm_last_launch_count(ctx) -> int:
+    return lib.adapm_last_launch_count(ctx)
+
+
+def adapm_algorithmic_bytes(ctx, refresh_step: bool) -> float:
+    return lib.adapm_algorithmic_bytes(ctx, 1 if refresh_step else 0)
+
+
+def adapm_algorithmic_flops(ctx, refresh_step: bool) -> float:
+    return lib.adapm_algorithmic_flops(ctx, 1 if refresh_step else 0)
+
+
+def adapm_destroy(ctx):
+    lib.adapm_destroy(ctx)
+
+
+def ptr_array(ptrs: Sequence[int]):
+    return (C.c_void_p * max(len(ptrs), 1))(*ptrs)

@@ -1,0 +1,644 @@
+// Host side of the AdaPM step library: table validation, state / workspace layout,
+// the launch plan ("multi-tensor block scheduler") and the C ABI of include/adapm.h.
+//
+// adapm_init() walks the block table once and emits, for every phase of a step, one
+// device-resident work list covering all blocks; adapm_step() then enqueues a short,
+// fixed sequence of launches on the caller's stream.  Nothing here computes any part of
+// the update on the host.
+#include "../../include/adapm.h"
+#include "adapm_plan.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace adapm;
+
+namespace {
+
+thread_local std::string g_err;
+
+adapm_status_t fail(adapm_status_t code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess) return fail(ADAPM_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr size_t ALIGN = 256;
+size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+constexpr int EW_CHUNK = 8192;      // elements per workgroup of the update kernel
+constexpr int VS_CHUNK = 16384;     // elements per wavefront of the v-statistics kernel
+
+struct Layout {                      // byte offsets, -1 = absent
+  int64_t sL = -1, sR = -1, sm = -1, sv = -1;               // state
+  int64_t wLa = -1, wRa = -1, wLb = -1, wRb = -1;           // ws: ping-pong factors of Alg. 2
+  int64_t wP = -1, wS = -1, wGrr = -1, wGpr = -1, wGll = -1, wGlp = -1;
+  int64_t wG64 = -1, wCinv = -1, wC = -1;
+  int64_t nv = 0;
+};
+
+enum OpKind { OP_GEMM, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE };
+
+struct GemmList {
+  std::vector<GemmProblem> probs;
+  std::vector<GemmTile> tiles;
+  GemmProblem* d_probs = nullptr;
+  GemmTile* d_tiles = nullptr;
+};
+
+struct Op {
+  OpKind kind;
+  int index;        // GEMM: gemm list; UPDATE: 0 = full/none blocks, 1 = low-rank blocks
+  float cG, cC;     // UPDATE of low-rank blocks
+};
+
+template <class T>
+struct DevList {
+  std::vector<T> h;
+  T* d = nullptr;
+};
+
+Mat mat(int32_t space, int32_t block, int64_t off, int64_t s0, int64_t s1, int32_t dtype) {
+  Mat m;
+  m.ref = Ref{space, block, off};
+  m.s0 = s0; m.s1 = s1; m.dtype = dtype; m.pad = 0;
+  return m;
+}
+Mat none_mat() { return mat(SP_NONE, 0, 0, 0, 0, DT_F32); }
+
+}  // namespace
+
+struct adapm_ctx {
+  std::vector<adapm_block_t> table;
+  adapm_hparams_t hp;
+  std::vector<Layout> lay;
+  size_t state_bytes = 0, ws_bytes = 0;
+  int64_t off_partials = -1;
+
+  DevList<BlockDev> blocks;
+  DevList<EwItem> ew_main, ew_lr;
+  DevList<VsItem> vs;
+  DevList<VfItem> vf;
+  DevList<SketchItem> sk;
+  DevList<CholItem> chol;
+  std::vector<GemmList> gemms;
+  std::vector<Op> seq_common, seq_refresh, seq_project;
+
+  bool uploaded = false;
+  int device = -1;
+  char* arena = nullptr;
+  void** d_ptrs = nullptr;              // [2 * nblocks]: params then grads
+  void** h_stage = nullptr;             // pinned staging of the same
+  std::vector<void*> cached;            // last uploaded pointers
+  hipEvent_t stage_free = nullptr;
+  int64_t last_launches = 0;
+  int n_lowrank = 0;
+};
+
+namespace {
+
+int64_t num_v(const adapm_block_t& b) {
+  if (b.v_mode == ADAPM_V_ELEMENT) return b.rows * b.cols;
+  if (b.v_mode == ADAPM_V_ROWGROUP) return b.rows / b.v_group_rows;
+  return 1;
+}
+int64_t group_elems(const adapm_block_t& b) {
+  if (b.v_mode == ADAPM_V_ELEMENT) return 1;
+  if (b.v_mode == ADAPM_V_ROWGROUP) return (int64_t)b.v_group_rows * b.cols;
+  return b.rows * b.cols;
+}
+int esize(int32_t dt) { return dt == ADAPM_BF16 ? 2 : 4; }
+
+adapm_status_t validate(const adapm_block_t* t, int64_t n, const adapm_hparams_t* hp) {
+  if (!t || !hp) return fail(ADAPM_EINVAL, "null table or hparams");
+  if (n <= 0 || n > (1 << 24)) return fail(ADAPM_EINVAL, "nblocks %lld out of range", (long long)n);
+  if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f))
+    return fail(ADAPM_EINVAL, "beta1/beta2 must lie in [0,1)");
+  if (!(hp->eps >= 0.f) || !(hp->clip > 0.f)) return fail(ADAPM_EINVAL, "eps must be >= 0 and clip > 0");
+  if (hp->refresh_iters_K < 1 || hp->refresh_iters_K > 1024) return fail(ADAPM_EINVAL, "refresh_iters_K out of range");
+  if (hp->refresh_period_T < 1) return fail(ADAPM_EINVAL, "refresh_period_T must be >= 1");
+  if (hp->adam_debias != 0 && hp->adam_debias != 1) return fail(ADAPM_EINVAL, "adam_debias must be 0 or 1");
+  if (hp->bias_correction != 0 && hp->bias_correction != 1) return fail(ADAPM_EINVAL, "bias_correction must be 0 or 1");
+  if (hp->contraction < ADAPM_CONTRACT_AUTO || hp->contraction > ADAPM_CONTRACT_BF16X2)
+    return fail(ADAPM_EINVAL, "unknown contraction mode %d", hp->contraction);
+  for (int64_t i = 0; i < n; ++i) {
+    const adapm_block_t& b = t[i];
+    if (b.rows < 1 || b.cols < 1) return fail(ADAPM_EINVAL, "block %lld: rows/cols must be >= 1", (long long)i);
+    if (b.rows > (1ll << 31) || b.cols > (1ll << 31) || b.rows * b.cols >= (1ll << 40))
+      return fail(ADAPM_EINVAL, "block %lld: too large", (long long)i);
+    if ((b.param_dtype != ADAPM_F32 && b.param_dtype != ADAPM_BF16) ||
+        (b.grad_dtype != ADAPM_F32 && b.grad_dtype != ADAPM_BF16))
+      return fail(ADAPM_EINVAL, "block %lld: unknown dtype", (long long)i);
+    if (b.mom_mode < ADAPM_MOM_NONE || b.mom_mode > ADAPM_MOM_LOWRANK)
+      return fail(ADAPM_EINVAL, "block %lld: unknown mom_mode %d", (long long)i, b.mom_mode);
+    if (b.mom_mode == ADAPM_MOM_LOWRANK) {
+      if (b.cols < 2 || b.rows < 2) return fail(ADAPM_EINVAL, "block %lld: low-rank momentum needs a matrix", (long long)i);
+      if (b.rank < 1 || b.rank > b.rows || b.rank > b.cols)
+        return fail(ADAPM_EINVAL, "block %lld: rank %d not in [1, min(rows, cols)]", (long long)i, b.rank);
+      if (b.rows >= (1ll << 22) || b.cols >= (1ll << 22))
+        return fail(ADAPM_EINVAL, "block %lld: low-rank blocks are limited to 2^22 rows/cols", (long long)i);
+    }
+    if (b.v_mode < ADAPM_V_ELEMENT || b.v_mode > ADAPM_V_WHOLE)
+      return fail(ADAPM_EINVAL, "block %lld: unknown v_mode %d", (long long)i, b.v_mode);
+    if (b.v_mode == ADAPM_V_ROWGROUP && (b.v_group_rows < 1 || b.rows % b.v_group_rows != 0))
+      return fail(ADAPM_EINVAL, "block %lld: rows %% v_group_rows != 0", (long long)i);
+    if (!std::isfinite(b.lr_scale) || !std::isfinite(b.weight_decay))
+      return fail(ADAPM_EINVAL, "block %lld: lr_scale / weight_decay not finite", (long long)i);
+    if (hp->contraction == ADAPM_CONTRACT_BF16X2 && b.mom_mode == ADAPM_MOM_LOWRANK && b.grad_dtype != ADAPM_BF16)
+      return fail(ADAPM_EINVAL, "block %lld: BF16X2 contraction needs bf16 gradients", (long long)i);
+  }
+  return ADAPM_OK;
+}
+
+uint64_t mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+void add_tiles(GemmList& gl, uint32_t prob, int M, int N) {
+  for (int ti = 0; ti < (M + 63) / 64; ++ti)
+    for (int tj = 0; tj < (N + 63) / 64; ++tj) gl.tiles.push_back(GemmTile{prob, (uint16_t)ti, (uint16_t)tj});
+}
+
+void add_problem(GemmList& gl, const GemmProblem& p) {
+  gl.probs.push_back(p);
+  add_tiles(gl, (uint32_t)gl.probs.size() - 1, p.M, p.N);
+}
+
+GemmProblem problem(int M, int N) {
+  GemmProblem p;
+  memset(&p, 0, sizeof p);
+  p.A1 = p.B1 = p.A2 = p.B2 = p.X = p.Y = p.Out = none_mat();
+  p.M = M; p.N = N;
+  return p;
+}
+
+std::vector<double> effective_step_sizes(int K) {
+  // App. B: eta_k = 0.5 (1 + cos(pi k / K)), k = 1..K.  A zero step changes nothing and is skipped.
+  std::vector<double> out;
+  for (int k = 1; k <= K; ++k) {
+    const double eta = 0.5 * (1.0 + std::cos(M_PI * (double)k / (double)K));
+    if (eta != 0.0) out.push_back(eta);
+  }
+  return out;
+}
+
+// Lay out state / workspace and build every work list.
+void build_plan(adapm_ctx* c) {
+  const int64_t nb = (int64_t)c->table.size();
+  const adapm_hparams_t& hp = c->hp;
+  c->lay.assign(nb, Layout());
+  size_t so = 0, wo = 0;
+  const double b1 = hp.beta1;
+
+  for (int64_t i = 0; i < nb; ++i) {
+    const adapm_block_t& b = c->table[i];
+    Layout& L = c->lay[i];
+    const int64_t m = b.rows, n = b.cols, r = b.rank;
+    auto salloc = [&](size_t bytes) { int64_t o = (int64_t)so; so += align_up(bytes); return o; };
+    auto walloc = [&](size_t bytes) { int64_t o = (int64_t)wo; wo += align_up(bytes); return o; };
+    if (b.mom_mode == ADAPM_MOM_LOWRANK) {
+      L.sL = salloc(4 * m * r);
+      L.sR = salloc(4 * r * n);
+      L.wLa = walloc(4 * m * r); L.wRa = walloc(4 * r * n);
+      L.wLb = walloc(4 * m * r); L.wRb = walloc(4 * r * n);
+      L.wP = walloc(4 * m * r); L.wS = walloc(4 * r * n);
+      L.wGrr = walloc(4 * r * r); L.wGpr = walloc(4 * r * r);
+      L.wGll = walloc(4 * r * r); L.wGlp = walloc(4 * r * r);
+      L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
+      L.wC = walloc(4 * m * n);
+      c->n_lowrank++;
+    } else if (b.mom_mode == ADAPM_MOM_FULL) {
+      L.sm = salloc(4 * m * n);
+    }
+    L.nv = num_v(b);
+    L.sv = salloc(4 * L.nv);
+  }
+  c->state_bytes = so;
+
+  // device block table, element-wise chunks, v statistics
+  int64_t npart = 0;
+  for (int64_t i = 0; i < nb; ++i) {
+    const adapm_block_t& b = c->table[i];
+    const Layout& L = c->lay[i];
+    BlockDev d;
+    d.numel = b.rows * b.cols;
+    d.group_elems = group_elems(b);
+    d.off_m = L.sm; d.off_v = L.sv; d.off_C = L.wC;
+    d.param_dtype = b.param_dtype; d.grad_dtype = b.grad_dtype;
+    d.mom_mode = b.mom_mode; d.v_mode = b.v_mode;
+    d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
+    c->blocks.h.push_back(d);
+    auto& ew = (b.mom_mode == ADAPM_MOM_LOWRANK) ? c->ew_lr.h : c->ew_main.h;
+    for (int64_t s = 0; s < d.numel; s += EW_CHUNK)
+      ew.push_back(EwItem{s, (int32_t)i, (int32_t)std::min<int64_t>(EW_CHUNK, d.numel - s)});
+    if (b.v_mode != ADAPM_V_ELEMENT) {
+      const int64_t ge = d.group_elems;
+      for (int64_t g = 0; g < L.nv; ++g) {
+        if (ge <= VS_CHUNK) {
+          c->vs.h.push_back(VsItem{g * ge, g, (int32_t)i, (int32_t)ge, 1, 0});
+        } else {
+          const int64_t np = (ge + VS_CHUNK - 1) / VS_CHUNK;
+          c->vf.h.push_back(VfItem{npart, g, (int32_t)i, (int32_t)np});
+          for (int64_t p = 0; p < np; ++p)
+            c->vs.h.push_back(VsItem{g * ge + p * VS_CHUNK, npart + p, (int32_t)i,
+                                     (int32_t)std::min<int64_t>(VS_CHUNK, ge - p * VS_CHUNK), 0, 0});
+          npart += np;
+        }
+      }
+    }
+    if (b.mom_mode == ADAPM_MOM_LOWRANK && hp.seed != 0) {
+      SketchItem s;
+      s.off_R = L.sR; s.count = (int64_t)b.rank * b.cols;
+      s.key = mix64(hp.seed ^ mix64((uint64_t)i));
+      s.amp = (float)(std::sqrt(3.0) / (std::sqrt((double)b.cols) + std::sqrt((double)b.rank)) * std::ldexp(1.0, -23));
+      s.pad = 0;
+      c->sk.h.push_back(s);
+    }
+  }
+  if (npart > 0) { c->off_partials = (int64_t)wo; wo += align_up(8 * (size_t)npart); }
+  c->ws_bytes = wo;
+
+  // ---- common prefix: v statistics, then full / no-momentum blocks
+  if (!c->vs.h.empty()) c->seq_common.push_back(Op{OP_VSTAT, 0, 0, 0});
+  if (!c->vf.h.empty()) c->seq_common.push_back(Op{OP_VFINAL, 0, 0, 0});
+  if (!c->ew_main.h.empty()) c->seq_common.push_back(Op{OP_UPDATE, 0, 0, 0});
+  if (c->n_lowrank == 0) return;
+
+  // ---- low-rank blocks, F64 contraction path
+  const std::vector<double> etas = effective_step_sizes(hp.refresh_iters_K);
+  const int n_eff = (int)etas.size();
+  auto new_list = [&]() { c->gemms.emplace_back(); return (int)c->gemms.size() - 1; };
+
+  // refresh step ------------------------------------------------------------
+  {
+    std::vector<int> listA(n_eff), listB(n_eff);
+    for (int e = 0; e < n_eff; ++e) { listA[e] = new_list(); listB[e] = new_list(); }
+    const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list() : -1;
+    const int l_epi = new_list();
+    const int l_gram = hp.refresh_period_T > 1 ? new_list() : -1;
+    const int l_fin = (hp.refresh_period_T > 1 || n_eff > 0) ? new_list() : -1;
+    for (int64_t i = 0; i < nb; ++i) {
+      const adapm_block_t& b = c->table[i];
+      if (b.mom_mode != ADAPM_MOM_LOWRANK) continue;
+      const Layout& L = c->lay[i];
+      const int m = (int)b.rows, n = (int)b.cols, r = b.rank;
+      const int gdt = b.grad_dtype == ADAPM_BF16 ? DT_BF16 : DT_F32;
+      const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
+      const Mat Lp = mat(SP_STATE, 0, L.sL, r, 1, DT_F32), Rp = mat(SP_STATE, 0, L.sR, n, 1, DT_F32);
+      auto T = [](const Mat& a) { Mat t = a; t.s0 = a.s1; t.s1 = a.s0; return t; };
+      auto fL = [&](int which) { return mat(SP_WS, 0, which ? L.wLb : L.wLa, r, 1, DT_F32); };
+      auto fR = [&](int which) { return mat(SP_WS, 0, which ? L.wRb : L.wRa, n, 1, DT_F32); };
+      const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F32), S = mat(SP_WS, 0, L.wS, n, 1, DT_F32);
+      const Mat Grr = mat(SP_WS, 0, L.wGrr, r, 1, DT_F32), Gpr = mat(SP_WS, 0, L.wGpr, r, 1, DT_F32);
+      const Mat Gll = mat(SP_WS, 0, L.wGll, r, 1, DT_F32), Glp = mat(SP_WS, 0, L.wGlp, r, 1, DT_F32);
+      Mat Lc = Lp, Rc = Rp;
+      for (int e = 0; e < n_eff; ++e) {
+        const double eta = etas[e];
+        const Mat Ln = fL(e & 1), Rn = fR(e & 1);
+        GemmList& A = c->gemms[listA[e]];
+        GemmProblem p;
+        // thin products of Alg. 2 written without forming L R - m_t:
+        //   (L R - m_t) R^T = L (R R^T) - (1-b1) G R^T - b1 L' (R' R^T)
+        //   L^T (L R - m_t) = (L^T L) R - (1-b1) L^T G - b1 (L^T L') R'
+        p = problem(m, r); p.A1 = G; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = P; add_problem(A, p);
+        p = problem(r, n); p.A1 = T(Lc); p.B1 = G; p.K1 = m; p.a1 = 1; p.Out = S; add_problem(A, p);
+        p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Grr; add_problem(A, p);
+        p = problem(r, r); p.A1 = Rp; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Gpr; add_problem(A, p);
+        p = problem(r, r); p.A1 = T(Lc); p.B1 = Lc; p.K1 = m; p.a1 = 1; p.Out = Gll; add_problem(A, p);
+        p = problem(r, r); p.A1 = T(Lc); p.B1 = Lp; p.K1 = m; p.a1 = 1; p.Out = Glp; add_problem(A, p);
+        GemmList& B = c->gemms[listB[e]];
+        p = problem(m, r);
+        p.A1 = Lc; p.B1 = Grr; p.K1 = r; p.a1 = -eta;
+        p.A2 = Lp; p.B2 = Gpr; p.K2 = r; p.a2 = eta * b1;
+        p.X = Lc; p.g = 1.0; p.Y = P; p.d = eta * (1.0 - b1); p.Out = Ln;
+        add_problem(B, p);
+        p = problem(r, n);
+        p.A1 = Gll; p.B1 = Rc; p.K1 = r; p.a1 = -eta;
+        p.A2 = Glp; p.B2 = Rp; p.K2 = r; p.a2 = eta * b1;
+        p.X = Rc; p.g = 1.0; p.Y = S; p.d = eta * (1.0 - b1); p.Out = Rn;
+        add_problem(B, p);
+        Lc = Ln; Rc = Rn;
+      }
+      GemmProblem p;
+      if (l_pre >= 0) {      // no effective iteration but an in-place re-gauge ahead: work on a copy
+        p = problem(m, r); p.X = Lp; p.g = 1.0; p.Out = fL(0); add_problem(c->gemms[l_pre], p);
+        p = problem(r, n); p.X = Rp; p.g = 1.0; p.Out = fR(0); add_problem(c->gemms[l_pre], p);
+        Lc = fL(0); Rc = fR(0);
+      }
+      // m x n low-rank term of m^c (eq. 4): C = L'R' - L R, or L R without the correction
+      const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
+      p = problem(m, n);
+      if (hp.bias_correction) {
+        p.A1 = Lp; p.B1 = Rp; p.K1 = r; p.a1 = 1.0;
+        p.A2 = Lc; p.B2 = Rc; p.K2 = r; p.a2 = -1.0;
+      } else {
+        p.A1 = Lc; p.B1 = Rc; p.K1 = r; p.a1 = 1.0;
+      }
+      p.Out = C;
+      add_problem(c->gemms[l_epi], p);
+      if (hp.refresh_period_T > 1) {
+        const Mat G64 = mat(SP_WS, 0, L.wG64, r, 1, DT_F64), Cinv = mat(SP_WS, 0, L.wCinv, r, 1, DT_F64);
+        p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1.0; p.Out = G64;
+        add_problem(c->gemms[l_gram], p);
+        c->chol.h.push_back(CholItem{L.wG64, L.wCinv, r, 0});
+        p = problem(r, n); p.A1 = Cinv; p.B1 = Rc; p.K1 = r; p.a1 = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
+        p = problem(m, r); p.A1 = Lc; p.B1 = G64; p.K1 = r; p.a1 = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
+      } else if (n_eff > 0) {
+        p = problem(m, r); p.X = Lc; p.g = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
+        p = problem(r, n); p.X = Rc; p.g = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
+      }
+    }
+    for (int e = 0; e < n_eff; ++e) {
+      c->seq_refresh.push_back(Op{OP_GEMM, listA[e], 0, 0});
+      c->seq_refresh.push_back(Op{OP_GEMM, listB[e], 0, 0});
+    }
+    if (l_pre >= 0) c->seq_refresh.push_back(Op{OP_GEMM, l_pre, 0, 0});
+    c->seq_refresh.push_back(Op{OP_GEMM, l_epi, 0, 0});
+    const float cG = hp.bias_correction ? 1.f : 0.f;
+    const float cC = hp.bias_correction ? (float)(b1 / (1.0 - b1)) : 1.f;
+    c->seq_refresh.push_back(Op{OP_UPDATE, 1, cG, cC});
+    if (l_gram >= 0) {
+      c->seq_refresh.push_back(Op{OP_GEMM, l_gram, 0, 0});
+      c->seq_refresh.push_back(Op{OP_CHOL, 0, 0, 0});
+    }
+    if (l_fin >= 0) c->seq_refresh.push_back(Op{OP_GEMM, l_fin, 0, 0});
+  }
+
+  // projection step (T > 1, R = Q held with orthonormal rows) ----------------
+  if (hp.refresh_period_T > 1) {
+    const int l_p = new_list(), l_d = new_list(), l_l = new_list(), l_c = new_list();
+    for (int64_t i = 0; i < nb; ++i) {
+      const adapm_block_t& b = c->table[i];
+      if (b.mom_mode != ADAPM_MOM_LOWRANK) continue;
+      const Layout& L = c->lay[i];
+      const int m = (int)b.rows, n = (int)b.cols, r = b.rank;
+      const int gdt = b.grad_dtype == ADAPM_BF16 ? DT_BF16 : DT_F32;
+      const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
+      const Mat Ls = mat(SP_STATE, 0, L.sL, r, 1, DT_F32), Q = mat(SP_STATE, 0, L.sR, n, 1, DT_F32);
+      Mat Qt = Q; Qt.s0 = Q.s1; Qt.s1 = Q.s0;
+      const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F32), D = mat(SP_WS, 0, L.wLa, r, 1, DT_F32);
+      const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
+      GemmProblem p;
+      p = problem(m, r); p.A1 = G; p.B1 = Qt; p.K1 = n; p.a1 = 1.0; p.Out = P; add_problem(c->gemms[l_p], p);
+      // L_t = b1 L' + (1-b1) G Q^T;  m^c = G + b1 (L' - G Q^T) Q   (or L_t Q without the correction)
+      p = problem(m, r); p.X = Ls; p.Y = P; p.Out = D;
+      if (hp.bias_correction) { p.g = b1; p.d = -b1; } else { p.g = b1; p.d = 1.0 - b1; }
+      add_problem(c->gemms[l_d], p);
+      p = problem(m, r); p.X = Ls; p.g = b1; p.Y = P; p.d = 1.0 - b1; p.Out = Ls; add_problem(c->gemms[l_l], p);
+      p = problem(m, n); p.A1 = D; p.B1 = Q; p.K1 = r; p.a1 = 1.0; p.Out = C; add_problem(c->gemms[l_c], p);
+    }
+    c->seq_project.push_back(Op{OP_GEMM, l_p, 0, 0});
+    c->seq_project.push_back(Op{OP_GEMM, l_d, 0, 0});
+    c->seq_project.push_back(Op{OP_GEMM, l_l, 0, 0});
+    c->seq_project.push_back(Op{OP_GEMM, l_c, 0, 0});
+    c->seq_project.push_back(Op{OP_UPDATE, 1, hp.bias_correction ? 1.f : 0.f, 1.f});
+  }
+}
+
+template <class T>
+size_t bytes_of(const std::vector<T>& v) { return align_up(v.size() * sizeof(T)); }
+
+adapm_status_t ensure_uploaded(adapm_ctx* c) {
+  if (c->uploaded) return ADAPM_OK;
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  const size_t nb = c->table.size();
+  size_t total = bytes_of(c->blocks.h) + bytes_of(c->ew_main.h) + bytes_of(c->ew_lr.h) + bytes_of(c->vs.h) +
+                 bytes_of(c->vf.h) + bytes_of(c->sk.h) + bytes_of(c->chol.h) + align_up(2 * nb * sizeof(void*));
+  for (auto& g : c->gemms) total += bytes_of(g.probs) + bytes_of(g.tiles);
+  HIP_TRY(hipMalloc((void**)&c->arena, total));
+  size_t off = 0;
+  hipError_t err = hipSuccess;
+  auto put = [&](const void* src, size_t n) -> void* {
+    void* dst = c->arena + off;
+    if (n && err == hipSuccess) err = hipMemcpy(dst, src, n, hipMemcpyHostToDevice);
+    off += align_up(n);
+    return dst;
+  };
+#define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
+  PUT_LIST(c->blocks); PUT_LIST(c->ew_main); PUT_LIST(c->ew_lr); PUT_LIST(c->vs); PUT_LIST(c->vf);
+  PUT_LIST(c->sk); PUT_LIST(c->chol);
+#undef PUT_LIST
+  for (auto& g : c->gemms) {
+    g.d_probs = (GemmProblem*)put(g.probs.data(), g.probs.size() * sizeof(GemmProblem));
+    g.d_tiles = (GemmTile*)put(g.tiles.data(), g.tiles.size() * sizeof(GemmTile));
+  }
+  c->d_ptrs = (void**)(c->arena + off);
+  off += align_up(2 * nb * sizeof(void*));
+  if (err != hipSuccess) return fail(ADAPM_EHIP, "plan upload: %s", hipGetErrorString(err));
+  HIP_TRY(hipHostMalloc((void**)&c->h_stage, 2 * nb * sizeof(void*), hipHostMallocDefault));
+  HIP_TRY(hipEventCreateWithFlags(&c->stage_free, hipEventDisableTiming));
+  c->cached.assign(2 * nb, nullptr);
+  c->device = dev;
+  c->uploaded = true;
+  return ADAPM_OK;
+}
+
+bool is_refresh(const adapm_ctx* c, int64_t step) {
+  return c->hp.refresh_period_T <= 1 || (step - 1) % c->hp.refresh_period_T == 0;
+}
+
+}  // namespace
+
+// ===========================================================================
+// C ABI
+// ===========================================================================
+extern "C" {
+
+const char* adapm_last_error(void) { return g_err.c_str(); }
+
+adapm_status_t adapm_init(adapm_ctx** out, const adapm_block_t* table, int64_t nblocks, const adapm_hparams_t* hp) {
+  if (!out) return fail(ADAPM_EINVAL, "out is null");
+  *out = nullptr;
+  adapm_status_t st = validate(table, nblocks, hp);
+  if (st != ADAPM_OK) return st;
+  adapm_ctx* c = new (std::nothrow) adapm_ctx();
+  if (!c) return fail(ADAPM_ENOMEM, "out of host memory");
+  try {
+    c->table.assign(table, table + nblocks);
+    c->hp = *hp;
+    build_plan(c);
+  } catch (const std::bad_alloc&) {
+    delete c;
+    return fail(ADAPM_ENOMEM, "out of host memory while planning");
+  }
+  *out = c;
+  return ADAPM_OK;
+}
+
+size_t adapm_state_bytes(const adapm_ctx* c) { return c ? c->state_bytes : 0; }
+size_t adapm_workspace_bytes(const adapm_ctx* c) { return c ? c->ws_bytes : 0; }
+
+adapm_status_t adapm_state_offsets(const adapm_ctx* c, int64_t block, size_t* L, size_t* R, size_t* m, size_t* v) {
+  if (!c) return fail(ADAPM_EINVAL, "ctx is null");
+  if (block < 0 || block >= (int64_t)c->table.size()) return fail(ADAPM_EINVAL, "block index out of range");
+  const Layout& l = c->lay[block];
+  if (L) *L = (size_t)l.sL;
+  if (R) *R = (size_t)l.sR;
+  if (m) *m = (size_t)l.sm;
+  if (v) *v = (size_t)l.sv;
+  return ADAPM_OK;
+}
+
+adapm_status_t adapm_state_init(adapm_ctx* c, void* state_dev, void* stream) {
+  if (!c) return fail(ADAPM_EINVAL, "ctx is null");
+  if (!state_dev && c->state_bytes) return fail(ADAPM_EINVAL, "state_dev is null");
+  if ((uintptr_t)state_dev & 15) return fail(ADAPM_EINVAL, "state_dev must be 16-byte aligned");
+  adapm_status_t st = ensure_uploaded(c);
+  if (st != ADAPM_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  launch_fill_zero(state_dev, c->state_bytes, s);
+  launch_sketch(c->sk.d, (int64_t)c->sk.h.size(), (char*)state_dev, s);
+  HIP_TRY(hipGetLastError());
+  return ADAPM_OK;
+}
+
+adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* const* grads_dev, void* state_dev,
+                          void* workspace_dev, int64_t step, float lr, void* stream) {
+  if (!c) return fail(ADAPM_EINVAL, "ctx is null");
+  if (step < 1) return fail(ADAPM_ESTATE, "step must be >= 1 (got %lld)", (long long)step);
+  if (!params_dev || !grads_dev) return fail(ADAPM_EINVAL, "params_dev / grads_dev is null");
+  if (!state_dev || ((uintptr_t)state_dev & 15)) return fail(ADAPM_EINVAL, "state_dev is null or misaligned");
+  if (c->ws_bytes && (!workspace_dev || ((uintptr_t)workspace_dev & 255)))
+    return fail(ADAPM_EINVAL, "workspace_dev is null or not 256-byte aligned");
+  const size_t nb = c->table.size();
+  for (size_t i = 0; i < nb; ++i) {
+    if (!params_dev[i] || !grads_dev[i]) return fail(ADAPM_EINVAL, "block %zu: null parameter or gradient pointer", i);
+    if (((uintptr_t)params_dev[i] | (uintptr_t)grads_dev[i]) & 15)
+      return fail(ADAPM_EINVAL, "block %zu: parameter / gradient pointer not 16-byte aligned", i);
+  }
+  adapm_status_t st = ensure_uploaded(c);
+  if (st != ADAPM_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+
+  // pointer tables: re-sent only when the caller's pointers changed
+  bool changed = false;
+  for (size_t i = 0; i < nb && !changed; ++i)
+    changed = c->cached[i] != params_dev[i] || c->cached[nb + i] != (void*)grads_dev[i];
+  if (changed) {
+    HIP_TRY(hipEventSynchronize(c->stage_free));
+    for (size_t i = 0; i < nb; ++i) {
+      c->h_stage[i] = c->cached[i] = params_dev[i];
+      c->h_stage[nb + i] = c->cached[nb + i] = (void*)grads_dev[i];
+    }
+    HIP_TRY(hipMemcpyAsync(c->d_ptrs, c->h_stage, 2 * nb * sizeof(void*), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipEventRecord(c->stage_free, s));
+  }
+
+  Bases bs;
+  bs.state = (char*)state_dev;
+  bs.ws = (char*)workspace_dev;
+  bs.params = (void* const*)c->d_ptrs;
+  bs.grads = (const void* const*)(c->d_ptrs + nb);
+
+  StepScalars sc;
+  sc.beta1 = c->hp.beta1; sc.beta2 = c->hp.beta2; sc.eps = c->hp.eps; sc.clip = c->hp.clip;
+  sc.lr = lr;
+  sc.inv_debias_m = sc.inv_debias_v = 1.f;
+  if (c->hp.adam_debias) {
+    sc.inv_debias_m = (float)(1.0 / (1.0 - std::pow((double)c->hp.beta1, (double)step)));
+    sc.inv_debias_v = (float)(1.0 / (1.0 - std::pow((double)c->hp.beta2, (double)step)));
+  }
+  sc.cG = sc.cC = 0.f;
+
+  int64_t launches = 0;
+  auto run = [&](const std::vector<Op>& seq) {
+    for (const Op& op : seq) {
+      switch (op.kind) {
+        case OP_VSTAT:
+          launch_vstat(c->blocks.d, c->vs.d, (int64_t)c->vs.h.size(),
+                       c->off_partials >= 0 ? (double*)(bs.ws + c->off_partials) : nullptr, bs, sc.beta2, s);
+          break;
+        case OP_VFINAL:
+          launch_vfinal(c->blocks.d, c->vf.d, (int64_t)c->vf.h.size(), (const double*)(bs.ws + c->off_partials), bs,
+                        sc.beta2, s);
+          break;
+        case OP_UPDATE: {
+          StepScalars x = sc;
+          x.cG = op.cG; x.cC = op.cC;
+          if (op.index == 0) launch_update(c->blocks.d, c->ew_main.d, (int64_t)c->ew_main.h.size(), bs, x, s);
+          else launch_update(c->blocks.d, c->ew_lr.d, (int64_t)c->ew_lr.h.size(), bs, x, s);
+          break;
+        }
+        case OP_GEMM: {
+          const GemmList& g = c->gemms[op.index];
+          launch_gemm64(g.d_probs, g.d_tiles, (int64_t)g.tiles.size(), bs, s);
+          break;
+        }
+        case OP_CHOL:
+          launch_chol(c->chol.d, (int64_t)c->chol.h.size(), bs, s);
+          break;
+      }
+      ++launches;
+    }
+  };
+  run(c->seq_common);
+  if (c->n_lowrank) run(is_refresh(c, step) ? c->seq_refresh : c->seq_project);
+  c->last_launches = launches;
+  HIP_TRY(hipGetLastError());
+  return ADAPM_OK;
+}
+
+int64_t adapm_last_launch_count(const adapm_ctx* c) { return c ? c->last_launches : 0; }
+
+double adapm_algorithmic_bytes(const adapm_ctx* c, int32_t refresh_step) {
+  if (!c) return 0.0;
+  const bool refresh = refresh_step != 0 || c->hp.refresh_period_T <= 1;
+  double tot = 0.0;
+  for (const adapm_block_t& b : c->table) {
+    const double mn = (double)b.rows * (double)b.cols;
+    tot += mn * (esize(b.grad_dtype) + 2.0 * esize(b.param_dtype));
+    if (b.mom_mode == ADAPM_MOM_FULL) tot += 8.0 * mn;
+    if (b.mom_mode == ADAPM_MOM_LOWRANK) {
+      const double m = (double)b.rows, n = (double)b.cols, r = b.rank;
+      tot += refresh ? 8.0 * (m + n) * r : 8.0 * m * r + 4.0 * r * n;
+    }
+    tot += 8.0 * (double)num_v(b);
+  }
+  return tot;
+}
+
+double adapm_algorithmic_flops(const adapm_ctx* c, int32_t refresh_step) {
+  if (!c) return 0.0;
+  const bool refresh = refresh_step != 0 || c->hp.refresh_period_T <= 1;
+  const double n_eff = (double)effective_step_sizes(c->hp.refresh_iters_K).size();
+  double tot = 0.0;
+  for (const adapm_block_t& b : c->table) {
+    if (b.mom_mode != ADAPM_MOM_LOWRANK) continue;
+    const double m = (double)b.rows, n = (double)b.cols, r = b.rank;
+    if (refresh) tot += n_eff * (4.0 * m * n * r + 8.0 * r * r * (m + n)) + (c->hp.bias_correction ? 4.0 : 2.0) * m * n * r;
+    else tot += 4.0 * m * n * r;
+  }
+  return tot;
+}
+
+void adapm_destroy(adapm_ctx* c) {
+  if (!c) return;
+  if (c->uploaded) {
+    if (c->stage_free) { (void)hipEventSynchronize(c->stage_free); (void)hipEventDestroy(c->stage_free); }
+    if (c->h_stage) (void)hipHostFree(c->h_stage);
+    if (c->arena) (void)hipFree(c->arena);
+  }
+  delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,137 @@
+// Internal structures shared by the host planner and the gfx950 kernels.
+//
+// The host turns the block table into a fixed list of launches at adapm_init();
+// every launch carries a device-resident work list, so a step is a short walk over
+// that list (the "multi-tensor block scheduler").  Buffers are named by
+// (space, block, byte offset) and resolved on the device against the base pointers
+// handed to adapm_step().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adapm {
+
+enum Space : int32_t { SP_STATE = 0, SP_WS = 1, SP_GRAD = 2, SP_PARAM = 3, SP_NONE = 4 };
+enum DType : int32_t { DT_F32 = 0, DT_BF16 = 1, DT_F64 = 2 };
+enum VMode : int32_t { VM_ELEMENT = 0, VM_ROWGROUP = 1, VM_WHOLE = 2 };
+enum MMode : int32_t { MM_NONE = 0, MM_FULL = 1, MM_LOWRANK = 2 };
+
+struct Ref {
+  int32_t space;
+  int32_t block;   // used by SP_GRAD / SP_PARAM
+  int64_t off;     // bytes from the base
+};
+
+struct Bases {
+  char* state;
+  char* ws;
+  const void* const* grads;   // device array of nblocks pointers
+  void* const* params;        // device array of nblocks pointers
+};
+
+__device__ __forceinline__ char* resolve(const Ref& r, const Bases& b) {
+  switch (r.space) {
+    case SP_STATE: return b.state + r.off;
+    case SP_WS: return b.ws + r.off;
+    case SP_GRAD: return (char*)b.grads[r.block] + r.off;
+    case SP_PARAM: return (char*)b.params[r.block] + r.off;
+    default: return nullptr;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// fp64-accumulate strided two-product GEMM
+//   Out[i,j] = a1 * sum_k A1[i,k] B1[k,j] + a2 * sum_k A2[i,k] B2[k,j] + g * X[i,j] + d * Y[i,j]
+// element (i,j) of a matrix lives at base + (i*s0 + j*s1) * sizeof(dtype)
+// ---------------------------------------------------------------------------
+struct Mat {
+  Ref ref;
+  int64_t s0, s1;
+  int32_t dtype;
+  int32_t pad;
+};
+
+struct GemmProblem {
+  Mat A1, B1, A2, B2, X, Y, Out;
+  int32_t M, N, K1, K2;
+  double a1, a2, g, d;
+};
+
+struct GemmTile {
+  uint32_t prob;
+  uint16_t ti, tj;   // 64 x 64 output tile coordinates
+};
+
+// ---------------------------------------------------------------------------
+// element-wise update (Alg. 1 last line, eq. 5, per-element v) and v statistics
+// ---------------------------------------------------------------------------
+struct BlockDev {
+  int64_t numel;
+  int64_t group_elems;   // elements sharing one v (1 for per-element v)
+  int64_t off_m;         // state byte offset of m (full momentum) or -1
+  int64_t off_v;         // state byte offset of v
+  int64_t off_C;         // workspace byte offset of the m x n low-rank term, or -1
+  int32_t param_dtype, grad_dtype, mom_mode, v_mode;
+  float lr_scale, wd;
+};
+
+struct EwItem {          // one workgroup: `count` elements from `start` of `block`
+  int64_t start;
+  int32_t block;
+  int32_t count;
+};
+
+struct VsItem {          // one wavefront: sum of g^2 over [start, start+count)
+  int64_t start;
+  int64_t out;           // direct: group index; else index into the partial-sum array
+  int32_t block;
+  int32_t count;
+  int32_t direct;        // 1: this piece is the whole group, finish v here
+  int32_t pad;
+};
+
+struct VfItem {          // one thread: fold the partial sums of one group
+  int64_t part0;
+  int64_t group;
+  int32_t block;
+  int32_t nparts;
+};
+
+struct StepScalars {
+  float beta1, beta2, eps, clip;
+  float lr;
+  float inv_debias_m, inv_debias_v;   // 1/(1-beta1^t), 1/(1-beta2^t) or 1
+  float cG, cC;                       // low-rank blocks: m^c = cG * G + cC * C
+};
+
+struct SketchItem {      // seeded start R_0 of one low-rank block
+  int64_t off_R;         // state byte offset
+  int64_t count;         // rank * cols
+  uint64_t key;
+  float amp;
+  int32_t pad;
+};
+
+// ---------------------------------------------------------------------------
+// fp64 Cholesky + triangular inverse used by the orthonormalisation of R (T > 1)
+// ---------------------------------------------------------------------------
+struct CholItem {
+  int64_t off_gram;      // ws: r x r fp64 Gram matrix R R^T, overwritten by its lower factor C (upper part zeroed)
+  int64_t off_inv;       // ws: r x r fp64, receives C^-1 (lower triangular, upper part zeroed)
+  int32_t r;
+  int32_t pad;
+};
+
+// launchers (defined next to their kernels)
+void launch_gemm64(const GemmProblem* probs, const GemmTile* tiles, int64_t ntiles, Bases b, hipStream_t s);
+void launch_vstat(const BlockDev* blocks, const VsItem* items, int64_t nitems, double* partials, Bases b,
+                  float beta2, hipStream_t s);
+void launch_vfinal(const BlockDev* blocks, const VfItem* items, int64_t nitems, const double* partials, Bases b,
+                   float beta2, hipStream_t s);
+void launch_update(const BlockDev* blocks, const EwItem* items, int64_t nitems, Bases b, StepScalars sc,
+                   hipStream_t s);
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+void launch_sketch(const SketchItem* items, int64_t nitems, char* state, hipStream_t s);
+void launch_chol(const CholItem* items, int64_t nitems, Bases b, hipStream_t s);
+
+}  // namespace adapm

@@ -1,0 +1,54 @@
+// fp64 Cholesky factorisation and triangular inverse of the r x r Gram matrix R R^T.
+// Used after Alg. 2 when the refresh period T exceeds 1: with R R^T = C C^T the factors are
+// re-expressed as (L C, C^-1 R), which keeps the product L R and makes the rows of R
+// orthonormal, so that the least-squares fit of L with R held is a plain projection.
+// One workgroup per low-rank block; fp64 keeps the orthonormality error at fp32 rounding
+// level whatever the conditioning of R.
+#include "adapm_plan.h"
+
+namespace adapm {
+
+namespace {
+
+__global__ __launch_bounds__(256) void chol_inv_kernel(const CholItem* __restrict__ items, Bases b) {
+  const CholItem it = items[blockIdx.x];
+  const int r = it.r, tid = threadIdx.x;
+  double* A = reinterpret_cast<double*>(b.ws + it.off_gram);
+  double* X = reinterpret_cast<double*>(b.ws + it.off_inv);
+  // right-looking Cholesky, lower triangle, in place
+  for (int j = 0; j < r; ++j) {
+    const double d = sqrt(A[(int64_t)j * r + j]);
+    __syncthreads();
+    for (int i = j + tid; i < r; i += 256) A[(int64_t)i * r + j] = (i == j) ? d : A[(int64_t)i * r + j] / d;
+    __syncthreads();
+    const int rem = r - j - 1;                       // trailing rows j+1 .. r-1
+    for (int64_t e = tid; e < (int64_t)rem * rem; e += 256) {
+      const int i = j + 1 + (int)(e / rem), k = j + 1 + (int)(e % rem);
+      if (k <= i) A[(int64_t)i * r + k] -= A[(int64_t)i * r + j] * A[(int64_t)k * r + j];
+    }
+    __syncthreads();
+  }
+  for (int64_t e = tid; e < (int64_t)r * r; e += 256) {
+    const int i = (int)(e / r), k = (int)(e % r);
+    if (k > i) A[e] = 0.0;
+  }
+  __syncthreads();
+  // X = C^-1 by forward substitution, one column per thread
+  for (int j = tid; j < r; j += 256) {
+    for (int a = 0; a < r; ++a) {
+      double s = (a == j) ? 1.0 : 0.0;
+      if (a < j) { X[(int64_t)a * r + j] = 0.0; continue; }
+      for (int c = j; c < a; ++c) s -= A[(int64_t)a * r + c] * X[(int64_t)c * r + j];
+      X[(int64_t)a * r + j] = s / A[(int64_t)a * r + a];
+    }
+  }
+}
+
+}  // namespace
+
+void launch_chol(const CholItem* items, int64_t nitems, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(chol_inv_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
+}
+
+}  // namespace adapm

@@ -1,0 +1,263 @@
+// Streaming kernels of the AdaPM step: blockwise second-moment statistics,
+// the fused element-wise update, state initialisation.
+//
+//  - v statistics: v_g <- beta2 v_g + (1-beta2) mean_{i in g} G_i^2 (Alg. 1 "v_t" with the
+//    blockwise mean of Sec. 5.1.3).  A group is a contiguous run of elements (whole rows),
+//    reduced by one wavefront with DPP-style shuffles; long groups go through fixed-order
+//    partial sums (deterministic, no float atomics).
+//  - update: m <- (1-beta1) G + beta1 m (eq. 5) or m^c = cG G + cC C for low-rank blocks
+//    (eq. 4 rewritten as m^c = G + beta1/(1-beta1) (L_{t-1}R_{t-1} - L_t R_t)), per-element v,
+//    then W <- W - lr (clip(m^c / (sqrt(v) + eps)) + lambda W)  (Alg. 1 last line).
+#include "adapm_plan.h"
+
+namespace adapm {
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ void load8(const char* base, int dtype, int64_t e, float out[8]) {
+  if (dtype == DT_BF16) {
+    uint4 q = *reinterpret_cast<const uint4*>(base + e * 2);
+    uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[2 * i] = __uint_as_float(w[i] << 16);
+      out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  } else {
+    float4 a = *reinterpret_cast<const float4*>(base + e * 4);
+    float4 b = *reinterpret_cast<const float4*>(base + e * 4 + 16);
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+    out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+  }
+}
+
+__device__ __forceinline__ void store8(char* base, int dtype, int64_t e, const float in[8]) {
+  if (dtype == DT_BF16) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      w[i] = (uint32_t)f32_to_bf16_rne(in[2 * i]) | ((uint32_t)f32_to_bf16_rne(in[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4*>(base + e * 2) = make_uint4(w[0], w[1], w[2], w[3]);
+  } else {
+    *reinterpret_cast<float4*>(base + e * 4) = make_float4(in[0], in[1], in[2], in[3]);
+    *reinterpret_cast<float4*>(base + e * 4 + 16) = make_float4(in[4], in[5], in[6], in[7]);
+  }
+}
+
+__device__ __forceinline__ float load1(const char* base, int dtype, int64_t e) {
+  return dtype == DT_BF16 ? bf16_to_f32(*reinterpret_cast<const uint16_t*>(base + e * 2))
+                          : *reinterpret_cast<const float*>(base + e * 4);
+}
+
+__device__ __forceinline__ void store1(char* base, int dtype, int64_t e, float x) {
+  if (dtype == DT_BF16) *reinterpret_cast<uint16_t*>(base + e * 2) = f32_to_bf16_rne(x);
+  else *reinterpret_cast<float*>(base + e * 4) = x;
+}
+
+// ---------------------------------------------------------------------------
+// v statistics
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+
+__global__ __launch_bounds__(256) void vstat_kernel(const BlockDev* __restrict__ blocks,
+                                                    const VsItem* __restrict__ items, int64_t nitems,
+                                                    double* __restrict__ partials, Bases b, float beta2) {
+  const int lane = threadIdx.x & 63;
+  const int64_t it = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (it >= nitems) return;
+  const VsItem item = items[it];
+  const BlockDev blk = blocks[item.block];
+  const char* G = (const char*)b.grads[item.block];
+  const int64_t s = item.start, e = item.start + item.count;
+  const int64_t a0 = min((s + 7) & ~(int64_t)7, e), a1 = max(e & ~(int64_t)7, a0);
+  float acc = 0.f;
+  for (int64_t i = s + lane; i < a0; i += 64) { float g = load1(G, blk.grad_dtype, i); acc += g * g; }
+  for (int64_t i = a0 + (int64_t)lane * 8; i < a1; i += 512) {
+    float g[8];
+    load8(G, blk.grad_dtype, i, g);
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += g[k] * g[k];
+    acc += t;
+  }
+  for (int64_t i = a1 + lane; i < e; i += 64) { float g = load1(G, blk.grad_dtype, i); acc += g * g; }
+  double sum = wave_sum((double)acc);
+  if (lane == 0) {
+    if (item.direct) {
+      float* v = reinterpret_cast<float*>(b.state + blk.off_v) + item.out;
+      *v = (float)((double)beta2 * (double)*v + (1.0 - (double)beta2) * (sum / (double)blk.group_elems));
+    } else {
+      partials[item.out] = sum;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void vfinal_kernel(const BlockDev* __restrict__ blocks,
+                                                     const VfItem* __restrict__ items, int64_t nitems,
+                                                     const double* __restrict__ partials, Bases b, float beta2) {
+  const int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (it >= nitems) return;
+  const VfItem item = items[it];
+  const BlockDev blk = blocks[item.block];
+  double sum = 0.0;
+  for (int p = 0; p < item.nparts; ++p) sum += partials[item.part0 + p];
+  float* v = reinterpret_cast<float*>(b.state + blk.off_v) + item.group;
+  *v = (float)((double)beta2 * (double)*v + (1.0 - (double)beta2) * (sum / (double)blk.group_elems));
+}
+
+// ---------------------------------------------------------------------------
+// fused update
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float update_one(float w, float mc, float v, const StepScalars& sc, float lrs, float wd) {
+  float u = (mc * sc.inv_debias_m) / (sqrtf(v * sc.inv_debias_v) + sc.eps);
+  u = fminf(fmaxf(u, -sc.clip), sc.clip);
+  return w - lrs * (u + wd * w);
+}
+
+__global__ __launch_bounds__(256) void update_kernel(const BlockDev* __restrict__ blocks,
+                                                     const EwItem* __restrict__ items, Bases b, StepScalars sc) {
+  const EwItem item = items[blockIdx.x];
+  const BlockDev blk = blocks[item.block];
+  const char* G = (const char*)b.grads[item.block];
+  char* W = (char*)b.params[item.block];
+  float* m = blk.off_m >= 0 ? reinterpret_cast<float*>(b.state + blk.off_m) : nullptr;
+  float* v = reinterpret_cast<float*>(b.state + blk.off_v);
+  const float* C = blk.off_C >= 0 ? reinterpret_cast<const float*>(b.ws + blk.off_C) : nullptr;
+  const float lrs = sc.lr * blk.lr_scale, wd = blk.wd;
+  const float ob1 = 1.f - sc.beta1, ob2 = 1.f - sc.beta2;
+  const int nvec = (item.count + 7) >> 3;
+  const int64_t end = item.start + item.count;
+  for (int iv = threadIdx.x; iv < nvec; iv += 256) {
+    const int64_t e = item.start + (int64_t)iv * 8;
+    if (e + 8 <= end) {
+      float g[8], w[8], vv[8], mc[8];
+      load8(G, blk.grad_dtype, e, g);
+      load8(W, blk.param_dtype, e, w);
+      if (blk.v_mode == VM_ELEMENT) {
+        load8((const char*)v, DT_F32, e, vv);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) vv[k] = sc.beta2 * vv[k] + ob2 * g[k] * g[k];
+        store8((char*)v, DT_F32, e, vv);
+      } else {
+        const int64_t g0 = e / blk.group_elems, g1 = (e + 7) / blk.group_elems;
+        if (g0 == g1) {
+          const float x = v[g0];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) vv[k] = x;
+        } else {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) vv[k] = v[(e + k) / blk.group_elems];
+        }
+      }
+      if (blk.mom_mode == MM_FULL) {            // full momentum, eq. 5
+        load8((const char*)m, DT_F32, e, mc);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) mc[k] = ob1 * g[k] + sc.beta1 * mc[k];
+        store8((char*)m, DT_F32, e, mc);
+      } else if (blk.mom_mode == MM_LOWRANK) {     // low-rank: m^c = cG G + cC C
+        load8((const char*)C, DT_F32, e, mc);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) mc[k] = sc.cG * g[k] + sc.cC * mc[k];
+      } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) mc[k] = g[k];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) w[k] = update_one(w[k], mc[k], vv[k], sc, lrs, wd);
+      store8(W, blk.param_dtype, e, w);
+    } else {
+      for (int64_t i = e; i < end; ++i) {
+        const float g = load1(G, blk.grad_dtype, i);
+        const float w = load1(W, blk.param_dtype, i);
+        float vv;
+        if (blk.v_mode == VM_ELEMENT) {
+          vv = sc.beta2 * v[i] + ob2 * g * g;
+          v[i] = vv;
+        } else {
+          vv = v[i / blk.group_elems];
+        }
+        float mc;
+        if (blk.mom_mode == MM_FULL) { mc = ob1 * g + sc.beta1 * m[i]; m[i] = mc; }
+        else if (blk.mom_mode == MM_LOWRANK) mc = sc.cG * g + sc.cC * C[i];
+        else mc = g;
+        store1(W, blk.param_dtype, i, update_one(w, mc, vv, sc, lrs, wd));
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// state initialisation
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* p, int64_t n16) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {   // SplitMix64 finaliser
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// R_0[i] = fp32(k_i) * amp,  k_i = (mix64(key + i) >> 40) - 2^23: a counter-based uniform sketch.
+__global__ __launch_bounds__(256) void sketch_kernel(const SketchItem* __restrict__ items, char* state) {
+  const SketchItem it = items[blockIdx.y];
+  float* R = reinterpret_cast<float*>(state + it.off_R);
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < it.count; i += (int64_t)gridDim.x * 256) {
+    const int32_t k = (int32_t)(mix64(it.key + (uint64_t)i) >> 40) - (1 << 23);
+    R[i] = __fmul_rn((float)k, it.amp);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+void launch_vstat(const BlockDev* blocks, const VsItem* items, int64_t nitems, double* partials, Bases b,
+                  float beta2, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(vstat_kernel, dim3((unsigned)((nitems + 3) / 4)), dim3(256), 0, s, blocks, items, nitems,
+                     partials, b, beta2);
+}
+
+void launch_vfinal(const BlockDev* blocks, const VfItem* items, int64_t nitems, const double* partials, Bases b,
+                   float beta2, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(vfinal_kernel, dim3((unsigned)((nitems + 255) / 256)), dim3(256), 0, s, blocks, items, nitems,
+                     partials, b, beta2);
+}
+
+void launch_update(const BlockDev* blocks, const EwItem* items, int64_t nitems, Bases b, StepScalars sc,
+                   hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(update_kernel, dim3((unsigned)nitems), dim3(256), 0, s, blocks, items, b, sc);
+}
+
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return;
+  const int64_t n16 = (int64_t)(bytes / 16);
+  const unsigned grid = (unsigned)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, s, reinterpret_cast<uint4*>(p), n16);
+}
+
+void launch_sketch(const SketchItem* items, int64_t nitems, char* state, hipStream_t s) {
+  if (nitems <= 0) return;
+  for (int64_t i0 = 0; i0 < nitems; i0 += 32768) {
+    const unsigned ny = (unsigned)(nitems - i0 < 32768 ? nitems - i0 : 32768);
+    hipLaunchKernelGGL(sketch_kernel, dim3(64, ny), dim3(256), 0, s, items + i0, state);
+  }
+}
+
+}  // namespace adapm

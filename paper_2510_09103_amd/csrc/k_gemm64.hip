@@ -1,0 +1,121 @@
+// fp64-accumulate strided two-product GEMM on the vector ALUs (the "F64" contraction mode):
+//   Out = a1 * A1 B1 + a2 * A2 B2 + g * X + d * Y
+// One launch covers a list of 64 x 64 output tiles drawn from many independent problems,
+// so every thin product of Alg. 2 (G R^T, L^T G, the four r x r Gram matrices, the factor
+// updates, the reconstruction L_{t-1}R_{t-1} - L_t R_t) of every low-rank block runs in a
+// handful of launches.  Operands (bf16 / fp32 / fp64) convert exactly to fp64; sums run in
+// ascending k, so results are deterministic.
+#include "adapm_plan.h"
+
+namespace adapm {
+
+namespace {
+
+constexpr int TM = 64, TN = 64, TK = 16, PAD = 2;
+
+__device__ __forceinline__ double load_el(const char* base, int dtype, int64_t idx) {
+  if (dtype == DT_F32) return (double)reinterpret_cast<const float*>(base)[idx];
+  if (dtype == DT_BF16) return (double)__uint_as_float(((uint32_t)reinterpret_cast<const uint16_t*>(base)[idx]) << 16);
+  return reinterpret_cast<const double*>(base)[idx];
+}
+
+__device__ __forceinline__ void product(const Mat& A, const Mat& B, int M, int N, int K, int i0, int j0,
+                                        const Bases& bs, double (*As)[TM + PAD], double (*Bs)[TN + PAD],
+                                        double acc[4][4]) {
+  const char* Ab = resolve(A.ref, bs);
+  const char* Bb = resolve(B.ref, bs);
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const bool a_kfast = (A.s1 == 1), b_jfast = (B.s1 == 1);
+  for (int k0 = 0; k0 < K; k0 += TK) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int idx = tid + p * 256;
+      int i, k;
+      if (a_kfast) { k = idx & 15; i = idx >> 4; } else { i = idx & 63; k = idx >> 6; }
+      double x = 0.0;
+      if (i0 + i < M && k0 + k < K) x = load_el(Ab, A.dtype, (int64_t)(i0 + i) * A.s0 + (int64_t)(k0 + k) * A.s1);
+      As[k][i] = x;
+      int j, kb;
+      if (b_jfast) { j = idx & 63; kb = idx >> 6; } else { kb = idx & 15; j = idx >> 4; }
+      double y = 0.0;
+      if (j0 + j < N && k0 + kb < K) y = load_el(Bb, B.dtype, (int64_t)(k0 + kb) * B.s0 + (int64_t)(j0 + j) * B.s1);
+      Bs[kb][j] = y;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < TK; ++kk) {
+      double a[4], b[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { a[q] = As[kk][ty * 4 + q]; b[q] = Bs[kk][tx * 4 + q]; }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[q][c] = fma(a[q], b[c], acc[q][c]);
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void gemm64_kernel(const GemmProblem* __restrict__ probs,
+                                                     const GemmTile* __restrict__ tiles, Bases bs) {
+  __shared__ double As[TK][TM + PAD];
+  __shared__ double Bs[TK][TN + PAD];
+  const GemmTile t = tiles[blockIdx.x];
+  const GemmProblem& P = probs[t.prob];
+  const int i0 = t.ti * TM, j0 = t.tj * TN;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  double acc[4][4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[q][c] = 0.0;
+  if (P.K1 > 0) {
+    product(P.A1, P.B1, P.M, P.N, P.K1, i0, j0, bs, As, Bs, acc);
+    const double a1 = P.a1;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[q][c] *= a1;
+  }
+  if (P.K2 > 0) {
+    double acc2[4][4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc2[q][c] = 0.0;
+    product(P.A2, P.B2, P.M, P.N, P.K2, i0, j0, bs, As, Bs, acc2);
+    const double a2 = P.a2;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[q][c] = fma(a2, acc2[q][c], acc[q][c]);
+  }
+  const char* Xb = P.X.ref.space != SP_NONE ? resolve(P.X.ref, bs) : nullptr;
+  const char* Yb = P.Y.ref.space != SP_NONE ? resolve(P.Y.ref, bs) : nullptr;
+  char* Ob = resolve(P.Out.ref, bs);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int i = i0 + ty * 4 + q;
+    if (i >= P.M) continue;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int j = j0 + tx * 4 + c;
+      if (j >= P.N) continue;
+      double val = acc[q][c];
+      if (Xb) val = fma(P.g, load_el(Xb, P.X.dtype, (int64_t)i * P.X.s0 + (int64_t)j * P.X.s1), val);
+      if (Yb) val = fma(P.d, load_el(Yb, P.Y.dtype, (int64_t)i * P.Y.s0 + (int64_t)j * P.Y.s1), val);
+      const int64_t o = (int64_t)i * P.Out.s0 + (int64_t)j * P.Out.s1;
+      if (P.Out.dtype == DT_F64) reinterpret_cast<double*>(Ob)[o] = val;
+      else reinterpret_cast<float*>(Ob)[o] = (float)val;
+    }
+  }
+}
+
+}  // namespace
+
+void launch_gemm64(const GemmProblem* probs, const GemmTile* tiles, int64_t ntiles, Bases b, hipStream_t s) {
+  if (ntiles <= 0) return;
+  hipLaunchKernelGGL(gemm64_kernel, dim3((unsigned)ntiles), dim3(256), 0, s, probs, tiles, b);
+}
+
+}  // namespace adapm

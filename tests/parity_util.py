@@ -1,0 +1,120 @@
+"""Helpers shared by the GPU parity tests: run the HIP library and the CPU oracle on the
+same seeded bits and compare element by element."""
+import math
+
+import numpy as np
+import torch
+
+from oracle import adapm_oracle as O
+from paper_2510_09103_amd import workloads as WL
+
+_DT = {"f32": O.F32, "bf16": O.BF16}
+_MOM = {"none": O.MOM_NONE, "full": O.MOM_FULL, "lowrank": O.MOM_LOWRANK}
+_VM = {"element": O.V_ELEMENT, "rowgroup": O.V_ROWGROUP, "whole": O.V_WHOLE}
+
+
+def oracle_block(b: WL.BlockSpec) -> O.Block:
+    return O.Block(b.rows, b.cols, _DT[b.param_dtype], _DT[b.grad_dtype], _MOM[b.mom], b.rank, _VM[b.v_mode],
+                   b.v_group_rows, b.lr_scale, b.weight_decay)
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    """device tensor -> numpy storage array (uint16 bit patterns for bf16)."""
+    if t.dtype == torch.bfloat16:
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.contiguous().cpu().numpy()
+
+
+def values(a: np.ndarray) -> np.ndarray:
+    return O.bf16_bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64)
+
+
+def rel_err_floor(got: np.ndarray, ref: np.ndarray) -> float:
+    """max |got-ref| / max(|ref|, RMS(ref)): per element, with a block-RMS floor."""
+    got, ref = got.astype(np.float64), ref.astype(np.float64)
+    rms = math.sqrt(float(np.mean(ref * ref))) if ref.size else 0.0
+    den = np.maximum(np.abs(ref), max(rms, 1e-300))
+    return float(np.max(np.abs(got - ref) / den)) if ref.size else 0.0
+
+
+def bf16_ulp_distance(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
+    """distance in representable bf16 values (sign-magnitude -> ordered integers)."""
+    def key(u):
+        u = u.astype(np.int32)
+        return np.where(u & 0x8000, -(u & 0x7FFF), u & 0x7FFF)
+    return np.abs(key(a_bits) - key(b_bits))
+
+
+def compare_params(got: np.ndarray, ref: np.ndarray, tol: float):
+    """fp32 params: relative error with RMS floor.  bf16 params: each element within tol
+    relative OR one bf16 ulp; returns (ok, worst_rel, frac_not_bit_equal)."""
+    if ref.dtype == np.uint16:
+        g, r = values(got), values(ref)
+        rel = np.abs(g - r) / np.maximum(np.abs(r), 1e-300)
+        ulp = bf16_ulp_distance(got, ref)
+        ok = bool(np.all((rel <= tol) | (ulp <= 1)))
+        return ok, float(rel.max()) if rel.size else 0.0, float(np.mean(ulp != 0)) if ulp.size else 0.0
+    e = rel_err_floor(got, ref)
+    return e <= tol, e, float(np.mean(got != ref)) if ref.size else 0.0
+
+
+class Pair:
+    """The library and the oracle stepping side by side on one workload."""
+
+    def __init__(self, wl: WL.Workload, hp_kwargs=None, device="cuda:0", grad_scale=1.0):
+        from paper_2510_09103_amd.optimizer import AdaPM, make_hparams
+        hp_kwargs = dict(hp_kwargs or {})
+        self.wl = wl
+        base = dict(beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, clip=wl.clip, K=wl.K)
+        base.update(hp_kwargs)
+        self.hp_c = make_hparams(**base)
+        ok = {k: v for k, v in base.items() if k != "contraction"}
+        self.hp_o = O.HParams(**ok) if "seed" in ok else O.HParams(**ok, seed=0x5EED)
+        self.opt = AdaPM(wl.blocks, self.hp_c, device=device)
+        self.blocks_o = [oracle_block(b) for b in wl.blocks]
+        self.state_o = O.init_state(self.blocks_o, self.hp_o)
+        self.params = WL.initial_params(wl, device=device)
+        self.W_o = [to_np(p) for p in self.params]
+        self.stream = WL.GradientStream(wl, device=device, scale=grad_scale)
+        self.t = 0
+
+    def step(self, lr=None, oracle_only=None):
+        self.t += 1
+        lr = self.wl.lr if lr is None else lr
+        grads = self.stream.next()
+        self.opt.step(self.params, grads, self.t, lr)
+        G_o = [to_np(g) for g in grads]
+        self.W_o, self.state_o = O.step(self.blocks_o, self.hp_o, self.W_o, G_o, self.state_o, self.t, lr,
+                                        only=oracle_only)
+        return grads
+
+    def compare(self, tol_state, tol_param, only=None, products_only=False):
+        """returns a report dict; raises AssertionError with the worst offender."""
+        torch.cuda.synchronize()
+        worst = {"state": 0.0, "param": 0.0, "flip_frac": 0.0}
+        idx = range(len(self.wl.blocks)) if only is None else only
+        for i in idx:
+            b = self.wl.blocks[i]
+            sv = {k: v.cpu().numpy() for k, v in self.opt.state_view(i).items()}
+            so = self.state_o[i]
+            for key in ("m", "v"):
+                if key in so:
+                    e = rel_err_floor(sv[key].reshape(-1), so[key].reshape(-1))
+                    worst["state"] = max(worst["state"], e)
+                    assert e <= tol_state, f"block {i} ({b.name}) state {key}: rel err {e:.3e} > {tol_state}"
+            if "L" in so:
+                prod_g = sv["L"].astype(np.float64) @ sv["R"].astype(np.float64)
+                prod_o = so["L"].astype(np.float64) @ so["R"].astype(np.float64)
+                e = rel_err_floor(prod_g, prod_o)
+                worst["state"] = max(worst["state"], e)
+                assert e <= tol_state, f"block {i} ({b.name}) product LR: rel err {e:.3e} > {tol_state}"
+                if not products_only:
+                    for key in ("L", "R"):
+                        e = rel_err_floor(sv[key], so[key])
+                        worst["state"] = max(worst["state"], e)
+                        assert e <= tol_state, f"block {i} ({b.name}) factor {key}: rel err {e:.3e} > {tol_state}"
+            ok, e, flips = compare_params(to_np(self.params[i]).reshape(-1), self.W_o[i].reshape(-1), tol_param)
+            worst["param"] = max(worst["param"], e)
+            worst["flip_frac"] = max(worst["flip_frac"], flips)
+            assert ok, f"block {i} ({b.name}) params: rel err {e:.3e} > {tol_param} (beyond one bf16 ulp)"
+        return worst
