@@ -247,11 +247,13 @@ def second_moment(blk: Block, hp: HParams, g: np.ndarray, v_prev: np.ndarray):
 def step_block(blk: Block, hp: HParams, W: np.ndarray, G: np.ndarray,
                st: Dict[str, np.ndarray], t: int, lr: float,
                refresh: str = "GD", state_dtype=np.float32,
-               want_aux: bool = False):
+               want_aux: bool = False, W_alt: Optional[np.ndarray] = None):
     """One optimizer step on one block.  t is 1-based.
 
     W, G: storage arrays (float32, or uint16 bit patterns for bf16), any shape
-    with rows*cols elements.  Returns (W_new storage, new state dict, aux)."""
+    with rows*cols elements.  Returns (W_new storage, new state dict, aux).
+    W_alt: a second parameter tensor pushed through the same last line (W enters Alg. 1
+    nowhere else); its result is returned as aux["W_alt_new"]."""
     m_, n_ = blk.rows, blk.cols
     g = load(G, blk.grad_dtype).reshape(m_, n_)
     w = load(W, blk.param_dtype).reshape(m_, n_)
@@ -309,19 +311,28 @@ def step_block(blk: Block, hp: HParams, W: np.ndarray, G: np.ndarray,
     w_new = w - (lr * blk.lr_scale) * (u + blk.weight_decay * w)
     if want_aux:
         aux.update(mc=mc, u=u, v_full=v_full, w_new=w_new)
+    if W_alt is not None:
+        wa = load(W_alt, blk.param_dtype).reshape(m_, n_)
+        wa_new = wa - (lr * blk.lr_scale) * (u + blk.weight_decay * wa)
+        aux["W_alt_new"] = store(wa_new, blk.param_dtype).reshape(np.shape(W_alt))
     return store(w_new, blk.param_dtype).reshape(np.shape(W)), new, aux
 
 
 def step(blocks: List[Block], hp: HParams, Ws: List[np.ndarray], Gs: List[np.ndarray],
          state: List[Dict[str, np.ndarray]], t: int, lr: float, refresh: str = "GD",
-         only: Optional[List[int]] = None):
-    """One step over a block table (blocks are independent; `only` selects a subset)."""
+         only: Optional[List[int]] = None, Ws_alt: Optional[List[np.ndarray]] = None):
+    """One step over a block table (blocks are independent; `only` selects a subset).
+    With Ws_alt, also returns the alternative parameters after the same update."""
     idx = range(len(blocks)) if only is None else only
     Ws = list(Ws)
     state = list(state)
+    alt = list(Ws_alt) if Ws_alt is not None else None
     for i in idx:
-        Ws[i], state[i], _ = step_block(blocks[i], hp, Ws[i], Gs[i], state[i], t, lr, refresh)
-    return Ws, state
+        Ws[i], state[i], aux = step_block(blocks[i], hp, Ws[i], Gs[i], state[i], t, lr, refresh,
+                                          W_alt=None if alt is None else alt[i])
+        if alt is not None:
+            alt[i] = aux["W_alt_new"]
+    return (Ws, state) if alt is None else (Ws, state, alt)
 
 
 def state_bytes_closed_form(blocks: List[Block]) -> int:

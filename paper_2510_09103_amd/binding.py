@@ -10,6 +10,10 @@ import ctypes as C
 import os
 from typing import Optional, Sequence
 
+# PyTorch ships its own HIP runtime.  It must be the one already loaded when libadapm.so
+# is opened, so that the library, the tensors and the streams share a single runtime.
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libadapm.so")
 

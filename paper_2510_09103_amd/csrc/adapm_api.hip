@@ -218,11 +218,12 @@ void build_plan(adapm_ctx* c) {
     if (b.mom_mode == ADAPM_MOM_LOWRANK) {
       L.sL = salloc(4 * m * r);
       L.sR = salloc(4 * r * n);
-      L.wLa = walloc(4 * m * r); L.wRa = walloc(4 * r * n);
-      L.wLb = walloc(4 * m * r); L.wRb = walloc(4 * r * n);
-      L.wP = walloc(4 * m * r); L.wS = walloc(4 * r * n);
-      L.wGrr = walloc(4 * r * r); L.wGpr = walloc(4 * r * r);
-      L.wGll = walloc(4 * r * r); L.wGlp = walloc(4 * r * r);
+      // every intermediate of a step stays in fp64; only the state is rounded to fp32, once per step
+      L.wLa = walloc(8 * m * r); L.wRa = walloc(8 * r * n);
+      L.wLb = walloc(8 * m * r); L.wRb = walloc(8 * r * n);
+      L.wP = walloc(8 * m * r); L.wS = walloc(8 * r * n);
+      L.wGrr = walloc(8 * r * r); L.wGpr = walloc(8 * r * r);
+      L.wGll = walloc(8 * r * r); L.wGlp = walloc(8 * r * r);
       L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
       L.wC = walloc(4 * m * n);
       c->n_lowrank++;
@@ -305,11 +306,11 @@ void build_plan(adapm_ctx* c) {
       const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
       const Mat Lp = mat(SP_STATE, 0, L.sL, r, 1, DT_F32), Rp = mat(SP_STATE, 0, L.sR, n, 1, DT_F32);
       auto T = [](const Mat& a) { Mat t = a; t.s0 = a.s1; t.s1 = a.s0; return t; };
-      auto fL = [&](int which) { return mat(SP_WS, 0, which ? L.wLb : L.wLa, r, 1, DT_F32); };
-      auto fR = [&](int which) { return mat(SP_WS, 0, which ? L.wRb : L.wRa, n, 1, DT_F32); };
-      const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F32), S = mat(SP_WS, 0, L.wS, n, 1, DT_F32);
-      const Mat Grr = mat(SP_WS, 0, L.wGrr, r, 1, DT_F32), Gpr = mat(SP_WS, 0, L.wGpr, r, 1, DT_F32);
-      const Mat Gll = mat(SP_WS, 0, L.wGll, r, 1, DT_F32), Glp = mat(SP_WS, 0, L.wGlp, r, 1, DT_F32);
+      auto fL = [&](int which) { return mat(SP_WS, 0, which ? L.wLb : L.wLa, r, 1, DT_F64); };
+      auto fR = [&](int which) { return mat(SP_WS, 0, which ? L.wRb : L.wRa, n, 1, DT_F64); };
+      const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F64), S = mat(SP_WS, 0, L.wS, n, 1, DT_F64);
+      const Mat Grr = mat(SP_WS, 0, L.wGrr, r, 1, DT_F64), Gpr = mat(SP_WS, 0, L.wGpr, r, 1, DT_F64);
+      const Mat Gll = mat(SP_WS, 0, L.wGll, r, 1, DT_F64), Glp = mat(SP_WS, 0, L.wGlp, r, 1, DT_F64);
       Mat Lc = Lp, Rc = Rp;
       for (int e = 0; e < n_eff; ++e) {
         const double eta = etas[e];
@@ -395,7 +396,7 @@ void build_plan(adapm_ctx* c) {
       const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
       const Mat Ls = mat(SP_STATE, 0, L.sL, r, 1, DT_F32), Q = mat(SP_STATE, 0, L.sR, n, 1, DT_F32);
       Mat Qt = Q; Qt.s0 = Q.s1; Qt.s1 = Q.s0;
-      const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F32), D = mat(SP_WS, 0, L.wLa, r, 1, DT_F32);
+      const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F64), D = mat(SP_WS, 0, L.wLa, r, 1, DT_F64);
       const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
       GemmProblem p;
       p = problem(m, r); p.A1 = G; p.B1 = Qt; p.K1 = n; p.a1 = 1.0; p.Out = P; add_problem(c->gemms[l_p], p);

@@ -1,0 +1,155 @@
+"""Host-side tests of the C-ABI library: it loads, exports what the header declares,
+validates its arguments, and lays the state out as Alg. 1 line 1 prescribes.  No GPU."""
+import ctypes as C
+import math
+import os
+import re
+
+import pytest
+
+from oracle import adapm_oracle as O
+from paper_2510_09103_amd import binding as B
+from paper_2510_09103_amd import workloads as WL
+from paper_2510_09103_amd.optimizer import make_hparams, to_c_block
+from parity_util import oracle_block
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "adapm.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(adapm_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    raw = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert getattr(raw, name) is not None
+
+
+def test_struct_sizes_match_header_layout():
+    assert C.sizeof(B.adapm_block_t) == 48
+    assert C.sizeof(B.adapm_hparams_t) == 48
+
+
+def blk(**kw):
+    d = dict(rows=8, cols=8, param_dtype=0, grad_dtype=0, mom_mode=B.ADAPM_MOM_LOWRANK, rank=2,
+             v_mode=0, v_group_rows=1, lr_scale=1.0, weight_decay=0.0)
+    d.update(kw)
+    return B.adapm_block_t(**d)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(rows=0), dict(cols=0), dict(rank=0), dict(rank=9), dict(mom_mode=3), dict(mom_mode=-1),
+    dict(v_mode=5), dict(v_mode=B.ADAPM_V_ROWGROUP, v_group_rows=3), dict(v_mode=B.ADAPM_V_ROWGROUP, v_group_rows=0),
+    dict(param_dtype=2), dict(grad_dtype=-1), dict(cols=1, rank=1), dict(lr_scale=float("nan")),
+    dict(weight_decay=float("inf")),
+])
+def test_init_rejects_bad_table_entries(bad):
+    with pytest.raises(B.AdapmError) as e:
+        B.adapm_init([blk(), blk(**bad)], make_hparams())
+    assert e.value.status == B.ADAPM_EINVAL
+    assert "block 1" in str(e.value)
+
+
+@pytest.mark.parametrize("bad", [dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1.0), dict(clip=0.0), dict(K=0),
+                                 dict(T=0), dict(adam_debias=2), dict(bias_correction=7), dict(contraction=9)])
+def test_init_rejects_bad_hparams(bad):
+    with pytest.raises(B.AdapmError) as e:
+        B.adapm_init([blk()], make_hparams(**bad))
+    assert e.value.status == B.ADAPM_EINVAL
+
+
+def test_init_rejects_null_and_empty():
+    ctx = C.c_void_p()
+    hp = make_hparams()
+    assert B.lib.adapm_init(C.byref(ctx), None, 1, C.byref(hp)) == B.ADAPM_EINVAL
+    assert B.lib.adapm_init(None, None, 1, C.byref(hp)) == B.ADAPM_EINVAL
+    arr = (B.adapm_block_t * 1)(blk())
+    assert B.lib.adapm_init(C.byref(ctx), arr, 0, C.byref(hp)) == B.ADAPM_EINVAL
+    assert B.lib.adapm_init(C.byref(ctx), arr, 1, None) == B.ADAPM_EINVAL
+    assert B.adapm_state_bytes(None) == 0 and B.adapm_workspace_bytes(None) == 0
+    B.adapm_destroy(None)
+
+
+def test_bf16x2_contraction_needs_bf16_gradients():
+    with pytest.raises(B.AdapmError):
+        B.adapm_init([blk(grad_dtype=B.ADAPM_F32)], make_hparams(contraction=B.ADAPM_CONTRACT_BF16X2))
+
+
+def test_step_argument_checks_do_not_need_a_device():
+    ctx = B.adapm_init([blk()], make_hparams())
+    pp, gp = B.ptr_array([256]), B.ptr_array([512])
+    with pytest.raises(B.AdapmError) as e:
+        B.adapm_step(ctx, pp, gp, 4096, 8192, 0, 1e-3)
+    assert e.value.status == B.ADAPM_ESTATE
+    with pytest.raises(B.AdapmError) as e:
+        B.adapm_step(ctx, B.ptr_array([0]), gp, 4096, 8192, 1, 1e-3)
+    assert e.value.status == B.ADAPM_EINVAL
+    with pytest.raises(B.AdapmError) as e:
+        B.adapm_step(ctx, B.ptr_array([260]), gp, 4096, 8192, 1, 1e-3)     # misaligned
+    assert e.value.status == B.ADAPM_EINVAL
+    with pytest.raises(B.AdapmError) as e:
+        B.adapm_step(ctx, pp, gp, 0, 8192, 1, 1e-3)
+    assert e.value.status == B.ADAPM_EINVAL
+    with pytest.raises(B.AdapmError):
+        B.adapm_state_offsets(ctx, 5)
+    B.adapm_destroy(ctx)
+
+
+@pytest.mark.parametrize("name", list(WL.CONFIGS))
+def test_state_bytes_closed_form_and_layout(name):
+    wl = WL.CONFIGS[name]()
+    ctx = B.adapm_init([to_c_block(b) for b in wl.blocks], make_hparams())
+    total = B.adapm_state_bytes(ctx)
+    exact = O.state_bytes_closed_form([oracle_block(b) for b in wl.blocks])
+    nsub = sum(3 if b.mom == "lowrank" else (2 if b.mom == "full" else 1) for b in wl.blocks)
+    assert exact <= total <= exact + 255 * nsub            # only alignment padding on top
+    end = 0
+    for i, b in enumerate(wl.blocks):                       # sub-buffers in table order, disjoint, aligned
+        oL, oR, om, ov = B.adapm_state_offsets(ctx, i)
+        spans = []
+        if b.mom == "lowrank":
+            assert om is None
+            spans += [(oL, 4 * b.rows * b.rank), (oR, 4 * b.rank * b.cols)]
+        elif b.mom == "full":
+            assert oL is None and oR is None
+            spans += [(om, 4 * b.numel)]
+        nv = b.numel if b.v_mode == "element" else (b.rows // b.v_group_rows if b.v_mode == "rowgroup" else 1)
+        spans += [(ov, 4 * nv)]
+        for off, size in spans:
+            assert off % 256 == 0 and off >= end
+            end = off + size
+    assert end <= total
+    B.adapm_destroy(ctx)
+
+
+def test_gpt2_1p5b_state_and_traffic_figures():
+    wl = WL.gpt2_1p5b()
+    ctx = B.adapm_init([to_c_block(b) for b in wl.blocks], make_hparams(T=100))
+    assert wl.numel == 1_637_176_000 and len(wl.blocks) == 388
+    sb = B.adapm_state_bytes(ctx)
+    assert abs(sb / 1e6 - 1360.8) < 0.5                     # L,R + m + blockwise v
+    adam = 8 * wl.numel                                     # two fp32 moments per parameter
+    assert 0.10 < sb / adam < 0.11
+    # Table 2 of the paper prints 12.48 G for Adam on GPT-2-1.5B (tied head: 1.5568 B parameters)
+    tied = wl.numel - 50257 * 1600
+    assert abs(8 * tied / 1e9 - 12.48) < 0.05
+    # compulsory traffic: every input once, every output once
+    want_refresh = 0.0
+    want_proj = 0.0
+    for b in wl.blocks:
+        mn = b.numel
+        base = mn * (2 + 2 * 2)
+        nv = b.rows // b.v_group_rows if b.v_mode == "rowgroup" else 1
+        base += 8 * nv
+        if b.mom == "full":
+            base += 8 * mn
+        want_refresh += base + (8 * (b.rows + b.cols) * b.rank if b.mom == "lowrank" else 0)
+        want_proj += base + ((8 * b.rows + 4 * b.cols) * b.rank if b.mom == "lowrank" else 0)
+    assert B.adapm_algorithmic_bytes(ctx, True) == pytest.approx(want_refresh, rel=1e-12)
+    assert B.adapm_algorithmic_bytes(ctx, False) == pytest.approx(want_proj, rel=1e-12)
+    assert abs(want_refresh / 1e9 - 12.54) < 0.01
+    lr_mnr = sum(b.numel * b.rank for b in wl.blocks if b.mom == "lowrank")
+    assert B.adapm_algorithmic_flops(ctx, False) == pytest.approx(4 * lr_mnr, rel=1e-12)
+    assert abs(4 * lr_mnr / 1e12 - 0.755) < 0.001
+    B.adapm_destroy(ctx)
