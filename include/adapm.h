@@ -128,6 +128,19 @@ double adapm_algorithmic_bytes(const adapm_ctx* ctx, int32_t refresh_step);
  * counted once per mathematical product (operand splitting not counted). */
 double adapm_algorithmic_flops(const adapm_ctx* ctx, int32_t refresh_step);
 
+/* Optional per-launch timing for benchmarks.  While enabled, adapm_step brackets every kernel
+ * launch with a pair of HIP events on the caller's stream (this serialises nothing but adds two
+ * event records per launch).  For callers that want the duration of each kernel class without an
+ * external profiler. */
+adapm_status_t adapm_profile_enable(adapm_ctx* ctx, int32_t on);
+
+/* After the caller has synchronised the stream: entry `index` of the per-kernel-class totals
+ * accumulated since the last read with index 0 (which folds and clears the pending records).
+ * name receives a NUL-terminated label (at most name_cap bytes), total_ms the summed duration,
+ * launches the number of launches.  Returns the number of entries. */
+int64_t adapm_profile_read(adapm_ctx* ctx, int64_t index, char* name, size_t name_cap, double* total_ms,
+                           int64_t* launches);
+
 const char* adapm_last_error(void);
 
 void adapm_destroy(adapm_ctx* ctx);

@@ -41,7 +41,8 @@ class adapm_hparams_t(C.Structure):
 
 EXPORTS = ["adapm_init", "adapm_state_bytes", "adapm_workspace_bytes", "adapm_state_offsets",
            "adapm_state_init", "adapm_step", "adapm_last_launch_count", "adapm_algorithmic_bytes",
-           "adapm_algorithmic_flops", "adapm_last_error", "adapm_destroy"]
+           "adapm_algorithmic_flops", "adapm_profile_enable", "adapm_profile_read", "adapm_last_error",
+           "adapm_destroy"]
 
 
 def _load() -> C.CDLL:
@@ -69,6 +70,11 @@ def _load() -> C.CDLL:
     lib.adapm_algorithmic_bytes.argtypes = [P, C.c_int32]
     lib.adapm_algorithmic_flops.restype = C.c_double
     lib.adapm_algorithmic_flops.argtypes = [P, C.c_int32]
+    lib.adapm_profile_enable.restype = C.c_int
+    lib.adapm_profile_enable.argtypes = [P, C.c_int32]
+    lib.adapm_profile_read.restype = C.c_int64
+    lib.adapm_profile_read.argtypes = [P, C.c_int64, C.c_char_p, C.c_size_t, C.POINTER(C.c_double),
+                                       C.POINTER(C.c_int64)]
     lib.adapm_last_error.restype = C.c_char_p
     lib.adapm_last_error.argtypes = []
     lib.adapm_destroy.restype = None
@@ -138,6 +144,23 @@ def adapm_algorithmic_bytes(ctx, refresh_step: bool) -> float:
 
 def adapm_algorithmic_flops(ctx, refresh_step: bool) -> float:
     return lib.adapm_algorithmic_flops(ctx, 1 if refresh_step else 0)
+
+
+def adapm_profile_enable(ctx, on: bool):
+    _check(lib.adapm_profile_enable(ctx, 1 if on else 0))
+
+
+def adapm_profile_read(ctx):
+    """{label: (total_ms, launches)} accumulated since the last read; synchronise the stream first."""
+    out = {}
+    name = C.create_string_buffer(64)
+    ms, cnt = C.c_double(), C.c_int64()
+    n = lib.adapm_profile_read(ctx, 0, name, 64, C.byref(ms), C.byref(cnt))
+    for i in range(n):
+        if i:
+            lib.adapm_profile_read(ctx, i, name, 64, C.byref(ms), C.byref(cnt))
+        out[name.value.decode()] = (ms.value, cnt.value)
+    return out
 
 
 def adapm_destroy(ctx):

@@ -15,6 +15,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <utility>
 #include <vector>
 
 using namespace adapm;
@@ -45,15 +46,19 @@ size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 constexpr int EW_CHUNK = 8192;      // elements per workgroup of the update kernel
 constexpr int VS_CHUNK = 16384;     // elements per wavefront of the v-statistics kernel
 
+enum Path { PATH_NONE = 0, PATH_F64 = 1, PATH_FAST = 2 };
+
 struct Layout {                      // byte offsets, -1 = absent
   int64_t sL = -1, sR = -1, sm = -1, sv = -1;               // state
   int64_t wLa = -1, wRa = -1, wLb = -1, wRb = -1;           // ws: ping-pong factors of Alg. 2
   int64_t wP = -1, wS = -1, wGrr = -1, wGpr = -1, wGll = -1, wGlp = -1;
   int64_t wG64 = -1, wCinv = -1, wC = -1;
+  int64_t wQth = -1, wQtl = -1;                             // ws: Q^T as bf16 (hi, lo)
   int64_t nv = 0;
+  int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -64,8 +69,9 @@ struct GemmList {
 
 struct Op {
   OpKind kind;
-  int index;        // GEMM: gemm list; UPDATE: 0 = full/none blocks, 1 = low-rank blocks
-  float cG, cC;     // UPDATE of low-rank blocks
+  int index;          // GEMM*: gemm list; UPDATE / VSTAT / VFINAL / PROJ: which item list
+  float cG, cC;       // UPDATE of low-rank blocks, PROJ
+  const char* label;  // profiling name
 };
 
 template <class T>
@@ -82,6 +88,11 @@ Mat mat(int32_t space, int32_t block, int64_t off, int64_t s0, int64_t s1, int32
 }
 Mat none_mat() { return mat(SP_NONE, 0, 0, 0, 0, DT_F32); }
 
+struct ProfRec {
+  const char* label;
+  hipEvent_t e0, e1;
+};
+
 }  // namespace
 
 struct adapm_ctx {
@@ -92,13 +103,16 @@ struct adapm_ctx {
   int64_t off_partials = -1;
 
   DevList<BlockDev> blocks;
-  DevList<EwItem> ew_main, ew_lr;
-  DevList<VsItem> vs;
-  DevList<VfItem> vf;
+  DevList<EwItem> ew[3];        // 0: full / no momentum; 1: low-rank, F64 path; 2: low-rank, MFMA path
+  DevList<VsItem> vs[2];        // 0: every step; 1: only on steps that run Alg. 2 (fused elsewhere)
+  DevList<VfItem> vf[2];
   DevList<SketchItem> sk;
-  DevList<CholItem> chol;
+  DevList<CholItem> chol[2];    // per path
+  DevList<LrBlockDev> lrb;
+  DevList<ProjItem> proj[3];    // rank 32 / 64 / 128
+  DevList<QsItem> qs;
   std::vector<GemmList> gemms;
-  std::vector<Op> seq_common, seq_refresh, seq_project;
+  std::vector<Op> seq_refresh, seq_project;
 
   bool uploaded = false;
   int device = -1;
@@ -109,6 +123,10 @@ struct adapm_ctx {
   hipEvent_t stage_free = nullptr;
   int64_t last_launches = 0;
   int n_lowrank = 0;
+
+  bool profiling = false;
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> event_pool;
 };
 
 namespace {
@@ -124,6 +142,19 @@ int64_t group_elems(const adapm_block_t& b) {
   return b.rows * b.cols;
 }
 int esize(int32_t dt) { return dt == ADAPM_BF16 ? 2 : 4; }
+
+// BF16X2 needs bf16 gradients, a rank of 32, 64 or 128 and 16-byte aligned rows; other blocks use F64.
+int path_of(const adapm_block_t& b, const adapm_hparams_t& hp) {
+  if (b.mom_mode != ADAPM_MOM_LOWRANK) return PATH_NONE;
+  const bool want = hp.contraction == ADAPM_CONTRACT_BF16X2 ||
+                    (hp.contraction == ADAPM_CONTRACT_AUTO && b.param_dtype == ADAPM_BF16);
+  const bool can = b.grad_dtype == ADAPM_BF16 && (b.rank == 32 || b.rank == 64 || b.rank == 128) && b.cols % 8 == 0;
+  return (want && can) ? PATH_FAST : PATH_F64;
+}
+// v of a block on the MFMA path can be finished inside the 64-row stripe of the fused kernel
+bool v_fusable(const adapm_block_t& b) {
+  return b.v_mode == ADAPM_V_ROWGROUP && b.v_group_rows <= 64 && 64 % b.v_group_rows == 0;
+}
 
 adapm_status_t validate(const adapm_block_t* t, int64_t n, const adapm_hparams_t* hp) {
   if (!t || !hp) return fail(ADAPM_EINVAL, "null table or hparams");
@@ -173,14 +204,11 @@ uint64_t mix64(uint64_t z) {
   return z ^ (z >> 31);
 }
 
-void add_tiles(GemmList& gl, uint32_t prob, int M, int N) {
-  for (int ti = 0; ti < (M + 63) / 64; ++ti)
-    for (int tj = 0; tj < (N + 63) / 64; ++tj) gl.tiles.push_back(GemmTile{prob, (uint16_t)ti, (uint16_t)tj});
-}
-
 void add_problem(GemmList& gl, const GemmProblem& p) {
   gl.probs.push_back(p);
-  add_tiles(gl, (uint32_t)gl.probs.size() - 1, p.M, p.N);
+  const uint32_t id = (uint32_t)gl.probs.size() - 1;
+  for (int ti = 0; ti < (p.M + 63) / 64; ++ti)
+    for (int tj = 0; tj < (p.N + 63) / 64; ++tj) gl.tiles.push_back(GemmTile{id, (uint16_t)ti, (uint16_t)tj});
 }
 
 GemmProblem problem(int M, int N) {
@@ -201,13 +229,218 @@ std::vector<double> effective_step_sizes(int K) {
   return out;
 }
 
+// Alg. 2 + eq. 3-4 for the low-rank blocks of one contraction path, as batched GEMM launches.
+//   fast = false: fp64 vector-ALU GEMM, every intermediate kept in fp64;
+//   fast = true : split-bf16 MFMA GEMM, fp32 intermediates.
+void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
+  const int want = fast ? PATH_FAST : PATH_F64;
+  const adapm_hparams_t& hp = c->hp;
+  const int64_t nb = (int64_t)c->table.size();
+  const double b1 = hp.beta1;
+  const int idt = fast ? DT_F32 : DT_F64;
+  const OpKind gk = fast ? OP_GEMM_MFMA : OP_GEMM;
+  bool any = false;
+  for (int64_t i = 0; i < nb; ++i) any = any || c->lay[i].path == want;
+  if (!any) return;
+  const std::vector<double> etas = effective_step_sizes(hp.refresh_iters_K);
+  const int n_eff = (int)etas.size();
+  auto new_list = [&]() { c->gemms.emplace_back(); return (int)c->gemms.size() - 1; };
+  std::vector<int> listA(n_eff), listB(n_eff);
+  for (int e = 0; e < n_eff; ++e) { listA[e] = new_list(); listB[e] = new_list(); }
+  const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list() : -1;
+  const int l_epi = new_list();
+  const int l_gram = hp.refresh_period_T > 1 ? new_list() : -1;
+  const int l_fin = (hp.refresh_period_T > 1 || n_eff > 0) ? new_list() : -1;
+  for (int64_t i = 0; i < nb; ++i) {
+    const adapm_block_t& b = c->table[i];
+    const Layout& L = c->lay[i];
+    if (L.path != want) continue;
+    const int m = (int)b.rows, n = (int)b.cols, r = b.rank;
+    const int gdt = b.grad_dtype == ADAPM_BF16 ? DT_BF16 : DT_F32;
+    const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
+    const Mat Lp = mat(SP_STATE, 0, L.sL, r, 1, DT_F32), Rp = mat(SP_STATE, 0, L.sR, n, 1, DT_F32);
+    auto T = [](const Mat& a) { Mat t = a; t.s0 = a.s1; t.s1 = a.s0; return t; };
+    auto fL = [&](int which) { return mat(SP_WS, 0, which ? L.wLb : L.wLa, r, 1, idt); };
+    auto fR = [&](int which) { return mat(SP_WS, 0, which ? L.wRb : L.wRa, n, 1, idt); };
+    const Mat P = mat(SP_WS, 0, L.wP, r, 1, idt), S = mat(SP_WS, 0, L.wS, n, 1, idt);
+    const Mat Grr = mat(SP_WS, 0, L.wGrr, r, 1, idt), Gpr = mat(SP_WS, 0, L.wGpr, r, 1, idt);
+    const Mat Gll = mat(SP_WS, 0, L.wGll, r, 1, idt), Glp = mat(SP_WS, 0, L.wGlp, r, 1, idt);
+    Mat Lc = Lp, Rc = Rp;
+    GemmProblem p;
+    for (int e = 0; e < n_eff; ++e) {
+      const double eta = etas[e];
+      const Mat Ln = fL(e & 1), Rn = fR(e & 1);
+      GemmList& A = c->gemms[listA[e]];
+      // thin products of Alg. 2 written without forming L R - m_t:
+      //   (L R - m_t) R^T = L (R R^T) - (1-b1) G R^T - b1 L' (R' R^T)
+      //   L^T (L R - m_t) = (L^T L) R - (1-b1) L^T G - b1 (L^T L') R'
+      p = problem(m, r); p.A1 = G; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = P; add_problem(A, p);
+      p = problem(r, n); p.A1 = T(Lc); p.B1 = G; p.K1 = m; p.a1 = 1; p.Out = S; add_problem(A, p);
+      p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Grr; add_problem(A, p);
+      p = problem(r, r); p.A1 = Rp; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Gpr; add_problem(A, p);
+      p = problem(r, r); p.A1 = T(Lc); p.B1 = Lc; p.K1 = m; p.a1 = 1; p.Out = Gll; add_problem(A, p);
+      p = problem(r, r); p.A1 = T(Lc); p.B1 = Lp; p.K1 = m; p.a1 = 1; p.Out = Glp; add_problem(A, p);
+      GemmList& Bl = c->gemms[listB[e]];
+      p = problem(m, r);
+      p.A1 = Lc; p.B1 = Grr; p.K1 = r; p.a1 = -eta;
+      p.A2 = Lp; p.B2 = Gpr; p.K2 = r; p.a2 = eta * b1;
+      p.X = Lc; p.g = 1.0; p.Y = P; p.d = eta * (1.0 - b1); p.Out = Ln;
+      add_problem(Bl, p);
+      p = problem(r, n);
+      p.A1 = Gll; p.B1 = Rc; p.K1 = r; p.a1 = -eta;
+      p.A2 = Glp; p.B2 = Rp; p.K2 = r; p.a2 = eta * b1;
+      p.X = Rc; p.g = 1.0; p.Y = S; p.d = eta * (1.0 - b1); p.Out = Rn;
+      add_problem(Bl, p);
+      Lc = Ln; Rc = Rn;
+    }
+    if (l_pre >= 0) {      // no effective iteration but an in-place re-gauge ahead: work on a copy
+      p = problem(m, r); p.X = Lp; p.g = 1.0; p.Out = fL(0); add_problem(c->gemms[l_pre], p);
+      p = problem(r, n); p.X = Rp; p.g = 1.0; p.Out = fR(0); add_problem(c->gemms[l_pre], p);
+      Lc = fL(0); Rc = fR(0);
+    }
+    // m x n low-rank term of m^c (eq. 4): C = L'R' - L R, or L R without the correction
+    const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
+    p = problem(m, n);
+    if (hp.bias_correction) {
+      p.A1 = Lp; p.B1 = Rp; p.K1 = r; p.a1 = 1.0;
+      p.A2 = Lc; p.B2 = Rc; p.K2 = r; p.a2 = -1.0;
+    } else {
+      p.A1 = Lc; p.B1 = Rc; p.K1 = r; p.a1 = 1.0;
+    }
+    p.Out = C;
+    add_problem(c->gemms[l_epi], p);
+    if (hp.refresh_period_T > 1) {
+      // product-preserving orthonormalisation of R, always in fp64
+      const Mat G64 = mat(SP_WS, 0, L.wG64, r, 1, DT_F64), Cinv = mat(SP_WS, 0, L.wCinv, r, 1, DT_F64);
+      p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1.0; p.Out = G64;
+      add_problem(c->gemms[l_gram], p);
+      c->chol[fast ? 1 : 0].h.push_back(CholItem{L.wG64, L.wCinv, r, 0});
+      p = problem(r, n); p.A1 = Cinv; p.B1 = Rc; p.K1 = r; p.a1 = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
+      p = problem(m, r); p.A1 = Lc; p.B1 = G64; p.K1 = r; p.a1 = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
+    } else if (n_eff > 0) {
+      p = problem(m, r); p.X = Lc; p.g = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
+      p = problem(r, n); p.X = Rc; p.g = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
+    }
+  }
+  std::vector<Op>& seq = c->seq_refresh;
+  for (int e = 0; e < n_eff; ++e) {
+    seq.push_back(Op{gk, listA[e], 0, 0, fast ? "alg2_products_mfma" : "alg2_products_f64"});
+    seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"});
+  }
+  if (l_pre >= 0) seq.push_back(Op{gk, l_pre, 0, 0, "copy_factors"});
+  seq.push_back(Op{gk, l_epi, 0, 0, fast ? "reconstruct_mfma" : "reconstruct_f64"});
+  const float cG = hp.bias_correction ? 1.f : 0.f;
+  const float cC = hp.bias_correction ? (float)(b1 / (1.0 - b1)) : 1.f;
+  seq.push_back(Op{OP_UPDATE, fast ? 2 : 1, cG, cC, "update_lowrank"});
+  if (l_gram >= 0) {
+    seq.push_back(Op{OP_GEMM, l_gram, 0, 0, "regauge_gram_f64"});
+    seq.push_back(Op{OP_CHOL, fast ? 1 : 0, 0, 0, "regauge_cholesky_f64"});
+  }
+  if (l_fin >= 0) {
+    const bool f64_fin = hp.refresh_period_T > 1;
+    seq.push_back(Op{f64_fin ? OP_GEMM : gk, l_fin, 0, 0, f64_fin ? "regauge_apply_f64" : "store_factors"});
+  }
+}
+
+// step with R held, F64 path: four batched GEMM launches and the update kernel
+void plan_lowrank_project_f64(adapm_ctx* c) {
+  const adapm_hparams_t& hp = c->hp;
+  const int64_t nb = (int64_t)c->table.size();
+  const double b1 = hp.beta1;
+  bool any = false;
+  for (int64_t i = 0; i < nb; ++i) any = any || c->lay[i].path == PATH_F64;
+  if (!any) return;
+  auto new_list = [&]() { c->gemms.emplace_back(); return (int)c->gemms.size() - 1; };
+  const int l_p = new_list(), l_d = new_list(), l_l = new_list(), l_c = new_list();
+  for (int64_t i = 0; i < nb; ++i) {
+    const adapm_block_t& b = c->table[i];
+    const Layout& L = c->lay[i];
+    if (L.path != PATH_F64) continue;
+    const int m = (int)b.rows, n = (int)b.cols, r = b.rank;
+    const int gdt = b.grad_dtype == ADAPM_BF16 ? DT_BF16 : DT_F32;
+    const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
+    const Mat Ls = mat(SP_STATE, 0, L.sL, r, 1, DT_F32), Q = mat(SP_STATE, 0, L.sR, n, 1, DT_F32);
+    Mat Qt = Q; Qt.s0 = Q.s1; Qt.s1 = Q.s0;
+    const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F64), D = mat(SP_WS, 0, L.wLa, r, 1, DT_F64);
+    const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
+    GemmProblem p;
+    p = problem(m, r); p.A1 = G; p.B1 = Qt; p.K1 = n; p.a1 = 1.0; p.Out = P; add_problem(c->gemms[l_p], p);
+    // L_t = b1 L' + (1-b1) G Q^T;  m^c = G + b1 (L' - G Q^T) Q   (or L_t Q without the correction)
+    p = problem(m, r); p.X = Ls; p.Y = P; p.Out = D;
+    if (hp.bias_correction) { p.g = b1; p.d = -b1; } else { p.g = b1; p.d = 1.0 - b1; }
+    add_problem(c->gemms[l_d], p);
+    p = problem(m, r); p.X = Ls; p.g = b1; p.Y = P; p.d = 1.0 - b1; p.Out = Ls; add_problem(c->gemms[l_l], p);
+    p = problem(m, n); p.A1 = D; p.B1 = Q; p.K1 = r; p.a1 = 1.0; p.Out = C; add_problem(c->gemms[l_c], p);
+  }
+  std::vector<Op>& seq = c->seq_project;
+  seq.push_back(Op{OP_GEMM, l_p, 0, 0, "project_f64"});
+  seq.push_back(Op{OP_GEMM, l_d, 0, 0, "project_residual_f64"});
+  seq.push_back(Op{OP_GEMM, l_l, 0, 0, "project_store_L_f64"});
+  seq.push_back(Op{OP_GEMM, l_c, 0, 0, "reconstruct_f64"});
+  seq.push_back(Op{OP_UPDATE, 1, hp.bias_correction ? 1.f : 0.f, 1.f, "update_lowrank"});
+}
+
+// step with R held, MFMA path: Q^T split once, then one fused launch per rank class.  Stripes of one
+// block are placed on one XCD (workgroup i runs on XCD i mod 8) so that they share Q through its L2.
+void plan_lowrank_project_fast(adapm_ctx* c) {
+  const int64_t nb = (int64_t)c->table.size();
+  constexpr int NXCD = 8;
+  std::vector<int64_t> lr_of(nb, -1);
+  for (int64_t i = 0; i < nb; ++i) {
+    const adapm_block_t& b = c->table[i];
+    const Layout& L = c->lay[i];
+    if (L.path != PATH_FAST) continue;
+    LrBlockDev d;
+    memset(&d, 0, sizeof d);
+    d.block = (int32_t)i; d.m = (int32_t)b.rows; d.n = (int32_t)b.cols; d.r = b.rank;
+    d.off_L = L.sL; d.off_Q = L.sR; d.off_v = L.sv; d.off_Qt_hi = L.wQth; d.off_Qt_lo = L.wQtl;
+    if (b.v_mode == ADAPM_V_ELEMENT) { d.v_kind = 0; d.v_group_rows = 1; }
+    else if (v_fusable(b)) { d.v_kind = 1; d.v_group_rows = b.v_group_rows; }
+    else { d.v_kind = 2; d.v_group_rows = b.v_mode == ADAPM_V_WHOLE ? (int32_t)b.rows : b.v_group_rows; }
+    d.param_dtype = b.param_dtype; d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
+    lr_of[i] = (int64_t)c->lrb.h.size();
+    c->lrb.h.push_back(d);
+    for (int a0 = 0; a0 < b.rank; a0 += 32)
+      for (int j0 = 0; j0 < b.cols; j0 += 64) c->qs.h.push_back(QsItem{(int32_t)lr_of[i], a0, j0});
+  }
+  if (c->lrb.h.empty()) return;
+  std::vector<Op>& seq = c->seq_project;
+  seq.push_back(Op{OP_QSPLIT, 0, 0, 0, "split_Qt"});
+  for (int cls = 0; cls < 3; ++cls) {
+    const int rank = 32 << cls;
+    std::vector<int64_t> ids;
+    for (int64_t i = 0; i < nb; ++i)
+      if (lr_of[i] >= 0 && c->table[i].rank == rank) ids.push_back(i);
+    if (ids.empty()) continue;
+    // longest rows first; whole blocks dealt to the least loaded XCD
+    std::stable_sort(ids.begin(), ids.end(), [&](int64_t a, int64_t b) {
+      const double ca = (double)c->table[a].rows * c->table[a].cols, cb = (double)c->table[b].rows * c->table[b].cols;
+      if (c->table[a].cols != c->table[b].cols) return c->table[a].cols > c->table[b].cols;
+      return ca > cb;
+    });
+    std::vector<ProjItem> per[NXCD];
+    double load[NXCD] = {0};
+    for (int64_t i : ids) {
+      int x = 0;
+      for (int k = 1; k < NXCD; ++k) if (load[k] < load[x]) x = k;
+      const adapm_block_t& b = c->table[i];
+      for (int64_t r0 = 0; r0 < b.rows; r0 += 64) per[x].push_back(ProjItem{(int32_t)lr_of[i], (int32_t)r0});
+      load[x] += (double)b.rows * b.cols;
+    }
+    size_t longest = 0;
+    for (auto& v : per) longest = std::max(longest, v.size());
+    for (size_t q = 0; q < longest; ++q)
+      for (int x = 0; x < NXCD; ++x) c->proj[cls].h.push_back(q < per[x].size() ? per[x][q] : ProjItem{-1, 0});
+    seq.push_back(Op{OP_PROJ, cls, 0, 0, cls == 0 ? "fused_project_r32" : (cls == 1 ? "fused_project_r64" : "fused_project_r128")});
+  }
+}
+
 // Lay out state / workspace and build every work list.
 void build_plan(adapm_ctx* c) {
   const int64_t nb = (int64_t)c->table.size();
   const adapm_hparams_t& hp = c->hp;
   c->lay.assign(nb, Layout());
   size_t so = 0, wo = 0;
-  const double b1 = hp.beta1;
 
   for (int64_t i = 0; i < nb; ++i) {
     const adapm_block_t& b = c->table[i];
@@ -215,17 +448,20 @@ void build_plan(adapm_ctx* c) {
     const int64_t m = b.rows, n = b.cols, r = b.rank;
     auto salloc = [&](size_t bytes) { int64_t o = (int64_t)so; so += align_up(bytes); return o; };
     auto walloc = [&](size_t bytes) { int64_t o = (int64_t)wo; wo += align_up(bytes); return o; };
+    L.path = path_of(b, hp);
     if (b.mom_mode == ADAPM_MOM_LOWRANK) {
       L.sL = salloc(4 * m * r);
       L.sR = salloc(4 * r * n);
-      // every intermediate of a step stays in fp64; only the state is rounded to fp32, once per step
-      L.wLa = walloc(8 * m * r); L.wRa = walloc(8 * r * n);
-      L.wLb = walloc(8 * m * r); L.wRb = walloc(8 * r * n);
-      L.wP = walloc(8 * m * r); L.wS = walloc(8 * r * n);
-      L.wGrr = walloc(8 * r * r); L.wGpr = walloc(8 * r * r);
-      L.wGll = walloc(8 * r * r); L.wGlp = walloc(8 * r * r);
+      // F64 path: every intermediate of a step stays in fp64, only the state is rounded to fp32
+      const size_t es = L.path == PATH_FAST ? 4 : 8;
+      L.wLa = walloc(es * m * r); L.wRa = walloc(es * r * n);
+      L.wLb = walloc(es * m * r); L.wRb = walloc(es * r * n);
+      L.wP = walloc(es * m * r); L.wS = walloc(es * r * n);
+      L.wGrr = walloc(es * r * r); L.wGpr = walloc(es * r * r);
+      L.wGll = walloc(es * r * r); L.wGlp = walloc(es * r * r);
       L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
       L.wC = walloc(4 * m * n);
+      if (L.path == PATH_FAST && hp.refresh_period_T > 1) { L.wQth = walloc(2 * n * r); L.wQtl = walloc(2 * n * r); }
       c->n_lowrank++;
     } else if (b.mom_mode == ADAPM_MOM_FULL) {
       L.sm = salloc(4 * m * n);
@@ -248,20 +484,22 @@ void build_plan(adapm_ctx* c) {
     d.mom_mode = b.mom_mode; d.v_mode = b.v_mode;
     d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
     c->blocks.h.push_back(d);
-    auto& ew = (b.mom_mode == ADAPM_MOM_LOWRANK) ? c->ew_lr.h : c->ew_main.h;
+    auto& ew = c->ew[L.path == PATH_NONE ? 0 : (L.path == PATH_F64 ? 1 : 2)].h;
     for (int64_t s = 0; s < d.numel; s += EW_CHUNK)
       ew.push_back(EwItem{s, (int32_t)i, (int32_t)std::min<int64_t>(EW_CHUNK, d.numel - s)});
     if (b.v_mode != ADAPM_V_ELEMENT) {
+      // on the MFMA path with T > 1 the fused kernel finishes fusable groups itself on steps with R held
+      const int which = (L.path == PATH_FAST && hp.refresh_period_T > 1 && v_fusable(b)) ? 1 : 0;
       const int64_t ge = d.group_elems;
       for (int64_t g = 0; g < L.nv; ++g) {
         if (ge <= VS_CHUNK) {
-          c->vs.h.push_back(VsItem{g * ge, g, (int32_t)i, (int32_t)ge, 1, 0});
+          c->vs[which].h.push_back(VsItem{g * ge, g, (int32_t)i, (int32_t)ge, 1, 0});
         } else {
           const int64_t np = (ge + VS_CHUNK - 1) / VS_CHUNK;
-          c->vf.h.push_back(VfItem{npart, g, (int32_t)i, (int32_t)np});
+          c->vf[which].h.push_back(VfItem{npart, g, (int32_t)i, (int32_t)np});
           for (int64_t p = 0; p < np; ++p)
-            c->vs.h.push_back(VsItem{g * ge + p * VS_CHUNK, npart + p, (int32_t)i,
-                                     (int32_t)std::min<int64_t>(VS_CHUNK, ge - p * VS_CHUNK), 0, 0});
+            c->vs[which].h.push_back(VsItem{g * ge + p * VS_CHUNK, npart + p, (int32_t)i,
+                                            (int32_t)std::min<int64_t>(VS_CHUNK, ge - p * VS_CHUNK), 0, 0});
           npart += np;
         }
       }
@@ -278,140 +516,23 @@ void build_plan(adapm_ctx* c) {
   if (npart > 0) { c->off_partials = (int64_t)wo; wo += align_up(8 * (size_t)npart); }
   c->ws_bytes = wo;
 
-  // ---- common prefix: v statistics, then full / no-momentum blocks
-  if (!c->vs.h.empty()) c->seq_common.push_back(Op{OP_VSTAT, 0, 0, 0});
-  if (!c->vf.h.empty()) c->seq_common.push_back(Op{OP_VFINAL, 0, 0, 0});
-  if (!c->ew_main.h.empty()) c->seq_common.push_back(Op{OP_UPDATE, 0, 0, 0});
-  if (c->n_lowrank == 0) return;
-
-  // ---- low-rank blocks, F64 contraction path
-  const std::vector<double> etas = effective_step_sizes(hp.refresh_iters_K);
-  const int n_eff = (int)etas.size();
-  auto new_list = [&]() { c->gemms.emplace_back(); return (int)c->gemms.size() - 1; };
-
-  // refresh step ------------------------------------------------------------
-  {
-    std::vector<int> listA(n_eff), listB(n_eff);
-    for (int e = 0; e < n_eff; ++e) { listA[e] = new_list(); listB[e] = new_list(); }
-    const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list() : -1;
-    const int l_epi = new_list();
-    const int l_gram = hp.refresh_period_T > 1 ? new_list() : -1;
-    const int l_fin = (hp.refresh_period_T > 1 || n_eff > 0) ? new_list() : -1;
-    for (int64_t i = 0; i < nb; ++i) {
-      const adapm_block_t& b = c->table[i];
-      if (b.mom_mode != ADAPM_MOM_LOWRANK) continue;
-      const Layout& L = c->lay[i];
-      const int m = (int)b.rows, n = (int)b.cols, r = b.rank;
-      const int gdt = b.grad_dtype == ADAPM_BF16 ? DT_BF16 : DT_F32;
-      const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
-      const Mat Lp = mat(SP_STATE, 0, L.sL, r, 1, DT_F32), Rp = mat(SP_STATE, 0, L.sR, n, 1, DT_F32);
-      auto T = [](const Mat& a) { Mat t = a; t.s0 = a.s1; t.s1 = a.s0; return t; };
-      auto fL = [&](int which) { return mat(SP_WS, 0, which ? L.wLb : L.wLa, r, 1, DT_F64); };
-      auto fR = [&](int which) { return mat(SP_WS, 0, which ? L.wRb : L.wRa, n, 1, DT_F64); };
-      const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F64), S = mat(SP_WS, 0, L.wS, n, 1, DT_F64);
-      const Mat Grr = mat(SP_WS, 0, L.wGrr, r, 1, DT_F64), Gpr = mat(SP_WS, 0, L.wGpr, r, 1, DT_F64);
-      const Mat Gll = mat(SP_WS, 0, L.wGll, r, 1, DT_F64), Glp = mat(SP_WS, 0, L.wGlp, r, 1, DT_F64);
-      Mat Lc = Lp, Rc = Rp;
-      for (int e = 0; e < n_eff; ++e) {
-        const double eta = etas[e];
-        const Mat Ln = fL(e & 1), Rn = fR(e & 1);
-        GemmList& A = c->gemms[listA[e]];
-        GemmProblem p;
-        // thin products of Alg. 2 written without forming L R - m_t:
-        //   (L R - m_t) R^T = L (R R^T) - (1-b1) G R^T - b1 L' (R' R^T)
-        //   L^T (L R - m_t) = (L^T L) R - (1-b1) L^T G - b1 (L^T L') R'
-        p = problem(m, r); p.A1 = G; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = P; add_problem(A, p);
-        p = problem(r, n); p.A1 = T(Lc); p.B1 = G; p.K1 = m; p.a1 = 1; p.Out = S; add_problem(A, p);
-        p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Grr; add_problem(A, p);
-        p = problem(r, r); p.A1 = Rp; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Gpr; add_problem(A, p);
-        p = problem(r, r); p.A1 = T(Lc); p.B1 = Lc; p.K1 = m; p.a1 = 1; p.Out = Gll; add_problem(A, p);
-        p = problem(r, r); p.A1 = T(Lc); p.B1 = Lp; p.K1 = m; p.a1 = 1; p.Out = Glp; add_problem(A, p);
-        GemmList& B = c->gemms[listB[e]];
-        p = problem(m, r);
-        p.A1 = Lc; p.B1 = Grr; p.K1 = r; p.a1 = -eta;
-        p.A2 = Lp; p.B2 = Gpr; p.K2 = r; p.a2 = eta * b1;
-        p.X = Lc; p.g = 1.0; p.Y = P; p.d = eta * (1.0 - b1); p.Out = Ln;
-        add_problem(B, p);
-        p = problem(r, n);
-        p.A1 = Gll; p.B1 = Rc; p.K1 = r; p.a1 = -eta;
-        p.A2 = Glp; p.B2 = Rp; p.K2 = r; p.a2 = eta * b1;
-        p.X = Rc; p.g = 1.0; p.Y = S; p.d = eta * (1.0 - b1); p.Out = Rn;
-        add_problem(B, p);
-        Lc = Ln; Rc = Rn;
-      }
-      GemmProblem p;
-      if (l_pre >= 0) {      // no effective iteration but an in-place re-gauge ahead: work on a copy
-        p = problem(m, r); p.X = Lp; p.g = 1.0; p.Out = fL(0); add_problem(c->gemms[l_pre], p);
-        p = problem(r, n); p.X = Rp; p.g = 1.0; p.Out = fR(0); add_problem(c->gemms[l_pre], p);
-        Lc = fL(0); Rc = fR(0);
-      }
-      // m x n low-rank term of m^c (eq. 4): C = L'R' - L R, or L R without the correction
-      const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
-      p = problem(m, n);
-      if (hp.bias_correction) {
-        p.A1 = Lp; p.B1 = Rp; p.K1 = r; p.a1 = 1.0;
-        p.A2 = Lc; p.B2 = Rc; p.K2 = r; p.a2 = -1.0;
-      } else {
-        p.A1 = Lc; p.B1 = Rc; p.K1 = r; p.a1 = 1.0;
-      }
-      p.Out = C;
-      add_problem(c->gemms[l_epi], p);
-      if (hp.refresh_period_T > 1) {
-        const Mat G64 = mat(SP_WS, 0, L.wG64, r, 1, DT_F64), Cinv = mat(SP_WS, 0, L.wCinv, r, 1, DT_F64);
-        p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1.0; p.Out = G64;
-        add_problem(c->gemms[l_gram], p);
-        c->chol.h.push_back(CholItem{L.wG64, L.wCinv, r, 0});
-        p = problem(r, n); p.A1 = Cinv; p.B1 = Rc; p.K1 = r; p.a1 = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
-        p = problem(m, r); p.A1 = Lc; p.B1 = G64; p.K1 = r; p.a1 = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
-      } else if (n_eff > 0) {
-        p = problem(m, r); p.X = Lc; p.g = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
-        p = problem(r, n); p.X = Rc; p.g = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
-      }
+  // ---- every step starts with the v statistics and the full / no-momentum blocks
+  for (int kind = 0; kind < 2; ++kind) {
+    std::vector<Op>& seq = kind == 0 ? c->seq_refresh : c->seq_project;
+    if (!c->vs[0].h.empty()) seq.push_back(Op{OP_VSTAT, 0, 0, 0, "v_statistics"});
+    if (!c->vf[0].h.empty()) seq.push_back(Op{OP_VFINAL, 0, 0, 0, "v_statistics_fold"});
+    if (kind == 0) {
+      if (!c->vs[1].h.empty()) seq.push_back(Op{OP_VSTAT, 1, 0, 0, "v_statistics"});
+      if (!c->vf[1].h.empty()) seq.push_back(Op{OP_VFINAL, 1, 0, 0, "v_statistics_fold"});
     }
-    for (int e = 0; e < n_eff; ++e) {
-      c->seq_refresh.push_back(Op{OP_GEMM, listA[e], 0, 0});
-      c->seq_refresh.push_back(Op{OP_GEMM, listB[e], 0, 0});
-    }
-    if (l_pre >= 0) c->seq_refresh.push_back(Op{OP_GEMM, l_pre, 0, 0});
-    c->seq_refresh.push_back(Op{OP_GEMM, l_epi, 0, 0});
-    const float cG = hp.bias_correction ? 1.f : 0.f;
-    const float cC = hp.bias_correction ? (float)(b1 / (1.0 - b1)) : 1.f;
-    c->seq_refresh.push_back(Op{OP_UPDATE, 1, cG, cC});
-    if (l_gram >= 0) {
-      c->seq_refresh.push_back(Op{OP_GEMM, l_gram, 0, 0});
-      c->seq_refresh.push_back(Op{OP_CHOL, 0, 0, 0});
-    }
-    if (l_fin >= 0) c->seq_refresh.push_back(Op{OP_GEMM, l_fin, 0, 0});
+    if (!c->ew[0].h.empty()) seq.push_back(Op{OP_UPDATE, 0, 0, 0, "update_full"});
   }
-
-  // projection step (T > 1, R = Q held with orthonormal rows) ----------------
+  if (c->n_lowrank == 0) return;
+  plan_lowrank_refresh(c, false);
+  plan_lowrank_refresh(c, true);
   if (hp.refresh_period_T > 1) {
-    const int l_p = new_list(), l_d = new_list(), l_l = new_list(), l_c = new_list();
-    for (int64_t i = 0; i < nb; ++i) {
-      const adapm_block_t& b = c->table[i];
-      if (b.mom_mode != ADAPM_MOM_LOWRANK) continue;
-      const Layout& L = c->lay[i];
-      const int m = (int)b.rows, n = (int)b.cols, r = b.rank;
-      const int gdt = b.grad_dtype == ADAPM_BF16 ? DT_BF16 : DT_F32;
-      const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
-      const Mat Ls = mat(SP_STATE, 0, L.sL, r, 1, DT_F32), Q = mat(SP_STATE, 0, L.sR, n, 1, DT_F32);
-      Mat Qt = Q; Qt.s0 = Q.s1; Qt.s1 = Q.s0;
-      const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F64), D = mat(SP_WS, 0, L.wLa, r, 1, DT_F64);
-      const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
-      GemmProblem p;
-      p = problem(m, r); p.A1 = G; p.B1 = Qt; p.K1 = n; p.a1 = 1.0; p.Out = P; add_problem(c->gemms[l_p], p);
-      // L_t = b1 L' + (1-b1) G Q^T;  m^c = G + b1 (L' - G Q^T) Q   (or L_t Q without the correction)
-      p = problem(m, r); p.X = Ls; p.Y = P; p.Out = D;
-      if (hp.bias_correction) { p.g = b1; p.d = -b1; } else { p.g = b1; p.d = 1.0 - b1; }
-      add_problem(c->gemms[l_d], p);
-      p = problem(m, r); p.X = Ls; p.g = b1; p.Y = P; p.d = 1.0 - b1; p.Out = Ls; add_problem(c->gemms[l_l], p);
-      p = problem(m, n); p.A1 = D; p.B1 = Q; p.K1 = r; p.a1 = 1.0; p.Out = C; add_problem(c->gemms[l_c], p);
-    }
-    c->seq_project.push_back(Op{OP_GEMM, l_p, 0, 0});
-    c->seq_project.push_back(Op{OP_GEMM, l_d, 0, 0});
-    c->seq_project.push_back(Op{OP_GEMM, l_l, 0, 0});
-    c->seq_project.push_back(Op{OP_GEMM, l_c, 0, 0});
-    c->seq_project.push_back(Op{OP_UPDATE, 1, hp.bias_correction ? 1.f : 0.f, 1.f});
+    plan_lowrank_project_f64(c);
+    plan_lowrank_project_fast(c);
   }
 }
 
@@ -423,8 +544,10 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   int dev = -1;
   HIP_TRY(hipGetDevice(&dev));
   const size_t nb = c->table.size();
-  size_t total = bytes_of(c->blocks.h) + bytes_of(c->ew_main.h) + bytes_of(c->ew_lr.h) + bytes_of(c->vs.h) +
-                 bytes_of(c->vf.h) + bytes_of(c->sk.h) + bytes_of(c->chol.h) + align_up(2 * nb * sizeof(void*));
+  size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
+                 align_up(2 * nb * sizeof(void*));
+  for (int i = 0; i < 3; ++i) total += bytes_of(c->ew[i].h) + bytes_of(c->proj[i].h);
+  for (int i = 0; i < 2; ++i) total += bytes_of(c->vs[i].h) + bytes_of(c->vf[i].h) + bytes_of(c->chol[i].h);
   for (auto& g : c->gemms) total += bytes_of(g.probs) + bytes_of(g.tiles);
   HIP_TRY(hipMalloc((void**)&c->arena, total));
   size_t off = 0;
@@ -436,8 +559,9 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     return dst;
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
-  PUT_LIST(c->blocks); PUT_LIST(c->ew_main); PUT_LIST(c->ew_lr); PUT_LIST(c->vs); PUT_LIST(c->vf);
-  PUT_LIST(c->sk); PUT_LIST(c->chol);
+  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs);
+  for (int i = 0; i < 3; ++i) { PUT_LIST(c->ew[i]); PUT_LIST(c->proj[i]); }
+  for (int i = 0; i < 2; ++i) { PUT_LIST(c->vs[i]); PUT_LIST(c->vf[i]); PUT_LIST(c->chol[i]); }
 #undef PUT_LIST
   for (auto& g : c->gemms) {
     g.d_probs = (GemmProblem*)put(g.probs.data(), g.probs.size() * sizeof(GemmProblem));
@@ -560,43 +684,100 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
     sc.inv_debias_v = (float)(1.0 / (1.0 - std::pow((double)c->hp.beta2, (double)step)));
   }
   sc.cG = sc.cC = 0.f;
+  // step with R held: D = beta1 (L' - P) with eq. 4, or D = L_t without it
+  sc.dL = c->hp.beta1;
+  sc.dP = c->hp.bias_correction ? -c->hp.beta1 : 1.f - c->hp.beta1;
 
+  double* partials = c->off_partials >= 0 ? (double*)(bs.ws + c->off_partials) : nullptr;
   int64_t launches = 0;
-  auto run = [&](const std::vector<Op>& seq) {
-    for (const Op& op : seq) {
-      switch (op.kind) {
-        case OP_VSTAT:
-          launch_vstat(c->blocks.d, c->vs.d, (int64_t)c->vs.h.size(),
-                       c->off_partials >= 0 ? (double*)(bs.ws + c->off_partials) : nullptr, bs, sc.beta2, s);
-          break;
-        case OP_VFINAL:
-          launch_vfinal(c->blocks.d, c->vf.d, (int64_t)c->vf.h.size(), (const double*)(bs.ws + c->off_partials), bs,
-                        sc.beta2, s);
-          break;
-        case OP_UPDATE: {
-          StepScalars x = sc;
-          x.cG = op.cG; x.cC = op.cC;
-          if (op.index == 0) launch_update(c->blocks.d, c->ew_main.d, (int64_t)c->ew_main.h.size(), bs, x, s);
-          else launch_update(c->blocks.d, c->ew_lr.d, (int64_t)c->ew_lr.h.size(), bs, x, s);
-          break;
-        }
-        case OP_GEMM: {
-          const GemmList& g = c->gemms[op.index];
-          launch_gemm64(g.d_probs, g.d_tiles, (int64_t)g.tiles.size(), bs, s);
-          break;
-        }
-        case OP_CHOL:
-          launch_chol(c->chol.d, (int64_t)c->chol.h.size(), bs, s);
-          break;
+  const std::vector<Op>& seq = is_refresh(c, step) ? c->seq_refresh : c->seq_project;
+  for (const Op& op : seq) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (c->profiling) {
+      for (hipEvent_t* e : {&e0, &e1}) {
+        if (!c->event_pool.empty()) { *e = c->event_pool.back(); c->event_pool.pop_back(); }
+        else HIP_TRY(hipEventCreate(e));
       }
-      ++launches;
+      HIP_TRY(hipEventRecord(e0, s));
     }
-  };
-  run(c->seq_common);
-  if (c->n_lowrank) run(is_refresh(c, step) ? c->seq_refresh : c->seq_project);
+    switch (op.kind) {
+      case OP_VSTAT:
+        launch_vstat(c->blocks.d, c->vs[op.index].d, (int64_t)c->vs[op.index].h.size(), partials, bs, sc.beta2, s);
+        break;
+      case OP_VFINAL:
+        launch_vfinal(c->blocks.d, c->vf[op.index].d, (int64_t)c->vf[op.index].h.size(), partials, bs, sc.beta2, s);
+        break;
+      case OP_UPDATE: {
+        StepScalars x = sc;
+        x.cG = op.cG; x.cC = op.cC;
+        launch_update(c->blocks.d, c->ew[op.index].d, (int64_t)c->ew[op.index].h.size(), bs, x, s);
+        break;
+      }
+      case OP_GEMM: {
+        const GemmList& g = c->gemms[op.index];
+        launch_gemm64(g.d_probs, g.d_tiles, (int64_t)g.tiles.size(), bs, s);
+        break;
+      }
+      case OP_GEMM_MFMA: {
+        const GemmList& g = c->gemms[op.index];
+        launch_gemm_mfma(g.d_probs, g.d_tiles, (int64_t)g.tiles.size(), bs, s);
+        break;
+      }
+      case OP_CHOL:
+        launch_chol(c->chol[op.index].d, (int64_t)c->chol[op.index].h.size(), bs, s);
+        break;
+      case OP_QSPLIT:
+        launch_qsplit(c->qs.d, (int64_t)c->qs.h.size(), c->lrb.d, bs, s);
+        break;
+      case OP_PROJ: {
+        StepScalars x = sc;
+        x.cG = c->hp.bias_correction ? 1.f : 0.f;
+        x.cC = 1.f;
+        launch_proj(1 << op.index, c->proj[op.index].d, (int64_t)c->proj[op.index].h.size(), c->lrb.d, bs, x, s);
+        break;
+      }
+    }
+    if (c->profiling) {
+      HIP_TRY(hipEventRecord(e1, s));
+      c->prof.push_back(ProfRec{op.label, e0, e1});
+    }
+    ++launches;
+  }
   c->last_launches = launches;
   HIP_TRY(hipGetLastError());
   return ADAPM_OK;
+}
+
+adapm_status_t adapm_profile_enable(adapm_ctx* c, int32_t on) {
+  if (!c) return fail(ADAPM_EINVAL, "ctx is null");
+  c->profiling = on != 0;
+  return ADAPM_OK;
+}
+
+int64_t adapm_profile_read(adapm_ctx* c, int64_t index, char* name, size_t name_cap, double* total_ms,
+                           int64_t* launches) {
+  if (!c) return 0;
+  // fold the finished event pairs into per-label totals (the caller has synchronised the stream)
+  static thread_local std::vector<std::pair<std::string, std::pair<double, int64_t>>> agg;
+  if (index == 0) {
+    agg.clear();
+    for (const ProfRec& r : c->prof) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) ms = 0.f;
+      c->event_pool.push_back(r.e0);
+      c->event_pool.push_back(r.e1);
+      bool found = false;
+      for (auto& a : agg)
+        if (a.first == r.label) { a.second.first += ms; a.second.second += 1; found = true; break; }
+      if (!found) agg.push_back({r.label, {ms, 1}});
+    }
+    c->prof.clear();
+  }
+  if (index < 0 || index >= (int64_t)agg.size()) return (int64_t)agg.size();
+  if (name && name_cap) { strncpy(name, agg[index].first.c_str(), name_cap - 1); name[name_cap - 1] = 0; }
+  if (total_ms) *total_ms = agg[index].second.first;
+  if (launches) *launches = agg[index].second.second;
+  return (int64_t)agg.size();
 }
 
 int64_t adapm_last_launch_count(const adapm_ctx* c) { return c ? c->last_launches : 0; }
@@ -637,6 +818,8 @@ void adapm_destroy(adapm_ctx* c) {
   if (c->uploaded) {
     if (c->stage_free) { (void)hipEventSynchronize(c->stage_free); (void)hipEventDestroy(c->stage_free); }
     if (c->h_stage) (void)hipHostFree(c->h_stage);
+    for (const ProfRec& r : c->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+    for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
     if (c->arena) (void)hipFree(c->arena);
   }
   delete c;

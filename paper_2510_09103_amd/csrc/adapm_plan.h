@@ -102,6 +102,34 @@ struct StepScalars {
   float lr;
   float inv_debias_m, inv_debias_v;   // 1/(1-beta1^t), 1/(1-beta2^t) or 1
   float cG, cC;                       // low-rank blocks: m^c = cG * G + cC * C
+  float dL, dP;                       // fused step with R held: D = dL * L_{t-1} + dP * (G Q^T)
+};
+
+// ---------------------------------------------------------------------------
+// fused step with R held (k_proj_mfma.hip)
+// ---------------------------------------------------------------------------
+struct LrBlockDev {
+  int32_t block;           // index into the gradient / parameter pointer tables
+  int32_t m, n, r;
+  int64_t off_L, off_Q;    // state: L (m x r), Q = R (r x n), fp32
+  int64_t off_v;           // state: v
+  int64_t off_Qt_hi, off_Qt_lo;   // ws: Q^T as bf16 (hi, lo), [n][r]
+  int32_t v_kind;          // 0 per element; 1 groups of v_group_rows rows finished inside the stripe;
+                           // 2 finished beforehand by the statistics kernel
+  int32_t v_group_rows;
+  int32_t param_dtype;
+  float lr_scale, wd;
+  int32_t pad;
+};
+
+struct ProjItem {          // one workgroup: 64 rows of one block; lr < 0 = padding
+  int32_t lr;
+  int32_t row0;
+};
+
+struct QsItem {            // one workgroup: 32 rows x 64 columns of Q
+  int32_t lr;
+  int32_t a0, j0;
 };
 
 struct SketchItem {      // seeded start R_0 of one low-rank block
@@ -133,5 +161,9 @@ void launch_update(const BlockDev* blocks, const EwItem* items, int64_t nitems, 
 void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 void launch_sketch(const SketchItem* items, int64_t nitems, char* state, hipStream_t s);
 void launch_chol(const CholItem* items, int64_t nitems, Bases b, hipStream_t s);
+void launch_gemm_mfma(const GemmProblem* probs, const GemmTile* tiles, int64_t ntiles, Bases b, hipStream_t s);
+void launch_proj(int rt, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, StepScalars sc,
+                 hipStream_t s);
+void launch_qsplit(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s);
 
 }  // namespace adapm
