@@ -9,6 +9,7 @@
 //    (eq. 4 rewritten as m^c = G + beta1/(1-beta1) (L_{t-1}R_{t-1} - L_t R_t)), per-element v,
 //    then W <- W - lr (clip(m^c / (sqrt(v) + eps)) + lambda W)  (Alg. 1 last line).
 #include "adapm_plan.h"
+#include "ew_math.h"
 
 namespace adapm {
 
@@ -40,11 +41,8 @@ __device__ __forceinline__ void load8(const char* base, int dtype, int64_t e, fl
 
 __device__ __forceinline__ void store8(char* base, int dtype, int64_t e, const float in[8]) {
   if (dtype == DT_BF16) {
-    uint32_t w[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      w[i] = (uint32_t)f32_to_bf16_rne(in[2 * i]) | ((uint32_t)f32_to_bf16_rne(in[2 * i + 1]) << 16);
-    *reinterpret_cast<uint4*>(base + e * 2) = make_uint4(w[0], w[1], w[2], w[3]);
+    *reinterpret_cast<uint4*>(base + e * 2) = make_uint4(pack_bf16x2(in[0], in[1]), pack_bf16x2(in[2], in[3]),
+                                                         pack_bf16x2(in[4], in[5]), pack_bf16x2(in[6], in[7]));
   } else {
     *reinterpret_cast<float4*>(base + e * 4) = make_float4(in[0], in[1], in[2], in[3]);
     *reinterpret_cast<float4*>(base + e * 4 + 16) = make_float4(in[4], in[5], in[6], in[7]);
@@ -83,13 +81,20 @@ __global__ __launch_bounds__(256) void vstat_kernel(const BlockDev* __restrict__
   const int64_t a0 = min((s + 7) & ~(int64_t)7, e), a1 = max(e & ~(int64_t)7, a0);
   float acc = 0.f;
   for (int64_t i = s + lane; i < a0; i += 64) { float g = load1(G, blk.grad_dtype, i); acc += g * g; }
-  for (int64_t i = a0 + (int64_t)lane * 8; i < a1; i += 512) {
-    float g[8];
-    load8(G, blk.grad_dtype, i, g);
-    float t = 0.f;
+  if (blk.grad_dtype == DT_BF16) {
+    for (int64_t i = a0 + (int64_t)lane * 8; i < a1; i += 512) {
+      const uint4 q = *reinterpret_cast<const uint4*>(G + i * 2);
+      acc += dot2_sq(q.w, dot2_sq(q.z, dot2_sq(q.y, dot2_sq(q.x, 0.f))));
+    }
+  } else {
+    for (int64_t i = a0 + (int64_t)lane * 8; i < a1; i += 512) {
+      float g[8];
+      load8(G, DT_F32, i, g);
+      float t = 0.f;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t += g[k] * g[k];
-    acc += t;
+      for (int k = 0; k < 8; ++k) t += g[k] * g[k];
+      acc += t;
+    }
   }
   for (int64_t i = a1 + lane; i < e; i += 64) { float g = load1(G, blk.grad_dtype, i); acc += g * g; }
   double sum = wave_sum((double)acc);
@@ -119,12 +124,6 @@ __global__ __launch_bounds__(256) void vfinal_kernel(const BlockDev* __restrict_
 // ---------------------------------------------------------------------------
 // fused update
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ float update_one(float w, float mc, float v, const StepScalars& sc, float lrs, float wd) {
-  float u = (mc * sc.inv_debias_m) / (sqrtf(v * sc.inv_debias_v) + sc.eps);
-  u = fminf(fmaxf(u, -sc.clip), sc.clip);
-  return w - lrs * (u + wd * w);
-}
-
 __global__ __launch_bounds__(256) void update_kernel(const BlockDev* __restrict__ blocks,
                                                      const EwItem* __restrict__ items, Bases b, StepScalars sc) {
   const EwItem item = items[blockIdx.x];
@@ -134,30 +133,43 @@ __global__ __launch_bounds__(256) void update_kernel(const BlockDev* __restrict_
   float* m = blk.off_m >= 0 ? reinterpret_cast<float*>(b.state + blk.off_m) : nullptr;
   float* v = reinterpret_cast<float*>(b.state + blk.off_v);
   const float* C = blk.off_C >= 0 ? reinterpret_cast<const float*>(b.ws + blk.off_C) : nullptr;
-  const float lrs = sc.lr * blk.lr_scale, wd = blk.wd;
+  const UpdCoef cf = make_coef(sc.lr, blk.lr_scale, blk.wd, sc.clip);
   const float ob1 = 1.f - sc.beta1, ob2 = 1.f - sc.beta2;
   const int nvec = (item.count + 7) >> 3;
   const int64_t end = item.start + item.count;
+  // group index of this thread's first vector; later vectors advance by 2048 elements
+  const int64_t ge = blk.group_elems;
+  int64_t grp = 0, rem = 0, dq = 0, dr = 0;
+  if (blk.v_mode != VM_ELEMENT) {
+    const int64_t e0 = item.start + (int64_t)threadIdx.x * 8;
+    if (ge < (1ll << 31) && e0 < (1ll << 31)) { grp = (uint32_t)e0 / (uint32_t)ge; rem = (uint32_t)e0 % (uint32_t)ge; dq = 2048u / (uint32_t)ge; dr = 2048u % (uint32_t)ge; }
+    else { grp = e0 / ge; rem = e0 % ge; dq = 2048 / ge; dr = 2048 % ge; }
+  }
   for (int iv = threadIdx.x; iv < nvec; iv += 256) {
     const int64_t e = item.start + (int64_t)iv * 8;
     if (e + 8 <= end) {
-      float g[8], w[8], vv[8], mc[8];
+      float g[8], w[8], inv[8], mc[8];
       load8(G, blk.grad_dtype, e, g);
       load8(W, blk.param_dtype, e, w);
       if (blk.v_mode == VM_ELEMENT) {
+        float vv[8];
         load8((const char*)v, DT_F32, e, vv);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) vv[k] = sc.beta2 * vv[k] + ob2 * g[k] * g[k];
+        for (int k = 0; k < 8; ++k) {
+          vv[k] = sc.beta2 * vv[k] + ob2 * g[k] * g[k];
+          inv[k] = inv_denom_fast(vv[k], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
+        }
         store8((char*)v, DT_F32, e, vv);
+      } else if (rem + 8 <= ge) {
+        const float x = inv_denom_fast(v[grp], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) inv[k] = x;
       } else {
-        const int64_t g0 = e / blk.group_elems, g1 = (e + 7) / blk.group_elems;
-        if (g0 == g1) {
-          const float x = v[g0];
+        int64_t gk = grp, rk = rem;
 #pragma unroll
-          for (int k = 0; k < 8; ++k) vv[k] = x;
-        } else {
-#pragma unroll
-          for (int k = 0; k < 8; ++k) vv[k] = v[(e + k) / blk.group_elems];
+        for (int k = 0; k < 8; ++k) {
+          inv[k] = inv_denom_fast(v[gk], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
+          if (++rk == ge) { rk = 0; ++gk; }
         }
       }
       if (blk.mom_mode == MM_FULL) {            // full momentum, eq. 5
@@ -165,7 +177,7 @@ __global__ __launch_bounds__(256) void update_kernel(const BlockDev* __restrict_
 #pragma unroll
         for (int k = 0; k < 8; ++k) mc[k] = ob1 * g[k] + sc.beta1 * mc[k];
         store8((char*)m, DT_F32, e, mc);
-      } else if (blk.mom_mode == MM_LOWRANK) {     // low-rank: m^c = cG G + cC C
+      } else if (blk.mom_mode == MM_LOWRANK) {  // low-rank: m^c = cG G + cC C
         load8((const char*)C, DT_F32, e, mc);
 #pragma unroll
         for (int k = 0; k < 8; ++k) mc[k] = sc.cG * g[k] + sc.cC * mc[k];
@@ -174,9 +186,10 @@ __global__ __launch_bounds__(256) void update_kernel(const BlockDev* __restrict_
         for (int k = 0; k < 8; ++k) mc[k] = g[k];
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) w[k] = update_one(w[k], mc[k], vv[k], sc, lrs, wd);
+      for (int k = 0; k < 8; ++k) w[k] = apply_update(w[k], mc[k], inv[k], cf);
       store8(W, blk.param_dtype, e, w);
     } else {
+      int64_t gk = grp, rk = rem;
       for (int64_t i = e; i < end; ++i) {
         const float g = load1(G, blk.grad_dtype, i);
         const float w = load1(W, blk.param_dtype, i);
@@ -185,14 +198,20 @@ __global__ __launch_bounds__(256) void update_kernel(const BlockDev* __restrict_
           vv = sc.beta2 * v[i] + ob2 * g * g;
           v[i] = vv;
         } else {
-          vv = v[i / blk.group_elems];
+          vv = v[gk];
+          if (++rk == ge) { rk = 0; ++gk; }
         }
         float mc;
         if (blk.mom_mode == MM_FULL) { mc = ob1 * g + sc.beta1 * m[i]; m[i] = mc; }
         else if (blk.mom_mode == MM_LOWRANK) mc = sc.cG * g + sc.cC * C[i];
         else mc = g;
-        store1(W, blk.param_dtype, i, update_one(w, mc, vv, sc, lrs, wd));
+        store1(W, blk.param_dtype, i,
+               apply_update(w, mc, inv_denom_fast(vv, sc.inv_debias_v, sc.inv_debias_m, sc.eps), cf));
       }
+    }
+    if (blk.v_mode != VM_ELEMENT) {
+      grp += dq; rem += dr;
+      if (rem >= ge) { rem -= ge; ++grp; }
     }
   }
 }

@@ -14,6 +14,7 @@
 // carried as a (hi, lo) pair of bf16 values, products hi*hi + lo*hi + hi*lo accumulated in fp32
 // (relative operand error 2^-17).
 #include "adapm_plan.h"
+#include "ew_math.h"
 
 namespace adapm {
 
@@ -28,19 +29,6 @@ constexpr int BN = 64;     // columns per chunk of pass 2
 constexpr int GS = BK + 8; // LDS row strides (elements), padded so 16-byte fragment reads spread over all banks
 constexpr int CS = BN + 8;
 
-__device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-// x -> (hi, lo) with hi = bf16(x), lo = bf16(x - hi)
-__device__ __forceinline__ void split2(float x, uint32_t& hi, uint32_t& lo) {
-  hi = bf16_rne_bits(x);
-  lo = bf16_rne_bits(x - __uint_as_float(hi << 16));
-}
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
 union Frag {
   bf16x8 v;
   uint4 q;
@@ -50,12 +38,6 @@ __device__ __forceinline__ bf16x8 lds_frag(const uint16_t* p) {
   Frag f;
   f.q = *reinterpret_cast<const uint4*>(p);
   return f.v;
-}
-
-__device__ __forceinline__ float update_elem(float w, float mc, float v, const StepScalars& sc, float lrs, float wd) {
-  float u = (mc * sc.inv_debias_m) / (sqrtf(v * sc.inv_debias_v) + sc.eps);
-  u = fminf(fmaxf(u, -sc.clip), sc.clip);
-  return w - lrs * (u + wd * w);
 }
 
 template <int RT>
@@ -101,32 +83,49 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   const int my_nt = (RT >= 4) ? wave : (wave % RT);
   const int my_mt0 = (RT >= 4) ? 0 : (wave / RT);
 
-  for (int k0 = 0; k0 < n; k0 += BK) {
-    // stage G chunk (bf16, 16-byte vectors) and accumulate the row sums of squares
+  // The next chunk travels from memory into registers while the matrix cores work on the
+  // current one (one memory round trip per chunk would otherwise be exposed at every barrier).
+  constexpr int QV = (R * BK / 4) / 256;                           // float4 loads of Q per thread and chunk
+  uint4 gpre[2];
+  float4 qpre[QV];
+  auto fetch1 = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
-      uint4 q = make_uint4(0, 0, 0, 0);
-      if (row0 + row < m && k0 + c8 < n) q = *reinterpret_cast<const uint4*>(G + (int64_t)(row0 + row) * n + k0 + c8);
-      *reinterpret_cast<uint4*>(Gs + row * GS + c8) = q;
-      const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-      float s = 0.f;
+      gpre[i] = make_uint4(0, 0, 0, 0);
+      if (row0 + row < m && k0 + c8 < n)
+        gpre[i] = *reinterpret_cast<const uint4*>(G + (int64_t)(row0 + row) * n + k0 + c8);
+    }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { const float a = bf16_lo(w[j]), b = bf16_hi(w[j]); s += a * a + b * b; }
+    for (int i = 0; i < QV; ++i) {
+      const int id = tid + 256 * i, a = id >> 4, c4 = (id & 15) * 4;
+      qpre[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (k0 + c4 < n) qpre[i] = *reinterpret_cast<const float4*>(Q + (int64_t)a * n + k0 + c4);
+    }
+  };
+  fetch1(0);
+  for (int k0 = 0; k0 < n; k0 += BK) {
+    // registers -> LDS: G as is (row sums of squares ride along), Q as (hi, lo) bf16
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
+      const uint4 q = gpre[i];
+      *reinterpret_cast<uint4*>(Gs + row * GS + c8) = q;
+      const float s = dot2_sq(q.w, dot2_sq(q.z, dot2_sq(q.y, dot2_sq(q.x, 0.f))));
       if (i == 0) ss0 += s; else ss1 += s;
     }
-    // stage Q chunk: fp32 -> (hi, lo) bf16
 #pragma unroll
-    for (int i = 0; i < (R * BK / 4) / 256; ++i) {
+    for (int i = 0; i < QV; ++i) {
       const int id = tid + 256 * i, a = id >> 4, c4 = (id & 15) * 4;
-      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (k0 + c4 < n) x = *reinterpret_cast<const float4*>(Q + (int64_t)a * n + k0 + c4);
-      uint32_t h0, l0, h1, l1, h2, l2, h3, l3;
-      split2(x.x, h0, l0); split2(x.y, h1, l1); split2(x.z, h2, l2); split2(x.w, h3, l3);
-      *reinterpret_cast<uint2*>(Qh + a * GS + c4) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-      *reinterpret_cast<uint2*>(Ql + a * GS + c4) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+      const float4 x = qpre[i];
+      uint32_t h0, l0, h1, l1;
+      split_pair(x.x, x.y, h0, l0);
+      split_pair(x.z, x.w, h1, l1);
+      *reinterpret_cast<uint2*>(Qh + a * GS + c4) = make_uint2(h0, h1);
+      *reinterpret_cast<uint2*>(Ql + a * GS + c4) = make_uint2(l0, l1);
     }
     __syncthreads();
+    if (k0 + BK < n) fetch1(k0 + BK);
     if (p1_active) {
 #pragma unroll
       for (int kk = 0; kk < BK / 16; ++kk) {
@@ -160,11 +159,13 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
         float* vp = vst + (row0 + r0) / g;
         const float vn = (float)((double)sc.beta2 * (double)*vp + (1.0 - (double)sc.beta2) * (s / ((double)g * (double)n)));
         *vp = vn;
-        for (int i = 0; i < g; ++i) vrow[r0 + i] = vn;
+        const float inv = inv_denom_exact(vn, sc.inv_debias_v, sc.inv_debias_m, sc.eps);
+        for (int i = 0; i < g; ++i) vrow[r0 + i] = inv;
       }
     }
   } else if (B.v_kind == 2) {      // v finished by the statistics kernel: one value per group of rows
-    if (tid < BM && row0 + tid < m) vrow[tid] = vst[(row0 + tid) / B.v_group_rows];
+    if (tid < BM && row0 + tid < m)
+      vrow[tid] = inv_denom_exact(vst[(row0 + tid) / B.v_group_rows], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
   }
 
   // ------------------------------------------------------------------ L_t and D = dL L' + dP P
@@ -187,7 +188,7 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
             d = sc.dL * lprev + sc.dP * pv;
           }
           uint32_t h, l;
-          split2(d, h, l);
+          split_pair(d, 0.f, h, l);
           Dh[row * DS + col] = (uint16_t)h;
           Dl[row * DS + col] = (uint16_t)l;
         }
@@ -208,21 +209,56 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   uint16_t* Th = reinterpret_cast<uint16_t*>(smem);               // [BN][DS]  Q^T hi
   uint16_t* Tl = Th + BN * DS;                                    // [BN][DS]  Q^T lo
   float* Cs = reinterpret_cast<float*>(smem + 2 * BN * DS * 2);   // [BM][CS]
-  const float lrs = sc.lr * B.lr_scale, wd = B.wd;
+  const UpdCoef cf = make_coef(sc.lr, B.lr_scale, B.wd, sc.clip);
   const float ob2 = 1.f - sc.beta2;
+  constexpr int TV = (BN * R / 8) / 256;                          // 16-byte loads of Q^T per thread, chunk and half
+  uint4 thp[TV], tlp[TV];                                          // next chunk of Q^T (hi, lo)
+  uint4 gcur[2], wcur[4], gnxt[2], wnxt[4];                        // G / W vectors of this and the next chunk
+  const bool w16 = B.param_dtype == DT_BF16;
+  auto fetch_t = [&](int j0) {
+#pragma unroll
+    for (int i = 0; i < TV; ++i) {
+      const int id = tid + 256 * i, j = id / (R / 8), a8 = (id % (R / 8)) * 8;
+      thp[i] = make_uint4(0, 0, 0, 0);
+      tlp[i] = make_uint4(0, 0, 0, 0);
+      if (j0 + j < n) {
+        thp[i] = *reinterpret_cast<const uint4*>(Qth_g + (int64_t)(j0 + j) * R + a8);
+        tlp[i] = *reinterpret_cast<const uint4*>(Qtl_g + (int64_t)(j0 + j) * R + a8);
+      }
+    }
+  };
+  auto fetch_gw = [&](int j0, uint4* gq, uint4* wq) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
+      gq[i] = make_uint4(0, 0, 0, 0);
+      wq[2 * i] = wq[2 * i + 1] = make_uint4(0, 0, 0, 0);
+      if (row0 + row < m && j0 + c8 < n) {
+        const int64_t e = (int64_t)(row0 + row) * n + j0 + c8;
+        gq[i] = *reinterpret_cast<const uint4*>(G + e);
+        if (w16) {
+          wq[2 * i] = *reinterpret_cast<const uint4*>(W + e * 2);
+        } else {
+          wq[2 * i] = *reinterpret_cast<const uint4*>(W + e * 4);
+          wq[2 * i + 1] = *reinterpret_cast<const uint4*>(W + e * 4 + 16);
+        }
+      }
+    }
+  };
+  fetch_t(0);
+  fetch_gw(0, gcur, wcur);
   for (int j0 = 0; j0 < n; j0 += BN) {
 #pragma unroll
-    for (int i = 0; i < (BN * R / 8) / 256; ++i) {
+    for (int i = 0; i < TV; ++i) {
       const int id = tid + 256 * i, j = id / (R / 8), a8 = (id % (R / 8)) * 8;
-      uint4 h = make_uint4(0, 0, 0, 0), l = make_uint4(0, 0, 0, 0);
-      if (j0 + j < n) {
-        h = *reinterpret_cast<const uint4*>(Qth_g + (int64_t)(j0 + j) * R + a8);
-        l = *reinterpret_cast<const uint4*>(Qtl_g + (int64_t)(j0 + j) * R + a8);
-      }
-      *reinterpret_cast<uint4*>(Th + j * DS + a8) = h;
-      *reinterpret_cast<uint4*>(Tl + j * DS + a8) = l;
+      *reinterpret_cast<uint4*>(Th + j * DS + a8) = thp[i];
+      *reinterpret_cast<uint4*>(Tl + j * DS + a8) = tlp[i];
     }
     __syncthreads();
+    if (j0 + BN < n) {
+      fetch_t(j0 + BN);
+      fetch_gw(j0 + BN, gnxt, wnxt);
+    }
     f32x16 c;
 #pragma unroll
     for (int i = 0; i < 16; ++i) c[i] = 0.f;
@@ -245,53 +281,52 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
       if (row0 + row >= m || j0 + c8 >= n) continue;
       const int64_t e = (int64_t)(row0 + row) * n + j0 + c8;
-      const uint4 gq = *reinterpret_cast<const uint4*>(G + e);
-      const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
-      float g[8], w[8], mc[8], vv[8];
+      const uint32_t gw[4] = {gcur[i].x, gcur[i].y, gcur[i].z, gcur[i].w};
+      float g[8], mc[8], inv[8];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { g[2 * j] = bf16_lo(gw[j]); g[2 * j + 1] = bf16_hi(gw[j]); }
+      for (int j = 0; j < 4; ++j) { g[2 * j] = bf16lo(gw[j]); g[2 * j + 1] = bf16hi(gw[j]); }
       const float4 ca = *reinterpret_cast<const float4*>(Cs + row * CS + c8);
       const float4 cb = *reinterpret_cast<const float4*>(Cs + row * CS + c8 + 4);
       const float cc[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
 #pragma unroll
-      for (int j = 0; j < 8; ++j) mc[j] = sc.cG * g[j] + sc.cC * cc[j];
+      for (int j = 0; j < 8; ++j) mc[j] = fmaf(sc.cC, cc[j], sc.cG * g[j]);
       if (B.v_kind == 0) {          // per-element second moment
         float4* vp = reinterpret_cast<float4*>(vst + e);
-        float4 va = vp[0], vb = vp[1];
-        vv[0] = va.x; vv[1] = va.y; vv[2] = va.z; vv[3] = va.w; vv[4] = vb.x; vv[5] = vb.y; vv[6] = vb.z; vv[7] = vb.w;
+        const float4 va = vp[0], vb = vp[1];
+        float vv[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) vv[j] = sc.beta2 * vv[j] + ob2 * g[j] * g[j];
+        for (int j = 0; j < 8; ++j) {
+          vv[j] = sc.beta2 * vv[j] + ob2 * g[j] * g[j];
+          inv[j] = inv_denom_fast(vv[j], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
+        }
         vp[0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
         vp[1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
       } else {
         const float x = vrow[row];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) vv[j] = x;
+        for (int j = 0; j < 8; ++j) inv[j] = x;
       }
-      if (B.param_dtype == DT_BF16) {
-        uint4* wp = reinterpret_cast<uint4*>(W + e * 2);
-        const uint4 wq = *wp;
-        const uint32_t ww[4] = {wq.x, wq.y, wq.z, wq.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { w[2 * j] = bf16_lo(ww[j]); w[2 * j + 1] = bf16_hi(ww[j]); }
+      if (w16) {
+        const uint32_t ww[4] = {wcur[2 * i].x, wcur[2 * i].y, wcur[2 * i].z, wcur[2 * i].w};
         uint32_t o[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float a = update_elem(w[2 * j], mc[2 * j], vv[2 * j], sc, lrs, wd);
-          const float b = update_elem(w[2 * j + 1], mc[2 * j + 1], vv[2 * j + 1], sc, lrs, wd);
-          o[j] = bf16_rne_bits(a) | (bf16_rne_bits(b) << 16);
-        }
-        *wp = make_uint4(o[0], o[1], o[2], o[3]);
+        for (int j = 0; j < 4; ++j)
+          o[j] = pack_bf16x2(apply_update(bf16lo(ww[j]), mc[2 * j], inv[2 * j], cf),
+                             apply_update(bf16hi(ww[j]), mc[2 * j + 1], inv[2 * j + 1], cf));
+        *reinterpret_cast<uint4*>(W + e * 2) = make_uint4(o[0], o[1], o[2], o[3]);
       } else {
-        float4* wp = reinterpret_cast<float4*>(W + e * 4);
-        const float4 wa = wp[0], wb = wp[1];
-        w[0] = wa.x; w[1] = wa.y; w[2] = wa.z; w[3] = wa.w; w[4] = wb.x; w[5] = wb.y; w[6] = wb.z; w[7] = wb.w;
+        const uint32_t ww[8] = {wcur[2 * i].x, wcur[2 * i].y, wcur[2 * i].z, wcur[2 * i].w,
+                                wcur[2 * i + 1].x, wcur[2 * i + 1].y, wcur[2 * i + 1].z, wcur[2 * i + 1].w};
+        float w[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) w[j] = update_elem(w[j], mc[j], vv[j], sc, lrs, wd);
+        for (int j = 0; j < 8; ++j) w[j] = apply_update(__uint_as_float(ww[j]), mc[j], inv[j], cf);
+        float4* wp = reinterpret_cast<float4*>(W + e * 4);
         wp[0] = make_float4(w[0], w[1], w[2], w[3]);
         wp[1] = make_float4(w[4], w[5], w[6], w[7]);
       }
     }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) { gcur[i] = gnxt[i]; wcur[2 * i] = wnxt[2 * i]; wcur[2 * i + 1] = wnxt[2 * i + 1]; }
   }
 }
 
@@ -319,7 +354,7 @@ __global__ __launch_bounds__(256) void qsplit_kernel(const QsItem* __restrict__ 
     const int id = tid + 256 * i, j = id >> 5, a = id & 31;
     if (a0 + a < R && j0 + j < n) {
       uint32_t h, l;
-      split2(tile[a][j], h, l);
+      split_pair(tile[a][j], 0.f, h, l);
       Th[(int64_t)(j0 + j) * R + a0 + a] = (uint16_t)h;
       Tl[(int64_t)(j0 + j) * R + a0 + a] = (uint16_t)l;
     }

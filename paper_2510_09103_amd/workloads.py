@@ -199,9 +199,11 @@ class GradientStream:
                 self.a.append(torch.randn(b.rows, 1, device=device, generator=g))
                 continue
             k = min(wl.signal_rank, b.rows, b.cols)
-            U, _ = torch.linalg.qr(torch.randn(b.rows, k, device=device, generator=g))
-            V, _ = torch.linalg.qr(torch.randn(b.cols, k, device=device, generator=g))
-            self.U.append(U); self.V.append(V.t().contiguous())
+            # orthonormal bases from a CPU-seeded QR: the same U, V whatever the device
+            gc = _gen("cpu", wl.seed, i, 3)
+            U, _ = torch.linalg.qr(torch.randn(b.rows, k, generator=gc))
+            V, _ = torch.linalg.qr(torch.randn(b.cols, k, generator=gc))
+            self.U.append(U.to(device)); self.V.append(V.t().contiguous().to(device))
             self.s.append(torch.arange(1, k + 1, device=device, dtype=torch.float32) ** (-wl.spectrum_p))
             self.a.append(torch.ones(k, device=device))
             D = None
