@@ -94,8 +94,10 @@ adapm_status_t adapm_init(adapm_ctx** out, const adapm_block_t* table, int64_t n
 size_t adapm_state_bytes(const adapm_ctx* ctx);
 
 /* Size of the caller-allocated scratch buffer used inside adapm_step (previous
- * factors, thin products, Gram matrices, partial sums).  Contents need not survive
- * between calls. */
+ * factors, thin products, Gram matrices, partial sums).  With refresh_period_T > 1 the
+ * library also keeps bf16 copies of R there between two runs of Alg. 2: pass the same,
+ * unmodified buffer on consecutive steps (a different pointer is detected and the copies
+ * are rebuilt; overwriting the contents between steps is not). */
 size_t adapm_workspace_bytes(const adapm_ctx* ctx);
 
 /* Byte offsets into the state buffer of block `block`'s sub-buffers; an absent
@@ -106,6 +108,11 @@ adapm_status_t adapm_state_offsets(const adapm_ctx* ctx, int64_t block, size_t* 
 /* Zero the state and write the seeded R_0 (Alg. 1 line 1 with L_0 R_0 = 0).
  * Asynchronous on `stream` (a hipStream_t, or NULL for the default stream). */
 adapm_status_t adapm_state_init(adapm_ctx* ctx, void* state_dev, void* stream);
+
+/* Tell the library that the caller has overwritten the state buffer (e.g. restored a
+ * checkpoint into it): anything derived from the old contents is dropped.  Not needed for
+ * a fresh context or after adapm_state_init. */
+adapm_status_t adapm_state_loaded(adapm_ctx* ctx);
 
 /* One optimizer step (Alg. 1) over all blocks.
  *  params_dev / grads_dev: HOST arrays of nblocks DEVICE pointers (table order);

@@ -40,7 +40,7 @@ class adapm_hparams_t(C.Structure):
 
 
 EXPORTS = ["adapm_init", "adapm_state_bytes", "adapm_workspace_bytes", "adapm_state_offsets",
-           "adapm_state_init", "adapm_step", "adapm_last_launch_count", "adapm_algorithmic_bytes",
+           "adapm_state_init", "adapm_state_loaded", "adapm_step", "adapm_last_launch_count", "adapm_algorithmic_bytes",
            "adapm_algorithmic_flops", "adapm_profile_enable", "adapm_profile_read", "adapm_last_error",
            "adapm_destroy"]
 
@@ -62,6 +62,8 @@ def _load() -> C.CDLL:
     lib.adapm_state_offsets.argtypes = [P, C.c_int64] + [C.POINTER(C.c_size_t)] * 4
     lib.adapm_state_init.restype = C.c_int
     lib.adapm_state_init.argtypes = [P, P, P]
+    lib.adapm_state_loaded.restype = C.c_int
+    lib.adapm_state_loaded.argtypes = [P]
     lib.adapm_step.restype = C.c_int
     lib.adapm_step.argtypes = [P, C.POINTER(P), C.POINTER(P), P, P, C.c_int64, C.c_float, P]
     lib.adapm_last_launch_count.restype = C.c_int64
@@ -125,6 +127,10 @@ def adapm_state_offsets(ctx, block: int):
 
 def adapm_state_init(ctx, state_ptr: int, stream: int = 0):
     _check(lib.adapm_state_init(ctx, C.c_void_p(state_ptr), C.c_void_p(stream)))
+
+
+def adapm_state_loaded(ctx):
+    _check(lib.adapm_state_loaded(ctx))
 
 
 def adapm_step(ctx, params_ptrs, grads_ptrs, state_ptr: int, workspace_ptr: int, step: int, lr: float,

@@ -13,6 +13,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <new>
 #include <string>
 #include <utility>
@@ -53,7 +54,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wLa = -1, wRa = -1, wLb = -1, wRb = -1;           // ws: ping-pong factors of Alg. 2
   int64_t wP = -1, wS = -1, wGrr = -1, wGpr = -1, wGll = -1, wGlp = -1;
   int64_t wG64 = -1, wCinv = -1, wC = -1;
-  int64_t wQth = -1, wQtl = -1;                             // ws: Q^T as bf16 (hi, lo)
+  int64_t wQth = -1, wQtl = -1, wQnh = -1, wQnl = -1;       // ws: Q^T and Q as bf16 (hi, lo)
   int64_t nv = 0;
   int path = PATH_NONE;
 };
@@ -123,6 +124,7 @@ struct adapm_ctx {
   hipEvent_t stage_free = nullptr;
   int64_t last_launches = 0;
   int n_lowrank = 0;
+  const void* split_ws = nullptr;       // workspace that holds valid bf16 copies of Q (T > 1, MFMA path)
 
   bool profiling = false;
   std::vector<ProfRec> prof;
@@ -393,7 +395,7 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
     LrBlockDev d;
     memset(&d, 0, sizeof d);
     d.block = (int32_t)i; d.m = (int32_t)b.rows; d.n = (int32_t)b.cols; d.r = b.rank;
-    d.off_L = L.sL; d.off_Q = L.sR; d.off_v = L.sv; d.off_Qt_hi = L.wQth; d.off_Qt_lo = L.wQtl;
+    d.off_L = L.sL; d.off_Q = L.sR; d.off_v = L.sv; d.off_Qt_hi = L.wQth; d.off_Qt_lo = L.wQtl; d.off_Qn_hi = L.wQnh; d.off_Qn_lo = L.wQnl;
     if (b.v_mode == ADAPM_V_ELEMENT) { d.v_kind = 0; d.v_group_rows = 1; }
     else if (v_fusable(b)) { d.v_kind = 1; d.v_group_rows = b.v_group_rows; }
     else { d.v_kind = 2; d.v_group_rows = b.v_mode == ADAPM_V_WHOLE ? (int32_t)b.rows : b.v_group_rows; }
@@ -405,7 +407,10 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
   }
   if (c->lrb.h.empty()) return;
   std::vector<Op>& seq = c->seq_project;
-  seq.push_back(Op{OP_QSPLIT, 0, 0, 0, "split_Qt"});
+  // the bf16 (hi, lo) copies of Q are rebuilt after every run of Alg. 2 (and whenever the caller
+  // hands in a different workspace); steps with R held reuse them
+  c->seq_refresh.push_back(Op{OP_QSPLIT, 0, 0, 0, "split_Q"});
+  seq.push_back(Op{OP_QSPLIT, 1, 0, 0, "split_Q"});
   for (int cls = 0; cls < 3; ++cls) {
     const int rank = 32 << cls;
     std::vector<int64_t> ids;
@@ -461,7 +466,10 @@ void build_plan(adapm_ctx* c) {
       L.wGll = walloc(es * r * r); L.wGlp = walloc(es * r * r);
       L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
       L.wC = walloc(4 * m * n);
-      if (L.path == PATH_FAST && hp.refresh_period_T > 1) { L.wQth = walloc(2 * n * r); L.wQtl = walloc(2 * n * r); }
+      if (L.path == PATH_FAST && hp.refresh_period_T > 1) {
+        L.wQth = walloc(2 * n * r); L.wQtl = walloc(2 * n * r);
+        L.wQnh = walloc(2 * n * r); L.wQnl = walloc(2 * n * r);
+      }
       c->n_lowrank++;
     } else if (b.mom_mode == ADAPM_MOM_FULL) {
       L.sm = salloc(4 * m * n);
@@ -631,6 +639,7 @@ adapm_status_t adapm_state_init(adapm_ctx* c, void* state_dev, void* stream) {
   adapm_status_t st = ensure_uploaded(c);
   if (st != ADAPM_OK) return st;
   hipStream_t s = (hipStream_t)stream;
+  c->split_ws = nullptr;
   launch_fill_zero(state_dev, c->state_bytes, s);
   launch_sketch(c->sk.d, (int64_t)c->sk.h.size(), (char*)state_dev, s);
   HIP_TRY(hipGetLastError());
@@ -684,6 +693,7 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
     sc.inv_debias_v = (float)(1.0 / (1.0 - std::pow((double)c->hp.beta2, (double)step)));
   }
   sc.cG = sc.cC = 0.f;
+  { const char* e_ = getenv("ADAPM_DEBUG_FLAGS"); sc.dbg = e_ ? atoi(e_) : 0; }
   // step with R held: D = beta1 (L' - P) with eq. 4, or D = L_t without it
   sc.dL = c->hp.beta1;
   sc.dP = c->hp.bias_correction ? -c->hp.beta1 : 1.f - c->hp.beta1;
@@ -693,6 +703,7 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
   const std::vector<Op>& seq = is_refresh(c, step) ? c->seq_refresh : c->seq_project;
   for (const Op& op : seq) {
     hipEvent_t e0 = nullptr, e1 = nullptr;
+    bool skipped = false;
     if (c->profiling) {
       for (hipEvent_t* e : {&e0, &e1}) {
         if (!c->event_pool.empty()) { *e = c->event_pool.back(); c->event_pool.pop_back(); }
@@ -727,7 +738,10 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         launch_chol(c->chol[op.index].d, (int64_t)c->chol[op.index].h.size(), bs, s);
         break;
       case OP_QSPLIT:
+        // index 1: only needed if the copies in the workspace are not the ones written last
+        if (op.index == 1 && c->split_ws == workspace_dev) { skipped = true; break; }
         launch_qsplit(c->qs.d, (int64_t)c->qs.h.size(), c->lrb.d, bs, s);
+        c->split_ws = workspace_dev;
         break;
       case OP_PROJ: {
         StepScalars x = sc;
@@ -738,10 +752,13 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
       }
     }
     if (c->profiling) {
-      HIP_TRY(hipEventRecord(e1, s));
-      c->prof.push_back(ProfRec{op.label, e0, e1});
+      if (skipped) { c->event_pool.push_back(e0); c->event_pool.push_back(e1); }
+      else {
+        HIP_TRY(hipEventRecord(e1, s));
+        c->prof.push_back(ProfRec{op.label, e0, e1});
+      }
     }
-    ++launches;
+    if (!skipped) ++launches;
   }
   c->last_launches = launches;
   HIP_TRY(hipGetLastError());
@@ -778,6 +795,12 @@ int64_t adapm_profile_read(adapm_ctx* c, int64_t index, char* name, size_t name_
   if (total_ms) *total_ms = agg[index].second.first;
   if (launches) *launches = agg[index].second.second;
   return (int64_t)agg.size();
+}
+
+adapm_status_t adapm_state_loaded(adapm_ctx* c) {
+  if (!c) return fail(ADAPM_EINVAL, "ctx is null");
+  c->split_ws = nullptr;
+  return ADAPM_OK;
 }
 
 int64_t adapm_last_launch_count(const adapm_ctx* c) { return c ? c->last_launches : 0; }

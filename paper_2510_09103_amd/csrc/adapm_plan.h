@@ -103,6 +103,7 @@ struct StepScalars {
   float inv_debias_m, inv_debias_v;   // 1/(1-beta1^t), 1/(1-beta2^t) or 1
   float cG, cC;                       // low-rank blocks: m^c = cG * G + cC * C
   float dL, dP;                       // fused step with R held: D = dL * L_{t-1} + dP * (G Q^T)
+  int dbg;
 };
 
 // ---------------------------------------------------------------------------
@@ -114,6 +115,7 @@ struct LrBlockDev {
   int64_t off_L, off_Q;    // state: L (m x r), Q = R (r x n), fp32
   int64_t off_v;           // state: v
   int64_t off_Qt_hi, off_Qt_lo;   // ws: Q^T as bf16 (hi, lo), [n][r]
+  int64_t off_Qn_hi, off_Qn_lo;   // ws: Q as bf16 (hi, lo), [r][n]
   int32_t v_kind;          // 0 per element; 1 groups of v_group_rows rows finished inside the stripe;
                            // 2 finished beforehand by the statistics kernel
   int32_t v_group_rows;

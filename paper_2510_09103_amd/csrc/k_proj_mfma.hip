@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   constexpr int TPW = (2 * RT >= 4) ? (2 * RT / 4) : 1;   // pass-1 output tiles per wave
   constexpr int P1_BYTES = (BM * GS + 2 * R * GS) * 2;
   constexpr int P2_BYTES = 2 * BN * DS * 2 + BM * CS * 4;
-  constexpr int D_BYTES = 2 * BM * DS * 2;
+  constexpr int D_BYTES = (2 * BM * DS * 2 > BM * (R + 4) * 4) ? 2 * BM * DS * 2 : BM * (R + 4) * 4;
   constexpr int SMEM = (P1_BYTES > P2_BYTES ? (P1_BYTES > D_BYTES ? P1_BYTES : D_BYTES)
                                             : (P2_BYTES > D_BYTES ? P2_BYTES : D_BYTES));
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
@@ -68,6 +68,8 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   float* __restrict__ vst = reinterpret_cast<float*>(bs.state + B.off_v);
   const uint16_t* __restrict__ Qth_g = reinterpret_cast<const uint16_t*>(bs.ws + B.off_Qt_hi);
   const uint16_t* __restrict__ Qtl_g = reinterpret_cast<const uint16_t*>(bs.ws + B.off_Qt_lo);
+  const uint16_t* __restrict__ Qnh_g = reinterpret_cast<const uint16_t*>(bs.ws + B.off_Qn_hi);
+  const uint16_t* __restrict__ Qnl_g = reinterpret_cast<const uint16_t*>(bs.ws + B.off_Qn_lo);
 
   // ------------------------------------------------------------------ pass 1: P = G Q^T
   uint16_t* Gs = reinterpret_cast<uint16_t*>(smem);               // [BM][GS]
@@ -85,48 +87,50 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
 
   // The next chunk travels from memory into registers while the matrix cores work on the
   // current one (one memory round trip per chunk would otherwise be exposed at every barrier).
-  constexpr int QV = (R * BK / 4) / 256;                           // float4 loads of Q per thread and chunk
-  uint4 gpre[2];
-  float4 qpre[QV];
-  auto fetch1 = [&](int k0) {
+  constexpr int QV = (R * BK / 8) / 256;                           // 16-byte loads of Q per thread, chunk and half
+  uint4 ga[2], gb[2];                                              // G: two chunks ahead (bytes in flight)
+  uint4 qhp[QV], qlp[QV];                                          // Q (hi, lo): one chunk ahead (comes from L2)
+  auto fetch_g = [&](int k0, uint4 (&dst)[2]) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
-      gpre[i] = make_uint4(0, 0, 0, 0);
-      if (row0 + row < m && k0 + c8 < n)
-        gpre[i] = *reinterpret_cast<const uint4*>(G + (int64_t)(row0 + row) * n + k0 + c8);
-    }
-#pragma unroll
-    for (int i = 0; i < QV; ++i) {
-      const int id = tid + 256 * i, a = id >> 4, c4 = (id & 15) * 4;
-      qpre[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (k0 + c4 < n) qpre[i] = *reinterpret_cast<const float4*>(Q + (int64_t)a * n + k0 + c4);
+      dst[i] = make_uint4(0, 0, 0, 0);
+      if (row0 + row < m && k0 + c8 < n && !(sc.dbg & 128))
+        dst[i] = *reinterpret_cast<const uint4*>(G + (int64_t)(row0 + row) * n + k0 + c8);
     }
   };
-  fetch1(0);
-  for (int k0 = 0; k0 < n; k0 += BK) {
-    // registers -> LDS: G as is (row sums of squares ride along), Q as (hi, lo) bf16
+  auto fetch_q = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < QV; ++i) {
+      const int id = tid + 256 * i, a = id >> 3, c8 = (id & 7) * 8;
+      qhp[i] = make_uint4(0, 0, 0, 0);
+      qlp[i] = make_uint4(0, 0, 0, 0);
+      if (k0 + c8 < n && !(sc.dbg & 2)) {
+        qhp[i] = *reinterpret_cast<const uint4*>(Qnh_g + (int64_t)a * n + k0 + c8);
+        qlp[i] = *reinterpret_cast<const uint4*>(Qnl_g + (int64_t)a * n + k0 + c8);
+      }
+    }
+  };
+  // one chunk: registers -> LDS, refill the registers, matrix cores on the LDS copy
+  auto chunk = [&](int k0, uint4 (&gcur)[2]) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
-      const uint4 q = gpre[i];
+      const uint4 q = gcur[i];
       *reinterpret_cast<uint4*>(Gs + row * GS + c8) = q;
       const float s = dot2_sq(q.w, dot2_sq(q.z, dot2_sq(q.y, dot2_sq(q.x, 0.f))));
       if (i == 0) ss0 += s; else ss1 += s;
     }
 #pragma unroll
     for (int i = 0; i < QV; ++i) {
-      const int id = tid + 256 * i, a = id >> 4, c4 = (id & 15) * 4;
-      const float4 x = qpre[i];
-      uint32_t h0, l0, h1, l1;
-      split_pair(x.x, x.y, h0, l0);
-      split_pair(x.z, x.w, h1, l1);
-      *reinterpret_cast<uint2*>(Qh + a * GS + c4) = make_uint2(h0, h1);
-      *reinterpret_cast<uint2*>(Ql + a * GS + c4) = make_uint2(l0, l1);
+      const int id = tid + 256 * i, a = id >> 3, c8 = (id & 7) * 8;
+      *reinterpret_cast<uint4*>(Qh + a * GS + c8) = qhp[i];
+      *reinterpret_cast<uint4*>(Ql + a * GS + c8) = qlp[i];
     }
     __syncthreads();
-    if (k0 + BK < n) fetch1(k0 + BK);
-    if (p1_active) {
+    if (k0 + 2 * BK < n) fetch_g(k0 + 2 * BK, gcur);
+    if (k0 + BK < n) fetch_q(k0 + BK);
+    if (p1_active && !(sc.dbg & 1)) {
 #pragma unroll
       for (int kk = 0; kk < BK / 16; ++kk) {
         const int ko = kk * 16 + 8 * lh;
@@ -141,6 +145,13 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
       }
     }
     __syncthreads();
+  };
+  fetch_g(0, ga);
+  fetch_g(BK, gb);
+  fetch_q(0);
+  for (int k0 = 0; k0 < ((sc.dbg & 1024) ? 0 : n); k0 += 2 * BK) {
+    chunk(k0, ga);
+    if (k0 + BK < n) chunk(k0 + BK, gb);
   }
 
   // ------------------------------------------------------------------ second moment of the stripe
@@ -149,7 +160,7 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   for (int o = 1; o < 8; o <<= 1) { ss0 += __shfl_xor(ss0, o, 64); ss1 += __shfl_xor(ss1, o, 64); }
   if ((tid & 7) == 0) { rsum[tid >> 3] = ss0; rsum[32 + (tid >> 3)] = ss1; }
   __syncthreads();
-  if (B.v_kind == 1) {             // groups of v_group_rows rows inside the stripe: finish v here
+  if (sc.dbg & 512) {} else if (B.v_kind == 1) {             // groups of v_group_rows rows inside the stripe: finish v here
     const int g = B.v_group_rows;
     if (tid < BM / g) {
       const int r0 = tid * g;
@@ -169,30 +180,50 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   }
 
   // ------------------------------------------------------------------ L_t and D = dL L' + dP P
-  uint16_t* Dh = reinterpret_cast<uint16_t*>(smem);               // [BM][DS]
-  uint16_t* Dl = Dh + BM * DS;
-  if (p1_active) {
+  // P leaves the accumulators through LDS so that L is read and written as whole rows (float4).
+  float* Ps = reinterpret_cast<float*>(smem);                     // [BM][R + 4] fp32
+  constexpr int PS = R + 4;
+  if (p1_active && !(sc.dbg & 256)) {
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
       const int col = 32 * my_nt + l32;
 #pragma unroll
       for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const int row = 32 * (my_mt0 + t) + 8 * q + 4 * lh + p;
-          float d = 0.f;
-          if (row0 + row < m) {
-            float* lp = Lst + (int64_t)(row0 + row) * R + col;
-            const float lprev = *lp, pv = acc[t][4 * q + p];
-            *lp = sc.beta1 * lprev + (1.f - sc.beta1) * pv;
-            d = sc.dL * lprev + sc.dP * pv;
-          }
-          uint32_t h, l;
-          split_pair(d, 0.f, h, l);
-          Dh[row * DS + col] = (uint16_t)h;
-          Dl[row * DS + col] = (uint16_t)l;
-        }
+        for (int p = 0; p < 4; ++p) Ps[(32 * (my_mt0 + t) + 8 * q + 4 * lh + p) * PS + col] = acc[t][4 * q + p];
     }
+  }
+  __syncthreads();
+  constexpr int LV = (BM * R / 4) / 256;                          // float4 per thread
+  uint2 dhv[LV], dlv[LV];
+#pragma unroll
+  for (int i = 0; i < LV; ++i) {
+    const int id = tid + 256 * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
+    float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (row0 + row < m && !(sc.dbg & 256)) {
+      float4* lp = reinterpret_cast<float4*>(Lst + (int64_t)(row0 + row) * R + c4);
+      const float4 lprev = *lp;
+      const float4 pv = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
+      const float b1 = sc.beta1, ob1 = 1.f - sc.beta1;
+      *lp = make_float4(b1 * lprev.x + ob1 * pv.x, b1 * lprev.y + ob1 * pv.y, b1 * lprev.z + ob1 * pv.z,
+                        b1 * lprev.w + ob1 * pv.w);
+      d = make_float4(sc.dL * lprev.x + sc.dP * pv.x, sc.dL * lprev.y + sc.dP * pv.y, sc.dL * lprev.z + sc.dP * pv.z,
+                      sc.dL * lprev.w + sc.dP * pv.w);
+    }
+    uint32_t h0, l0, h1, l1;
+    split_pair(d.x, d.y, h0, l0);
+    split_pair(d.z, d.w, h1, l1);
+    dhv[i] = make_uint2(h0, h1);
+    dlv[i] = make_uint2(l0, l1);
+  }
+  __syncthreads();                                                 // Ps is dead, D takes its place
+  uint16_t* Dh = reinterpret_cast<uint16_t*>(smem);               // [BM][DS]
+  uint16_t* Dl = Dh + BM * DS;
+#pragma unroll
+  for (int i = 0; i < LV; ++i) {
+    const int id = tid + 256 * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
+    *reinterpret_cast<uint2*>(Dh + row * DS + c4) = dhv[i];
+    *reinterpret_cast<uint2*>(Dl + row * DS + c4) = dlv[i];
   }
   __syncthreads();
   // A fragments of D for this wave's 32 rows stay in registers for the whole of pass 2
@@ -221,7 +252,7 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
       const int id = tid + 256 * i, j = id / (R / 8), a8 = (id % (R / 8)) * 8;
       thp[i] = make_uint4(0, 0, 0, 0);
       tlp[i] = make_uint4(0, 0, 0, 0);
-      if (j0 + j < n) {
+      if (j0 + j < n && !(sc.dbg & 8)) {
         thp[i] = *reinterpret_cast<const uint4*>(Qth_g + (int64_t)(j0 + j) * R + a8);
         tlp[i] = *reinterpret_cast<const uint4*>(Qtl_g + (int64_t)(j0 + j) * R + a8);
       }
@@ -233,7 +264,7 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
       gq[i] = make_uint4(0, 0, 0, 0);
       wq[2 * i] = wq[2 * i + 1] = make_uint4(0, 0, 0, 0);
-      if (row0 + row < m && j0 + c8 < n) {
+      if (row0 + row < m && j0 + c8 < n && !(sc.dbg & 16)) {
         const int64_t e = (int64_t)(row0 + row) * n + j0 + c8;
         gq[i] = *reinterpret_cast<const uint4*>(G + e);
         if (w16) {
@@ -247,7 +278,7 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   };
   fetch_t(0);
   fetch_gw(0, gcur, wcur);
-  for (int j0 = 0; j0 < n; j0 += BN) {
+  for (int j0 = 0; j0 < ((sc.dbg & 64) ? 0 : n); j0 += BN) {
 #pragma unroll
     for (int i = 0; i < TV; ++i) {
       const int id = tid + 256 * i, j = id / (R / 8), a8 = (id % (R / 8)) * 8;
@@ -262,6 +293,7 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
     f32x16 c;
 #pragma unroll
     for (int i = 0; i < 16; ++i) c[i] = 0.f;
+if (!(sc.dbg & 4))
 #pragma unroll
     for (int ks = 0; ks < 2 * RT; ++ks) {
       const bf16x8 bh = lds_frag(Th + (32 * wc + l32) * DS + 16 * ks + 8 * lh);
@@ -279,7 +311,7 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
-      if (row0 + row >= m || j0 + c8 >= n) continue;
+      if (row0 + row >= m || j0 + c8 >= n || (sc.dbg & 32)) continue;
       const int64_t e = (int64_t)(row0 + row) * n + j0 + c8;
       const uint32_t gw[4] = {gcur[i].x, gcur[i].y, gcur[i].z, gcur[i].w};
       float g[8], mc[8], inv[8];
@@ -330,7 +362,7 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   }
 }
 
-// Q (r x n fp32, state) -> Q^T as bf16 (hi, lo) pairs, [n][r], in the workspace.
+// Q (r x n fp32, state) -> bf16 (hi, lo) pairs in the workspace, both as Q [r][n] and as Q^T [n][r].
 __global__ __launch_bounds__(256) void qsplit_kernel(const QsItem* __restrict__ items,
                                                      const LrBlockDev* __restrict__ lrb, Bases bs) {
   __shared__ float tile[32][65];
@@ -340,12 +372,22 @@ __global__ __launch_bounds__(256) void qsplit_kernel(const QsItem* __restrict__ 
   const float* __restrict__ Q = reinterpret_cast<const float*>(bs.state + B.off_Q);
   uint16_t* __restrict__ Th = reinterpret_cast<uint16_t*>(bs.ws + B.off_Qt_hi);
   uint16_t* __restrict__ Tl = reinterpret_cast<uint16_t*>(bs.ws + B.off_Qt_lo);
+  uint16_t* __restrict__ Nh = reinterpret_cast<uint16_t*>(bs.ws + B.off_Qn_hi);
+  uint16_t* __restrict__ Nl = reinterpret_cast<uint16_t*>(bs.ws + B.off_Qn_lo);
   const int a0 = it.a0, j0 = it.j0, tid = threadIdx.x;
   // read 32 rows (a) x 64 columns (j), j fastest
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int id = tid + 256 * i, a = id >> 6, j = id & 63;
-    tile[a][j] = (a0 + a < R && j0 + j < n) ? Q[(int64_t)(a0 + a) * n + j0 + j] : 0.f;
+    const bool in = a0 + a < R && j0 + j < n;
+    const float x = in ? Q[(int64_t)(a0 + a) * n + j0 + j] : 0.f;
+    tile[a][j] = x;
+    if (in) {
+      uint32_t h, l;
+      split_pair(x, 0.f, h, l);
+      Nh[(int64_t)(a0 + a) * n + j0 + j] = (uint16_t)h;
+      Nl[(int64_t)(a0 + a) * n + j0 + j] = (uint16_t)l;
+    }
   }
   __syncthreads();
   // write 64 rows (j) x 32 columns (a), a fastest

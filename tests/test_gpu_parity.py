@@ -163,6 +163,33 @@ def test_two_runs_are_bit_identical_and_resume_from_a_state_copy():
     assert torch.equal(s1, s2) and torch.equal(s1, s3)
 
 
+def test_restoring_a_state_into_a_live_optimizer():
+    """bf16 blocks on the MFMA path keep derived copies of R between refreshes: after the caller
+    overwrites the state buffer, adapm_state_loaded() must make the next step rebuild them."""
+    wl = WL.subset(WL.gpt2_350m(), ["h0.attn.q", "h0.mlp.fc"])
+    hp = dict(T=4)
+    a = Pair(wl, hp)
+    for _ in range(6):
+        a.step()                                  # t = 5 refreshed; the copies of R belong to that refresh
+    torch.cuda.synchronize()
+    b = Pair(wl, hp)
+    for _ in range(2):
+        b.step()                                  # t = 1 refreshed
+    torch.cuda.synchronize()
+    saved_state, saved_params = b.opt.state.clone(), [p.clone() for p in b.params]
+    # continue b to t = 3 for the expected result
+    g3 = b.step()
+    torch.cuda.synchronize()
+    want = [p.clone() for p in b.params]
+    # restore b's t = 2 checkpoint into optimizer a (same workspace as its last refresh) and redo t = 3
+    a.opt.state.copy_(saved_state)
+    B.adapm_state_loaded(a.opt.ctx)
+    a.opt.step(saved_params, g3, 3, wl.lr)
+    torch.cuda.synchronize()
+    for x, y in zip(saved_params, want):
+        assert torch.equal(x, y)
+
+
 def test_step_rejects_bad_arguments_on_device():
     wl = WL.subset(WL.tiny_block(), ["norm1"])
     pair = Pair(wl)
