@@ -156,7 +156,14 @@ def main():
         per_launch = B.adapm_algorithmic_flops(opt.ctx, True) / max(1, kernels[dominant]["launches"] // max(1, n_refresh_prof))
         roof = {"bound": "mfma", "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "achieved": per_launch / (kernels[dominant]["avg_ms"] * 1e-3) / 1e12}
-    roof.update(kernel=dominant, frac=roof["achieved"] / roof["peak"], traffic=None,
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+    if args.workload == "gpt2_1p5b" and args.T == 100 and os.path.exists(tfile):
+        for line in open(tfile):
+            parts = line.split()
+            if len(parts) == 2 and parts[0] == dominant:
+                traffic = float(parts[1])
+    roof.update(kernel=dominant, frac=roof["achieved"] / roof["peak"], traffic=traffic,
                 avg_ms=kernels[dominant]["avg_ms"])
 
     bytes_refresh = B.adapm_algorithmic_bytes(opt.ctx, True)
