@@ -13,7 +13,6 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
-#include <cstdlib>
 #include <new>
 #include <string>
 #include <utility>
@@ -54,7 +53,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wLa = -1, wRa = -1, wLb = -1, wRb = -1;           // ws: ping-pong factors of Alg. 2
   int64_t wP = -1, wS = -1, wGrr = -1, wGpr = -1, wGll = -1, wGlp = -1;
   int64_t wG64 = -1, wCinv = -1, wC = -1;
-  int64_t wQth = -1, wQtl = -1, wQnh = -1, wQnl = -1;       // ws: Q^T and Q as bf16 (hi, lo)
+  int64_t wQf = -1, wTimg = -1;                             // ws: bf16 (hi, lo) images of Q and Q^T
   int64_t nv = 0;
   int path = PATH_NONE;
 };
@@ -110,7 +109,7 @@ struct adapm_ctx {
   DevList<SketchItem> sk;
   DevList<CholItem> chol[2];    // per path
   DevList<LrBlockDev> lrb;
-  DevList<ProjItem> proj[3];    // rank 32 / 64 / 128
+  DevList<ProjItem> proj[6];    // (rank 32 / 64 / 128) x (fp32 / bf16 parameters)
   DevList<QsItem> qs;
   std::vector<GemmList> gemms;
   std::vector<Op> seq_refresh, seq_project;
@@ -395,15 +394,14 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
     LrBlockDev d;
     memset(&d, 0, sizeof d);
     d.block = (int32_t)i; d.m = (int32_t)b.rows; d.n = (int32_t)b.cols; d.r = b.rank;
-    d.off_L = L.sL; d.off_Q = L.sR; d.off_v = L.sv; d.off_Qt_hi = L.wQth; d.off_Qt_lo = L.wQtl; d.off_Qn_hi = L.wQnh; d.off_Qn_lo = L.wQnl;
+    d.off_L = L.sL; d.off_Q = L.sR; d.off_v = L.sv; d.off_Qf = L.wQf; d.off_Timg = L.wTimg;
     if (b.v_mode == ADAPM_V_ELEMENT) { d.v_kind = 0; d.v_group_rows = 1; }
     else if (v_fusable(b)) { d.v_kind = 1; d.v_group_rows = b.v_group_rows; }
     else { d.v_kind = 2; d.v_group_rows = b.v_mode == ADAPM_V_WHOLE ? (int32_t)b.rows : b.v_group_rows; }
     d.param_dtype = b.param_dtype; d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
     lr_of[i] = (int64_t)c->lrb.h.size();
     c->lrb.h.push_back(d);
-    for (int a0 = 0; a0 < b.rank; a0 += 32)
-      for (int j0 = 0; j0 < b.cols; j0 += 64) c->qs.h.push_back(QsItem{(int32_t)lr_of[i], a0, j0});
+    for (int ch = 0; ch < (int)((b.cols + 63) / 64); ++ch) c->qs.h.push_back(QsItem{(int32_t)lr_of[i], ch});
   }
   if (c->lrb.h.empty()) return;
   std::vector<Op>& seq = c->seq_project;
@@ -411,11 +409,12 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
   // hands in a different workspace); steps with R held reuse them
   c->seq_refresh.push_back(Op{OP_QSPLIT, 0, 0, 0, "split_Q"});
   seq.push_back(Op{OP_QSPLIT, 1, 0, 0, "split_Q"});
-  for (int cls = 0; cls < 3; ++cls) {
-    const int rank = 32 << cls;
+  for (int cls = 0; cls < 6; ++cls) {       // (rank 32 / 64 / 128) x (fp32 / bf16 parameters)
+    const int rank = 32 << (cls >> 1);
+    const int pdt = (cls & 1) ? ADAPM_BF16 : ADAPM_F32;
     std::vector<int64_t> ids;
     for (int64_t i = 0; i < nb; ++i)
-      if (lr_of[i] >= 0 && c->table[i].rank == rank) ids.push_back(i);
+      if (lr_of[i] >= 0 && c->table[i].rank == rank && c->table[i].param_dtype == pdt) ids.push_back(i);
     if (ids.empty()) continue;
     // longest rows first; whole blocks dealt to the least loaded XCD
     std::stable_sort(ids.begin(), ids.end(), [&](int64_t a, int64_t b) {
@@ -436,7 +435,7 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
     for (auto& v : per) longest = std::max(longest, v.size());
     for (size_t q = 0; q < longest; ++q)
       for (int x = 0; x < NXCD; ++x) c->proj[cls].h.push_back(q < per[x].size() ? per[x][q] : ProjItem{-1, 0});
-    seq.push_back(Op{OP_PROJ, cls, 0, 0, cls == 0 ? "fused_project_r32" : (cls == 1 ? "fused_project_r64" : "fused_project_r128")});
+    seq.push_back(Op{OP_PROJ, cls, 0, 0, (cls >> 1) == 0 ? "fused_project_r32" : ((cls >> 1) == 1 ? "fused_project_r64" : "fused_project_r128")});
   }
 }
 
@@ -467,8 +466,8 @@ void build_plan(adapm_ctx* c) {
       L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
       L.wC = walloc(4 * m * n);
       if (L.path == PATH_FAST && hp.refresh_period_T > 1) {
-        L.wQth = walloc(2 * n * r); L.wQtl = walloc(2 * n * r);
-        L.wQnh = walloc(2 * n * r); L.wQnl = walloc(2 * n * r);
+        L.wQf = walloc(proj_qf_bytes((int)r, (int)n));
+        L.wTimg = walloc(proj_timg_bytes((int)r, (int)n));
       }
       c->n_lowrank++;
     } else if (b.mom_mode == ADAPM_MOM_FULL) {
@@ -554,7 +553,8 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   const size_t nb = c->table.size();
   size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
                  align_up(2 * nb * sizeof(void*));
-  for (int i = 0; i < 3; ++i) total += bytes_of(c->ew[i].h) + bytes_of(c->proj[i].h);
+  for (int i = 0; i < 3; ++i) total += bytes_of(c->ew[i].h);
+  for (int i = 0; i < 6; ++i) total += bytes_of(c->proj[i].h);
   for (int i = 0; i < 2; ++i) total += bytes_of(c->vs[i].h) + bytes_of(c->vf[i].h) + bytes_of(c->chol[i].h);
   for (auto& g : c->gemms) total += bytes_of(g.probs) + bytes_of(g.tiles);
   HIP_TRY(hipMalloc((void**)&c->arena, total));
@@ -568,7 +568,8 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
   PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs);
-  for (int i = 0; i < 3; ++i) { PUT_LIST(c->ew[i]); PUT_LIST(c->proj[i]); }
+  for (int i = 0; i < 3; ++i) PUT_LIST(c->ew[i]);
+  for (int i = 0; i < 6; ++i) PUT_LIST(c->proj[i]);
   for (int i = 0; i < 2; ++i) { PUT_LIST(c->vs[i]); PUT_LIST(c->vf[i]); PUT_LIST(c->chol[i]); }
 #undef PUT_LIST
   for (auto& g : c->gemms) {
@@ -693,7 +694,6 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
     sc.inv_debias_v = (float)(1.0 / (1.0 - std::pow((double)c->hp.beta2, (double)step)));
   }
   sc.cG = sc.cC = 0.f;
-  { const char* e_ = getenv("ADAPM_DEBUG_FLAGS"); sc.dbg = e_ ? atoi(e_) : 0; }
   // step with R held: D = beta1 (L' - P) with eq. 4, or D = L_t without it
   sc.dL = c->hp.beta1;
   sc.dP = c->hp.bias_correction ? -c->hp.beta1 : 1.f - c->hp.beta1;
@@ -740,14 +740,15 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
       case OP_QSPLIT:
         // index 1: only needed if the copies in the workspace are not the ones written last
         if (op.index == 1 && c->split_ws == workspace_dev) { skipped = true; break; }
-        launch_qsplit(c->qs.d, (int64_t)c->qs.h.size(), c->lrb.d, bs, s);
+        launch_qimage(c->qs.d, (int64_t)c->qs.h.size(), c->lrb.d, bs, s);
         c->split_ws = workspace_dev;
         break;
       case OP_PROJ: {
         StepScalars x = sc;
         x.cG = c->hp.bias_correction ? 1.f : 0.f;
         x.cC = 1.f;
-        launch_proj(1 << op.index, c->proj[op.index].d, (int64_t)c->proj[op.index].h.size(), c->lrb.d, bs, x, s);
+        launch_proj(1 << (op.index >> 1), (op.index & 1) != 0, c->proj[op.index].d, (int64_t)c->proj[op.index].h.size(),
+                    c->lrb.d, bs, x, s);
         break;
       }
     }

@@ -103,7 +103,6 @@ struct StepScalars {
   float inv_debias_m, inv_debias_v;   // 1/(1-beta1^t), 1/(1-beta2^t) or 1
   float cG, cC;                       // low-rank blocks: m^c = cG * G + cC * C
   float dL, dP;                       // fused step with R held: D = dL * L_{t-1} + dP * (G Q^T)
-  int dbg;
 };
 
 // ---------------------------------------------------------------------------
@@ -114,8 +113,8 @@ struct LrBlockDev {
   int32_t m, n, r;
   int64_t off_L, off_Q;    // state: L (m x r), Q = R (r x n), fp32
   int64_t off_v;           // state: v
-  int64_t off_Qt_hi, off_Qt_lo;   // ws: Q^T as bf16 (hi, lo), [n][r]
-  int64_t off_Qn_hi, off_Qn_lo;   // ws: Q as bf16 (hi, lo), [r][n]
+  int64_t off_Qf;          // ws: Q as bf16 (hi, lo) MFMA fragments, per 64-column chunk
+  int64_t off_Timg;        // ws: Q^T as bf16 (hi, lo) padded LDS images, per 64-column chunk
   int32_t v_kind;          // 0 per element; 1 groups of v_group_rows rows finished inside the stripe;
                            // 2 finished beforehand by the statistics kernel
   int32_t v_group_rows;
@@ -129,9 +128,9 @@ struct ProjItem {          // one workgroup: 64 rows of one block; lr < 0 = padd
   int32_t row0;
 };
 
-struct QsItem {            // one workgroup: 32 rows x 64 columns of Q
+struct QsItem {            // one workgroup: one 64-column chunk of Q
   int32_t lr;
-  int32_t a0, j0;
+  int32_t c;
 };
 
 struct SketchItem {      // seeded start R_0 of one low-rank block
@@ -164,8 +163,10 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 void launch_sketch(const SketchItem* items, int64_t nitems, char* state, hipStream_t s);
 void launch_chol(const CholItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gemm_mfma(const GemmProblem* probs, const GemmTile* tiles, int64_t ntiles, Bases b, hipStream_t s);
-void launch_proj(int rt, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, StepScalars sc,
-                 hipStream_t s);
-void launch_qsplit(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s);
+void launch_proj(int rt, bool w16, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
+                 StepScalars sc, hipStream_t s);
+void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s);
+size_t proj_qf_bytes(int r, int n);     // sizes of the two images of Q kept for the fused step
+size_t proj_timg_bytes(int r, int n);
 
 }  // namespace adapm

@@ -6,13 +6,17 @@
 //   m^c = G + beta1 (L_{t-1} - P) Q              (eq. 3-4 with r_t = L_t Q - m_t)
 //   W  <- W - lr (clip(m^c / (sqrt(v) + eps)) + lambda W)     (Alg. 1 last line)
 // One workgroup owns a stripe of 64 rows of one block and makes two passes over it:
-//   pass 1 streams G (HBM) and Q (L2) and accumulates P on the matrix cores; row sums of G^2 for
-//          the blockwise second moment ride along;
-//   pass 2 re-reads G (cache), reconstructs D Q tile by tile (D = beta1 (L_{t-1} - P)) and applies
-//          the update to W.
+//   pass 1 streams G (HBM, through LDS) and accumulates P on the matrix cores; the Q operand arrives
+//          already laid out as MFMA fragments and goes straight from L2 into registers; row sums of
+//          G^2 for the blockwise second moment ride along;
+//   pass 2 re-reads G, reconstructs D Q tile by tile (D = beta1 (L_{t-1} - P), held in registers as
+//          A fragments) and applies the update to W; Q^T arrives as a ready-made padded LDS image,
+//          copied by direct global->LDS loads that overlap the element-wise tail of the previous tile.
 // Matrix work uses v_mfma_f32_32x32x16_bf16.  G is bf16 (exact); every fp32 operand (Q, D) is
 // carried as a (hi, lo) pair of bf16 values, products hi*hi + lo*hi + hi*lo accumulated in fp32
-// (relative operand error 2^-17).
+// (relative operand error 2^-17).  The two images of Q are written by qimage_kernel after each run
+// of Alg. 2.  Three workgroups fit on a CU (LDS 53.8 KB, <= 168 VGPRs), so the phases of different
+// stripes overlap.
 #include "adapm_plan.h"
 #include "ew_math.h"
 
@@ -24,33 +28,41 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int BM = 64;     // rows per stripe
-constexpr int BK = 64;     // columns per chunk of pass 1
-constexpr int BN = 64;     // columns per chunk of pass 2
-constexpr int GS = BK + 8; // LDS row strides (elements), padded so 16-byte fragment reads spread over all banks
-constexpr int CS = BN + 8;
+constexpr int BK = 64;     // columns per chunk (both passes)
+constexpr int GS = BK + 8; // LDS row stride of the G tile (elements): 16-byte fragment reads hit all banks
+constexpr int CS = BK + 8; // LDS row stride of the fp32 C tile
 
 union Frag {
   bf16x8 v;
   uint4 q;
 };
-
-__device__ __forceinline__ bf16x8 lds_frag(const uint16_t* p) {
+__device__ __forceinline__ bf16x8 as_frag(const uint4& q) {
   Frag f;
-  f.q = *reinterpret_cast<const uint4*>(p);
+  f.q = q;
   return f.v;
 }
+__device__ __forceinline__ bf16x8 lds_frag(const uint16_t* p) { return as_frag(*reinterpret_cast<const uint4*>(p)); }
 
-template <int RT>
-__global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict__ items,
+// geometry of the two images of Q
+__host__ __device__ constexpr int timg_row_stride(int R) { return R + 8; }                             // elements
+__host__ __device__ constexpr int timg_chunk_bytes(int R) { return 2 * BK * timg_row_stride(R) * 2; }  // hi + lo
+__host__ __device__ constexpr int qf_chunk_bytes(int R) { return (BK / 16) * (R / 32) * 2 * 64 * 16; }
+
+template <int RT, bool W16>
+__global__ __launch_bounds__(256, 3) void proj_kernel(const ProjItem* __restrict__ items,
                                                       const LrBlockDev* __restrict__ lrb, Bases bs, StepScalars sc) {
   constexpr int R = 32 * RT;
-  constexpr int DS = R + 8;                         // LDS row stride of the r-contiguous arrays
+  constexpr int DS = timg_row_stride(R);
   constexpr int TPW = (2 * RT >= 4) ? (2 * RT / 4) : 1;   // pass-1 output tiles per wave
-  constexpr int P1_BYTES = (BM * GS + 2 * R * GS) * 2;
-  constexpr int P2_BYTES = 2 * BN * DS * 2 + BM * CS * 4;
-  constexpr int D_BYTES = (2 * BM * DS * 2 > BM * (R + 4) * 4) ? 2 * BM * DS * 2 : BM * (R + 4) * 4;
-  constexpr int SMEM = (P1_BYTES > P2_BYTES ? (P1_BYTES > D_BYTES ? P1_BYTES : D_BYTES)
-                                            : (P2_BYTES > D_BYTES ? P2_BYTES : D_BYTES));
+  constexpr int PS = R + 4;
+  constexpr int G_BYTES = BM * GS * 2;
+  constexpr int P_BYTES = BM * PS * 4;
+  constexpr int D_BYTES = 2 * BM * DS * 2;
+  constexpr int T_BYTES = timg_chunk_bytes(R);
+  constexpr int P2_BYTES = T_BYTES + BM * CS * 4;
+  constexpr int m1 = G_BYTES > P_BYTES ? G_BYTES : P_BYTES;
+  constexpr int m2 = D_BYTES > P2_BYTES ? D_BYTES : P2_BYTES;
+  constexpr int SMEM = m1 > m2 ? m1 : m2;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
   __shared__ float vrow[BM];
   __shared__ float rsum[BM];
@@ -58,23 +70,19 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   const ProjItem item = items[blockIdx.x];
   if (item.lr < 0) return;
   const LrBlockDev B = lrb[item.lr];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, lh = lane >> 5;
   const int m = B.m, n = B.n, row0 = item.row0;
   const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(bs.grads[B.block]);
   char* __restrict__ W = reinterpret_cast<char*>(bs.params[B.block]);
   float* __restrict__ Lst = reinterpret_cast<float*>(bs.state + B.off_L);
-  const float* __restrict__ Q = reinterpret_cast<const float*>(bs.state + B.off_Q);
   float* __restrict__ vst = reinterpret_cast<float*>(bs.state + B.off_v);
-  const uint16_t* __restrict__ Qth_g = reinterpret_cast<const uint16_t*>(bs.ws + B.off_Qt_hi);
-  const uint16_t* __restrict__ Qtl_g = reinterpret_cast<const uint16_t*>(bs.ws + B.off_Qt_lo);
-  const uint16_t* __restrict__ Qnh_g = reinterpret_cast<const uint16_t*>(bs.ws + B.off_Qn_hi);
-  const uint16_t* __restrict__ Qnl_g = reinterpret_cast<const uint16_t*>(bs.ws + B.off_Qn_lo);
+  const char* __restrict__ Qf = bs.ws + B.off_Qf;       // fragment-major image of Q (pass 1)
+  const char* __restrict__ Timg = bs.ws + B.off_Timg;   // LDS image of Q^T per 64-column chunk (pass 2)
 
   // ------------------------------------------------------------------ pass 1: P = G Q^T
   uint16_t* Gs = reinterpret_cast<uint16_t*>(smem);               // [BM][GS]
-  uint16_t* Qh = Gs + BM * GS;                                    // [R][GS]
-  uint16_t* Ql = Qh + R * GS;                                     // [R][GS]
   f32x16 acc[TPW];
 #pragma unroll
   for (int t = 0; t < TPW; ++t)
@@ -85,34 +93,28 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   const int my_nt = (RT >= 4) ? wave : (wave % RT);
   const int my_mt0 = (RT >= 4) ? 0 : (wave / RT);
 
-  // The next chunk travels from memory into registers while the matrix cores work on the
-  // current one (one memory round trip per chunk would otherwise be exposed at every barrier).
-  constexpr int QV = (R * BK / 8) / 256;                           // 16-byte loads of Q per thread, chunk and half
-  uint4 ga[2], gb[2];                                              // G: two chunks ahead (bytes in flight)
-  uint4 qhp[QV], qlp[QV];                                          // Q (hi, lo): one chunk ahead (comes from L2)
+  uint4 ga[2], gb[2];                                              // G: two chunks ahead
+  uint4 qa[BK / 16][2], qb[BK / 16][2];                            // Q fragments (hi, lo): this chunk / the next
   auto fetch_g = [&](int k0, uint4 (&dst)[2]) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
       dst[i] = make_uint4(0, 0, 0, 0);
-      if (row0 + row < m && k0 + c8 < n && !(sc.dbg & 128))
+      if (row0 + row < m && k0 + c8 < n)
         dst[i] = *reinterpret_cast<const uint4*>(G + (int64_t)(row0 + row) * n + k0 + c8);
     }
   };
-  auto fetch_q = [&](int k0) {
+  // fragment (chunk c, k-step kk, r-tile, hi/lo) is 1 KB: lane l holds Q[32 tile + l%32][64 c + 16 kk + 8 (l/32) .. +7]
+  auto fetch_q = [&](int k0, uint4 (&dst)[BK / 16][2]) {
+    if (!p1_active) return;
+    const char* base = Qf + (int64_t)(k0 / BK) * qf_chunk_bytes(R);
 #pragma unroll
-    for (int i = 0; i < QV; ++i) {
-      const int id = tid + 256 * i, a = id >> 3, c8 = (id & 7) * 8;
-      qhp[i] = make_uint4(0, 0, 0, 0);
-      qlp[i] = make_uint4(0, 0, 0, 0);
-      if (k0 + c8 < n && !(sc.dbg & 2)) {
-        qhp[i] = *reinterpret_cast<const uint4*>(Qnh_g + (int64_t)a * n + k0 + c8);
-        qlp[i] = *reinterpret_cast<const uint4*>(Qnl_g + (int64_t)a * n + k0 + c8);
-      }
-    }
+    for (int kk = 0; kk < BK / 16; ++kk)
+#pragma unroll
+      for (int hl = 0; hl < 2; ++hl)
+        dst[kk][hl] = *reinterpret_cast<const uint4*>(base + ((((kk * RT + my_nt) * 2 + hl) * 64 + lane) << 4));
   };
-  // one chunk: registers -> LDS, refill the registers, matrix cores on the LDS copy
-  auto chunk = [&](int k0, uint4 (&gcur)[2]) {
+  auto chunk = [&](int k0, uint4 (&gcur)[2], uint4 (&qcur)[BK / 16][2], uint4 (&qnxt)[BK / 16][2]) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
@@ -121,21 +123,14 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
       const float s = dot2_sq(q.w, dot2_sq(q.z, dot2_sq(q.y, dot2_sq(q.x, 0.f))));
       if (i == 0) ss0 += s; else ss1 += s;
     }
-#pragma unroll
-    for (int i = 0; i < QV; ++i) {
-      const int id = tid + 256 * i, a = id >> 3, c8 = (id & 7) * 8;
-      *reinterpret_cast<uint4*>(Qh + a * GS + c8) = qhp[i];
-      *reinterpret_cast<uint4*>(Ql + a * GS + c8) = qlp[i];
-    }
     __syncthreads();
     if (k0 + 2 * BK < n) fetch_g(k0 + 2 * BK, gcur);
-    if (k0 + BK < n) fetch_q(k0 + BK);
-    if (p1_active && !(sc.dbg & 1)) {
+    if (k0 + BK < n) fetch_q(k0 + BK, qnxt);
+    if (p1_active) {
 #pragma unroll
       for (int kk = 0; kk < BK / 16; ++kk) {
         const int ko = kk * 16 + 8 * lh;
-        const bf16x8 bh = lds_frag(Qh + (32 * my_nt + l32) * GS + ko);
-        const bf16x8 bl = lds_frag(Ql + (32 * my_nt + l32) * GS + ko);
+        const bf16x8 bh = as_frag(qcur[kk][0]), bl = as_frag(qcur[kk][1]);
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
           const bf16x8 a = lds_frag(Gs + (32 * (my_mt0 + t) + l32) * GS + ko);
@@ -148,10 +143,10 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   };
   fetch_g(0, ga);
   fetch_g(BK, gb);
-  fetch_q(0);
-  for (int k0 = 0; k0 < ((sc.dbg & 1024) ? 0 : n); k0 += 2 * BK) {
-    chunk(k0, ga);
-    if (k0 + BK < n) chunk(k0 + BK, gb);
+  fetch_q(0, qa);
+  for (int k0 = 0; k0 < n; k0 += 2 * BK) {
+    chunk(k0, ga, qa, qb);
+    if (k0 + BK < n) chunk(k0 + BK, gb, qb, qa);
   }
 
   // ------------------------------------------------------------------ second moment of the stripe
@@ -159,8 +154,22 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
 #pragma unroll
   for (int o = 1; o < 8; o <<= 1) { ss0 += __shfl_xor(ss0, o, 64); ss1 += __shfl_xor(ss1, o, 64); }
   if ((tid & 7) == 0) { rsum[tid >> 3] = ss0; rsum[32 + (tid >> 3)] = ss1; }
+
+  // ------------------------------------------------------------------ L_t and D = dL L' + dP P
+  // P leaves the accumulators through LDS so that L is read and written as whole rows (float4).
+  float* Ps = reinterpret_cast<float*>(smem);                     // [BM][PS] fp32
+  if (p1_active) {
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+      const int col = 32 * my_nt + l32;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) Ps[(32 * (my_mt0 + t) + 8 * q + 4 * lh + p) * PS + col] = acc[t][4 * q + p];
+    }
+  }
   __syncthreads();
-  if (sc.dbg & 512) {} else if (B.v_kind == 1) {             // groups of v_group_rows rows inside the stripe: finish v here
+  if (B.v_kind == 1) {             // groups of v_group_rows rows inside the stripe: finish v here
     const int g = B.v_group_rows;
     if (tid < BM / g) {
       const int r0 = tid * g;
@@ -178,29 +187,13 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
     if (tid < BM && row0 + tid < m)
       vrow[tid] = inv_denom_exact(vst[(row0 + tid) / B.v_group_rows], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
   }
-
-  // ------------------------------------------------------------------ L_t and D = dL L' + dP P
-  // P leaves the accumulators through LDS so that L is read and written as whole rows (float4).
-  float* Ps = reinterpret_cast<float*>(smem);                     // [BM][R + 4] fp32
-  constexpr int PS = R + 4;
-  if (p1_active && !(sc.dbg & 256)) {
-#pragma unroll
-    for (int t = 0; t < TPW; ++t) {
-      const int col = 32 * my_nt + l32;
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int p = 0; p < 4; ++p) Ps[(32 * (my_mt0 + t) + 8 * q + 4 * lh + p) * PS + col] = acc[t][4 * q + p];
-    }
-  }
-  __syncthreads();
   constexpr int LV = (BM * R / 4) / 256;                          // float4 per thread
   uint2 dhv[LV], dlv[LV];
 #pragma unroll
   for (int i = 0; i < LV; ++i) {
     const int id = tid + 256 * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
     float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (row0 + row < m && !(sc.dbg & 256)) {
+    if (row0 + row < m) {
       float4* lp = reinterpret_cast<float4*>(Lst + (int64_t)(row0 + row) * R + c4);
       const float4 lprev = *lp;
       const float4 pv = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
@@ -237,63 +230,49 @@ __global__ __launch_bounds__(256, 2) void proj_kernel(const ProjItem* __restrict
   __syncthreads();
 
   // ------------------------------------------------------------------ pass 2: C = D Q, update W
-  uint16_t* Th = reinterpret_cast<uint16_t*>(smem);               // [BN][DS]  Q^T hi
-  uint16_t* Tl = Th + BN * DS;                                    // [BN][DS]  Q^T lo
-  float* Cs = reinterpret_cast<float*>(smem + 2 * BN * DS * 2);   // [BM][CS]
+  uint16_t* Th = reinterpret_cast<uint16_t*>(smem);               // [BK][DS]  Q^T hi   (image chunk, as stored)
+  uint16_t* Tl = Th + BK * DS;                                    // [BK][DS]  Q^T lo
+  float* Cs = reinterpret_cast<float*>(smem + T_BYTES);           // [BM][CS]
   const UpdCoef cf = make_coef(sc.lr, B.lr_scale, B.wd, sc.clip);
   const float ob2 = 1.f - sc.beta2;
-  constexpr int TV = (BN * R / 8) / 256;                          // 16-byte loads of Q^T per thread, chunk and half
-  uint4 thp[TV], tlp[TV];                                          // next chunk of Q^T (hi, lo)
-  uint4 gcur[2], wcur[4], gnxt[2], wnxt[4];                        // G / W vectors of this and the next chunk
-  const bool w16 = B.param_dtype == DT_BF16;
-  auto fetch_t = [&](int j0) {
+  constexpr int WV = W16 ? 1 : 2;                                  // 16-byte pieces of W per 8 elements
+  uint4 gcur[2], wcur[2][WV], gnxt[2], wnxt[2][WV];
+  // asynchronous copy of one image chunk into LDS: every wave moves whole kilobytes
+  auto dma_t = [&](int j0) {
+    const char* src = Timg + (int64_t)(j0 / BK) * T_BYTES;
+    constexpr int NI = T_BYTES / 1024;
 #pragma unroll
-    for (int i = 0; i < TV; ++i) {
-      const int id = tid + 256 * i, j = id / (R / 8), a8 = (id % (R / 8)) * 8;
-      thp[i] = make_uint4(0, 0, 0, 0);
-      tlp[i] = make_uint4(0, 0, 0, 0);
-      if (j0 + j < n && !(sc.dbg & 8)) {
-        thp[i] = *reinterpret_cast<const uint4*>(Qth_g + (int64_t)(j0 + j) * R + a8);
-        tlp[i] = *reinterpret_cast<const uint4*>(Qtl_g + (int64_t)(j0 + j) * R + a8);
-      }
+    for (int i = 0; i < (NI + 3) / 4; ++i) {
+      const int k = wave + 4 * i;
+      if (k < NI)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + k * 1024 + lane * 16),
+                                         (__attribute__((address_space(3))) void*)(smem + k * 1024), 16, 0, 0);
     }
   };
-  auto fetch_gw = [&](int j0, uint4* gq, uint4* wq) {
+  auto fetch_gw = [&](int j0, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
       gq[i] = make_uint4(0, 0, 0, 0);
-      wq[2 * i] = wq[2 * i + 1] = make_uint4(0, 0, 0, 0);
-      if (row0 + row < m && j0 + c8 < n && !(sc.dbg & 16)) {
+#pragma unroll
+      for (int k = 0; k < WV; ++k) wq[i][k] = make_uint4(0, 0, 0, 0);
+      if (row0 + row < m && j0 + c8 < n) {
         const int64_t e = (int64_t)(row0 + row) * n + j0 + c8;
         gq[i] = *reinterpret_cast<const uint4*>(G + e);
-        if (w16) {
-          wq[2 * i] = *reinterpret_cast<const uint4*>(W + e * 2);
-        } else {
-          wq[2 * i] = *reinterpret_cast<const uint4*>(W + e * 4);
-          wq[2 * i + 1] = *reinterpret_cast<const uint4*>(W + e * 4 + 16);
-        }
+#pragma unroll
+        for (int k = 0; k < WV; ++k) wq[i][k] = *reinterpret_cast<const uint4*>(W + e * (W16 ? 2 : 4) + 16 * k);
       }
     }
   };
-  fetch_t(0);
+  dma_t(0);
   fetch_gw(0, gcur, wcur);
-  for (int j0 = 0; j0 < ((sc.dbg & 64) ? 0 : n); j0 += BN) {
-#pragma unroll
-    for (int i = 0; i < TV; ++i) {
-      const int id = tid + 256 * i, j = id / (R / 8), a8 = (id % (R / 8)) * 8;
-      *reinterpret_cast<uint4*>(Th + j * DS + a8) = thp[i];
-      *reinterpret_cast<uint4*>(Tl + j * DS + a8) = tlp[i];
-    }
+  for (int j0 = 0; j0 < n; j0 += BK) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");              // this chunk's image (and G, W) have landed
     __syncthreads();
-    if (j0 + BN < n) {
-      fetch_t(j0 + BN);
-      fetch_gw(j0 + BN, gnxt, wnxt);
-    }
+    if (j0 + BK < n) fetch_gw(j0 + BK, gnxt, wnxt);
     f32x16 c;
 #pragma unroll
     for (int i = 0; i < 16; ++i) c[i] = 0.f;
-if (!(sc.dbg & 4))
 #pragma unroll
     for (int ks = 0; ks < 2 * RT; ++ks) {
       const bf16x8 bh = lds_frag(Th + (32 * wc + l32) * DS + 16 * ks + 8 * lh);
@@ -307,11 +286,12 @@ if (!(sc.dbg & 4))
 #pragma unroll
       for (int p = 0; p < 4; ++p) Cs[(32 * wr + 8 * q + 4 * lh + p) * CS + 32 * wc + l32] = c[4 * q + p];
     __syncthreads();
+    if (j0 + BK < n) dma_t(j0 + BK);                               // overlaps the element-wise tail below
     // element-wise tail on 8 consecutive columns per thread
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
-      if (row0 + row >= m || j0 + c8 >= n || (sc.dbg & 32)) continue;
+      if (row0 + row >= m || j0 + c8 >= n) continue;
       const int64_t e = (int64_t)(row0 + row) * n + j0 + c8;
       const uint32_t gw[4] = {gcur[i].x, gcur[i].y, gcur[i].z, gcur[i].w};
       float g[8], mc[8], inv[8];
@@ -338,8 +318,8 @@ if (!(sc.dbg & 4))
 #pragma unroll
         for (int j = 0; j < 8; ++j) inv[j] = x;
       }
-      if (w16) {
-        const uint32_t ww[4] = {wcur[2 * i].x, wcur[2 * i].y, wcur[2 * i].z, wcur[2 * i].w};
+      if (W16) {
+        const uint32_t ww[4] = {wcur[i][0].x, wcur[i][0].y, wcur[i][0].z, wcur[i][0].w};
         uint32_t o[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -347,8 +327,8 @@ if (!(sc.dbg & 4))
                              apply_update(bf16hi(ww[j]), mc[2 * j + 1], inv[2 * j + 1], cf));
         *reinterpret_cast<uint4*>(W + e * 2) = make_uint4(o[0], o[1], o[2], o[3]);
       } else {
-        const uint32_t ww[8] = {wcur[2 * i].x, wcur[2 * i].y, wcur[2 * i].z, wcur[2 * i].w,
-                                wcur[2 * i + 1].x, wcur[2 * i + 1].y, wcur[2 * i + 1].z, wcur[2 * i + 1].w};
+        const uint32_t ww[8] = {wcur[i][0].x, wcur[i][0].y, wcur[i][0].z, wcur[i][0].w,
+                                wcur[i][WV - 1].x, wcur[i][WV - 1].y, wcur[i][WV - 1].z, wcur[i][WV - 1].w};
         float w[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) w[j] = apply_update(__uint_as_float(ww[j]), mc[j], inv[j], cf);
@@ -358,65 +338,86 @@ if (!(sc.dbg & 4))
       }
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) { gcur[i] = gnxt[i]; wcur[2 * i] = wnxt[2 * i]; wcur[2 * i + 1] = wnxt[2 * i + 1]; }
+    for (int i = 0; i < 2; ++i) {
+      gcur[i] = gnxt[i];
+#pragma unroll
+      for (int k = 0; k < WV; ++k) wcur[i][k] = wnxt[i][k];
+    }
   }
 }
 
-// Q (r x n fp32, state) -> bf16 (hi, lo) pairs in the workspace, both as Q [r][n] and as Q^T [n][r].
-__global__ __launch_bounds__(256) void qsplit_kernel(const QsItem* __restrict__ items,
+// After Alg. 2: R (r x n fp32, state) -> the two bf16 (hi, lo) images used by proj_kernel, in the workspace.
+//  * fragment-major image for pass 1: [chunk][k-step][r-tile][hi|lo][lane][8]  (see fetch_q)
+//  * padded LDS image of Q^T for pass 2: [chunk][hi|lo][64 columns j][R + 8], zero beyond n and in the padding
+// One workgroup per (block, 64-column chunk); a thread writes 16-byte pieces.
+__global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ items,
                                                      const LrBlockDev* __restrict__ lrb, Bases bs) {
-  __shared__ float tile[32][65];
   const QsItem it = items[blockIdx.x];
   const LrBlockDev B = lrb[it.lr];
-  const int n = B.n, R = B.r;
+  const int n = B.n, R = B.r, RT = R / 32, c = it.c;
   const float* __restrict__ Q = reinterpret_cast<const float*>(bs.state + B.off_Q);
-  uint16_t* __restrict__ Th = reinterpret_cast<uint16_t*>(bs.ws + B.off_Qt_hi);
-  uint16_t* __restrict__ Tl = reinterpret_cast<uint16_t*>(bs.ws + B.off_Qt_lo);
-  uint16_t* __restrict__ Nh = reinterpret_cast<uint16_t*>(bs.ws + B.off_Qn_hi);
-  uint16_t* __restrict__ Nl = reinterpret_cast<uint16_t*>(bs.ws + B.off_Qn_lo);
-  const int a0 = it.a0, j0 = it.j0, tid = threadIdx.x;
-  // read 32 rows (a) x 64 columns (j), j fastest
+  char* qf = bs.ws + B.off_Qf + (int64_t)c * qf_chunk_bytes(R);
+  char* ti = bs.ws + B.off_Timg + (int64_t)c * timg_chunk_bytes(R);
+  const int DS = timg_row_stride(R);
+  // pass-1 fragments: piece p = ((kk * RT + tile) * 2 + hl) * 64 + lane
+  const int np1 = (BK / 16) * RT * 2 * 64;
+  for (int p = threadIdx.x; p < np1; p += 256) {
+    const int lane = p & 63, hl = (p >> 6) & 1, rest = p >> 7, tile = rest % RT, kk = rest / RT;
+    const int a = 32 * tile + (lane & 31), k = c * BK + kk * 16 + 8 * (lane >> 5);
+    uint32_t o[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int id = tid + 256 * i, a = id >> 6, j = id & 63;
-    const bool in = a0 + a < R && j0 + j < n;
-    const float x = in ? Q[(int64_t)(a0 + a) * n + j0 + j] : 0.f;
-    tile[a][j] = x;
-    if (in) {
+    for (int e = 0; e < 4; ++e) {
+      const float x0 = (k + 2 * e < n) ? Q[(int64_t)a * n + k + 2 * e] : 0.f;
+      const float x1 = (k + 2 * e + 1 < n) ? Q[(int64_t)a * n + k + 2 * e + 1] : 0.f;
       uint32_t h, l;
-      split_pair(x, 0.f, h, l);
-      Nh[(int64_t)(a0 + a) * n + j0 + j] = (uint16_t)h;
-      Nl[(int64_t)(a0 + a) * n + j0 + j] = (uint16_t)l;
+      split_pair(x0, x1, h, l);
+      o[e] = hl ? l : h;
     }
+    *reinterpret_cast<uint4*>(qf + (int64_t)p * 16) = make_uint4(o[0], o[1], o[2], o[3]);
   }
-  __syncthreads();
-  // write 64 rows (j) x 32 columns (a), a fastest
+  // pass-2 image: piece p = (hl * BK + j) * (DS / 8) + a8 / 8
+  const int np2 = 2 * BK * (DS / 8);
+  for (int p = threadIdx.x; p < np2; p += 256) {
+    const int a8 = (p % (DS / 8)) * 8, j = (p / (DS / 8)) % BK, hl = p / (BK * (DS / 8));
+    const int col = c * BK + j;
+    uint32_t o[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int id = tid + 256 * i, j = id >> 5, a = id & 31;
-    if (a0 + a < R && j0 + j < n) {
+    for (int e = 0; e < 4; ++e) {
+      const int a0 = a8 + 2 * e;
+      const float x0 = (a0 < R && col < n) ? Q[(int64_t)a0 * n + col] : 0.f;
+      const float x1 = (a0 + 1 < R && col < n) ? Q[(int64_t)(a0 + 1) * n + col] : 0.f;
       uint32_t h, l;
-      split_pair(tile[a][j], 0.f, h, l);
-      Th[(int64_t)(j0 + j) * R + a0 + a] = (uint16_t)h;
-      Tl[(int64_t)(j0 + j) * R + a0 + a] = (uint16_t)l;
+      split_pair(x0, x1, h, l);
+      o[e] = hl ? l : h;
     }
+    *reinterpret_cast<uint4*>(ti + (int64_t)p * 16) = make_uint4(o[0], o[1], o[2], o[3]);
   }
+}
+
+template <int RT>
+void launch_proj_rt(bool w16, dim3 grid, const ProjItem* items, const LrBlockDev* lrb, Bases b, StepScalars sc,
+                    hipStream_t s) {
+  if (w16) hipLaunchKernelGGL((proj_kernel<RT, true>), grid, dim3(256), 0, s, items, lrb, b, sc);
+  else hipLaunchKernelGGL((proj_kernel<RT, false>), grid, dim3(256), 0, s, items, lrb, b, sc);
 }
 
 }  // namespace
 
-void launch_proj(int rt, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, StepScalars sc,
-                 hipStream_t s) {
+size_t proj_qf_bytes(int r, int n) { return (size_t)((n + BK - 1) / BK) * qf_chunk_bytes(r); }
+size_t proj_timg_bytes(int r, int n) { return (size_t)((n + BK - 1) / BK) * timg_chunk_bytes(r); }
+
+void launch_proj(int rt, bool w16, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
+                 StepScalars sc, hipStream_t s) {
   if (nitems <= 0) return;
-  const dim3 grid((unsigned)nitems), block(256);
-  if (rt == 1) hipLaunchKernelGGL(proj_kernel<1>, grid, block, 0, s, items, lrb, b, sc);
-  else if (rt == 2) hipLaunchKernelGGL(proj_kernel<2>, grid, block, 0, s, items, lrb, b, sc);
-  else hipLaunchKernelGGL(proj_kernel<4>, grid, block, 0, s, items, lrb, b, sc);
+  const dim3 grid((unsigned)nitems);
+  if (rt == 1) launch_proj_rt<1>(w16, grid, items, lrb, b, sc, s);
+  else if (rt == 2) launch_proj_rt<2>(w16, grid, items, lrb, b, sc, s);
+  else launch_proj_rt<4>(w16, grid, items, lrb, b, sc, s);
 }
 
-void launch_qsplit(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s) {
+void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s) {
   if (nitems <= 0) return;
-  hipLaunchKernelGGL(qsplit_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, lrb, b);
+  hipLaunchKernelGGL(qimage_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, lrb, b);
 }
 
 }  // namespace adapm
