@@ -65,6 +65,7 @@ struct GemmList {
   std::vector<GemmTile> tiles;
   GemmProblem* d_probs = nullptr;
   GemmTile* d_tiles = nullptr;
+  int tile = 64;
 };
 
 struct Op {
@@ -205,11 +206,14 @@ uint64_t mix64(uint64_t z) {
   return z ^ (z >> 31);
 }
 
-void add_problem(GemmList& gl, const GemmProblem& p) {
+// output tile edge: 64 for the fp64 kernel, 128 for the MFMA kernel
+void add_problem(GemmList& gl, const GemmProblem& p, int tile = 0) {
+  if (tile) gl.tile = tile;
   gl.probs.push_back(p);
   const uint32_t id = (uint32_t)gl.probs.size() - 1;
-  for (int ti = 0; ti < (p.M + 63) / 64; ++ti)
-    for (int tj = 0; tj < (p.N + 63) / 64; ++tj) gl.tiles.push_back(GemmTile{id, (uint16_t)ti, (uint16_t)tj});
+  const int T = gl.tile;
+  for (int ti = 0; ti < (p.M + T - 1) / T; ++ti)
+    for (int tj = 0; tj < (p.N + T - 1) / T; ++tj) gl.tiles.push_back(GemmTile{id, (uint16_t)ti, (uint16_t)tj});
 }
 
 GemmProblem problem(int M, int N) {
@@ -245,13 +249,17 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   if (!any) return;
   const std::vector<double> etas = effective_step_sizes(hp.refresh_iters_K);
   const int n_eff = (int)etas.size();
-  auto new_list = [&]() { c->gemms.emplace_back(); return (int)c->gemms.size() - 1; };
+  auto new_list = [&](bool mfma) {
+    c->gemms.emplace_back();
+    c->gemms.back().tile = mfma ? 128 : 64;
+    return (int)c->gemms.size() - 1;
+  };
   std::vector<int> listA(n_eff), listB(n_eff);
-  for (int e = 0; e < n_eff; ++e) { listA[e] = new_list(); listB[e] = new_list(); }
-  const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list() : -1;
-  const int l_epi = new_list();
-  const int l_gram = hp.refresh_period_T > 1 ? new_list() : -1;
-  const int l_fin = (hp.refresh_period_T > 1 || n_eff > 0) ? new_list() : -1;
+  for (int e = 0; e < n_eff; ++e) { listA[e] = new_list(fast); listB[e] = new_list(fast); }
+  const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list(fast) : -1;
+  const int l_epi = new_list(fast);
+  const int l_gram = hp.refresh_period_T > 1 ? new_list(false) : -1;
+  const int l_fin = (hp.refresh_period_T > 1 || n_eff > 0) ? new_list(fast && hp.refresh_period_T <= 1) : -1;
   for (int64_t i = 0; i < nb; ++i) {
     const adapm_block_t& b = c->table[i];
     const Layout& L = c->lay[i];

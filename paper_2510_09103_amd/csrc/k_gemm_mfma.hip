@@ -4,11 +4,12 @@
 // reconstruction L_{t-1}R_{t-1} - L_t R_t of eq. 3-4 on blocks with bf16 gradients.
 // bf16 operands (G) are exact; an fp32 operand x travels as hi = bf16(x), lo = bf16(x - hi), and a
 // product of two operands keeps hi*hi + lo*hi + hi*lo (the lo*lo term, 2^-18 relative, is dropped).
-// One workgroup computes a 64 x 64 output tile; each of its four waves owns a 32 x 32 MFMA tile.
+// One workgroup computes a 128 x 128 output tile; each of its four waves owns 64 x 64 (2 x 2 MFMA tiles).
 // Operand tiles are staged through LDS with the contraction index contiguous, whatever the strides
 // in memory (a transposed view is transposed on the way into LDS).  The next k-chunk is fetched
 // into registers while the current one feeds the matrix cores.
 #include "adapm_plan.h"
+#include "ew_math.h"
 
 namespace adapm {
 
@@ -17,7 +18,7 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int TM = 64, TN = 64, TK = 32;
+constexpr int TM = 128, TN = 128, TK = 32;
 constexpr int LS = TK + 8;                     // LDS row stride in bf16 elements (80 bytes)
 
 __device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
@@ -36,105 +37,141 @@ __device__ __forceinline__ bf16x8 lds_frag(const uint16_t* p) {
   return f.v;
 }
 
-// 8 values of one operand tile held by a thread between the global load and the LDS store.
+// 16 values of one 128 x 32 operand tile held by a thread between the global load and the LDS store.
 struct Stage {
-  float x[8];
+  float x[16];
 };
 
 // Tile element (u, k): u = row of A or column of B, k = contraction index.  Memory address of
-// (u, k) is base + (u * su + k * sk) elements.  kfast (sk == 1): a thread takes 8 consecutive k of
-// one u; otherwise (su == 1) it takes 8 consecutive u of one k.
+// (u, k) is base + (u * su + k * sk) elements.
+//  kfast (sk == 1): a thread takes 8 consecutive k of rows u and u + 64 (16-byte vector loads);
+//  otherwise (su == 1): lanes run along u (coalesced scalar loads) and a thread takes 16 consecutive
+//  k of one u, so that the transposed tile is written to LDS as whole 16-byte vectors.
 __device__ __forceinline__ void fetch(const char* base, int dtype, int64_t su, int64_t sk, bool kfast, int u0, int k0,
-                                      int U, int K, Stage& st) {
+                                      int U, int K, float alpha, Stage& st) {
   const int tid = threadIdx.x;
-  int u, k, du, dk;
-  if (kfast) { u = tid >> 2; k = (tid & 3) * 8; du = 0; dk = 1; }
-  else { k = tid >> 3; u = (tid & 7) * 8; du = 1; dk = 0; }
-  const int gu = u0 + u, gk = k0 + k;
-  const int64_t idx = (int64_t)gu * su + (int64_t)gk * sk;
-  const bool full = kfast ? (gu < U && gk + 8 <= K) : (gk < K && gu + 8 <= U);
-  if (full) {
-    if (dtype == DT_BF16) {
-      const uint4 q = *reinterpret_cast<const uint4*>(base + idx * 2);
-      const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+  if (kfast) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { st.x[2 * i] = __uint_as_float(w[i] << 16); st.x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
-    } else {
-      const float4 a = *reinterpret_cast<const float4*>(base + idx * 4);
-      const float4 b = *reinterpret_cast<const float4*>(base + idx * 4 + 16);
-      st.x[0] = a.x; st.x[1] = a.y; st.x[2] = a.z; st.x[3] = a.w; st.x[4] = b.x; st.x[5] = b.y; st.x[6] = b.z; st.x[7] = b.w;
+    for (int h = 0; h < 2; ++h) {
+      const int gu = u0 + (tid >> 2) + 64 * h, gk = k0 + (tid & 3) * 8;
+      const int64_t idx = (int64_t)gu * su + gk;
+      if (gu < U && gk + 8 <= K) {
+        if (dtype == DT_BF16) {
+          const uint4 q = *reinterpret_cast<const uint4*>(base + idx * 2);
+          const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { st.x[8 * h + 2 * i] = __uint_as_float(w[i] << 16); st.x[8 * h + 2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
+        } else {
+          const float4 a = *reinterpret_cast<const float4*>(base + idx * 4);
+          const float4 b = *reinterpret_cast<const float4*>(base + idx * 4 + 16);
+          st.x[8 * h + 0] = a.x; st.x[8 * h + 1] = a.y; st.x[8 * h + 2] = a.z; st.x[8 * h + 3] = a.w;
+          st.x[8 * h + 4] = b.x; st.x[8 * h + 5] = b.y; st.x[8 * h + 6] = b.z; st.x[8 * h + 7] = b.w;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float v = 0.f;
+          if (gu < U && gk + i < K)
+            v = dtype == DT_BF16 ? __uint_as_float(((uint32_t)reinterpret_cast<const uint16_t*>(base)[idx + i]) << 16)
+                                 : reinterpret_cast<const float*>(base)[idx + i];
+          st.x[8 * h + i] = v;
+        }
+      }
     }
   } else {
+    const int gu = u0 + (tid & 127), gk = k0 + 16 * (tid >> 7);
+    const bool uin = gu < U;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int eu = gu + i * du, ek = gk + i * dk;
+    for (int i = 0; i < 16; ++i) {
       float v = 0.f;
-      if (eu < U && ek < K) {
-        const int64_t j = (int64_t)eu * su + (int64_t)ek * sk;
+      if (uin && gk + i < K) {
+        const int64_t j = (int64_t)gu * su + (int64_t)(gk + i) * sk;
         v = dtype == DT_BF16 ? __uint_as_float(((uint32_t)reinterpret_cast<const uint16_t*>(base)[j]) << 16)
                              : reinterpret_cast<const float*>(base)[j];
       }
       st.x[i] = v;
     }
   }
+  if (alpha != 1.f) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.x[i] *= alpha;
+  }
 }
 
-// registers -> LDS [u][k] as (hi, lo) bf16
+// registers -> LDS [u][k] as (hi, lo) bf16, 16-byte vectors in both cases
 __device__ __forceinline__ void stash(const Stage& st, bool kfast, bool split, uint16_t* hi, uint16_t* lo) {
   const int tid = threadIdx.x;
-  uint32_t h[8], l[8];
+  uint32_t h[8], l[8];                    // packed pairs
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    h[i] = bf16_rne_bits(st.x[i]);
-    l[i] = split ? bf16_rne_bits(st.x[i] - __uint_as_float(h[i] << 16)) : 0u;
+    if (split) split_pair(st.x[2 * i], st.x[2 * i + 1], h[i], l[i]);
+    else { h[i] = pack_bf16x2(st.x[2 * i], st.x[2 * i + 1]); l[i] = 0u; }
   }
-  if (kfast) {
-    const int u = tid >> 2, k = (tid & 3) * 8;
-    *reinterpret_cast<uint4*>(hi + u * LS + k) = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    if (split)
-      *reinterpret_cast<uint4*>(lo + u * LS + k) = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
-  } else {
-    const int k = tid >> 3, u = (tid & 7) * 8;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      hi[(u + i) * LS + k] = (uint16_t)h[i];
-      if (split) lo[(u + i) * LS + k] = (uint16_t)l[i];
-    }
+  for (int hh = 0; hh < 2; ++hh) {
+    int u, k;
+    if (kfast) { u = (tid >> 2) + 64 * hh; k = (tid & 3) * 8; }
+    else { u = tid & 127; k = 16 * (tid >> 7) + 8 * hh; }
+    const int o = 4 * hh;
+    *reinterpret_cast<uint4*>(hi + u * LS + k) = make_uint4(h[o], h[o + 1], h[o + 2], h[o + 3]);
+    if (split) *reinterpret_cast<uint4*>(lo + u * LS + k) = make_uint4(l[o], l[o + 1], l[o + 2], l[o + 3]);
   }
 }
 
-__device__ __forceinline__ void product(const Mat& A, const Mat& B, int M, int N, int K, int i0, int j0, const Bases& bs,
-                                        uint16_t* Ah, uint16_t* Al, uint16_t* Bh, uint16_t* Bl, f32x16& acc) {
+// acc += alpha * A B over the whole contraction; each wave owns a 64 x 64 block = 2 x 2 MFMA tiles
+__device__ __forceinline__ void product(const Mat& A, const Mat& B, float alpha, int M, int N, int K, int i0, int j0,
+                                        const Bases& bs, uint16_t* Ah, uint16_t* Al, uint16_t* Bh, uint16_t* Bl,
+                                        f32x16 (&acc)[2][2]) {
   const char* Ab = resolve(A.ref, bs);
   const char* Bb = resolve(B.ref, bs);
   const bool a_kfast = (A.s1 == 1), b_kfast = (B.s0 == 1);
-  const bool a_split = (A.dtype != DT_BF16), b_split = (B.dtype != DT_BF16);
+  const bool a_split = (A.dtype != DT_BF16) || alpha != 1.f, b_split = (B.dtype != DT_BF16);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
   const int wm = wave & 1, wn = wave >> 1;
   Stage sa, sb;
-  fetch(Ab, A.dtype, A.s0, A.s1, a_kfast, i0, 0, M, K, sa);
-  fetch(Bb, B.dtype, B.s1, B.s0, b_kfast, j0, 0, N, K, sb);
+  fetch(Ab, A.dtype, A.s0, A.s1, a_kfast, i0, 0, M, K, alpha, sa);
+  fetch(Bb, B.dtype, B.s1, B.s0, b_kfast, j0, 0, N, K, 1.f, sb);
   for (int k0 = 0; k0 < K; k0 += TK) {
     stash(sa, a_kfast, a_split, Ah, Al);
     stash(sb, b_kfast, b_split, Bh, Bl);
     __syncthreads();
     if (k0 + TK < K) {
-      fetch(Ab, A.dtype, A.s0, A.s1, a_kfast, i0, k0 + TK, M, K, sa);
-      fetch(Bb, B.dtype, B.s1, B.s0, b_kfast, j0, k0 + TK, N, K, sb);
+      fetch(Ab, A.dtype, A.s0, A.s1, a_kfast, i0, k0 + TK, M, K, alpha, sa);
+      fetch(Bb, B.dtype, B.s1, B.s0, b_kfast, j0, k0 + TK, N, K, 1.f, sb);
     }
 #pragma unroll
     for (int kk = 0; kk < TK / 16; ++kk) {
       const int ko = kk * 16 + 8 * lh;
-      const bf16x8 ah = lds_frag(Ah + (32 * wm + l32) * LS + ko);
-      const bf16x8 bh = lds_frag(Bh + (32 * wn + l32) * LS + ko);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc, 0, 0, 0);
+      bf16x8 ah[2], bh[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        ah[t] = lds_frag(Ah + (64 * wm + 32 * t + l32) * LS + ko);
+        bh[t] = lds_frag(Bh + (64 * wn + 32 * t + l32) * LS + ko);
+      }
+#pragma unroll
+      for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[tm], bh[tn], acc[tm][tn], 0, 0, 0);
       if (a_split) {
-        const bf16x8 al = lds_frag(Al + (32 * wm + l32) * LS + ko);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc, 0, 0, 0);
+        bf16x8 al[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) al[t] = lds_frag(Al + (64 * wm + 32 * t + l32) * LS + ko);
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+          for (int tn = 0; tn < 2; ++tn)
+            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[tm], bh[tn], acc[tm][tn], 0, 0, 0);
       }
       if (b_split) {
-        const bf16x8 bl = lds_frag(Bl + (32 * wn + l32) * LS + ko);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc, 0, 0, 0);
+        bf16x8 bl[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) bl[t] = lds_frag(Bl + (64 * wn + 32 * t + l32) * LS + ko);
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+          for (int tn = 0; tn < 2; ++tn)
+            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[tm], bl[tn], acc[tm][tn], 0, 0, 0);
       }
     }
     __syncthreads();
@@ -155,40 +192,37 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmProblem* __res
   const int i0 = t.ti * TM, j0 = t.tj * TN;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
   const int wm = wave & 1, wn = wave >> 1;
-  f32x16 acc;
+  f32x16 acc[2][2];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-  if (P.K1 > 0) {
-    product(P.A1, P.B1, P.M, P.N, P.K1, i0, j0, bs, Ah, Al, Bh, Bl, acc);
-    const float a1 = (float)P.a1;
+  for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] *= a1;
-  }
-  if (P.K2 > 0) {
-    f32x16 acc2;
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc2[i] = 0.f;
-    product(P.A2, P.B2, P.M, P.N, P.K2, i0, j0, bs, Ah, Al, Bh, Bl, acc2);
-    const float a2 = (float)P.a2;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] += a2 * acc2[i];
-  }
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+  // the scalar factors ride on the A operand, so both products land in the same accumulators
+  if (P.K1 > 0) product(P.A1, P.B1, (float)P.a1, P.M, P.N, P.K1, i0, j0, bs, Ah, Al, Bh, Bl, acc);
+  if (P.K2 > 0) product(P.A2, P.B2, (float)P.a2, P.M, P.N, P.K2, i0, j0, bs, Ah, Al, Bh, Bl, acc);
   const char* Xb = P.X.ref.space != SP_NONE ? resolve(P.X.ref, bs) : nullptr;
   const char* Yb = P.Y.ref.space != SP_NONE ? resolve(P.Y.ref, bs) : nullptr;
   float* Ob = reinterpret_cast<float*>(resolve(P.Out.ref, bs));
   const float g = (float)P.g, d = (float)P.d;
-  const int j = j0 + 32 * wn + l32;
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
+  for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int i = i0 + 32 * wm + 8 * q + 4 * lh + p;
-      if (i < P.M && j < P.N) {
-        float val = acc[4 * q + p];
-        if (Xb) val += g * load_f(Xb, P.X.dtype, (int64_t)i * P.X.s0 + (int64_t)j * P.X.s1);
-        if (Yb) val += d * load_f(Yb, P.Y.dtype, (int64_t)i * P.Y.s0 + (int64_t)j * P.Y.s1);
-        Ob[(int64_t)i * P.Out.s0 + (int64_t)j * P.Out.s1] = val;
-      }
+    for (int tn = 0; tn < 2; ++tn) {
+      const int j = j0 + 64 * wn + 32 * tn + l32;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int i = i0 + 64 * wm + 32 * tm + 8 * q + 4 * lh + p;
+          if (i < P.M && j < P.N) {
+            float val = acc[tm][tn][4 * q + p];
+            if (Xb) val += g * load_f(Xb, P.X.dtype, (int64_t)i * P.X.s0 + (int64_t)j * P.X.s1);
+            if (Yb) val += d * load_f(Yb, P.Y.dtype, (int64_t)i * P.Y.s0 + (int64_t)j * P.Y.s1);
+            Ob[(int64_t)i * P.Out.s0 + (int64_t)j * P.Out.s1] = val;
+          }
+        }
     }
 }
 
