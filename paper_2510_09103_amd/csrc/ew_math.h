@@ -63,4 +63,10 @@ __device__ __forceinline__ float apply_update(float w, float mc, float inv, cons
   return fmaf(c.neg_lrs, u, w * c.decay);
 }
 
+// The same with the factor -lr folded into the per-row inverse: ninv = -lr * inv, bound = lr * clip.
+// Three instructions per element (multiply, median, fused multiply-add).
+__device__ __forceinline__ float apply_update_scaled(float w, float mc, float ninv, float bound, float decay) {
+  return fmaf(w, decay, __builtin_amdgcn_fmed3f(mc * ninv, -bound, bound));
+}
+
 }  // namespace adapm

@@ -184,7 +184,7 @@ __device__ __forceinline__ float load_f(const char* base, int dtype, int64_t idx
   return (float)reinterpret_cast<const double*>(base)[idx];
 }
 
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const GemmProblem* __restrict__ probs,
+__global__ __launch_bounds__(256, 3) void gemm_mfma_kernel(const GemmProblem* __restrict__ probs,
                                                         const GemmTile* __restrict__ tiles, Bases bs) {
   __shared__ __attribute__((aligned(16))) uint16_t Ah[TM * LS], Al[TM * LS], Bh[TN * LS], Bl[TN * LS];
   const GemmTile t = tiles[blockIdx.x];

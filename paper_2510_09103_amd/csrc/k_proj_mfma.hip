@@ -300,8 +300,13 @@ __global__ __launch_bounds__(256, 3) void proj_kernel(const ProjItem* __restrict
       const float4 ca = *reinterpret_cast<const float4*>(Cs + row * CS + c8);
       const float4 cb = *reinterpret_cast<const float4*>(Cs + row * CS + c8 + 4);
       const float cc[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
+      if (sc.cG == 1.f) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) mc[j] = fmaf(sc.cC, cc[j], sc.cG * g[j]);
+        for (int j = 0; j < 8; ++j) mc[j] = fmaf(sc.cC, cc[j], g[j]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mc[j] = fmaf(sc.cC, cc[j], sc.cG * g[j]);
+      }
       if (B.v_kind == 0) {          // per-element second moment
         float4* vp = reinterpret_cast<float4*>(vst + e);
         const float4 va = vp[0], vb = vp[1];
@@ -309,29 +314,30 @@ __global__ __launch_bounds__(256, 3) void proj_kernel(const ProjItem* __restrict
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           vv[j] = sc.beta2 * vv[j] + ob2 * g[j] * g[j];
-          inv[j] = inv_denom_fast(vv[j], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
+          inv[j] = inv_denom_fast(vv[j], sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);   // -lr folded in
         }
         vp[0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
         vp[1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
       } else {
-        const float x = vrow[row];
+        const float x = vrow[row] * cf.neg_lrs;                     // -lr folded into the inverse denominator
 #pragma unroll
         for (int j = 0; j < 8; ++j) inv[j] = x;
       }
+      const float bound = -cf.neg_lrs * cf.clip;
       if (W16) {
         const uint32_t ww[4] = {wcur[i][0].x, wcur[i][0].y, wcur[i][0].z, wcur[i][0].w};
         uint32_t o[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          o[j] = pack_bf16x2(apply_update(bf16lo(ww[j]), mc[2 * j], inv[2 * j], cf),
-                             apply_update(bf16hi(ww[j]), mc[2 * j + 1], inv[2 * j + 1], cf));
+          o[j] = pack_bf16x2(apply_update_scaled(bf16lo(ww[j]), mc[2 * j], inv[2 * j], bound, cf.decay),
+                             apply_update_scaled(bf16hi(ww[j]), mc[2 * j + 1], inv[2 * j + 1], bound, cf.decay));
         *reinterpret_cast<uint4*>(W + e * 2) = make_uint4(o[0], o[1], o[2], o[3]);
       } else {
         const uint32_t ww[8] = {wcur[i][0].x, wcur[i][0].y, wcur[i][0].z, wcur[i][0].w,
                                 wcur[i][WV - 1].x, wcur[i][WV - 1].y, wcur[i][WV - 1].z, wcur[i][WV - 1].w};
         float w[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) w[j] = apply_update(__uint_as_float(ww[j]), mc[j], inv[j], cf);
+        for (int j = 0; j < 8; ++j) w[j] = apply_update_scaled(__uint_as_float(ww[j]), mc[j], inv[j], bound, cf.decay);
         float4* wp = reinterpret_cast<float4*>(W + e * 4);
         wp[0] = make_float4(w[0], w[1], w[2], w[3]);
         wp[1] = make_float4(w[4], w[5], w[6], w[7]);

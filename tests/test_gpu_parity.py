@@ -73,6 +73,25 @@ def test_mixed_table_all_modes(hp):
     run(wl, 6, hp, tol_state=TOL32, tol_param=TOL32, check_every=2)
 
 
+def ragged_bf16_table():
+    """bf16 blocks on the MFMA path whose sizes are not multiples of the 64-row stripes, the
+    64-column chunks or the 128 x 128 GEMM tiles; every rank class; every kind of v."""
+    mk = BlockSpec
+    return WL.Workload("ragged_bf16", (
+        mk("r32_cols1000", 200, 1000, "bf16", "bf16", "lowrank", 32, "rowgroup", 1, 1.0, 0.1),
+        mk("r64_small", 96, 136, "bf16", "bf16", "lowrank", 64, "element", 1, 1.0, 0.1),
+        mk("r128_rows130", 130, 264, "bf16", "bf16", "lowrank", 128, "rowgroup", 65, 1.0, 0.1),
+        mk("r32_f32params", 70, 72, "f32", "bf16", "lowrank", 32, "whole", 1, 1.0, 0.0),
+        mk("r64_heads16", 192, 320, "bf16", "bf16", "lowrank", 64, "rowgroup", 16, 1.0, 0.1, 16),
+    ), steps=6, seed=5, signal_rank=40)
+
+
+@pytest.mark.parametrize("hp", [dict(T=1), dict(T=3), dict(T=2, bias_correction=0)])
+def test_ragged_shapes_on_the_mfma_path(hp):
+    hp = dict(hp, contraction=B.ADAPM_CONTRACT_BF16X2)
+    run(ragged_bf16_table(), 6, hp, tol_state=TOL16, tol_param=TOL16, check_every=2)
+
+
 def test_literal_zero_start_stays_zero_on_gpu():
     wl = WL.subset(WL.tiny_block(), ["attn.q"])
     pair, _ = run(wl, 3, dict(seed=0))
