@@ -150,12 +150,13 @@ int path_of(const adapm_block_t& b, const adapm_hparams_t& hp) {
   if (b.mom_mode != ADAPM_MOM_LOWRANK) return PATH_NONE;
   const bool want = hp.contraction == ADAPM_CONTRACT_BF16X2 ||
                     (hp.contraction == ADAPM_CONTRACT_AUTO && b.param_dtype == ADAPM_BF16);
-  const bool can = b.grad_dtype == ADAPM_BF16 && (b.rank == 32 || b.rank == 64 || b.rank == 128) && b.cols % 8 == 0;
+  const bool can = b.grad_dtype == ADAPM_BF16 && (b.rank == 32 || b.rank == 64 || b.rank == 128) && b.cols % 8 == 0 &&
+                   b.cols <= (1 << 21);   // 128 rows of a stripe stay inside one 32-bit buffer range
   return (want && can) ? PATH_FAST : PATH_F64;
 }
-// v of a block on the MFMA path can be finished inside the 64-row stripe of the fused kernel
+// v of a block on the MFMA path can be finished inside the 128-row stripe of the fused kernel
 bool v_fusable(const adapm_block_t& b) {
-  return b.v_mode == ADAPM_V_ROWGROUP && b.v_group_rows <= 64 && 64 % b.v_group_rows == 0;
+  return b.v_mode == ADAPM_V_ROWGROUP && b.v_group_rows <= 128 && 128 % b.v_group_rows == 0;
 }
 
 adapm_status_t validate(const adapm_block_t* t, int64_t n, const adapm_hparams_t* hp) {
@@ -436,7 +437,7 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
       int x = 0;
       for (int k = 1; k < NXCD; ++k) if (load[k] < load[x]) x = k;
       const adapm_block_t& b = c->table[i];
-      for (int64_t r0 = 0; r0 < b.rows; r0 += 64) per[x].push_back(ProjItem{(int32_t)lr_of[i], (int32_t)r0});
+      for (int64_t r0 = 0; r0 < b.rows; r0 += 128) per[x].push_back(ProjItem{(int32_t)lr_of[i], (int32_t)r0});
       load[x] += (double)b.rows * b.cols;
     }
     size_t longest = 0;

@@ -115,7 +115,7 @@ struct LrBlockDev {
   int64_t off_v;           // state: v
   int64_t off_Qf;          // ws: Q as bf16 (hi, lo) MFMA fragments, per 64-column chunk
   int64_t off_Timg;        // ws: Q^T as bf16 (hi, lo) padded LDS images, per 64-column chunk
-  int32_t v_kind;          // 0 per element; 1 groups of v_group_rows rows finished inside the stripe;
+  int32_t v_kind;          // 0 per element; 1 groups of v_group_rows rows finished inside the 128-row stripe;
                            // 2 finished beforehand by the statistics kernel
   int32_t v_group_rows;
   int32_t param_dtype;
@@ -123,7 +123,7 @@ struct LrBlockDev {
   int32_t pad;
 };
 
-struct ProjItem {          // one workgroup: 64 rows of one block; lr < 0 = padding
+struct ProjItem {          // one workgroup: 128 rows of one block; lr < 0 = padding
   int32_t lr;
   int32_t row0;
 };

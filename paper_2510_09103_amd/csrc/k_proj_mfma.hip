@@ -5,18 +5,19 @@
 //   L_t = beta1 L_{t-1} + (1-beta1) P            (least-squares fit of m_t = (1-beta1) G + beta1 L_{t-1} Q)
 //   m^c = G + beta1 (L_{t-1} - P) Q              (eq. 3-4 with r_t = L_t Q - m_t)
 //   W  <- W - lr (clip(m^c / (sqrt(v) + eps)) + lambda W)     (Alg. 1 last line)
-// One workgroup owns a stripe of 64 rows of one block and makes two passes over it:
-//   pass 1 streams G (HBM, through LDS) and accumulates P on the matrix cores; the Q operand arrives
-//          already laid out as MFMA fragments and goes straight from L2 into registers; row sums of
-//          G^2 for the blockwise second moment ride along;
-//   pass 2 re-reads G, reconstructs D Q tile by tile (D = beta1 (L_{t-1} - P), held in registers as
-//          A fragments) and applies the update to W; Q^T arrives as a ready-made padded LDS image,
-//          copied by direct global->LDS loads that overlap the element-wise tail of the previous tile.
+// One workgroup (16 waves) owns a stripe of 128 rows of one block and makes two passes over it.  Waves
+// 0-7 feed the matrix cores, waves 8-15 stream G and W and do the element-wise work; the two groups
+// hand tiles to each other through double-buffered LDS with one barrier per 64-column chunk:
+//   pass 1: the streaming waves put chunk c of G into LDS (row sums of G^2 for the blockwise second
+//           moment ride along) while the matrix-core waves accumulate P on chunk c-1; the Q operand
+//           arrives already laid out as MFMA fragments, copied global -> LDS without touching registers;
+//   pass 2: the matrix-core waves build tile j of D Q (D = beta1 (L_{t-1} - P), held in registers as
+//           A fragments; Q^T arrives as a ready-made, bank-swizzled LDS image) while the streaming
+//           waves apply the update of tile j-1 to W and prefetch G, W of the next tiles.
 // Matrix work uses v_mfma_f32_32x32x16_bf16.  G is bf16 (exact); every fp32 operand (Q, D) is
 // carried as a (hi, lo) pair of bf16 values, products hi*hi + lo*hi + hi*lo accumulated in fp32
 // (relative operand error 2^-17).  The two images of Q are written by qimage_kernel after each run
-// of Alg. 2.  Three workgroups fit on a CU (LDS 53.8 KB, <= 168 VGPRs), so the phases of different
-// stripes overlap.
+// of Alg. 2.
 #include "adapm_plan.h"
 #include "ew_math.h"
 
@@ -27,10 +28,11 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int BM = 64;     // rows per stripe
+constexpr int BM = 128;    // rows per stripe (one workgroup)
 constexpr int BK = 64;     // columns per chunk (both passes)
 constexpr int GS = BK + 8; // LDS row stride of the G tile (elements): 16-byte fragment reads hit all banks
 constexpr int CS = BK + 8; // LDS row stride of the fp32 C tile
+constexpr int NT = 1024;   // threads: waves 0-7 feed the matrix cores, waves 8-15 stream G, W and do the element-wise work
 
 union Frag {
   bf16x8 v;
@@ -41,26 +43,50 @@ __device__ __forceinline__ bf16x8 as_frag(const uint4& q) {
   f.q = q;
   return f.v;
 }
-__device__ __forceinline__ bf16x8 lds_frag(const uint16_t* p) { return as_frag(*reinterpret_cast<const uint4*>(p)); }
+// Range-checked buffer access: a lane whose offset is at or beyond the descriptor's size reads zeros /
+// writes nothing, so ragged edges need no branches and the compiler can count outstanding loads.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr unsigned OOB = 0x80000000u;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, unsigned off, uint4 q) {
+  u32x4 v;
+  v.x = q.x; v.y = q.y; v.z = q.z; v.w = q.w;
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 0);
+}
+__device__ __forceinline__ bf16x8 lds_frag(const unsigned char* p) { return as_frag(*reinterpret_cast<const uint4*>(p)); }
 
-// geometry of the two images of Q
-__host__ __device__ constexpr int timg_row_stride(int R) { return R + 8; }                             // elements
-__host__ __device__ constexpr int timg_chunk_bytes(int R) { return 2 * BK * timg_row_stride(R) * 2; }  // hi + lo
+// Geometry of the two images of Q (per 64-column chunk, bf16 (hi, lo)):
+//  * pass 1, fragment-major: [k-step][r-tile][hi|lo][lane][8]; lane l holds Q[32 tile + l%32][64 c + 16 kk + 8 (l/32) .. +7]
+//  * pass 2, rows of Q^T:    [hi|lo][column j][R], the 16-byte pieces of a row XOR-swizzled with the row
+//    index so that the fragment reads of 16 consecutive rows fall on different banks without padding.
 __host__ __device__ constexpr int qf_chunk_bytes(int R) { return (BK / 16) * (R / 32) * 2 * 64 * 16; }
+__host__ __device__ constexpr int timg_chunk_bytes(int R) { return 2 * BK * R * 2; }
+__host__ __device__ __forceinline__ int timg_piece(int R, int j, int q) {   // physical 16-byte piece of logical piece q of row j
+  const int pr = R / 8, rp = 16 / pr;
+  return q ^ ((j / rp) & (pr - 1));
+}
 
 template <int RT, bool W16>
-__global__ __launch_bounds__(256, 3) void proj_kernel(const ProjItem* __restrict__ items,
-                                                      const LrBlockDev* __restrict__ lrb, Bases bs, StepScalars sc) {
+__global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict__ items,
+                                                     const LrBlockDev* __restrict__ lrb, Bases bs, StepScalars sc) {
   constexpr int R = 32 * RT;
-  constexpr int DS = timg_row_stride(R);
-  constexpr int TPW = (2 * RT >= 4) ? (2 * RT / 4) : 1;   // pass-1 output tiles per wave
-  constexpr int PS = R + 4;
-  constexpr int G_BYTES = BM * GS * 2;
+  constexpr int DS = R + 8;                               // LDS row stride of D (elements)
+  constexpr int PS = R + 4;                               // LDS row stride of P (floats)
+  constexpr int QF = qf_chunk_bytes(R);
+  constexpr int TB = timg_chunk_bytes(R);
+  constexpr int G_TILE = BM * GS * 2;
+  constexpr int C_TILE = BM * CS * 4;
+  constexpr int P1_BYTES = 2 * QF + 2 * G_TILE;
   constexpr int P_BYTES = BM * PS * 4;
   constexpr int D_BYTES = 2 * BM * DS * 2;
-  constexpr int T_BYTES = timg_chunk_bytes(R);
-  constexpr int P2_BYTES = T_BYTES + BM * CS * 4;
-  constexpr int m1 = G_BYTES > P_BYTES ? G_BYTES : P_BYTES;
+  constexpr int P2_BYTES = 2 * TB + 2 * C_TILE;
+  constexpr int m1 = P1_BYTES > P_BYTES ? P1_BYTES : P_BYTES;
   constexpr int m2 = D_BYTES > P2_BYTES ? D_BYTES : P2_BYTES;
   constexpr int SMEM = m1 > m2 ? m1 : m2;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
@@ -72,96 +98,115 @@ __global__ __launch_bounds__(256, 3) void proj_kernel(const ProjItem* __restrict
   const LrBlockDev B = lrb[item.lr];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool mrole = wave < 8;                       // matrix-core waves / streaming waves
+  const int mw = wave & 7;                           // index within the role
+  const int t512 = tid & 511;                        // thread index within the role
   const int l32 = lane & 31, lh = lane >> 5;
   const int m = B.m, n = B.n, row0 = item.row0;
+  const int nc = (n + BK - 1) / BK;
   const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(bs.grads[B.block]);
   char* __restrict__ W = reinterpret_cast<char*>(bs.params[B.block]);
   float* __restrict__ Lst = reinterpret_cast<float*>(bs.state + B.off_L);
   float* __restrict__ vst = reinterpret_cast<float*>(bs.state + B.off_v);
-  const char* __restrict__ Qf = bs.ws + B.off_Qf;       // fragment-major image of Q (pass 1)
-  const char* __restrict__ Timg = bs.ws + B.off_Timg;   // LDS image of Q^T per 64-column chunk (pass 2)
+  const char* __restrict__ Qf = bs.ws + B.off_Qf;
+  const char* __restrict__ Timg = bs.ws + B.off_Timg;
+  // the stripe's rows of G and W as range-checked buffers; this thread's two 8-element vectors per
+  // 64-column chunk sit in rows t512/8 and 64 + t512/8 at columns 8 (t512 % 8) ..
+  constexpr unsigned WE = W16 ? 2 : 4;
+  const unsigned rows_valid = (unsigned)(m - row0 < BM ? m - row0 : BM);
+  const __amdgpu_buffer_rsrc_t rG = make_rsrc(G + (int64_t)row0 * n, rows_valid * (unsigned)n * 2u);
+  const __amdgpu_buffer_rsrc_t rW = make_rsrc(W + (int64_t)row0 * n * WE, rows_valid * (unsigned)n * WE);
+  const int c8 = (t512 & 7) * 8;
+  const unsigned eoff[2] = {(unsigned)((t512 >> 3) * n + c8), (unsigned)((64 + (t512 >> 3)) * n + c8)};
+  const int NR = (nc + 2) & ~1;                      // rounds per pass: nc + 1, rounded up to even
+
+  // asynchronous global -> LDS copy of `bytes` (a multiple of 8 KB) by the eight matrix-core waves
+  auto dma = [&](const char* src, unsigned char* dst, int bytes) {
+    for (int k = mw; k < bytes / 1024; k += 8)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + k * 1024 + lane * 16),
+                                       (__attribute__((address_space(3))) void*)(dst + k * 1024), 16, 0, 0);
+  };
 
   // ------------------------------------------------------------------ pass 1: P = G Q^T
-  uint16_t* Gs = reinterpret_cast<uint16_t*>(smem);               // [BM][GS]
+  // Streaming waves put chunk c of G into LDS (and sum g^2 per row) while the matrix-core waves
+  // multiply chunk c-1; the Q fragments of chunk c arrive by direct-to-LDS copy.  One barrier per chunk.
+  unsigned char* Qs = smem;                           // [2][QF]
+  unsigned char* Gs = smem + 2 * QF;                  // [2][BM][GS] bf16
+  constexpr int TPW = (4 * RT >= 8) ? (4 * RT / 8) : 1;          // output tiles per matrix-core wave
+  const bool p1_active = mrole && (mw < 4 * RT);
+  const int my_rt = mw % RT;                                      // r-tile
+  const int my_mt0 = (mw / RT) * TPW;                             // first row tile
   f32x16 acc[TPW];
 #pragma unroll
   for (int t = 0; t < TPW; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
-  float ss0 = 0.f, ss1 = 0.f;                                      // sums of g^2: rows tid/8 and 32 + tid/8
-  const bool p1_active = wave < 2 * RT;                           // r = 32: only two output tiles
-  const int my_nt = (RT >= 4) ? wave : (wave % RT);
-  const int my_mt0 = (RT >= 4) ? 0 : (wave / RT);
-
-  uint4 ga[2], gb[2];                                              // G: two chunks ahead
-  uint4 qa[BK / 16][2], qb[BK / 16][2];                            // Q fragments (hi, lo): this chunk / the next
-  auto fetch_g = [&](int k0, uint4 (&dst)[2]) {
+  float ss0 = 0.f, ss1 = 0.f;                        // streaming thread: sums of g^2 of rows t512/8 and 64 + t512/8
+  auto fetch_g = [&](int c, uint4 (&dst)[2]) {
+    const bool ok = c * BK + c8 < n;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) dst[i] = buf_load16(rG, ok ? (eoff[i] + (unsigned)(c * BK)) * 2u : OOB);
+  };
+  auto stage_g = [&](int c, uint4 (&src)[2]) {
+    uint16_t* gs = reinterpret_cast<uint16_t*>(Gs + (c & 1) * G_TILE);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
-      dst[i] = make_uint4(0, 0, 0, 0);
-      if (row0 + row < m && k0 + c8 < n)
-        dst[i] = *reinterpret_cast<const uint4*>(G + (int64_t)(row0 + row) * n + k0 + c8);
-    }
-  };
-  // fragment (chunk c, k-step kk, r-tile, hi/lo) is 1 KB: lane l holds Q[32 tile + l%32][64 c + 16 kk + 8 (l/32) .. +7]
-  auto fetch_q = [&](int k0, uint4 (&dst)[BK / 16][2]) {
-    if (!p1_active) return;
-    const char* base = Qf + (int64_t)(k0 / BK) * qf_chunk_bytes(R);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk)
-#pragma unroll
-      for (int hl = 0; hl < 2; ++hl)
-        dst[kk][hl] = *reinterpret_cast<const uint4*>(base + ((((kk * RT + my_nt) * 2 + hl) * 64 + lane) << 4));
-  };
-  auto chunk = [&](int k0, uint4 (&gcur)[2], uint4 (&qcur)[BK / 16][2], uint4 (&qnxt)[BK / 16][2]) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
-      const uint4 q = gcur[i];
-      *reinterpret_cast<uint4*>(Gs + row * GS + c8) = q;
+      const int row = (t512 >> 3) + 64 * i;
+      const uint4 q = src[i];
+      *reinterpret_cast<uint4*>(gs + row * GS + c8) = q;
       const float s = dot2_sq(q.w, dot2_sq(q.z, dot2_sq(q.y, dot2_sq(q.x, 0.f))));
       if (i == 0) ss0 += s; else ss1 += s;
     }
-    __syncthreads();
-    if (k0 + 2 * BK < n) fetch_g(k0 + 2 * BK, gcur);
-    if (k0 + BK < n) fetch_q(k0 + BK, qnxt);
-    if (p1_active) {
+  };
+  // Both roles run NR rounds and meet at one barrier per round (the branch is wave-uniform).  The
+  // streaming loop has no conditions, so loads issued two rounds ahead stay in flight across barriers.
+  if (mrole) {
+    for (int cc = 0; cc < NR; ++cc) {
+      if (cc < nc) dma(Qf + (int64_t)cc * QF, Qs + (cc & 1) * QF, QF);
+      if (cc >= 1 && cc <= nc && p1_active) {
+        const unsigned char* qs = Qs + ((cc - 1) & 1) * QF;
+        const unsigned char* gs = Gs + ((cc - 1) & 1) * G_TILE;
 #pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        const int ko = kk * 16 + 8 * lh;
-        const bf16x8 bh = as_frag(qcur[kk][0]), bl = as_frag(qcur[kk][1]);
+        for (int kk = 0; kk < BK / 16; ++kk) {
+          const bf16x8 bh = lds_frag(qs + (((kk * RT + my_rt) * 2 + 0) * 64 + lane) * 16);
+          const bf16x8 bl = lds_frag(qs + (((kk * RT + my_rt) * 2 + 1) * 64 + lane) * 16);
 #pragma unroll
-        for (int t = 0; t < TPW; ++t) {
-          const bf16x8 a = lds_frag(Gs + (32 * (my_mt0 + t) + l32) * GS + ko);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bh, acc[t], 0, 0, 0);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bl, acc[t], 0, 0, 0);
+          for (int t = 0; t < TPW; ++t) {
+            const bf16x8 a = lds_frag(gs + ((32 * (my_mt0 + t) + l32) * GS + kk * 16 + 8 * lh) * 2);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bh, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bl, acc[t], 0, 0, 0);
+          }
         }
       }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // this wave's share of the Q fragments has landed
+      __syncthreads();
     }
-    __syncthreads();
-  };
-  fetch_g(0, ga);
-  fetch_g(BK, gb);
-  fetch_q(0, qa);
-  for (int k0 = 0; k0 < n; k0 += 2 * BK) {
-    chunk(k0, ga, qa, qb);
-    if (k0 + BK < n) chunk(k0 + BK, gb, qb, qa);
+  } else {
+    uint4 ga[2], gb[2];
+    fetch_g(0, ga);
+    __builtin_amdgcn_sched_barrier(0);   // keep issue order = use order, or the loop's first wait drains everything
+    fetch_g(1, gb);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int cc = 0; cc < NR; cc += 2) {       // chunks at or beyond nc read zeros (harmless: their LDS slot is idle)
+      stage_g(cc, ga);
+      fetch_g(cc + 2, ga);
+      __syncthreads();
+      stage_g(cc + 1, gb);
+      fetch_g(cc + 3, gb);
+      __syncthreads();
+    }
   }
 
-  // ------------------------------------------------------------------ second moment of the stripe
-  // a row is covered by 8 consecutive lanes
-#pragma unroll
-  for (int o = 1; o < 8; o <<= 1) { ss0 += __shfl_xor(ss0, o, 64); ss1 += __shfl_xor(ss1, o, 64); }
-  if ((tid & 7) == 0) { rsum[tid >> 3] = ss0; rsum[32 + (tid >> 3)] = ss1; }
-
-  // ------------------------------------------------------------------ L_t and D = dL L' + dP P
-  // P leaves the accumulators through LDS so that L is read and written as whole rows (float4).
+  // ------------------------------------------------------------------ second moment of the stripe, P to LDS
   float* Ps = reinterpret_cast<float*>(smem);                     // [BM][PS] fp32
-  if (p1_active) {
+  if (!mrole) {                     // a row is covered by 8 consecutive lanes
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) { ss0 += __shfl_xor(ss0, o, 64); ss1 += __shfl_xor(ss1, o, 64); }
+    if ((t512 & 7) == 0) { rsum[t512 >> 3] = ss0; rsum[64 + (t512 >> 3)] = ss1; }
+  } else if (p1_active) {
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
-      const int col = 32 * my_nt + l32;
+      const int col = 32 * my_rt + l32;
 #pragma unroll
       for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -187,11 +232,12 @@ __global__ __launch_bounds__(256, 3) void proj_kernel(const ProjItem* __restrict
     if (tid < BM && row0 + tid < m)
       vrow[tid] = inv_denom_exact(vst[(row0 + tid) / B.v_group_rows], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
   }
-  constexpr int LV = (BM * R / 4) / 256;                          // float4 per thread
+  // ------------------------------------------------------------------ L_t and D = dL L' + dP P (whole rows, float4)
+  constexpr int LV = (BM * R / 4) / NT;
   uint2 dhv[LV], dlv[LV];
 #pragma unroll
   for (int i = 0; i < LV; ++i) {
-    const int id = tid + 256 * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
+    const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
     float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
     if (row0 + row < m) {
       float4* lp = reinterpret_cast<float4*>(Lst + (int64_t)(row0 + row) * R + c4);
@@ -214,147 +260,159 @@ __global__ __launch_bounds__(256, 3) void proj_kernel(const ProjItem* __restrict
   uint16_t* Dl = Dh + BM * DS;
 #pragma unroll
   for (int i = 0; i < LV; ++i) {
-    const int id = tid + 256 * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
+    const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
     *reinterpret_cast<uint2*>(Dh + row * DS + c4) = dhv[i];
     *reinterpret_cast<uint2*>(Dl + row * DS + c4) = dlv[i];
   }
   __syncthreads();
-  // A fragments of D for this wave's 32 rows stay in registers for the whole of pass 2
-  const int wr = wave & 1, wc = wave >> 1;
-  bf16x8 dh[2 * RT], dl[2 * RT];
-#pragma unroll
-  for (int ks = 0; ks < 2 * RT; ++ks) {
-    dh[ks] = lds_frag(Dh + (32 * wr + l32) * DS + 16 * ks + 8 * lh);
-    dl[ks] = lds_frag(Dl + (32 * wr + l32) * DS + 16 * ks + 8 * lh);
-  }
-  __syncthreads();
-
   // ------------------------------------------------------------------ pass 2: C = D Q, update W
-  uint16_t* Th = reinterpret_cast<uint16_t*>(smem);               // [BK][DS]  Q^T hi   (image chunk, as stored)
-  uint16_t* Tl = Th + BK * DS;                                    // [BK][DS]  Q^T lo
-  float* Cs = reinterpret_cast<float*>(smem + T_BYTES);           // [BM][CS]
+  // Matrix-core waves build tile j of D Q (Q^T image j came by direct-to-LDS copy during tile j-1) while
+  // the streaming waves run the element-wise tail of tile j-1 and prefetch G, W.  One barrier per tile.
+  unsigned char* Ts = smem;                           // [2][TB]
+  unsigned char* Cs = smem + 2 * TB;                  // [2][BM][CS] fp32
   const UpdCoef cf = make_coef(sc.lr, B.lr_scale, B.wd, sc.clip);
   const float ob2 = 1.f - sc.beta2;
+  const float bound = -cf.neg_lrs * cf.clip;
   constexpr int WV = W16 ? 1 : 2;                                  // 16-byte pieces of W per 8 elements
-  uint4 gcur[2], wcur[2][WV], gnxt[2], wnxt[2][WV];
-  // asynchronous copy of one image chunk into LDS: every wave moves whole kilobytes
-  auto dma_t = [&](int j0) {
-    const char* src = Timg + (int64_t)(j0 / BK) * T_BYTES;
-    constexpr int NI = T_BYTES / 1024;
-#pragma unroll
-    for (int i = 0; i < (NI + 3) / 4; ++i) {
-      const int k = wave + 4 * i;
-      if (k < NI)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + k * 1024 + lane * 16),
-                                         (__attribute__((address_space(3))) void*)(smem + k * 1024), 16, 0, 0);
-    }
-  };
-  auto fetch_gw = [&](int j0, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
+  auto fetch_gw = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
+    const bool ok = j * BK + c8 < n;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
-      gq[i] = make_uint4(0, 0, 0, 0);
+      const unsigned e = eoff[i] + (unsigned)(j * BK);
+      gq[i] = buf_load16(rG, ok ? e * 2u : OOB);
 #pragma unroll
-      for (int k = 0; k < WV; ++k) wq[i][k] = make_uint4(0, 0, 0, 0);
-      if (row0 + row < m && j0 + c8 < n) {
-        const int64_t e = (int64_t)(row0 + row) * n + j0 + c8;
-        gq[i] = *reinterpret_cast<const uint4*>(G + e);
-#pragma unroll
-        for (int k = 0; k < WV; ++k) wq[i][k] = *reinterpret_cast<const uint4*>(W + e * (W16 ? 2 : 4) + 16 * k);
-      }
+      for (int k = 0; k < WV; ++k) wq[i][k] = buf_load16(rW, ok ? e * WE + 16u * k : OOB);
     }
   };
-  dma_t(0);
-  fetch_gw(0, gcur, wcur);
-  for (int j0 = 0; j0 < n; j0 += BK) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");              // this chunk's image (and G, W) have landed
-    __syncthreads();
-    if (j0 + BK < n) fetch_gw(j0 + BK, gnxt, wnxt);
-    f32x16 c;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) c[i] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 2 * RT; ++ks) {
-      const bf16x8 bh = lds_frag(Th + (32 * wc + l32) * DS + 16 * ks + 8 * lh);
-      const bf16x8 bl = lds_frag(Tl + (32 * wc + l32) * DS + 16 * ks + 8 * lh);
-      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bh, c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks], bh, c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bl, c, 0, 0, 0);
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int p = 0; p < 4; ++p) Cs[(32 * wr + 8 * q + 4 * lh + p) * CS + 32 * wc + l32] = c[4 * q + p];
-    __syncthreads();
-    if (j0 + BK < n) dma_t(j0 + BK);                               // overlaps the element-wise tail below
-    // element-wise tail on 8 consecutive columns per thread
+  // tile j < 0 or at / beyond nc: every store falls outside the buffer and is dropped
+  auto tail = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
+    const float* cs = reinterpret_cast<const float*>(Cs + (j & 1) * C_TILE);
+    const bool ok = j >= 0 && j * BK + c8 < n;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int id = tid + 256 * i, row = id >> 3, c8 = (id & 7) * 8;
-      if (row0 + row >= m || j0 + c8 >= n) continue;
-      const int64_t e = (int64_t)(row0 + row) * n + j0 + c8;
-      const uint32_t gw[4] = {gcur[i].x, gcur[i].y, gcur[i].z, gcur[i].w};
+      const int row = (t512 >> 3) + 64 * i;
+      const unsigned e = eoff[i] + (unsigned)(j * BK);
+      const uint32_t gw[4] = {gq[i].x, gq[i].y, gq[i].z, gq[i].w};
       float g[8], mc[8], inv[8];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { g[2 * j] = bf16lo(gw[j]); g[2 * j + 1] = bf16hi(gw[j]); }
-      const float4 ca = *reinterpret_cast<const float4*>(Cs + row * CS + c8);
-      const float4 cb = *reinterpret_cast<const float4*>(Cs + row * CS + c8 + 4);
+      for (int k = 0; k < 4; ++k) { g[2 * k] = bf16lo(gw[k]); g[2 * k + 1] = bf16hi(gw[k]); }
+      const float4 ca = *reinterpret_cast<const float4*>(cs + row * CS + c8);
+      const float4 cb = *reinterpret_cast<const float4*>(cs + row * CS + c8 + 4);
       const float cc[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
       if (sc.cG == 1.f) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) mc[j] = fmaf(sc.cC, cc[j], g[j]);
+        for (int k = 0; k < 8; ++k) mc[k] = fmaf(sc.cC, cc[k], g[k]);
       } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) mc[j] = fmaf(sc.cC, cc[j], sc.cG * g[j]);
+        for (int k = 0; k < 8; ++k) mc[k] = fmaf(sc.cC, cc[k], sc.cG * g[k]);
       }
       if (B.v_kind == 0) {          // per-element second moment
-        float4* vp = reinterpret_cast<float4*>(vst + e);
-        const float4 va = vp[0], vb = vp[1];
-        float vv[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          vv[j] = sc.beta2 * vv[j] + ob2 * g[j] * g[j];
-          inv[j] = inv_denom_fast(vv[j], sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);   // -lr folded in
+        float vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        float4* vp = reinterpret_cast<float4*>(vst + (int64_t)row0 * n + e);
+        const bool live = ok && row0 + row < m;
+        if (live) {
+          const float4 va = vp[0], vb = vp[1];
+          vv[0] = va.x; vv[1] = va.y; vv[2] = va.z; vv[3] = va.w;
+          vv[4] = vb.x; vv[5] = vb.y; vv[6] = vb.z; vv[7] = vb.w;
         }
-        vp[0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
-        vp[1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          vv[k] = sc.beta2 * vv[k] + ob2 * g[k] * g[k];
+          inv[k] = inv_denom_fast(vv[k], sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);   // -lr folded in
+        }
+        if (live) {
+          vp[0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+          vp[1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
+        }
       } else {
         const float x = vrow[row] * cf.neg_lrs;                     // -lr folded into the inverse denominator
 #pragma unroll
-        for (int j = 0; j < 8; ++j) inv[j] = x;
+        for (int k = 0; k < 8; ++k) inv[k] = x;
       }
-      const float bound = -cf.neg_lrs * cf.clip;
       if (W16) {
-        const uint32_t ww[4] = {wcur[i][0].x, wcur[i][0].y, wcur[i][0].z, wcur[i][0].w};
+        const uint32_t ww[4] = {wq[i][0].x, wq[i][0].y, wq[i][0].z, wq[i][0].w};
         uint32_t o[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          o[j] = pack_bf16x2(apply_update_scaled(bf16lo(ww[j]), mc[2 * j], inv[2 * j], bound, cf.decay),
-                             apply_update_scaled(bf16hi(ww[j]), mc[2 * j + 1], inv[2 * j + 1], bound, cf.decay));
-        *reinterpret_cast<uint4*>(W + e * 2) = make_uint4(o[0], o[1], o[2], o[3]);
+        for (int k = 0; k < 4; ++k)
+          o[k] = pack_bf16x2(apply_update_scaled(bf16lo(ww[k]), mc[2 * k], inv[2 * k], bound, cf.decay),
+                             apply_update_scaled(bf16hi(ww[k]), mc[2 * k + 1], inv[2 * k + 1], bound, cf.decay));
+        buf_store16(rW, ok ? e * 2u : OOB, make_uint4(o[0], o[1], o[2], o[3]));
       } else {
-        const uint32_t ww[8] = {wcur[i][0].x, wcur[i][0].y, wcur[i][0].z, wcur[i][0].w,
-                                wcur[i][WV - 1].x, wcur[i][WV - 1].y, wcur[i][WV - 1].z, wcur[i][WV - 1].w};
-        float w[8];
+        const uint32_t ww[8] = {wq[i][0].x, wq[i][0].y, wq[i][0].z, wq[i][0].w,
+                                wq[i][WV - 1].x, wq[i][WV - 1].y, wq[i][WV - 1].z, wq[i][WV - 1].w};
+        uint32_t w[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) w[j] = apply_update_scaled(__uint_as_float(ww[j]), mc[j], inv[j], bound, cf.decay);
-        float4* wp = reinterpret_cast<float4*>(W + e * 4);
-        wp[0] = make_float4(w[0], w[1], w[2], w[3]);
-        wp[1] = make_float4(w[4], w[5], w[6], w[7]);
+        for (int k = 0; k < 8; ++k)
+          w[k] = __float_as_uint(apply_update_scaled(__uint_as_float(ww[k]), mc[k], inv[k], bound, cf.decay));
+        buf_store16(rW, ok ? e * 4u : OOB, make_uint4(w[0], w[1], w[2], w[3]));
+        buf_store16(rW, ok ? e * 4u + 16u : OOB, make_uint4(w[4], w[5], w[6], w[7]));
       }
     }
+  };
+  if (mrole) {
+    // A fragments of D: wave (wr, wc) owns rows 32 wr .. and columns 32 wc .. of every 128 x 64 tile
+    const int wr = mw & 3, wc = mw >> 2;
+    bf16x8 dh[2 * RT], dl[2 * RT];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      gcur[i] = gnxt[i];
+    for (int ks = 0; ks < 2 * RT; ++ks) {
+      dh[ks] = lds_frag(reinterpret_cast<const unsigned char*>(Dh + (32 * wr + l32) * DS + 16 * ks + 8 * lh));
+      dl[ks] = lds_frag(reinterpret_cast<const unsigned char*>(Dl + (32 * wr + l32) * DS + 16 * ks + 8 * lh));
+    }
+    __syncthreads();                                               // D is in registers, its LDS is free
+    dma(Timg, Ts, TB);
+    const int jl = 32 * wc + l32;                                  // column of this lane inside the tile
+    int toff[2 * RT];
 #pragma unroll
-      for (int k = 0; k < WV; ++k) wcur[i][k] = wnxt[i][k];
+    for (int ks = 0; ks < 2 * RT; ++ks) toff[ks] = jl * R * 2 + timg_piece(R, jl, 2 * ks + lh) * 16;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int j = 0; j < NR; ++j) {
+      if (j + 1 < nc) dma(Timg + (int64_t)(j + 1) * TB, Ts + ((j + 1) & 1) * TB, TB);
+      if (j < nc) {
+        const unsigned char* th = Ts + (j & 1) * TB;
+        const unsigned char* tl = th + BK * R * 2;
+        f32x16 c;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 2 * RT; ++ks) {
+          const bf16x8 bh = lds_frag(th + toff[ks]);
+          const bf16x8 bl = lds_frag(tl + toff[ks]);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bh, c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks], bh, c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bl, c, 0, 0, 0);
+        }
+        float* cs = reinterpret_cast<float*>(Cs + (j & 1) * C_TILE);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int p = 0; p < 4; ++p) cs[(32 * wr + 8 * q + 4 * lh + p) * CS + 32 * wc + l32] = c[4 * q + p];
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // the next image has landed
+      __syncthreads();
+    }
+  } else {
+    uint4 gx[2], wx[2][WV], gy[2], wy[2][WV];                      // G / W vectors of two tiles in flight
+    __syncthreads();
+    fetch_gw(0, gx, wx);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_gw(1, gy, wy);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    // round j: tail of tile j-1, whose vectors sit in (gx, wx) when j-1 is even, else in (gy, wy); no
+    // conditions in the loop, so the loads of the next two tiles stay in flight across the barriers
+    for (int j = 0; j < NR; j += 2) {
+      tail(j - 1, gy, wy);
+      fetch_gw(j + 1, gy, wy);
+      __syncthreads();
+      tail(j, gx, wx);
+      fetch_gw(j + 2, gx, wx);
+      __syncthreads();
     }
   }
 }
 
 // After Alg. 2: R (r x n fp32, state) -> the two bf16 (hi, lo) images used by proj_kernel, in the workspace.
-//  * fragment-major image for pass 1: [chunk][k-step][r-tile][hi|lo][lane][8]  (see fetch_q)
-//  * padded LDS image of Q^T for pass 2: [chunk][hi|lo][64 columns j][R + 8], zero beyond n and in the padding
 // One workgroup per (block, 64-column chunk); a thread writes 16-byte pieces.
 __global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ items,
                                                      const LrBlockDev* __restrict__ lrb, Bases bs) {
@@ -364,7 +422,6 @@ __global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ 
   const float* __restrict__ Q = reinterpret_cast<const float*>(bs.state + B.off_Q);
   char* qf = bs.ws + B.off_Qf + (int64_t)c * qf_chunk_bytes(R);
   char* ti = bs.ws + B.off_Timg + (int64_t)c * timg_chunk_bytes(R);
-  const int DS = timg_row_stride(R);
   // pass-1 fragments: piece p = ((kk * RT + tile) * 2 + hl) * 64 + lane
   const int np1 = (BK / 16) * RT * 2 * 64;
   for (int p = threadIdx.x; p < np1; p += 256) {
@@ -381,30 +438,31 @@ __global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ 
     }
     *reinterpret_cast<uint4*>(qf + (int64_t)p * 16) = make_uint4(o[0], o[1], o[2], o[3]);
   }
-  // pass-2 image: piece p = (hl * BK + j) * (DS / 8) + a8 / 8
-  const int np2 = 2 * BK * (DS / 8);
+  // pass-2 image: logical piece q (8 consecutive r) of row j of half hl sits at physical piece timg_piece(R, j, q)
+  const int pr = R / 8;
+  const int np2 = 2 * BK * pr;
   for (int p = threadIdx.x; p < np2; p += 256) {
-    const int a8 = (p % (DS / 8)) * 8, j = (p / (DS / 8)) % BK, hl = p / (BK * (DS / 8));
+    const int q = p % pr, j = (p / pr) % BK, hl = p / (BK * pr);
     const int col = c * BK + j;
     uint32_t o[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int a0 = a8 + 2 * e;
-      const float x0 = (a0 < R && col < n) ? Q[(int64_t)a0 * n + col] : 0.f;
-      const float x1 = (a0 + 1 < R && col < n) ? Q[(int64_t)(a0 + 1) * n + col] : 0.f;
+      const int a0 = 8 * q + 2 * e;
+      const float x0 = (col < n) ? Q[(int64_t)a0 * n + col] : 0.f;
+      const float x1 = (col < n) ? Q[(int64_t)(a0 + 1) * n + col] : 0.f;
       uint32_t h, l;
       split_pair(x0, x1, h, l);
       o[e] = hl ? l : h;
     }
-    *reinterpret_cast<uint4*>(ti + (int64_t)p * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+    *reinterpret_cast<uint4*>(ti + ((int64_t)(hl * BK + j) * pr + timg_piece(R, j, q)) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
 
 template <int RT>
 void launch_proj_rt(bool w16, dim3 grid, const ProjItem* items, const LrBlockDev* lrb, Bases b, StepScalars sc,
                     hipStream_t s) {
-  if (w16) hipLaunchKernelGGL((proj_kernel<RT, true>), grid, dim3(256), 0, s, items, lrb, b, sc);
-  else hipLaunchKernelGGL((proj_kernel<RT, false>), grid, dim3(256), 0, s, items, lrb, b, sc);
+  if (w16) hipLaunchKernelGGL((proj_kernel<RT, true>), grid, dim3(NT), 0, s, items, lrb, b, sc);
+  else hipLaunchKernelGGL((proj_kernel<RT, false>), grid, dim3(NT), 0, s, items, lrb, b, sc);
 }
 
 }  // namespace
