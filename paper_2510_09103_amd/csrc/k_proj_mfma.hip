@@ -59,7 +59,6 @@ __device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, unsigned o
   v.x = q.x; v.y = q.y; v.z = q.z; v.w = q.w;
   __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 0);
 }
-__device__ __forceinline__ bf16x8 lds_frag(const unsigned char* p) { return as_frag(*reinterpret_cast<const uint4*>(p)); }
 
 // Geometry of the two images of Q (per 64-column chunk, bf16 (hi, lo)):
 //  * pass 1, fragment-major: [k-step][r-tile][hi|lo][lane][8]; lane l holds Q[32 tile + l%32][64 c + 16 kk + 8 (l/32) .. +7]
@@ -72,6 +71,107 @@ __host__ __device__ __forceinline__ int timg_piece(int R, int j, int q) {   // p
   return q ^ ((j / rp) & (pr - 1));
 }
 
+// LDS access of the matrix-core waves inside the role loops.  The compiler cannot see that a fragment
+// read never touches the buffer a direct-to-LDS copy is still filling, and would make every LDS read
+// wait for all outstanding copies (copy latency and matrix work then add up instead of overlapping).
+// So these reads are issued as opaque instructions on LDS byte addresses and waited for explicitly;
+// the wait names the registers it protects, which orders their consumers after it.
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+typedef __attribute__((address_space(3))) float lds_f32;
+__device__ __forceinline__ unsigned lds_addr(const lds_u8* p) { return (unsigned)(__UINTPTR_TYPE__)p; }
+__device__ __forceinline__ bf16x8 lds_frag(const lds_u8* p) {
+  const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(p);
+  return __builtin_bit_cast(bf16x8, v);
+}
+__device__ __forceinline__ bf16x8 lds_frag_raw(unsigned addr) {
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+__device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c, bf16x8& d) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d)::"memory");
+}
+__device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c)::"memory");
+}
+
+// Barrier of the role loops: LDS traffic of this wave is complete, global loads / copies stay in flight
+// (__syncthreads() would also drain every outstanding global access, and with it the prefetches).
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// asynchronous global -> LDS copy of `bytes` (a multiple of 8 KB) shared by the eight matrix-core waves
+__device__ __forceinline__ void dma_copy(const char* src, lds_u8* dst, int bytes, int mw, int lane) {
+  for (int k = mw; k < bytes / 1024; k += 8)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + k * 1024 + lane * 16),
+                                     (__attribute__((address_space(3))) void*)(dst + k * 1024), 16, 0, 0);
+}
+
+// pass-1 round of a matrix-core wave: start the copy of the next Q fragments, multiply one chunk
+// (qs, gs: LDS byte addresses of the fragment buffer and the G tile to read)
+template <int RT, int TPW>
+__device__ __forceinline__ void p1_round(unsigned qs, unsigned gs, lds_u8* dst, const char* src, bool mma,
+                                         f32x16 (&acc)[TPW], int my_rt, int my_mt0, int mw, int lane) {
+  static_assert(TPW == 1 || TPW == 2, "tiles per wave");
+  constexpr int QF = qf_chunk_bytes(32 * RT);
+  dma_copy(src, dst, QF, mw, lane);
+  if (mma) {
+    const int l32 = lane & 31, lh = lane >> 5;
+    const unsigned qa = qs + (unsigned)((my_rt * 2 * 64 + lane) * 16);
+    const unsigned ga = gs + (unsigned)(((32 * my_mt0 + l32) * GS + 8 * lh) * 2);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 bh = lds_frag_raw(qa + kk * RT * 2048);
+      bf16x8 bl = lds_frag_raw(qa + kk * RT * 2048 + 1024);
+      bf16x8 a0 = lds_frag_raw(ga + kk * 32);
+      if (TPW == 2) {
+        bf16x8 a1 = lds_frag_raw(ga + kk * 32 + 32 * GS * 2);
+        lds_wait(bh, bl, a0, a1);
+        acc[TPW - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bh, acc[TPW - 1], 0, 0, 0);
+        acc[TPW - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bl, acc[TPW - 1], 0, 0, 0);
+      } else {
+        lds_wait(bh, bl, a0);
+      }
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bh, acc[0], 0, 0, 0);
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bl, acc[0], 0, 0, 0);
+    }
+  }
+}
+
+// pass-2 round of a matrix-core wave: start the copy of the next Q^T image, build one 32 x 32 tile of D Q
+// (th: LDS byte address of the image to read; the C tile is written with ordinary stores at the end of
+// the round, where the copy has to have landed anyway)
+template <int RT>
+__device__ __forceinline__ void p2_round(unsigned th, lds_u8* dst, lds_f32* cs, const char* src, bool copy, bool mma,
+                                         const bf16x8 (&dh)[2 * RT], const bf16x8 (&dl)[2 * RT],
+                                         const int (&toff)[2 * RT], int coff, int mw, int lane) {
+  constexpr int R = 32 * RT;
+  if (copy) dma_copy(src, dst, timg_chunk_bytes(R), mw, lane);
+  if (mma) {
+    const unsigned tl = th + BK * R * 2;
+    f32x16 c;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 2 * RT; ks += 2) {
+      bf16x8 bh0 = lds_frag_raw(th + toff[ks]);
+      bf16x8 bl0 = lds_frag_raw(tl + toff[ks]);
+      bf16x8 bh1 = lds_frag_raw(th + toff[ks + 1]);
+      bf16x8 bl1 = lds_frag_raw(tl + toff[ks + 1]);
+      lds_wait(bh0, bl0, bh1, bl1);
+      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bh0, c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks], bh0, c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bl0, c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks + 1], bh1, c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks + 1], bh1, c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks + 1], bl1, c, 0, 0, 0);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int p = 0; p < 4; ++p) cs[coff + (8 * q + p) * CS] = c[4 * q + p];
+  }
+}
+
 template <int RT, bool W16>
 __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict__ items,
                                                      const LrBlockDev* __restrict__ lrb, Bases bs, StepScalars sc) {
@@ -82,7 +182,8 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   constexpr int TB = timg_chunk_bytes(R);
   constexpr int G_TILE = BM * GS * 2;
   constexpr int C_TILE = BM * CS * 4;
-  constexpr int P1_BYTES = 2 * QF + 2 * G_TILE;
+  constexpr int NB1 = 3;                                  // pass-1 buffers: a chunk is consumed two rounds after its copy starts
+  constexpr int P1_BYTES = NB1 * QF + NB1 * G_TILE;
   constexpr int P_BYTES = BM * PS * 4;
   constexpr int D_BYTES = 2 * BM * DS * 2;
   constexpr int P2_BYTES = 2 * TB + 2 * C_TILE;
@@ -118,20 +219,14 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   const __amdgpu_buffer_rsrc_t rW = make_rsrc(W + (int64_t)row0 * n * WE, rows_valid * (unsigned)n * WE);
   const int c8 = (t512 & 7) * 8;
   const unsigned eoff[2] = {(unsigned)((t512 >> 3) * n + c8), (unsigned)((64 + (t512 >> 3)) * n + c8)};
-  const int NR = (nc + 2) & ~1;                      // rounds per pass: nc + 1, rounded up to even
-
-  // asynchronous global -> LDS copy of `bytes` (a multiple of 8 KB) by the eight matrix-core waves
-  auto dma = [&](const char* src, unsigned char* dst, int bytes) {
-    for (int k = mw; k < bytes / 1024; k += 8)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + k * 1024 + lane * 16),
-                                       (__attribute__((address_space(3))) void*)(dst + k * 1024), 16, 0, 0);
-  };
+  const int NR = (nc + 3) & ~1;                      // rounds per pass: nc + 2, rounded up to even
 
   // ------------------------------------------------------------------ pass 1: P = G Q^T
   // Streaming waves put chunk c of G into LDS (and sum g^2 per row) while the matrix-core waves
   // multiply chunk c-1; the Q fragments of chunk c arrive by direct-to-LDS copy.  One barrier per chunk.
-  unsigned char* Qs = smem;                           // [2][QF]
-  unsigned char* Gs = smem + 2 * QF;                  // [2][BM][GS] bf16
+  lds_u8* const lds = (lds_u8*)smem;
+  lds_u8* const Qs = lds;                             // [NB1][QF]
+  unsigned char* Gs = smem + NB1 * QF;                // [NB1][BM][GS] bf16
   constexpr int TPW = (4 * RT >= 8) ? (4 * RT / 8) : 1;          // output tiles per matrix-core wave
   const bool p1_active = mrole && (mw < 4 * RT);
   const int my_rt = mw % RT;                                      // r-tile
@@ -147,8 +242,8 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
 #pragma unroll
     for (int i = 0; i < 2; ++i) dst[i] = buf_load16(rG, ok ? (eoff[i] + (unsigned)(c * BK)) * 2u : OOB);
   };
-  auto stage_g = [&](int c, uint4 (&src)[2]) {
-    uint16_t* gs = reinterpret_cast<uint16_t*>(Gs + (c & 1) * G_TILE);
+  auto stage_g = [&](int buf, uint4 (&src)[2]) {
+    uint16_t* gs = reinterpret_cast<uint16_t*>(Gs + buf * G_TILE);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int row = (t512 >> 3) + 64 * i;
@@ -158,28 +253,24 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
       if (i == 0) ss0 += s; else ss1 += s;
     }
   };
-  // Both roles run NR rounds and meet at one barrier per round (the branch is wave-uniform).  The
-  // streaming loop has no conditions, so loads issued two rounds ahead stay in flight across barriers.
+  // Both roles run NR rounds and meet at one barrier per round (the branch is wave-uniform).  Round cc:
+  // the streaming waves stage chunk cc of G and fetch chunk cc+2; the matrix-core waves start the copy of
+  // fragments cc and multiply chunk cc-2, whose G tile and fragments were completed one round ago.  Three
+  // buffers of each, so nothing is waited for in the round it was started in.  The streaming loop has no
+  // conditions, so the compiler can count its outstanding loads and keeps them in flight across barriers.
   if (mrole) {
+    int b_cur = 0, b_mma = 1;                         // cc % NB1, (cc - 2) % NB1
     for (int cc = 0; cc < NR; ++cc) {
-      if (cc < nc) dma(Qf + (int64_t)cc * QF, Qs + (cc & 1) * QF, QF);
-      if (cc >= 1 && cc <= nc && p1_active) {
-        const unsigned char* qs = Qs + ((cc - 1) & 1) * QF;
-        const unsigned char* gs = Gs + ((cc - 1) & 1) * G_TILE;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-          const bf16x8 bh = lds_frag(qs + (((kk * RT + my_rt) * 2 + 0) * 64 + lane) * 16);
-          const bf16x8 bl = lds_frag(qs + (((kk * RT + my_rt) * 2 + 1) * 64 + lane) * 16);
-#pragma unroll
-          for (int t = 0; t < TPW; ++t) {
-            const bf16x8 a = lds_frag(gs + ((32 * (my_mt0 + t) + l32) * GS + kk * 16 + 8 * lh) * 2);
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bh, acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bl, acc[t], 0, 0, 0);
-          }
-        }
-      }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // this wave's share of the Q fragments has landed
-      __syncthreads();
+      // always RT copy instructions per wave, so the wait below leaves exactly the newest copy in flight;
+      // past the end the last chunk is copied again into a buffer nobody reads
+      p1_round<RT, TPW>(lds_addr(Qs) + b_mma * QF, lds_addr(Qs) + NB1 * QF + b_mma * G_TILE, Qs + b_cur * QF,
+                        Qf + (int64_t)(cc < nc ? cc : nc - 1) * QF, cc >= 2 && cc < nc + 2 && p1_active, acc, my_rt, my_mt0,
+                        mw, lane);
+      b_cur = b_cur + 1 == NB1 ? 0 : b_cur + 1;
+      b_mma = b_mma + 1 == NB1 ? 0 : b_mma + 1;
+      if (cc + 1 < NR) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(RT) : "memory");   // this wave's share of fragments cc-1
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                        // last round: nothing may still be landing
+      wg_barrier();
     }
   } else {
     uint4 ga[2], gb[2];
@@ -187,15 +278,19 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
     __builtin_amdgcn_sched_barrier(0);   // keep issue order = use order, or the loop's first wait drains everything
     fetch_g(1, gb);
     __builtin_amdgcn_sched_barrier(0);
-    for (int cc = 0; cc < NR; cc += 2) {       // chunks at or beyond nc read zeros (harmless: their LDS slot is idle)
-      stage_g(cc, ga);
+    int b0 = 0, b1 = 1;                  // cc % NB1, (cc + 1) % NB1
+    for (int cc = 0; cc < NR; cc += 2) {       // chunks at or beyond nc read zeros into a tile nobody multiplies
+      stage_g(b0, ga);
       fetch_g(cc + 2, ga);
-      __syncthreads();
-      stage_g(cc + 1, gb);
+      wg_barrier();
+      stage_g(b1, gb);
       fetch_g(cc + 3, gb);
-      __syncthreads();
+      wg_barrier();
+      b0 = b0 + 2 >= NB1 ? b0 + 2 - NB1 : b0 + 2;
+      b1 = b1 + 2 >= NB1 ? b1 + 2 - NB1 : b1 + 2;
     }
   }
+  __syncthreads();
 
   // ------------------------------------------------------------------ second moment of the stripe, P to LDS
   float* Ps = reinterpret_cast<float*>(smem);                     // [BM][PS] fp32
@@ -268,7 +363,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   // ------------------------------------------------------------------ pass 2: C = D Q, update W
   // Matrix-core waves build tile j of D Q (Q^T image j came by direct-to-LDS copy during tile j-1) while
   // the streaming waves run the element-wise tail of tile j-1 and prefetch G, W.  One barrier per tile.
-  unsigned char* Ts = smem;                           // [2][TB]
+  lds_u8* const Ts = lds;                             // [2][TB]
   unsigned char* Cs = smem + 2 * TB;                  // [2][BM][CS] fp32
   const UpdCoef cf = make_coef(sc.lr, B.lr_scale, B.wd, sc.clip);
   const float ob2 = 1.f - sc.beta2;
@@ -355,59 +450,41 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
     bf16x8 dh[2 * RT], dl[2 * RT];
 #pragma unroll
     for (int ks = 0; ks < 2 * RT; ++ks) {
-      dh[ks] = lds_frag(reinterpret_cast<const unsigned char*>(Dh + (32 * wr + l32) * DS + 16 * ks + 8 * lh));
-      dl[ks] = lds_frag(reinterpret_cast<const unsigned char*>(Dl + (32 * wr + l32) * DS + 16 * ks + 8 * lh));
+      dh[ks] = lds_frag(lds + ((32 * wr + l32) * DS + 16 * ks + 8 * lh) * 2);
+      dl[ks] = lds_frag(lds + ((BM + 32 * wr + l32) * DS + 16 * ks + 8 * lh) * 2);
     }
     __syncthreads();                                               // D is in registers, its LDS is free
-    dma(Timg, Ts, TB);
     const int jl = 32 * wc + l32;                                  // column of this lane inside the tile
     int toff[2 * RT];
 #pragma unroll
     for (int ks = 0; ks < 2 * RT; ++ks) toff[ks] = jl * R * 2 + timg_piece(R, jl, 2 * ks + lh) * 16;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    const int coff = (32 * wr + 4 * lh) * CS + 32 * wc + l32;      // this lane's first result inside a C tile
+    // round j: start the copy of image j, build tile j-1 from the image that landed in the last round
     for (int j = 0; j < NR; ++j) {
-      if (j + 1 < nc) dma(Timg + (int64_t)(j + 1) * TB, Ts + ((j + 1) & 1) * TB, TB);
-      if (j < nc) {
-        const unsigned char* th = Ts + (j & 1) * TB;
-        const unsigned char* tl = th + BK * R * 2;
-        f32x16 c;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) c[i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 2 * RT; ++ks) {
-          const bf16x8 bh = lds_frag(th + toff[ks]);
-          const bf16x8 bl = lds_frag(tl + toff[ks]);
-          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bh, c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks], bh, c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bl, c, 0, 0, 0);
-        }
-        float* cs = reinterpret_cast<float*>(Cs + (j & 1) * C_TILE);
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int p = 0; p < 4; ++p) cs[(32 * wr + 8 * q + 4 * lh + p) * CS + 32 * wc + l32] = c[4 * q + p];
-      }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // the next image has landed
-      __syncthreads();
+      p2_round<RT>(lds_addr(Ts) + ((j - 1) & 1) * TB, Ts + (j & 1) * TB, (lds_f32*)(lds + 2 * TB + ((j - 1) & 1) * C_TILE),
+                   Timg + (int64_t)j * TB, j < nc, j >= 1 && j <= nc, dh, dl, toff, coff, mw, lane);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // image j has landed
+      wg_barrier();
     }
   } else {
     uint4 gx[2], wx[2][WV], gy[2], wy[2][WV];                      // G / W vectors of two tiles in flight
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      gx[i] = gy[i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int k = 0; k < WV; ++k) wx[i][k] = wy[i][k] = make_uint4(0, 0, 0, 0);
+    }
     __syncthreads();
-    fetch_gw(0, gx, wx);
-    __builtin_amdgcn_sched_barrier(0);
-    fetch_gw(1, gy, wy);
-    __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
-    // round j: tail of tile j-1, whose vectors sit in (gx, wx) when j-1 is even, else in (gy, wy); no
-    // conditions in the loop, so the loads of the next two tiles stay in flight across the barriers
+    // round j: tail of tile j-2 (built in the last round), then fetch G, W of tile j into the registers
+    // just freed; even tiles live in (gx, wx), odd ones in (gy, wy).  No conditions in the loop, so the
+    // loads of the next two tiles stay in flight across the barriers.
     for (int j = 0; j < NR; j += 2) {
+      tail(j - 2, gx, wx);
+      fetch_gw(j, gx, wx);
+      wg_barrier();
       tail(j - 1, gy, wy);
       fetch_gw(j + 1, gy, wy);
-      __syncthreads();
-      tail(j, gx, wx);
-      fetch_gw(j + 2, gx, wx);
-      __syncthreads();
+      wg_barrier();
     }
   }
 }
