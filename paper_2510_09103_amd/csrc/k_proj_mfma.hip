@@ -219,7 +219,12 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   const __amdgpu_buffer_rsrc_t rW = make_rsrc(W + (int64_t)row0 * n * WE, rows_valid * (unsigned)n * WE);
   const int c8 = (t512 & 7) * 8;
   const unsigned eoff[2] = {(unsigned)((t512 >> 3) * n + c8), (unsigned)((64 + (t512 >> 3)) * n + c8)};
-  const int NR = (nc + 3) & ~1;                      // rounds per pass: nc + 2, rounded up to even
+  // rounds per pass: nc + 2, rounded up to the prefetch depth of the streaming waves (their loop is
+  // unrolled by the depth so that every register set has a fixed name)
+  constexpr int D1 = 4;                              // pass 1: chunks of G in flight per thread
+  constexpr int D2 = W16 ? 3 : 2;                    // pass 2: tiles of G and W in flight per thread
+  const int NR1 = (nc + 1 + D1) / D1 * D1;
+  const int NR2 = (nc + 1 + D2) / D2 * D2;
 
   // ------------------------------------------------------------------ pass 1: P = G Q^T
   // Streaming waves put chunk c of G into LDS (and sum g^2 per row) while the matrix-core waves
@@ -253,14 +258,14 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
       if (i == 0) ss0 += s; else ss1 += s;
     }
   };
-  // Both roles run NR rounds and meet at one barrier per round (the branch is wave-uniform).  Round cc:
+  // Both roles run NR1 rounds and meet at one barrier per round (the branch is wave-uniform).  Round cc:
   // the streaming waves stage chunk cc of G and fetch chunk cc+2; the matrix-core waves start the copy of
   // fragments cc and multiply chunk cc-2, whose G tile and fragments were completed one round ago.  Three
   // buffers of each, so nothing is waited for in the round it was started in.  The streaming loop has no
   // conditions, so the compiler can count its outstanding loads and keeps them in flight across barriers.
   if (mrole) {
     int b_cur = 0, b_mma = 1;                         // cc % NB1, (cc - 2) % NB1
-    for (int cc = 0; cc < NR; ++cc) {
+    for (int cc = 0; cc < NR1; ++cc) {
       // always RT copy instructions per wave, so the wait below leaves exactly the newest copy in flight;
       // past the end the last chunk is copied again into a buffer nobody reads
       p1_round<RT, TPW>(lds_addr(Qs) + b_mma * QF, lds_addr(Qs) + NB1 * QF + b_mma * G_TILE, Qs + b_cur * QF,
@@ -268,26 +273,26 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
                         mw, lane);
       b_cur = b_cur + 1 == NB1 ? 0 : b_cur + 1;
       b_mma = b_mma + 1 == NB1 ? 0 : b_mma + 1;
-      if (cc + 1 < NR) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(RT) : "memory");   // this wave's share of fragments cc-1
+      if (cc + 1 < NR1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(RT) : "memory");  // this wave's share of fragments cc-1
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                        // last round: nothing may still be landing
       wg_barrier();
     }
   } else {
-    uint4 ga[2], gb[2];
-    fetch_g(0, ga);
-    __builtin_amdgcn_sched_barrier(0);   // keep issue order = use order, or the loop's first wait drains everything
-    fetch_g(1, gb);
-    __builtin_amdgcn_sched_barrier(0);
-    int b0 = 0, b1 = 1;                  // cc % NB1, (cc + 1) % NB1
-    for (int cc = 0; cc < NR; cc += 2) {       // chunks at or beyond nc read zeros into a tile nobody multiplies
-      stage_g(b0, ga);
-      fetch_g(cc + 2, ga);
-      wg_barrier();
-      stage_g(b1, gb);
-      fetch_g(cc + 3, gb);
-      wg_barrier();
-      b0 = b0 + 2 >= NB1 ? b0 + 2 - NB1 : b0 + 2;
-      b1 = b1 + 2 >= NB1 ? b1 + 2 - NB1 : b1 + 2;
+    uint4 gq[D1][2];
+#pragma unroll
+    for (int u = 0; u < D1; ++u) {
+      fetch_g(u, gq[u]);
+      __builtin_amdgcn_sched_barrier(0);   // keep issue order = use order, or the loop's first wait drains everything
+    }
+    int buf = 0;                               // cc % NB1
+    for (int cb = 0; cb < NR1; cb += D1) {     // chunks at or beyond nc read zeros into a tile nobody multiplies
+#pragma unroll
+      for (int u = 0; u < D1; ++u) {
+        stage_g(buf, gq[u]);
+        fetch_g(cb + u + D1, gq[u]);
+        wg_barrier();
+        buf = buf + 1 == NB1 ? 0 : buf + 1;
+      }
     }
   }
   __syncthreads();
@@ -460,31 +465,39 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
     for (int ks = 0; ks < 2 * RT; ++ks) toff[ks] = jl * R * 2 + timg_piece(R, jl, 2 * ks + lh) * 16;
     const int coff = (32 * wr + 4 * lh) * CS + 32 * wc + l32;      // this lane's first result inside a C tile
     // round j: start the copy of image j, build tile j-1 from the image that landed in the last round
-    for (int j = 0; j < NR; ++j) {
+    for (int j = 0; j < NR2; ++j) {
       p2_round<RT>(lds_addr(Ts) + ((j - 1) & 1) * TB, Ts + (j & 1) * TB, (lds_f32*)(lds + 2 * TB + ((j - 1) & 1) * C_TILE),
                    Timg + (int64_t)j * TB, j < nc, j >= 1 && j <= nc, dh, dl, toff, coff, mw, lane);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // image j has landed
       wg_barrier();
     }
   } else {
-    uint4 gx[2], wx[2][WV], gy[2], wy[2][WV];                      // G / W vectors of two tiles in flight
+    uint4 gq[D2][2], wq[D2][2][WV];                                // G / W vectors of D2 tiles in flight
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      gx[i] = gy[i] = make_uint4(0, 0, 0, 0);
+    for (int u = 0; u < D2; ++u)
 #pragma unroll
-      for (int k = 0; k < WV; ++k) wx[i][k] = wy[i][k] = make_uint4(0, 0, 0, 0);
-    }
+      for (int i = 0; i < 2; ++i) {
+        gq[u][i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int k = 0; k < WV; ++k) wq[u][i][k] = make_uint4(0, 0, 0, 0);
+      }
     __syncthreads();
-    // round j: tail of tile j-2 (built in the last round), then fetch G, W of tile j into the registers
-    // just freed; even tiles live in (gx, wx), odd ones in (gy, wy).  No conditions in the loop, so the
-    // loads of the next two tiles stay in flight across the barriers.
-    for (int j = 0; j < NR; j += 2) {
-      tail(j - 2, gx, wx);
-      fetch_gw(j, gx, wx);
-      wg_barrier();
-      tail(j - 1, gy, wy);
-      fetch_gw(j + 1, gy, wy);
-      wg_barrier();
+#pragma unroll
+    for (int u = 0; u + 2 < D2; ++u) {                             // tiles the loop does not fetch itself
+      fetch_gw(u, gq[u], wq[u]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // round j: tail of tile j-2 (built in the last round) from register set (j-2) % D2, then fetch tile
+    // j-2+D2 into the set just freed.  No conditions in the loop, so the loads of the next tiles stay in
+    // flight across the barriers.
+    for (int jb = 0; jb < NR2; jb += D2) {
+#pragma unroll
+      for (int u = 0; u < D2; ++u) {
+        const int su = (u + 2 * D2 - 2) % D2;
+        tail(jb + u - 2, gq[su], wq[su]);
+        fetch_gw(jb + u - 2 + D2, gq[su], wq[su]);
+        wg_barrier();
+      }
     }
   }
 }
