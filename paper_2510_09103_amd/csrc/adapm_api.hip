@@ -54,11 +54,12 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wP = -1, wS = -1, wGrr = -1, wGpr = -1, wGll = -1, wGlp = -1;
   int64_t wG64 = -1, wCinv = -1, wC = -1;
   int64_t wQf = -1, wTimg = -1;                             // ws: bf16 (hi, lo) images of Q and Q^T
+  int64_t wGt = -1, wIr = -1, wIl = -1;                     // ws: G^T (bf16) and the fragment images of R, L^T during Alg. 2
   int64_t nv = 0;
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -70,7 +71,7 @@ struct GemmList {
 
 struct Op {
   OpKind kind;
-  int index;          // GEMM*: gemm list; UPDATE / VSTAT / VFINAL / PROJ: which item list
+  int index;          // GEMM*: gemm list; UPDATE / VSTAT / VFINAL / PROJ / QFIMG / STRIPE: which item list
   float cG, cC;       // UPDATE of low-rank blocks, PROJ
   const char* label;  // profiling name
 };
@@ -112,6 +113,10 @@ struct adapm_ctx {
   DevList<LrBlockDev> lrb;
   DevList<ProjItem> proj[6];    // (rank 32 / 64 / 128) x (fp32 / bf16 parameters)
   DevList<QsItem> qs;
+  DevList<TrItem> tr;                   // Alg. 2, MFMA path: transposed copies of G
+  DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
+  std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T
+  std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
   std::vector<GemmList> gemms;
   std::vector<Op> seq_refresh, seq_project;
 
@@ -154,6 +159,9 @@ int path_of(const adapm_block_t& b, const adapm_hparams_t& hp) {
                    b.cols <= (1 << 21);   // 128 rows of a stripe stay inside one 32-bit buffer range
   return (want && can) ? PATH_FAST : PATH_F64;
 }
+// Alg. 2 on the MFMA path: the two products that stream G (G R^T and L^T G) run as stripe products when
+// the transposed copy of G also has 16-byte rows and fits the kernel's 32-bit buffer ranges
+bool stripe_ok(const adapm_block_t& b) { return b.rows % 8 == 0 && b.rows <= (1 << 21); }
 // v of a block on the MFMA path can be finished inside the 128-row stripe of the fused kernel
 bool v_fusable(const adapm_block_t& b) {
   return b.v_mode == ADAPM_V_ROWGROUP && b.v_group_rows <= 128 && 128 % b.v_group_rows == 0;
@@ -257,6 +265,11 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   };
   std::vector<int> listA(n_eff), listB(n_eff);
   for (int e = 0; e < n_eff; ++e) { listA[e] = new_list(fast); listB[e] = new_list(fast); }
+  // MFMA path: per GD iteration the images of (R, L^T) and, per rank class, the stripe problems
+  constexpr int NXCD = 8;
+  struct StripeWork { int prob; int64_t M, K; };
+  std::vector<std::vector<StripeWork>> swork(fast ? 3 * n_eff : 0);
+  if (fast) { c->img.resize(n_eff); c->sit.resize(3 * n_eff); }
   const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list(fast) : -1;
   const int l_epi = new_list(fast);
   const int l_gram = hp.refresh_period_T > 1 ? new_list(false) : -1;
@@ -284,8 +297,27 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       // thin products of Alg. 2 written without forming L R - m_t:
       //   (L R - m_t) R^T = L (R R^T) - (1-b1) G R^T - b1 L' (R' R^T)
       //   L^T (L R - m_t) = (L^T L) R - (1-b1) L^T G - b1 (L^T L') R'
-      p = problem(m, r); p.A1 = G; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = P; add_problem(A, p);
-      p = problem(r, n); p.A1 = T(Lc); p.B1 = G; p.K1 = m; p.a1 = 1; p.Out = S; add_problem(A, p);
+      if (fast && stripe_ok(b)) {
+        // P = G R^T and S = L^T G = (G^T L)^T as stripe products on images of the current factors
+        if (e == 0)
+          for (int ti = 0; ti < (m + 63) / 64; ++ti)
+            for (int tj = 0; tj < (n + 63) / 64; ++tj) c->tr.h.push_back(TrItem{(int32_t)i, m, n, ti, tj, 0, L.wGt});
+        Mat LcT = T(Lc);
+        for (int ch = 0; ch < (n + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{Rc, r, n, ch, 0, L.wIr});
+        for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, 0, L.wIl});
+        const int cls = r == 32 ? 0 : (r == 64 ? 1 : 2);
+        StripeProb sp;
+        memset(&sp, 0, sizeof sp);
+        sp.a = G.ref; sp.M = m; sp.K = n; sp.r = r; sp.transpose_out = 0; sp.off_img = L.wIr; sp.off_out = L.wP;
+        c->sprob.h.push_back(sp);
+        swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
+        sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = L.wIl; sp.off_out = L.wS;
+        c->sprob.h.push_back(sp);
+        swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, n, m});
+      } else {
+        p = problem(m, r); p.A1 = G; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = P; add_problem(A, p);
+        p = problem(r, n); p.A1 = T(Lc); p.B1 = G; p.K1 = m; p.a1 = 1; p.Out = S; add_problem(A, p);
+      }
       p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Grr; add_problem(A, p);
       p = problem(r, r); p.A1 = Rp; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Gpr; add_problem(A, p);
       p = problem(r, r); p.A1 = T(Lc); p.B1 = Lc; p.K1 = m; p.a1 = 1; p.Out = Gll; add_problem(A, p);
@@ -332,8 +364,37 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       p = problem(r, n); p.X = Rc; p.g = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
     }
   }
+  // stripes of one problem go to one XCD (workgroup i runs on XCD i mod 8) so that they share the image
+  // through its L2; longest contraction first, problems dealt to the least loaded XCD
+  for (size_t w = 0; w < swork.size(); ++w) {
+    std::vector<StripeWork>& v = swork[w];
+    std::stable_sort(v.begin(), v.end(), [](const StripeWork& a, const StripeWork& b) {
+      if (a.K != b.K) return a.K > b.K;
+      return a.M > b.M;
+    });
+    std::vector<StripeItem> per[NXCD];
+    double load[NXCD] = {0};
+    for (const StripeWork& sw : v) {
+      int x = 0;
+      for (int k = 1; k < NXCD; ++k) if (load[k] < load[x]) x = k;
+      for (int64_t r0 = 0; r0 < sw.M; r0 += 128) per[x].push_back(StripeItem{sw.prob, (int32_t)r0});
+      load[x] += (double)sw.M * sw.K;
+    }
+    size_t longest = 0;
+    for (auto& q : per) longest = std::max(longest, q.size());
+    for (size_t q = 0; q < longest; ++q)
+      for (int x = 0; x < NXCD; ++x) c->sit[w].h.push_back(q < per[x].size() ? per[x][q] : StripeItem{-1, 0});
+  }
   std::vector<Op>& seq = c->seq_refresh;
+  if (fast && !c->tr.h.empty()) seq.push_back(Op{OP_TRANSPOSE, 0, 0, 0, "transpose_G"});
   for (int e = 0; e < n_eff; ++e) {
+    if (fast && !c->img[e].h.empty()) {
+      seq.push_back(Op{OP_QFIMG, e, 0, 0, "alg2_factor_images"});
+      static const char* names[3] = {"alg2_stripe_products_r32", "alg2_stripe_products_r64", "alg2_stripe_products_r128"};
+      for (int cls = 0; cls < 3; ++cls)
+        if (!c->sit[3 * e + cls].h.empty()) seq.push_back(Op{OP_STRIPE, 3 * e + cls, 0, 0, names[cls]});
+    }
+    if (c->gemms[listA[e]].tiles.empty()) { seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"}); continue; }
     seq.push_back(Op{gk, listA[e], 0, 0, fast ? "alg2_products_mfma" : "alg2_products_f64"});
     seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"});
   }
@@ -474,6 +535,11 @@ void build_plan(adapm_ctx* c) {
       L.wGll = walloc(es * r * r); L.wGlp = walloc(es * r * r);
       L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
       L.wC = walloc(4 * m * n);
+      if (L.path == PATH_FAST && stripe_ok(b)) {
+        L.wGt = walloc(2 * m * n);
+        L.wIr = walloc(proj_qf_bytes((int)r, (int)n));
+        L.wIl = walloc(proj_qf_bytes((int)r, (int)m));
+      }
       if (L.path == PATH_FAST && hp.refresh_period_T > 1) {
         L.wQf = walloc(proj_qf_bytes((int)r, (int)n));
         L.wTimg = walloc(proj_timg_bytes((int)r, (int)n));
@@ -561,7 +627,9 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   HIP_TRY(hipGetDevice(&dev));
   const size_t nb = c->table.size();
   size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
-                 align_up(2 * nb * sizeof(void*));
+                 bytes_of(c->tr.h) + bytes_of(c->sprob.h) + align_up(2 * nb * sizeof(void*));
+  for (auto& l : c->img) total += bytes_of(l.h);
+  for (auto& l : c->sit) total += bytes_of(l.h);
   for (int i = 0; i < 3; ++i) total += bytes_of(c->ew[i].h);
   for (int i = 0; i < 6; ++i) total += bytes_of(c->proj[i].h);
   for (int i = 0; i < 2; ++i) total += bytes_of(c->vs[i].h) + bytes_of(c->vf[i].h) + bytes_of(c->chol[i].h);
@@ -576,7 +644,9 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     return dst;
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
-  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs);
+  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->tr); PUT_LIST(c->sprob);
+  for (auto& l : c->img) PUT_LIST(l);
+  for (auto& l : c->sit) PUT_LIST(l);
   for (int i = 0; i < 3; ++i) PUT_LIST(c->ew[i]);
   for (int i = 0; i < 6; ++i) PUT_LIST(c->proj[i]);
   for (int i = 0; i < 2; ++i) { PUT_LIST(c->vs[i]); PUT_LIST(c->vf[i]); PUT_LIST(c->chol[i]); }
@@ -751,6 +821,15 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         if (op.index == 1 && c->split_ws == workspace_dev) { skipped = true; break; }
         launch_qimage(c->qs.d, (int64_t)c->qs.h.size(), c->lrb.d, bs, s);
         c->split_ws = workspace_dev;
+        break;
+      case OP_TRANSPOSE:
+        launch_transpose_bf16(c->tr.d, (int64_t)c->tr.h.size(), bs, s);
+        break;
+      case OP_QFIMG:
+        launch_qf_image(c->img[op.index].d, (int64_t)c->img[op.index].h.size(), bs, s);
+        break;
+      case OP_STRIPE:
+        launch_stripe(1 << (op.index % 3), c->sit[op.index].d, (int64_t)c->sit[op.index].h.size(), c->sprob.d, bs, s);
         break;
       case OP_PROJ: {
         StepScalars x = sc;

@@ -133,6 +133,30 @@ struct QsItem {            // one workgroup: one 64-column chunk of Q
   int32_t c;
 };
 
+// Stripe product of Alg. 2 (MFMA path): Out = A Q^T with A a bf16 matrix streamed once, Q (r x K, fp32)
+// given as a bf16 (hi, lo) fragment image.  Used for G R^T (A = G) and, on the transposed copy of G,
+// for (L^T G)^T = G^T L (A = G^T, Q = L^T), whose result is written back transposed.
+struct StripeProb {
+  Ref a;                   // A: M x K bf16, row-major, row stride K
+  int32_t M, K, r;
+  int32_t transpose_out;   // 0: Out is M x r (row stride r); 1: Out is r x M (row stride M)
+  int64_t off_img;         // workspace: fragment image of Q
+  int64_t off_out;         // workspace: fp32 result
+};
+struct StripeItem {        // one workgroup: 128 rows of A; prob < 0 = padding
+  int32_t prob;
+  int32_t row0;
+};
+struct ImgItem {           // one workgroup: one 64-column chunk of the fragment image of Q(a, k) = q[a * s0 + k * s1]
+  Mat q;                   // fp32
+  int32_t r, K, c, pad;
+  int64_t off_img;
+};
+struct TrItem {            // one workgroup: one 64 x 64 tile of the bf16 transpose G (m x n) -> G^T (n x m)
+  int32_t block, m, n, ti, tj, pad;
+  int64_t off_out;         // workspace
+};
+
 struct SketchItem {      // seeded start R_0 of one low-rank block
   int64_t off_R;         // state byte offset
   int64_t count;         // rank * cols
@@ -166,6 +190,9 @@ void launch_gemm_mfma(const GemmProblem* probs, const GemmTile* tiles, int64_t n
 void launch_proj(int rt, bool w16, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
                  StepScalars sc, hipStream_t s);
 void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s);
+void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s);
+void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
+void launch_transpose_bf16(const TrItem* items, int64_t nitems, Bases b, hipStream_t s);
 size_t proj_qf_bytes(int r, int n);     // sizes of the two images of Q kept for the fused step
 size_t proj_timg_bytes(int r, int n);
 

@@ -172,61 +172,35 @@ __device__ __forceinline__ void p2_round(unsigned th, lds_u8* dst, lds_f32* cs, 
   }
 }
 
-template <int RT, bool W16>
-__global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict__ items,
-                                                     const LrBlockDev* __restrict__ lrb, Bases bs, StepScalars sc) {
-  constexpr int R = 32 * RT;
-  constexpr int DS = R + 8;                               // LDS row stride of D (elements)
-  constexpr int PS = R + 4;                               // LDS row stride of P (floats)
-  constexpr int QF = qf_chunk_bytes(R);
-  constexpr int TB = timg_chunk_bytes(R);
-  constexpr int G_TILE = BM * GS * 2;
-  constexpr int C_TILE = BM * CS * 4;
-  constexpr int NB1 = 3;                                  // pass-1 buffers: a chunk is consumed two rounds after its copy starts
-  constexpr int P1_BYTES = NB1 * QF + NB1 * G_TILE;
-  constexpr int P_BYTES = BM * PS * 4;
-  constexpr int D_BYTES = 2 * BM * DS * 2;
-  constexpr int P2_BYTES = 2 * TB + 2 * C_TILE;
-  constexpr int m1 = P1_BYTES > P_BYTES ? P1_BYTES : P_BYTES;
-  constexpr int m2 = D_BYTES > P2_BYTES ? D_BYTES : P2_BYTES;
-  constexpr int SMEM = m1 > m2 ? m1 : m2;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
-  __shared__ float vrow[BM];
-  __shared__ float rsum[BM];
+// Geometry of pass 1 (shared by the held-R kernel and the stripe product of Alg. 2)
+template <int RT>
+struct Pass1 {
+  static constexpr int R = 32 * RT;
+  static constexpr int PS = R + 4;                        // LDS row stride of P (floats)
+  static constexpr int QF = qf_chunk_bytes(R);
+  static constexpr int G_TILE = BM * GS * 2;
+  static constexpr int NB1 = 3;                           // buffers: a chunk is consumed two rounds after its copy starts
+  static constexpr int BYTES = NB1 * QF + NB1 * G_TILE;   // LDS during the pass
+  static constexpr int P_BYTES = BM * PS * 4;             // LDS holding P afterwards
+  static constexpr int D1 = 4;                            // chunks of A in flight per streaming thread
+};
 
-  const ProjItem item = items[blockIdx.x];
-  if (item.lr < 0) return;
-  const LrBlockDev B = lrb[item.lr];
+// P = A Q^T for the 128 rows of A behind the range-checked buffer rG (bf16, n columns, row stride n),
+// Q given as its fragment image Qf.  Leaves P in LDS at smem as [BM][R + 4] fp32 (the caller has to
+// __syncthreads() before reading it) and returns, in the streaming waves, this thread's sums of
+// squares of its two rows of A (rows t512/8 and 64 + t512/8, columns 8 (t512 % 8) .. of every chunk).
+template <int RT>
+__device__ __forceinline__ void stripe_pass1(unsigned char* smem, __amdgpu_buffer_rsrc_t rG, int n,
+                                             const char* __restrict__ Qf, float& ss0, float& ss1) {
+  constexpr int QF = Pass1<RT>::QF, G_TILE = Pass1<RT>::G_TILE, NB1 = Pass1<RT>::NB1, PS = Pass1<RT>::PS, D1 = Pass1<RT>::D1;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const bool mrole = wave < 8;                       // matrix-core waves / streaming waves
-  const int mw = wave & 7;                           // index within the role
-  const int t512 = tid & 511;                        // thread index within the role
-  const int l32 = lane & 31, lh = lane >> 5;
-  const int m = B.m, n = B.n, row0 = item.row0;
+  const bool mrole = wave < 8;
+  const int mw = wave & 7, t512 = tid & 511, l32 = lane & 31, lh = lane >> 5;
   const int nc = (n + BK - 1) / BK;
-  const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(bs.grads[B.block]);
-  char* __restrict__ W = reinterpret_cast<char*>(bs.params[B.block]);
-  float* __restrict__ Lst = reinterpret_cast<float*>(bs.state + B.off_L);
-  float* __restrict__ vst = reinterpret_cast<float*>(bs.state + B.off_v);
-  const char* __restrict__ Qf = bs.ws + B.off_Qf;
-  const char* __restrict__ Timg = bs.ws + B.off_Timg;
-  // the stripe's rows of G and W as range-checked buffers; this thread's two 8-element vectors per
-  // 64-column chunk sit in rows t512/8 and 64 + t512/8 at columns 8 (t512 % 8) ..
-  constexpr unsigned WE = W16 ? 2 : 4;
-  const unsigned rows_valid = (unsigned)(m - row0 < BM ? m - row0 : BM);
-  const __amdgpu_buffer_rsrc_t rG = make_rsrc(G + (int64_t)row0 * n, rows_valid * (unsigned)n * 2u);
-  const __amdgpu_buffer_rsrc_t rW = make_rsrc(W + (int64_t)row0 * n * WE, rows_valid * (unsigned)n * WE);
   const int c8 = (t512 & 7) * 8;
   const unsigned eoff[2] = {(unsigned)((t512 >> 3) * n + c8), (unsigned)((64 + (t512 >> 3)) * n + c8)};
-  // rounds per pass: nc + 2, rounded up to the prefetch depth of the streaming waves (their loop is
-  // unrolled by the depth so that every register set has a fixed name)
-  constexpr int D1 = 4;                              // pass 1: chunks of G in flight per thread
-  constexpr int D2 = W16 ? 3 : 2;                    // pass 2: tiles of G and W in flight per thread
-  const int NR1 = (nc + 1 + D1) / D1 * D1;
-  const int NR2 = (nc + 1 + D2) / D2 * D2;
-
-  // ------------------------------------------------------------------ pass 1: P = G Q^T
+  const int NR1 = (nc + 1 + D1) / D1 * D1;             // rounds: nc + 2, rounded up to the prefetch depth
   // Streaming waves put chunk c of G into LDS (and sum g^2 per row) while the matrix-core waves
   // multiply chunk c-1; the Q fragments of chunk c arrive by direct-to-LDS copy.  One barrier per chunk.
   lds_u8* const lds = (lds_u8*)smem;
@@ -241,7 +215,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   for (int t = 0; t < TPW; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
-  float ss0 = 0.f, ss1 = 0.f;                        // streaming thread: sums of g^2 of rows t512/8 and 64 + t512/8
+  ss0 = 0.f; ss1 = 0.f;
   auto fetch_g = [&](int c, uint4 (&dst)[2]) {
     const bool ok = c * BK + c8 < n;
 #pragma unroll
@@ -296,14 +270,8 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
     }
   }
   __syncthreads();
-
-  // ------------------------------------------------------------------ second moment of the stripe, P to LDS
-  float* Ps = reinterpret_cast<float*>(smem);                     // [BM][PS] fp32
-  if (!mrole) {                     // a row is covered by 8 consecutive lanes
-#pragma unroll
-    for (int o = 1; o < 8; o <<= 1) { ss0 += __shfl_xor(ss0, o, 64); ss1 += __shfl_xor(ss1, o, 64); }
-    if ((t512 & 7) == 0) { rsum[t512 >> 3] = ss0; rsum[64 + (t512 >> 3)] = ss1; }
-  } else if (p1_active) {
+  if (p1_active) {
+    float* Ps = reinterpret_cast<float*>(smem);
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
       const int col = 32 * my_rt + l32;
@@ -312,6 +280,69 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
 #pragma unroll
         for (int p = 0; p < 4; ++p) Ps[(32 * (my_mt0 + t) + 8 * q + 4 * lh + p) * PS + col] = acc[t][4 * q + p];
     }
+  }
+}
+
+template <int RT, bool W16>
+__global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict__ items,
+                                                     const LrBlockDev* __restrict__ lrb, Bases bs, StepScalars sc) {
+  constexpr int R = 32 * RT;
+  constexpr int DS = R + 8;                               // LDS row stride of D (elements)
+  constexpr int PS = R + 4;                               // LDS row stride of P (floats)
+  constexpr int TB = timg_chunk_bytes(R);
+  constexpr int C_TILE = BM * CS * 4;
+  constexpr int P1_BYTES = Pass1<RT>::BYTES;
+  constexpr int P_BYTES = Pass1<RT>::P_BYTES;
+  constexpr int D_BYTES = 2 * BM * DS * 2;
+  constexpr int P2_BYTES = 2 * TB + 2 * C_TILE;
+  constexpr int m1 = P1_BYTES > P_BYTES ? P1_BYTES : P_BYTES;
+  constexpr int m2 = D_BYTES > P2_BYTES ? D_BYTES : P2_BYTES;
+  constexpr int SMEM = m1 > m2 ? m1 : m2;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+  __shared__ float vrow[BM];
+  __shared__ float rsum[BM];
+
+  const ProjItem item = items[blockIdx.x];
+  if (item.lr < 0) return;
+  const LrBlockDev B = lrb[item.lr];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool mrole = wave < 8;                       // matrix-core waves / streaming waves
+  const int mw = wave & 7;                           // index within the role
+  const int t512 = tid & 511;                        // thread index within the role
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int m = B.m, n = B.n, row0 = item.row0;
+  const int nc = (n + BK - 1) / BK;
+  const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(bs.grads[B.block]);
+  char* __restrict__ W = reinterpret_cast<char*>(bs.params[B.block]);
+  float* __restrict__ Lst = reinterpret_cast<float*>(bs.state + B.off_L);
+  float* __restrict__ vst = reinterpret_cast<float*>(bs.state + B.off_v);
+  const char* __restrict__ Qf = bs.ws + B.off_Qf;
+  const char* __restrict__ Timg = bs.ws + B.off_Timg;
+  // the stripe's rows of G and W as range-checked buffers; this thread's two 8-element vectors per
+  // 64-column chunk sit in rows t512/8 and 64 + t512/8 at columns 8 (t512 % 8) ..
+  constexpr unsigned WE = W16 ? 2 : 4;
+  const unsigned rows_valid = (unsigned)(m - row0 < BM ? m - row0 : BM);
+  const __amdgpu_buffer_rsrc_t rG = make_rsrc(G + (int64_t)row0 * n, rows_valid * (unsigned)n * 2u);
+  const __amdgpu_buffer_rsrc_t rW = make_rsrc(W + (int64_t)row0 * n * WE, rows_valid * (unsigned)n * WE);
+  const int c8 = (t512 & 7) * 8;
+  const unsigned eoff[2] = {(unsigned)((t512 >> 3) * n + c8), (unsigned)((64 + (t512 >> 3)) * n + c8)};
+  // rounds of pass 2: nc + 2, rounded up to the prefetch depth of the streaming waves (their loop is
+  // unrolled by the depth so that every register set has a fixed name)
+  constexpr int D2 = W16 ? 3 : 2;                    // tiles of G and W in flight per thread
+  const int NR2 = (nc + 1 + D2) / D2 * D2;
+
+  // ------------------------------------------------------------------ pass 1: P = G Q^T, left in LDS
+  float ss0, ss1;                                    // streaming thread: sums of g^2 of rows t512/8 and 64 + t512/8
+  stripe_pass1<RT>(smem, rG, n, Qf, ss0, ss1);
+  lds_u8* const lds = (lds_u8*)smem;
+
+  // ------------------------------------------------------------------ second moment of the stripe, P to LDS
+  const float* Ps = reinterpret_cast<const float*>(smem);         // [BM][PS] fp32
+  if (!mrole) {                     // a row is covered by 8 consecutive lanes
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) { ss0 += __shfl_xor(ss0, o, 64); ss1 += __shfl_xor(ss1, o, 64); }
+    if ((t512 & 7) == 0) { rsum[t512 >> 3] = ss0; rsum[64 + (t512 >> 3)] = ss1; }
   }
   __syncthreads();
   if (B.v_kind == 1) {             // groups of v_group_rows rows inside the stripe: finish v here
@@ -548,6 +579,99 @@ __global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ 
   }
 }
 
+// Alg. 2 stripe product: Out = A Q^T for 128 rows of A per workgroup (pass 1 of the kernel above, then a store).
+template <int RT>
+__global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restrict__ items,
+                                                       const StripeProb* __restrict__ probs, Bases bs) {
+  constexpr int R = 32 * RT, PS = Pass1<RT>::PS;
+  constexpr int SMEM = Pass1<RT>::BYTES > Pass1<RT>::P_BYTES ? Pass1<RT>::BYTES : Pass1<RT>::P_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+  const StripeItem item = items[blockIdx.x];
+  if (item.prob < 0) return;
+  const StripeProb P = probs[item.prob];
+  const int M = P.M, K = P.K, row0 = item.row0, tid = threadIdx.x;
+  const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(resolve(P.a, bs));
+  const unsigned rows_valid = (unsigned)(M - row0 < BM ? M - row0 : BM);
+  const __amdgpu_buffer_rsrc_t rA = make_rsrc(A + (int64_t)row0 * K, rows_valid * (unsigned)K * 2u);
+  float ss0, ss1;
+  stripe_pass1<RT>(smem, rA, K, bs.ws + P.off_img, ss0, ss1);
+  __syncthreads();
+  const float* Ps = reinterpret_cast<const float*>(smem);
+  float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);
+  if (!P.transpose_out) {
+#pragma unroll
+    for (int i = 0; i < (BM * R / 4) / NT; ++i) {
+      const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
+      if (row0 + row < M)
+        *reinterpret_cast<float4*>(Out + (int64_t)(row0 + row) * R + c4) = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
+    }
+  } else {
+    // Out[a][row0 + j] = P[j][a]: lanes run along j, so the global stores are contiguous
+#pragma unroll 4
+    for (int i = 0; i < (BM * R) / NT; ++i) {
+      const int id = tid + NT * i, j = id % BM, a = id / BM;
+      if (row0 + j < M) Out[(int64_t)a * M + row0 + j] = Ps[j * PS + a];
+    }
+  }
+}
+
+// Fragment image of Q(a, k) = q[a * s0 + k * s1] (fp32, r x K): per 64-column chunk
+// [k-step][r-tile][hi|lo][lane][8]; lane l holds Q[32 tile + l%32][64 c + 16 kk + 8 (l/32) .. +7].
+__global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict__ items, Bases bs) {
+  const ImgItem it = items[blockIdx.x];
+  const int R = it.r, RT = R / 32, K = it.K, c = it.c;
+  const float* __restrict__ Q = reinterpret_cast<const float*>(resolve(it.q.ref, bs));
+  const int64_t s0 = it.q.s0, s1 = it.q.s1;
+  char* qf = bs.ws + it.off_img + (int64_t)c * qf_chunk_bytes(R);
+  const int np = (BK / 16) * RT * 64;                 // (hi, lo) pairs of pieces
+  for (int p = threadIdx.x; p < np; p += 256) {
+    const int lane = p & 63, rest = p >> 6, tile = rest % RT, kk = rest / RT;
+    const int a = 32 * tile + (lane & 31), k = c * BK + kk * 16 + 8 * (lane >> 5);
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float x0 = (k + 2 * e < K) ? Q[(int64_t)a * s0 + (int64_t)(k + 2 * e) * s1] : 0.f;
+      const float x1 = (k + 2 * e + 1 < K) ? Q[(int64_t)a * s0 + (int64_t)(k + 2 * e + 1) * s1] : 0.f;
+      split_pair(x0, x1, h[e], l[e]);
+    }
+    char* dst = qf + ((int64_t)((kk * RT + tile) * 2) * 64 + lane) * 16;
+    *reinterpret_cast<uint4*>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+    *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(l[0], l[1], l[2], l[3]);
+  }
+}
+
+// bf16 transpose through LDS, 64 x 64 tiles; needs m % 8 == 0 and n % 8 == 0 (16-byte vectors both ways)
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const TrItem* __restrict__ items, Bases bs) {
+  __shared__ uint16_t tile[64][66];
+  const TrItem it = items[blockIdx.x];
+  const int m = it.m, n = it.n, i0 = it.ti * 64, j0 = it.tj * 64, t = threadIdx.x;
+  const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(bs.grads[it.block]);
+  uint16_t* __restrict__ Gt = reinterpret_cast<uint16_t*>(bs.ws + it.off_out);
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int r = (t >> 3) + 32 * h, c8 = (t & 7) * 8;
+    uint4 q = make_uint4(0, 0, 0, 0);
+    if (i0 + r < m && j0 + c8 < n) q = *reinterpret_cast<const uint4*>(G + (int64_t)(i0 + r) * n + j0 + c8);
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      tile[r][c8 + 2 * e] = (uint16_t)(w[e] & 0xffffu);
+      tile[r][c8 + 2 * e + 1] = (uint16_t)(w[e] >> 16);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int j = (t >> 3) + 32 * h, r8 = (t & 7) * 8;
+    if (j0 + j < n && i0 + r8 < m) {
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[r8 + 2 * e][j] | ((uint32_t)tile[r8 + 2 * e + 1][j] << 16);
+      *reinterpret_cast<uint4*>(Gt + (int64_t)(j0 + j) * m + i0 + r8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
+}
+
 template <int RT>
 void launch_proj_rt(bool w16, dim3 grid, const ProjItem* items, const LrBlockDev* lrb, Bases b, StepScalars sc,
                     hipStream_t s) {
@@ -567,6 +691,24 @@ void launch_proj(int rt, bool w16, const ProjItem* items, int64_t nitems, const 
   if (rt == 1) launch_proj_rt<1>(w16, grid, items, lrb, b, sc, s);
   else if (rt == 2) launch_proj_rt<2>(w16, grid, items, lrb, b, sc, s);
   else launch_proj_rt<4>(w16, grid, items, lrb, b, sc, s);
+}
+
+void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  const dim3 grid((unsigned)nitems);
+  if (rt == 1) hipLaunchKernelGGL((stripe_kernel<1>), grid, dim3(NT), 0, s, items, probs, b);
+  else if (rt == 2) hipLaunchKernelGGL((stripe_kernel<2>), grid, dim3(NT), 0, s, items, probs, b);
+  else hipLaunchKernelGGL((stripe_kernel<4>), grid, dim3(NT), 0, s, items, probs, b);
+}
+
+void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(qf_image_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
+}
+
+void launch_transpose_bf16(const TrItem* items, int64_t nitems, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
 }
 
 void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s) {
