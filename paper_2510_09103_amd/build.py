@@ -33,6 +33,12 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if out.returncode != 0:
         raise RuntimeError("link failed:\n" + out.stdout)
+    # stand-alone bandwidth measurement (no part of the library): ./hbm_ceiling prints what HBM
+    # delivers for the access patterns of the fused kernels
+    cmd = [hipcc, *FLAGS, os.path.join(CSRC, "hbm_ceiling.hip"), "-o", os.path.join(HERE, "hbm_ceiling")]
+    out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if out.returncode != 0:
+        raise RuntimeError("hipcc failed on hbm_ceiling.hip:\n" + out.stdout)
     return LIB
 
 
