@@ -79,17 +79,25 @@ __device__ __forceinline__ void fetch(const char* base, int dtype, int64_t su, i
       }
     }
   } else {
+    // every load is issued unconditionally on a clamped (always valid) index and masked afterwards: a
+    // load inside its own bounds check would wait for the previous one, 16 latencies per chunk
     const int gu = u0 + (tid & 127), gk = k0 + 16 * (tid >> 7);
     const bool uin = gu < U;
+    const int64_t jb = (int64_t)(uin ? gu : 0) * su;
+    if (dtype == DT_BF16) {
+      const uint16_t* src = reinterpret_cast<const uint16_t*>(base);
+      uint16_t raw[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      float v = 0.f;
-      if (uin && gk + i < K) {
-        const int64_t j = (int64_t)gu * su + (int64_t)(gk + i) * sk;
-        v = dtype == DT_BF16 ? __uint_as_float(((uint32_t)reinterpret_cast<const uint16_t*>(base)[j]) << 16)
-                             : reinterpret_cast<const float*>(base)[j];
-      }
-      st.x[i] = v;
+      for (int i = 0; i < 16; ++i) raw[i] = src[jb + (int64_t)(gk + i < K ? gk + i : 0) * sk];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st.x[i] = (uin && gk + i < K) ? __uint_as_float(((uint32_t)raw[i]) << 16) : 0.f;
+    } else {
+      const float* src = reinterpret_cast<const float*>(base);
+      float raw[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) raw[i] = src[jb + (int64_t)(gk + i < K ? gk + i : 0) * sk];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st.x[i] = (uin && gk + i < K) ? raw[i] : 0.f;
     }
   }
   if (alpha != 1.f) {
@@ -206,23 +214,28 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma_kernel(const GemmProblem* __
   const char* Yb = P.Y.ref.space != SP_NONE ? resolve(P.Y.ref, bs) : nullptr;
   float* Ob = reinterpret_cast<float*>(resolve(P.Out.ref, bs));
   const float g = (float)P.g, d = (float)P.d;
+  // X and Y are read unconditionally on clamped indices (16 independent loads at a time) and the
+  // bounds check is applied to the store only
 #pragma unroll
   for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
     for (int tn = 0; tn < 2; ++tn) {
       const int j = j0 + 64 * wn + 32 * tn + l32;
+      const int jc = j < P.N ? j : 0;
+      float xv[16], yv[16];
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int e = 0; e < 16; ++e) {
+        const int i = i0 + 64 * wm + 32 * tm + 8 * (e >> 2) + 4 * lh + (e & 3);
+        const int ic = i < P.M ? i : 0;
+        xv[e] = Xb ? load_f(Xb, P.X.dtype, (int64_t)ic * P.X.s0 + (int64_t)jc * P.X.s1) : 0.f;
+        yv[e] = Yb ? load_f(Yb, P.Y.dtype, (int64_t)ic * P.Y.s0 + (int64_t)jc * P.Y.s1) : 0.f;
+      }
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const int i = i0 + 64 * wm + 32 * tm + 8 * q + 4 * lh + p;
-          if (i < P.M && j < P.N) {
-            float val = acc[tm][tn][4 * q + p];
-            if (Xb) val += g * load_f(Xb, P.X.dtype, (int64_t)i * P.X.s0 + (int64_t)j * P.X.s1);
-            if (Yb) val += d * load_f(Yb, P.Y.dtype, (int64_t)i * P.Y.s0 + (int64_t)j * P.Y.s1);
-            Ob[(int64_t)i * P.Out.s0 + (int64_t)j * P.Out.s1] = val;
-          }
-        }
+      for (int e = 0; e < 16; ++e) {
+        const int i = i0 + 64 * wm + 32 * tm + 8 * (e >> 2) + 4 * lh + (e & 3);
+        if (i < P.M && j < P.N)
+          Ob[(int64_t)i * P.Out.s0 + (int64_t)j * P.Out.s1] = acc[tm][tn][e] + g * xv[e] + d * yv[e];
+      }
     }
 }
 
