@@ -151,11 +151,14 @@ int64_t group_elems(const adapm_block_t& b) {
 int esize(int32_t dt) { return dt == ADAPM_BF16 ? 2 : 4; }
 
 // BF16X2 needs bf16 gradients, a rank of 32, 64 or 128 and 16-byte aligned rows; other blocks use F64.
+// rank class the MFMA kernels are compiled for (the bf16 images of the factors are zero-padded to it); 0 = none
+int rank_class(int r) { return r <= 32 ? 32 : (r <= 64 ? 64 : (r <= 128 ? 128 : 0)); }
+
 int path_of(const adapm_block_t& b, const adapm_hparams_t& hp) {
   if (b.mom_mode != ADAPM_MOM_LOWRANK) return PATH_NONE;
   const bool want = hp.contraction == ADAPM_CONTRACT_BF16X2 ||
                     (hp.contraction == ADAPM_CONTRACT_AUTO && b.param_dtype == ADAPM_BF16);
-  const bool can = b.grad_dtype == ADAPM_BF16 && (b.rank == 32 || b.rank == 64 || b.rank == 128) && b.cols % 8 == 0 &&
+  const bool can = b.grad_dtype == ADAPM_BF16 && rank_class(b.rank) != 0 && b.cols % 8 == 0 &&
                    b.cols <= (1 << 21);   // 128 rows of a stripe stay inside one 32-bit buffer range
   return (want && can) ? PATH_FAST : PATH_F64;
 }
@@ -303,12 +306,13 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
           for (int ti = 0; ti < (m + 63) / 64; ++ti)
             for (int tj = 0; tj < (n + 63) / 64; ++tj) c->tr.h.push_back(TrItem{(int32_t)i, m, n, ti, tj, 0, L.wGt});
         Mat LcT = T(Lc);
-        for (int ch = 0; ch < (n + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{Rc, r, n, ch, 0, L.wIr});
-        for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, 0, L.wIl});
-        const int cls = r == 32 ? 0 : (r == 64 ? 1 : 2);
+        const int rc = rank_class(r);
+        for (int ch = 0; ch < (n + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{Rc, r, n, ch, rc, L.wIr});
+        for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, rc, L.wIl});
+        const int cls = rc == 32 ? 0 : (rc == 64 ? 1 : 2);
         StripeProb sp;
         memset(&sp, 0, sizeof sp);
-        sp.a = G.ref; sp.M = m; sp.K = n; sp.r = r; sp.transpose_out = 0; sp.off_img = L.wIr; sp.off_out = L.wP;
+        sp.a = G.ref; sp.M = m; sp.K = n; sp.r = r; sp.rc = rc; sp.transpose_out = 0; sp.off_img = L.wIr; sp.off_out = L.wP;
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
         sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = L.wIl; sp.off_out = L.wS;
@@ -463,7 +467,7 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
     if (L.path != PATH_FAST) continue;
     LrBlockDev d;
     memset(&d, 0, sizeof d);
-    d.block = (int32_t)i; d.m = (int32_t)b.rows; d.n = (int32_t)b.cols; d.r = b.rank;
+    d.block = (int32_t)i; d.m = (int32_t)b.rows; d.n = (int32_t)b.cols; d.r = b.rank; d.rc = rank_class(b.rank);
     d.off_L = L.sL; d.off_Q = L.sR; d.off_v = L.sv; d.off_Qf = L.wQf; d.off_Timg = L.wTimg;
     if (b.v_mode == ADAPM_V_ELEMENT) { d.v_kind = 0; d.v_group_rows = 1; }
     else if (v_fusable(b)) { d.v_kind = 1; d.v_group_rows = b.v_group_rows; }
@@ -484,7 +488,7 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
     const int pdt = (cls & 1) ? ADAPM_BF16 : ADAPM_F32;
     std::vector<int64_t> ids;
     for (int64_t i = 0; i < nb; ++i)
-      if (lr_of[i] >= 0 && c->table[i].rank == rank && c->table[i].param_dtype == pdt) ids.push_back(i);
+      if (lr_of[i] >= 0 && rank_class(c->table[i].rank) == rank && c->table[i].param_dtype == pdt) ids.push_back(i);
     if (ids.empty()) continue;
     // longest rows first; whole blocks dealt to the least loaded XCD
     std::stable_sort(ids.begin(), ids.end(), [&](int64_t a, int64_t b) {
@@ -537,12 +541,12 @@ void build_plan(adapm_ctx* c) {
       L.wC = walloc(4 * m * n);
       if (L.path == PATH_FAST && stripe_ok(b)) {
         L.wGt = walloc(2 * m * n);
-        L.wIr = walloc(proj_qf_bytes((int)r, (int)n));
-        L.wIl = walloc(proj_qf_bytes((int)r, (int)m));
+        L.wIr = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
+        L.wIl = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
       }
       if (L.path == PATH_FAST && hp.refresh_period_T > 1) {
-        L.wQf = walloc(proj_qf_bytes((int)r, (int)n));
-        L.wTimg = walloc(proj_timg_bytes((int)r, (int)n));
+        L.wQf = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
+        L.wTimg = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
       }
       c->n_lowrank++;
     } else if (b.mom_mode == ADAPM_MOM_FULL) {

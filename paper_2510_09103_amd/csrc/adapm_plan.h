@@ -110,7 +110,7 @@ struct StepScalars {
 // ---------------------------------------------------------------------------
 struct LrBlockDev {
   int32_t block;           // index into the gradient / parameter pointer tables
-  int32_t m, n, r;
+  int32_t m, n, r;         // r: the block's rank (any value up to 128)
   int64_t off_L, off_Q;    // state: L (m x r), Q = R (r x n), fp32
   int64_t off_v;           // state: v
   int64_t off_Qf;          // ws: Q as bf16 (hi, lo) MFMA fragments, per 64-column chunk
@@ -120,7 +120,7 @@ struct LrBlockDev {
   int32_t v_group_rows;
   int32_t param_dtype;
   float lr_scale, wd;
-  int32_t pad;
+  int32_t rc;              // rank class the kernels are compiled for: 32, 64 or 128 >= r (images are zero-padded to it)
 };
 
 struct ProjItem {          // one workgroup: 128 rows of one block; lr < 0 = padding
@@ -138,8 +138,9 @@ struct QsItem {            // one workgroup: one 64-column chunk of Q
 // for (L^T G)^T = G^T L (A = G^T, Q = L^T), whose result is written back transposed.
 struct StripeProb {
   Ref a;                   // A: M x K bf16, row-major, row stride K
-  int32_t M, K, r;
+  int32_t M, K, r;         // r: rows of Q actually present
   int32_t transpose_out;   // 0: Out is M x r (row stride r); 1: Out is r x M (row stride M)
+  int32_t rc, pad;         // rank class of the image: 32, 64 or 128 >= r
   int64_t off_img;         // workspace: fragment image of Q
   int64_t off_out;         // workspace: fp32 result
 };
@@ -149,7 +150,7 @@ struct StripeItem {        // one workgroup: 128 rows of A; prob < 0 = padding
 };
 struct ImgItem {           // one workgroup: one 64-column chunk of the fragment image of Q(a, k) = q[a * s0 + k * s1]
   Mat q;                   // fp32
-  int32_t r, K, c, pad;
+  int32_t r, K, c, rc;     // rows of Q, columns, chunk, rank class of the image (rows r .. rc-1 are zero)
   int64_t off_img;
 };
 struct TrItem {            // one workgroup: one 64 x 64 tile of the bf16 transpose G (m x n) -> G^T (n x m)

@@ -364,25 +364,37 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
       vrow[tid] = inv_denom_exact(vst[(row0 + tid) / B.v_group_rows], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
   }
   // ------------------------------------------------------------------ L_t and D = dL L' + dP P (whole rows, float4)
+  // The kernel is compiled for the rank class R; the block's own rank r <= R sets the row stride of L.
+  // Columns r .. R-1 of P are zero (the images of Q are zero-padded), and so are those of D.
   constexpr int LV = (BM * R / 4) / NT;
+  const int r = B.r;
+  const bool vec4 = (r & 3) == 0;
   uint2 dhv[LV], dlv[LV];
 #pragma unroll
   for (int i = 0; i < LV; ++i) {
     const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
-    float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (row0 + row < m) {
-      float4* lp = reinterpret_cast<float4*>(Lst + (int64_t)(row0 + row) * R + c4);
-      const float4 lprev = *lp;
-      const float4 pv = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
+    float lprev[4] = {0.f, 0.f, 0.f, 0.f}, d[4] = {0.f, 0.f, 0.f, 0.f};
+    if (row0 + row < m && c4 < r) {
+      float* lp = Lst + (int64_t)(row0 + row) * r + c4;
+      const float4 pv4 = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
+      const float pv[4] = {pv4.x, pv4.y, pv4.z, pv4.w};
       const float b1 = sc.beta1, ob1 = 1.f - sc.beta1;
-      *lp = make_float4(b1 * lprev.x + ob1 * pv.x, b1 * lprev.y + ob1 * pv.y, b1 * lprev.z + ob1 * pv.z,
-                        b1 * lprev.w + ob1 * pv.w);
-      d = make_float4(sc.dL * lprev.x + sc.dP * pv.x, sc.dL * lprev.y + sc.dP * pv.y, sc.dL * lprev.z + sc.dP * pv.z,
-                      sc.dL * lprev.w + sc.dP * pv.w);
+      if (vec4) {
+        const float4 t = *reinterpret_cast<const float4*>(lp);
+        lprev[0] = t.x; lprev[1] = t.y; lprev[2] = t.z; lprev[3] = t.w;
+        *reinterpret_cast<float4*>(lp) = make_float4(b1 * lprev[0] + ob1 * pv[0], b1 * lprev[1] + ob1 * pv[1],
+                                                     b1 * lprev[2] + ob1 * pv[2], b1 * lprev[3] + ob1 * pv[3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (c4 + e < r) { lprev[e] = lp[e]; lp[e] = b1 * lprev[e] + ob1 * pv[e]; }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) d[e] = (c4 + e < r) ? sc.dL * lprev[e] + sc.dP * pv[e] : 0.f;
     }
     uint32_t h0, l0, h1, l1;
-    split_pair(d.x, d.y, h0, l0);
-    split_pair(d.z, d.w, h1, l1);
+    split_pair(d[0], d[1], h0, l0);
+    split_pair(d[2], d[3], h1, l1);
     dhv[i] = make_uint2(h0, h1);
     dlv[i] = make_uint2(l0, l1);
   }
@@ -539,7 +551,7 @@ __global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ 
                                                      const LrBlockDev* __restrict__ lrb, Bases bs) {
   const QsItem it = items[blockIdx.x];
   const LrBlockDev B = lrb[it.lr];
-  const int n = B.n, R = B.r, RT = R / 32, c = it.c;
+  const int n = B.n, R = B.rc, RT = R / 32, c = it.c, rows = B.r;      // rows rows .. R-1 of both images are zero
   const float* __restrict__ Q = reinterpret_cast<const float*>(bs.state + B.off_Q);
   char* qf = bs.ws + B.off_Qf + (int64_t)c * qf_chunk_bytes(R);
   char* ti = bs.ws + B.off_Timg + (int64_t)c * timg_chunk_bytes(R);
@@ -551,8 +563,8 @@ __global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ 
     uint32_t o[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float x0 = (k + 2 * e < n) ? Q[(int64_t)a * n + k + 2 * e] : 0.f;
-      const float x1 = (k + 2 * e + 1 < n) ? Q[(int64_t)a * n + k + 2 * e + 1] : 0.f;
+      const float x0 = (a < rows && k + 2 * e < n) ? Q[(int64_t)a * n + k + 2 * e] : 0.f;
+      const float x1 = (a < rows && k + 2 * e + 1 < n) ? Q[(int64_t)a * n + k + 2 * e + 1] : 0.f;
       uint32_t h, l;
       split_pair(x0, x1, h, l);
       o[e] = hl ? l : h;
@@ -569,8 +581,8 @@ __global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ 
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int a0 = 8 * q + 2 * e;
-      const float x0 = (col < n) ? Q[(int64_t)a0 * n + col] : 0.f;
-      const float x1 = (col < n) ? Q[(int64_t)(a0 + 1) * n + col] : 0.f;
+      const float x0 = (col < n && a0 < rows) ? Q[(int64_t)a0 * n + col] : 0.f;
+      const float x1 = (col < n && a0 + 1 < rows) ? Q[(int64_t)(a0 + 1) * n + col] : 0.f;
       uint32_t h, l;
       split_pair(x0, x1, h, l);
       o[e] = hl ? l : h;
@@ -598,19 +610,30 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   __syncthreads();
   const float* Ps = reinterpret_cast<const float*>(smem);
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);
+  const int r = P.r;                  // rows of Q actually present (the image is zero-padded to R)
   if (!P.transpose_out) {
+    const bool vec4 = (r & 3) == 0;
 #pragma unroll
     for (int i = 0; i < (BM * R / 4) / NT; ++i) {
       const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
-      if (row0 + row < M)
-        *reinterpret_cast<float4*>(Out + (int64_t)(row0 + row) * R + c4) = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
+      if (row0 + row < M && c4 < r) {
+        float* o = Out + (int64_t)(row0 + row) * r + c4;
+        const float4 v = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
+        if (vec4) *reinterpret_cast<float4*>(o) = v;
+        else {
+          const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (c4 + e < r) o[e] = x[e];
+        }
+      }
     }
   } else {
     // Out[a][row0 + j] = P[j][a]: lanes run along j, so the global stores are contiguous
 #pragma unroll 4
     for (int i = 0; i < (BM * R) / NT; ++i) {
       const int id = tid + NT * i, j = id % BM, a = id / BM;
-      if (row0 + j < M) Out[(int64_t)a * M + row0 + j] = Ps[j * PS + a];
+      if (row0 + j < M && a < r) Out[(int64_t)a * M + row0 + j] = Ps[j * PS + a];
     }
   }
 }
@@ -619,7 +642,7 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
 // [k-step][r-tile][hi|lo][lane][8]; lane l holds Q[32 tile + l%32][64 c + 16 kk + 8 (l/32) .. +7].
 __global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict__ items, Bases bs) {
   const ImgItem it = items[blockIdx.x];
-  const int R = it.r, RT = R / 32, K = it.K, c = it.c;
+  const int R = it.rc, RT = R / 32, K = it.K, c = it.c, rows = it.r;
   const float* __restrict__ Q = reinterpret_cast<const float*>(resolve(it.q.ref, bs));
   const int64_t s0 = it.q.s0, s1 = it.q.s1;
   char* qf = bs.ws + it.off_img + (int64_t)c * qf_chunk_bytes(R);
@@ -630,8 +653,8 @@ __global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict
     uint32_t h[4], l[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float x0 = (k + 2 * e < K) ? Q[(int64_t)a * s0 + (int64_t)(k + 2 * e) * s1] : 0.f;
-      const float x1 = (k + 2 * e + 1 < K) ? Q[(int64_t)a * s0 + (int64_t)(k + 2 * e + 1) * s1] : 0.f;
+      const float x0 = (a < rows && k + 2 * e < K) ? Q[(int64_t)a * s0 + (int64_t)(k + 2 * e) * s1] : 0.f;
+      const float x1 = (a < rows && k + 2 * e + 1 < K) ? Q[(int64_t)a * s0 + (int64_t)(k + 2 * e + 1) * s1] : 0.f;
       split_pair(x0, x1, h[e], l[e]);
     }
     char* dst = qf + ((int64_t)((kk * RT + tile) * 2) * 64 + lane) * 16;

@@ -69,7 +69,9 @@ def mixed_table(pd="f32", gd="f32"):
 ])
 def test_mixed_table_all_modes(hp):
     wl = mixed_table()
-    # bf16-parameter blocks are held to the bf16 criterion inside compare_params
+    # every mode on the exact (fp64 contraction) path at the fp32 tolerance; the MFMA path has its own
+    # tables below.  bf16-parameter blocks are held to the bf16 criterion inside compare_params
+    hp = dict(hp, contraction=B.ADAPM_CONTRACT_F64)
     run(wl, 6, hp, tol_state=TOL32, tol_param=TOL32, check_every=2)
 
 
@@ -86,10 +88,34 @@ def ragged_bf16_table():
     ), steps=6, seed=5, signal_rank=40)
 
 
-@pytest.mark.parametrize("hp", [dict(T=1), dict(T=3), dict(T=2, bias_correction=0)])
+@pytest.mark.parametrize("hp", [
+    dict(T=1), dict(T=3), dict(T=2, bias_correction=0), dict(T=1, adam_debias=1, clip=float("inf")),
+    dict(T=2, K=1), dict(T=1, beta1=0.0),
+])
 def test_ragged_shapes_on_the_mfma_path(hp):
     hp = dict(hp, contraction=B.ADAPM_CONTRACT_BF16X2)
     run(ragged_bf16_table(), 6, hp, tol_state=TOL16, tol_param=TOL16, check_every=2)
+
+
+def odd_rank_table():
+    """bf16 blocks whose rank is not 32, 64 or 128 (the paper takes r = 5 % of the smaller dimension): the
+    MFMA kernels run them in the next rank class with zero-padded images of the factors.  Ranks that are
+    and are not multiples of 4 (vector / scalar access to the rows of L), rows that are and are not
+    multiples of 8 (stripe products / batched GEMM in Alg. 2)."""
+    mk = BlockSpec
+    return WL.Workload("odd_ranks", (
+        mk("r8", 136, 200, "bf16", "bf16", "lowrank", 8, "rowgroup", 1, 1.0, 0.1),
+        mk("r20_rows130", 130, 264, "bf16", "bf16", "lowrank", 20, "element", 1, 1.0, 0.1),
+        mk("r51", 264, 1024, "bf16", "bf16", "lowrank", 51, "rowgroup", 1, 1.0, 0.1),
+        mk("r80_f32params", 160, 320, "f32", "bf16", "lowrank", 80, "whole", 1, 1.0, 0.0),
+        mk("r100", 256, 136, "bf16", "bf16", "lowrank", 100, "rowgroup", 64, 1.0, 0.1),
+    ), steps=6, seed=9, signal_rank=40)
+
+
+@pytest.mark.parametrize("hp", [dict(T=1), dict(T=3)])
+def test_ranks_between_the_classes_on_the_mfma_path(hp):
+    hp = dict(hp, contraction=B.ADAPM_CONTRACT_BF16X2)
+    run(odd_rank_table(), 6, hp, tol_state=TOL16, tol_param=TOL16, check_every=2)
 
 
 def test_literal_zero_start_stays_zero_on_gpu():
