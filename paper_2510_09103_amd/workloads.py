@@ -142,7 +142,53 @@ def gpt2_1p5b() -> Workload:
     return Workload("gpt2_1p5b", tuple(b), steps=20, seed=0, spectrum_p=1.5)
 
 
+def paper_partition(shape: str = "gpt2_1p5b", mini: bool = False) -> Workload:
+    """The paper's own assignment of momentum regimes (Sec. 4.1) on the two shapes of its memory table
+    (Table 2): embeddings and the attention output projection carry no momentum and run at 0.75 x lr
+    (Sec. 5.1, set-ups); query, key and MLP matrices carry low-rank momentum with r = 5 % of the smaller
+    dimension; value matrices (and the norm vectors, which the paper does not mention) keep full momentum.
+    mini = False: per-element second moment ("AdaPM"); mini = True: blockwise second moment in the
+    Adam-mini partition ("AdaPM-mini": per head for Q, K, per output row elsewhere, one value per norm).
+    bf16 parameters and gradients, weight decay 0.1 on matrices, tied input / output embedding."""
+    if shape == "gpt2_1p5b":
+        L, d, f, hd, vocab, pos, gated = 48, 1600, 6400, 64, 50257, 1024, False
+    elif shape == "llama_350m":
+        L, d, f, hd, vocab, pos, gated = 24, 1024, 2736, 64, 32000, 0, True
+    else:
+        raise ValueError(shape)
+    pd = gd = "bf16"
+    rg = dict(v_mode="rowgroup") if mini else {}
+
+    def rank(rows, cols):
+        return max(1, round(0.05 * min(rows, cols)))
+
+    def none(name, rows, cols, **kw):
+        return BlockSpec(name, rows, cols, pd, gd, "none", 0, kw.get("v_mode", "element"), kw.get("v_group_rows", 1),
+                         0.75, 0.1, kw.get("head_rows", 0))
+
+    b = [none("wte", vocab, d, **rg)]
+    if pos:
+        b.append(none("wpe", pos, d, **rg))
+    for l in range(L):
+        for n in ("q", "k"):
+            kw = dict(v_mode="rowgroup", v_group_rows=hd) if mini else {}
+            b.append(_mat(f"h{l}.attn.{n}", d, d, pd, gd, rank(d, d), head_rows=hd, **kw))
+        b.append(_full(f"h{l}.attn.v", d, d, pd, gd, **rg))
+        b.append(none(f"h{l}.attn.o", d, d, head_rows=hd, **rg))
+        mlp = (("gate", f, d), ("up", f, d), ("down", d, f)) if gated else (("fc", f, d), ("proj", d, f))
+        for n, rows, cols in mlp:
+            b.append(_mat(f"h{l}.mlp.{n}", rows, cols, pd, gd, rank(rows, cols), **rg))
+        for i in (1, 2):
+            b.append(_full(f"h{l}.ln{i}", d, 1, pd, gd, wd=0.0, v_mode="whole" if mini else "element", is_norm=True))
+    b.append(_full("ln_f", d, 1, pd, gd, wd=0.0, v_mode="whole" if mini else "element", is_norm=True))
+    return Workload(f"{shape}_paper{'_mini' if mini else ''}", tuple(b), steps=20, seed=0, spectrum_p=1.5)
+
+
 CONFIGS = {
+    "gpt2_1p5b_paper": lambda: paper_partition("gpt2_1p5b", False),
+    "gpt2_1p5b_paper_mini": lambda: paper_partition("gpt2_1p5b", True),
+    "llama_350m_paper": lambda: paper_partition("llama_350m", False),
+    "llama_350m_paper_mini": lambda: paper_partition("llama_350m", True),
     "tiny_block": tiny_block,
     "llama_60m": llama_60m,
     "gpt2_350m": gpt2_350m,

@@ -123,6 +123,48 @@ def test_state_bytes_closed_form_and_layout(name):
     B.adapm_destroy(ctx)
 
 
+def _table2():
+    out = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "table2_memory.txt")):
+        if line.strip() and not line.startswith("#"):
+            shape, alg, mem = line.split()
+            out[(shape, alg)] = float(mem)
+    return out
+
+
+@pytest.mark.parametrize("shape", ["gpt2_1p5b", "llama_350m"])
+def test_paper_partition_state_size_beside_table2(shape):
+    """Sec. 4.1's assignment of regimes with r = 5 %, sized by the library, next to the paper's Table 2.
+    The table is a weak pin (the paper does not say which tensors it counted): the per-element-v variant
+    must agree within 3 %; for the blockwise variant the table's own claim (at least 93 % less state
+    than Adam) must hold and the low-rank factors must be the small part of what is left."""
+    t2 = _table2()
+    sizes = {}
+    for mini in (False, True):
+        wl = WL.paper_partition(shape, mini)
+        ctx = B.adapm_init([to_c_block(b) for b in wl.blocks], make_hparams(T=100))
+        sizes[mini] = B.adapm_state_bytes(ctx)
+        exact = O.state_bytes_closed_form([oracle_block(b) for b in wl.blocks])
+        assert exact <= sizes[mini] <= exact + 255 * 3 * len(wl.blocks)
+        B.adapm_destroy(ctx)
+    wl = WL.paper_partition(shape, False)
+    adam = 8 * wl.numel
+    assert abs(adam / 1e9 - t2[(shape, "Adam")]) / t2[(shape, "Adam")] < 0.02
+    assert abs(sizes[False] / 1e9 - t2[(shape, "AdaPM")]) / t2[(shape, "AdaPM")] < 0.03
+    assert sizes[True] / adam < 0.07 and t2[(shape, "AdaPM-mini")] / t2[(shape, "Adam")] < 0.07
+    # regimes: no momentum on embeddings and attention output (0.75 x lr), full on values, rank = 5 % elsewhere
+    by = {b.name: b for b in wl.blocks}
+    assert by["wte"].mom == "none" and by["wte"].lr_scale == 0.75 and by["h0.attn.o"].mom == "none"
+    assert by["h0.attn.v"].mom == "full" and by["h0.attn.q"].mom == "lowrank"
+    d = by["h0.attn.q"].rows
+    assert by["h0.attn.q"].rank == round(0.05 * d)
+    lowrank = sum(4 * (b.rows + b.cols) * b.rank for b in wl.blocks if b.mom == "lowrank")
+    full = sum(4 * b.numel for b in wl.blocks if b.mom == "full")
+    assert lowrank < full                                   # the value matrices dominate what momentum is left
+    print(f"{shape}: Adam {adam / 1e9:.2f} G (Table 2: {t2[(shape, 'Adam')]}), AdaPM {sizes[False] / 1e9:.3f} G "
+          f"({t2[(shape, 'AdaPM')]}), AdaPM-mini {sizes[True] / 1e9:.3f} G ({t2[(shape, 'AdaPM-mini')]})")
+
+
 def test_gpt2_1p5b_state_and_traffic_figures():
     wl = WL.gpt2_1p5b()
     ctx = B.adapm_init([to_c_block(b) for b in wl.blocks], make_hparams(T=100))

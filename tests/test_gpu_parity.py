@@ -118,6 +118,17 @@ def test_ranks_between_the_classes_on_the_mfma_path(hp):
     run(odd_rank_table(), 6, hp, tol_state=TOL16, tol_param=TOL16, check_every=2)
 
 
+@pytest.mark.parametrize("shape,mini", [("gpt2_1p5b", False), ("gpt2_1p5b", True), ("llama_350m", False), ("llama_350m", True)])
+def test_paper_partition_layer(shape, mini):
+    """One layer (plus an embedding-like block) of the paper's own partition (Sec. 4.1): no momentum at
+    0.75 x lr, full momentum, low-rank momentum with r = 5 % (80 resp. 51: between the rank classes)."""
+    full = WL.paper_partition(shape, mini)
+    names = [b.name for b in full.blocks if b.name.startswith("h0.")]
+    if shape == "gpt2_1p5b":
+        names = ["wpe"] + names
+    run(WL.subset(full, names), 5, dict(T=3), tol_state=TOL16, tol_param=TOL16, check_every=2)
+
+
 def test_literal_zero_start_stays_zero_on_gpu():
     wl = WL.subset(WL.tiny_block(), ["attn.q"])
     pair, _ = run(wl, 3, dict(seed=0))
