@@ -85,6 +85,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-literal", action="store_true")
     ap.add_argument("--grad-sets", type=int, default=2)
+    ap.add_argument("--rank", type=int, default=0, help="override the rank of every low-rank block (rank / T sweeps)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (blocks are independent, the library has no collectives); "
@@ -99,6 +100,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     wl = WL.CONFIGS[args.workload]()
+    if args.rank > 0:
+        from dataclasses import replace
+        wl = replace(wl, blocks=tuple(replace(b, rank=min(args.rank, b.rows, b.cols)) if b.mom == "lowrank" else b
+                                      for b in wl.blocks))
     lr = wl.lr
     params = WL.initial_params(wl, device=dev)
     stream = WL.GradientStream(wl, device=dev)
@@ -159,7 +164,7 @@ def main():
                 "achieved": per_launch / (kernels[dominant]["avg_ms"] * 1e-3) / 1e12}
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
-    if args.workload == "gpt2_1p5b" and args.T == 100 and os.path.exists(tfile):
+    if args.workload == "gpt2_1p5b" and args.T == 100 and args.rank == 0 and os.path.exists(tfile):
         for line in open(tfile):
             parts = line.split()
             if len(parts) == 2 and parts[0] == dominant:
