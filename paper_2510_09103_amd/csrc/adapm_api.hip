@@ -55,11 +55,12 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wG64 = -1, wCinv = -1, wC = -1;
   int64_t wQf = -1, wTimg = -1;                             // ws: bf16 (hi, lo) images of Q and Q^T
   int64_t wGt = -1, wIr = -1, wIl = -1;                     // ws: G^T (bf16) and the fragment images of R, L^T during Alg. 2
+  int64_t wT1 = -1, wT2 = -1;                               // ws: images of R_{t-1}^T and R_t^T for the fused update after Alg. 2
   int64_t nv = 0;
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -117,6 +118,9 @@ struct adapm_ctx {
   DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
   std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T
   std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
+  DevList<RuBlockDev> rub;              // fused update after Alg. 2 (MFMA path): blocks, images of R^T, stripes
+  DevList<ImgItem> qt;
+  DevList<ProjItem> ru[6];              //   (rank class 32 / 64 / 128) x (fp32 / bf16 parameters)
   std::vector<GemmList> gemms;
   std::vector<Op> seq_refresh, seq_project;
 
@@ -344,17 +348,34 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       p = problem(r, n); p.X = Rp; p.g = 1.0; p.Out = fR(0); add_problem(c->gemms[l_pre], p);
       Lc = fL(0); Rc = fR(0);
     }
-    // m x n low-rank term of m^c (eq. 4): C = L'R' - L R, or L R without the correction
-    const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
-    p = problem(m, n);
-    if (hp.bias_correction) {
-      p.A1 = Lp; p.B1 = Rp; p.K1 = r; p.a1 = 1.0;
-      p.A2 = Lc; p.B2 = Rc; p.K2 = r; p.a2 = -1.0;
+    if (fast) {
+      // eq. 3-4 fused into the update: L'R' - L R (or L R without the correction) is built tile by tile
+      RuBlockDev d;
+      memset(&d, 0, sizeof d);
+      d.block = (int32_t)i; d.m = m; d.n = n; d.r = r; d.rc = rank_class(r);
+      if (b.v_mode == ADAPM_V_ELEMENT) { d.v_kind = 0; d.v_group_rows = 1; }
+      else { d.v_kind = 2; d.v_group_rows = b.v_mode == ADAPM_V_WHOLE ? (int32_t)b.rows : b.v_group_rows; }
+      d.param_dtype = b.param_dtype; d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
+      d.a1 = hp.bias_correction ? 1.f : 0.f; d.a2 = hp.bias_correction ? -1.f : 1.f;
+      d.l1 = Lp.ref; d.l2 = Lc.ref; d.off_img1 = L.wT1; d.off_img2 = L.wT2; d.off_v = L.sv;
+      c->rub.h.push_back(d);
+      for (int ch = 0; ch < (n + 63) / 64; ++ch) {
+        if (hp.bias_correction) c->qt.h.push_back(ImgItem{Rp, r, n, ch, d.rc, L.wT1});
+        c->qt.h.push_back(ImgItem{Rc, r, n, ch, d.rc, L.wT2});
+      }
     } else {
-      p.A1 = Lc; p.B1 = Rc; p.K1 = r; p.a1 = 1.0;
+      // m x n low-rank term of m^c (eq. 4): C = L'R' - L R, or L R without the correction
+      const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
+      p = problem(m, n);
+      if (hp.bias_correction) {
+        p.A1 = Lp; p.B1 = Rp; p.K1 = r; p.a1 = 1.0;
+        p.A2 = Lc; p.B2 = Rc; p.K2 = r; p.a2 = -1.0;
+      } else {
+        p.A1 = Lc; p.B1 = Rc; p.K1 = r; p.a1 = 1.0;
+      }
+      p.Out = C;
+      add_problem(c->gemms[l_epi], p);
     }
-    p.Out = C;
-    add_problem(c->gemms[l_epi], p);
     if (hp.refresh_period_T > 1) {
       // product-preserving orthonormalisation of R, always in fp64
       const Mat G64 = mat(SP_WS, 0, L.wG64, r, 1, DT_F64), Cinv = mat(SP_WS, 0, L.wCinv, r, 1, DT_F64);
@@ -403,10 +424,43 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
     seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"});
   }
   if (l_pre >= 0) seq.push_back(Op{gk, l_pre, 0, 0, "copy_factors"});
-  seq.push_back(Op{gk, l_epi, 0, 0, fast ? "reconstruct_mfma" : "reconstruct_f64"});
   const float cG = hp.bias_correction ? 1.f : 0.f;
   const float cC = hp.bias_correction ? (float)(b1 / (1.0 - b1)) : 1.f;
-  seq.push_back(Op{OP_UPDATE, fast ? 2 : 1, cG, cC, "update_lowrank"});
+  if (fast) {
+    // stripes of the fused update, per (rank class, parameter type), whole blocks dealt to XCDs
+    seq.push_back(Op{OP_QTIMG, 0, 0, 0, "update_factor_images"});
+    for (int cls = 0; cls < 6; ++cls) {
+      const int rank = 32 << (cls >> 1);
+      const int pdt = (cls & 1) ? ADAPM_BF16 : ADAPM_F32;
+      std::vector<size_t> ids;
+      for (size_t k = 0; k < c->rub.h.size(); ++k)
+        if (c->rub.h[k].rc == rank && c->rub.h[k].param_dtype == pdt) ids.push_back(k);
+      if (ids.empty()) continue;
+      std::stable_sort(ids.begin(), ids.end(), [&](size_t a, size_t b2) {
+        const RuBlockDev &x = c->rub.h[a], &y = c->rub.h[b2];
+        if (x.n != y.n) return x.n > y.n;
+        return (double)x.m * x.n > (double)y.m * y.n;
+      });
+      std::vector<ProjItem> per[NXCD];
+      double load[NXCD] = {0};
+      for (size_t k : ids) {
+        int x = 0;
+        for (int q = 1; q < NXCD; ++q) if (load[q] < load[x]) x = q;
+        const RuBlockDev& d = c->rub.h[k];
+        for (int r0 = 0; r0 < d.m; r0 += 128) per[x].push_back(ProjItem{(int32_t)k, r0});
+        load[x] += (double)d.m * d.n;
+      }
+      size_t longest = 0;
+      for (auto& q : per) longest = std::max(longest, q.size());
+      for (size_t q = 0; q < longest; ++q)
+        for (int x = 0; x < NXCD; ++x) c->ru[cls].h.push_back(q < per[x].size() ? per[x][q] : ProjItem{-1, 0});
+      static const char* names[3] = {"fused_refresh_update_r32", "fused_refresh_update_r64", "fused_refresh_update_r128"};
+      seq.push_back(Op{OP_REFRESH_UPDATE, cls, cG, cC, names[cls >> 1]});
+    }
+  } else {
+    seq.push_back(Op{gk, l_epi, 0, 0, "reconstruct_f64"});
+    seq.push_back(Op{OP_UPDATE, 1, cG, cC, "update_lowrank"});
+  }
   if (l_gram >= 0) {
     seq.push_back(Op{OP_GEMM, l_gram, 0, 0, "regauge_gram_f64"});
     seq.push_back(Op{OP_CHOL, fast ? 1 : 0, 0, 0, "regauge_cholesky_f64"});
@@ -538,7 +592,12 @@ void build_plan(adapm_ctx* c) {
       L.wGrr = walloc(es * r * r); L.wGpr = walloc(es * r * r);
       L.wGll = walloc(es * r * r); L.wGlp = walloc(es * r * r);
       L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
-      L.wC = walloc(4 * m * n);
+      if (L.path == PATH_FAST) {
+        L.wT1 = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
+        L.wT2 = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
+      } else {
+        L.wC = walloc(4 * m * n);
+      }
       if (L.path == PATH_FAST && stripe_ok(b)) {
         L.wGt = walloc(2 * m * n);
         L.wIr = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
@@ -570,9 +629,12 @@ void build_plan(adapm_ctx* c) {
     d.mom_mode = b.mom_mode; d.v_mode = b.v_mode;
     d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
     c->blocks.h.push_back(d);
-    auto& ew = c->ew[L.path == PATH_NONE ? 0 : (L.path == PATH_F64 ? 1 : 2)].h;
-    for (int64_t s = 0; s < d.numel; s += EW_CHUNK)
-      ew.push_back(EwItem{s, (int32_t)i, (int32_t)std::min<int64_t>(EW_CHUNK, d.numel - s)});
+    // low-rank blocks on the MFMA path are updated by the fused stripe kernels, not by the element-wise kernel
+    if (L.path != PATH_FAST) {
+      auto& ew = c->ew[L.path == PATH_NONE ? 0 : 1].h;
+      for (int64_t s = 0; s < d.numel; s += EW_CHUNK)
+        ew.push_back(EwItem{s, (int32_t)i, (int32_t)std::min<int64_t>(EW_CHUNK, d.numel - s)});
+    }
     if (b.v_mode != ADAPM_V_ELEMENT) {
       // on the MFMA path with T > 1 the fused kernel finishes fusable groups itself on steps with R held
       const int which = (L.path == PATH_FAST && hp.refresh_period_T > 1 && v_fusable(b)) ? 1 : 0;
@@ -631,7 +693,9 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   HIP_TRY(hipGetDevice(&dev));
   const size_t nb = c->table.size();
   size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
-                 bytes_of(c->tr.h) + bytes_of(c->sprob.h) + align_up(2 * nb * sizeof(void*));
+                 bytes_of(c->tr.h) + bytes_of(c->sprob.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) +
+                 align_up(2 * nb * sizeof(void*));
+  for (int i = 0; i < 6; ++i) total += bytes_of(c->ru[i].h);
   for (auto& l : c->img) total += bytes_of(l.h);
   for (auto& l : c->sit) total += bytes_of(l.h);
   for (int i = 0; i < 3; ++i) total += bytes_of(c->ew[i].h);
@@ -648,7 +712,8 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     return dst;
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
-  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->tr); PUT_LIST(c->sprob);
+  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->tr); PUT_LIST(c->sprob); PUT_LIST(c->rub); PUT_LIST(c->qt);
+  for (int i = 0; i < 6; ++i) PUT_LIST(c->ru[i]);
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
   for (int i = 0; i < 3; ++i) PUT_LIST(c->ew[i]);
@@ -835,6 +900,16 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
       case OP_STRIPE:
         launch_stripe(1 << (op.index % 3), c->sit[op.index].d, (int64_t)c->sit[op.index].h.size(), c->sprob.d, bs, s);
         break;
+      case OP_QTIMG:
+        launch_qt_image(c->qt.d, (int64_t)c->qt.h.size(), bs, s);
+        break;
+      case OP_REFRESH_UPDATE: {
+        StepScalars x = sc;
+        x.cG = op.cG; x.cC = op.cC;
+        launch_refresh_update(1 << (op.index >> 1), (op.index & 1) != 0, c->ru[op.index].d, (int64_t)c->ru[op.index].h.size(),
+                              c->rub.d, bs, x, s);
+        break;
+      }
       case OP_PROJ: {
         StepScalars x = sc;
         x.cG = c->hp.bias_correction ? 1.f : 0.f;

@@ -158,6 +158,21 @@ struct TrItem {            // one workgroup: one 64 x 64 tile of the bf16 transp
   int64_t off_out;         // workspace
 };
 
+// Fused update of a step that ran Alg. 2 (MFMA path): m^c = cG G + cC (a1 L1 Q1 + a2 L2 Q2) tile by tile, never
+// stored; (L1, Q1) = (L_{t-1}, R_{t-1}), (L2, Q2) = (L_t, R_t), (a1, a2) = (1, -1) with the bias correction of
+// eq. 4 and (0, 1) without it.  Q1, Q2 are given as bf16 (hi, lo) images of their transposes.
+struct RuBlockDev {
+  int32_t block;           // index into the gradient / parameter pointer tables
+  int32_t m, n, r, rc;     // rank and the rank class (32 / 64 / 128) of the kernel and the images
+  int32_t v_kind;          // 0 per element (updated here); 2 finished beforehand, one value per v_group_rows rows
+  int32_t v_group_rows;
+  int32_t param_dtype;
+  float lr_scale, wd, a1, a2;
+  Ref l1, l2;              // fp32, m x r, row stride r
+  int64_t off_img1, off_img2;   // workspace: images of Q1^T, Q2^T (layout of the held-R kernel's second image)
+  int64_t off_v;           // state
+};
+
 struct SketchItem {      // seeded start R_0 of one low-rank block
   int64_t off_R;         // state byte offset
   int64_t count;         // rank * cols
@@ -193,6 +208,9 @@ void launch_proj(int rt, bool w16, const ProjItem* items, int64_t nitems, const 
 void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s);
 void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s);
 void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
+void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
+void launch_refresh_update(int rt, bool w16, const ProjItem* items, int64_t nitems, const RuBlockDev* blocks, Bases b,
+                           StepScalars sc, hipStream_t s);
 void launch_transpose_bf16(const TrItem* items, int64_t nitems, Bases b, hipStream_t s);
 size_t proj_qf_bytes(int r, int n);     // sizes of the two images of Q kept for the fused step
 size_t proj_timg_bytes(int r, int n);

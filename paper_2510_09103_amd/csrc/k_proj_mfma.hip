@@ -591,6 +591,277 @@ __global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ 
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Fused update of a step that ran Alg. 2: W <- update(m^c), m^c = cG G + cC (a1 L1 Q1 + a2 L2 Q2), one
+// workgroup per 128-row stripe.  The rank-2r term is built tile by tile and never stored (eq. 3-4 fused
+// into the last line of Alg. 1).  Rounds of 32 columns: matrix-core wave (wr, p) holds rows 32 wr .. of
+// a_p L_p as A-fragments and builds the 32 x 32 tile of product p from the image of Q_p^T (copied
+// global -> LDS without registers, two buffers); the streaming waves add the two partial tiles, apply the
+// update and keep G, W of the next tiles in flight.
+template <bool W16>
+struct RuTail {
+  // one 8-element vector of a row: columns col .. col+7 of the stripe
+  static __device__ __forceinline__ void run(const float (&c)[8], const uint4& gq, const uint4 (&wq)[W16 ? 1 : 2],
+                                             bool ok, unsigned e, __amdgpu_buffer_rsrc_t rW, float* vp, bool v_elem,
+                                             float vinv, const StepScalars& sc, const UpdCoef& cf, float bound) {
+    const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
+    float g[8], mc[8], inv[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { g[2 * k] = bf16lo(gw[k]); g[2 * k + 1] = bf16hi(gw[k]); }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) mc[k] = fmaf(sc.cC, c[k], sc.cG * g[k]);
+    if (v_elem) {                   // per-element second moment
+      float vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if (ok) {
+        const float4 va = reinterpret_cast<const float4*>(vp)[0], vb = reinterpret_cast<const float4*>(vp)[1];
+        vv[0] = va.x; vv[1] = va.y; vv[2] = va.z; vv[3] = va.w;
+        vv[4] = vb.x; vv[5] = vb.y; vv[6] = vb.z; vv[7] = vb.w;
+      }
+      const float ob2 = 1.f - sc.beta2;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        vv[k] = sc.beta2 * vv[k] + ob2 * g[k] * g[k];
+        inv[k] = inv_denom_fast(vv[k], sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);   // -lr folded in
+      }
+      if (ok) {
+        reinterpret_cast<float4*>(vp)[0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+        reinterpret_cast<float4*>(vp)[1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) inv[k] = vinv;                    // -lr already folded in
+    }
+    if (W16) {
+      const uint32_t ww[4] = {wq[0].x, wq[0].y, wq[0].z, wq[0].w};
+      uint32_t o[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        o[k] = pack_bf16x2(apply_update_scaled(bf16lo(ww[k]), mc[2 * k], inv[2 * k], bound, cf.decay),
+                           apply_update_scaled(bf16hi(ww[k]), mc[2 * k + 1], inv[2 * k + 1], bound, cf.decay));
+      buf_store16(rW, ok ? e * 2u : OOB, make_uint4(o[0], o[1], o[2], o[3]));
+    } else {
+      const uint32_t ww[8] = {wq[0].x, wq[0].y, wq[0].z, wq[0].w, wq[W16 ? 0 : 1].x, wq[W16 ? 0 : 1].y, wq[W16 ? 0 : 1].z,
+                              wq[W16 ? 0 : 1].w};
+      uint32_t w[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        w[k] = __float_as_uint(apply_update_scaled(__uint_as_float(ww[k]), mc[k], inv[k], bound, cf.decay));
+      buf_store16(rW, ok ? e * 4u : OOB, make_uint4(w[0], w[1], w[2], w[3]));
+      buf_store16(rW, ok ? e * 4u + 16u : OOB, make_uint4(w[4], w[5], w[6], w[7]));
+    }
+  }
+};
+
+template <int RT, bool W16>
+__global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* __restrict__ items,
+                                                               const RuBlockDev* __restrict__ blocks, Bases bs,
+                                                               StepScalars sc) {
+  constexpr int R = 32 * RT;
+  constexpr int DS = R + 8;                       // LDS row stride of the staged factors (elements)
+  constexpr int BR = 32;                          // columns per round
+  constexpr int CR = BR + 8;                      // LDS row stride of a partial C tile (floats)
+  constexpr int TH = BR * R * 2;                  // bytes of one (hi or lo) half of a round's image of one product
+  constexpr int TP = 2 * TH;                      // ... of one product
+  constexpr int TBUF = 2 * TP;                    // ... of one round (both products)
+  constexpr int T64 = timg_chunk_bytes(R);        // the images are stored in 64-column chunks [hi|lo][64][R]
+  constexpr int C_TILE = BM * CR * 4;
+  constexpr int D_ONE = BM * DS * 2;              // one of (hi, lo) of one staged factor
+  constexpr int D_BYTES = 4 * D_ONE;
+  constexpr int P2_BYTES = 2 * TBUF + 4 * C_TILE;
+  constexpr int SMEM = D_BYTES > P2_BYTES ? D_BYTES : P2_BYTES;
+  constexpr int WV = W16 ? 1 : 2;
+  constexpr unsigned WE = W16 ? 2 : 4;
+  constexpr int D2 = 4;                           // tiles of G and W in flight per streaming thread
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+  __shared__ float vrow[BM];
+
+  const ProjItem item = items[blockIdx.x];
+  if (item.lr < 0) return;
+  const RuBlockDev B = blocks[item.lr];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool mrole = wave < 8;
+  const int mw = wave & 7, t512 = tid & 511, l32 = lane & 31, lh = lane >> 5;
+  const int m = B.m, n = B.n, r = B.r, row0 = item.row0;
+  const int nr = (n + BR - 1) / BR;               // 32-column tiles
+  const int NR = (nr + 1 + D2) / D2 * D2;         // rounds: nr + 2, rounded up to the prefetch depth
+  const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(bs.grads[B.block]);
+  char* __restrict__ W = reinterpret_cast<char*>(bs.params[B.block]);
+  float* __restrict__ vst = reinterpret_cast<float*>(bs.state + B.off_v);
+  lds_u8* const lds = (lds_u8*)smem;
+
+  if (B.v_kind != 0 && tid < BM && row0 + tid < m)
+    vrow[tid] = inv_denom_exact(vst[(row0 + tid) / B.v_group_rows], sc.inv_debias_v, sc.inv_debias_m, sc.eps);
+
+  // ------------------------------------------------------------------ a_p L_p -> bf16 (hi, lo) in LDS -> A-fragments
+  {
+    const bool vec4 = (r & 3) == 0;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const float* __restrict__ Lp = reinterpret_cast<const float*>(resolve(p == 0 ? B.l1 : B.l2, bs));
+      const float a = p == 0 ? B.a1 : B.a2;
+      uint16_t* Dh = reinterpret_cast<uint16_t*>(smem + (2 * p) * D_ONE);
+      uint16_t* Dl = reinterpret_cast<uint16_t*>(smem + (2 * p + 1) * D_ONE);
+#pragma unroll
+      for (int i = 0; i < (BM * R / 4) / NT; ++i) {
+        const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
+        float d[4] = {0.f, 0.f, 0.f, 0.f};
+        if (row0 + row < m && c4 < r && a != 0.f) {
+          const float* lp = Lp + (int64_t)(row0 + row) * r + c4;
+          if (vec4) {
+            const float4 t = *reinterpret_cast<const float4*>(lp);
+            d[0] = a * t.x; d[1] = a * t.y; d[2] = a * t.z; d[3] = a * t.w;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (c4 + e < r) d[e] = a * lp[e];
+          }
+        }
+        uint32_t h0, l0, h1, l1;
+        split_pair(d[0], d[1], h0, l0);
+        split_pair(d[2], d[3], h1, l1);
+        *reinterpret_cast<uint2*>(Dh + row * DS + c4) = make_uint2(h0, h1);
+        *reinterpret_cast<uint2*>(Dl + row * DS + c4) = make_uint2(l0, l1);
+      }
+    }
+  }
+  __syncthreads();
+
+  unsigned char* Cs = smem + 2 * TBUF;            // [2 buffers][2 products][BM][CR] fp32
+  const UpdCoef cf = make_coef(sc.lr, B.lr_scale, B.wd, sc.clip);
+  const float bound = -cf.neg_lrs * cf.clip;
+  if (mrole) {
+    const int wr = mw & 3, prod = mw >> 2;
+    bf16x8 dh[2 * RT], dl[2 * RT];
+#pragma unroll
+    for (int ks = 0; ks < 2 * RT; ++ks) {
+      dh[ks] = lds_frag(lds + (2 * prod) * D_ONE + ((32 * wr + l32) * DS + 16 * ks + 8 * lh) * 2);
+      dl[ks] = lds_frag(lds + (2 * prod + 1) * D_ONE + ((32 * wr + l32) * DS + 16 * ks + 8 * lh) * 2);
+    }
+    __syncthreads();                               // the factors are in registers, their LDS is free
+    // fragment offsets inside one half-image: row = column l32 of the tile; the swizzle of the stored image
+    // depends on the column inside its 64-column chunk, which agrees with l32 in the bits it uses
+    unsigned toff[2 * RT];
+#pragma unroll
+    for (int ks = 0; ks < 2 * RT; ++ks) toff[ks] = (unsigned)(l32 * R * 2 + timg_piece(R, l32, 2 * ks + lh) * 16);
+    const int coff = (32 * wr + 4 * lh) * CR + l32;
+    const char* img[2] = {bs.ws + B.off_img1, bs.ws + B.off_img2};
+    for (int j = 0; j < NR; ++j) {
+      // round j: start the copies of tile j (hi and lo halves of both products: 4 pieces of TH bytes shared
+      // by the eight waves), build tile j-1 from what landed in the last round
+      if (j < nr) {
+        for (int k = mw; k < 4 * TH / 1024; k += 8) {
+          const int q = k / (TH / 1024), piece = k % (TH / 1024);     // q = 2 * product + (lo half)
+          const char* src = img[q >> 1] + (int64_t)(j >> 1) * T64 + (q & 1) * (BK * R * 2) + (j & 1) * TH + piece * 1024;
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + lane * 16),
+                                           (__attribute__((address_space(3))) void*)(lds + (j & 1) * TBUF + q * TH + piece * 1024),
+                                           16, 0, 0);
+        }
+      }
+      if (j >= 1 && j <= nr) {
+        const unsigned th = lds_addr(lds) + ((j - 1) & 1) * TBUF + prod * TP, tl = th + TH;
+        f32x16 c;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 2 * RT; ks += 2) {
+          bf16x8 bh0 = lds_frag_raw(th + toff[ks]);
+          bf16x8 bl0 = lds_frag_raw(tl + toff[ks]);
+          bf16x8 bh1 = lds_frag_raw(th + toff[ks + 1]);
+          bf16x8 bl1 = lds_frag_raw(tl + toff[ks + 1]);
+          lds_wait(bh0, bl0, bh1, bl1);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bh0, c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks], bh0, c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bl0, c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks + 1], bh1, c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks + 1], bh1, c, 0, 0, 0);
+          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks + 1], bl1, c, 0, 0, 0);
+        }
+        lds_f32* cs = (lds_f32*)(lds + 2 * TBUF + (((j - 1) & 1) * 2 + prod) * C_TILE);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int p = 0; p < 4; ++p) cs[coff + (8 * q + p) * CR] = c[4 * q + p];
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // the images of tile j have landed
+      wg_barrier();
+    }
+  } else {
+    // this thread's 8-element vector of every 32-column tile: row t512 / 4, columns 8 (t512 % 4) ..
+    const unsigned rows_valid = (unsigned)(m - row0 < BM ? m - row0 : BM);
+    const __amdgpu_buffer_rsrc_t rG = make_rsrc(G + (int64_t)row0 * n, rows_valid * (unsigned)n * 2u);
+    const __amdgpu_buffer_rsrc_t rW = make_rsrc(W + (int64_t)row0 * n * WE, rows_valid * (unsigned)n * WE);
+    const int row = t512 >> 2, c8 = (t512 & 3) * 8;
+    const unsigned eoff = (unsigned)(row * n + c8);
+    const bool v_elem = B.v_kind == 0;
+    uint4 gq[D2], wq[D2][WV];
+#pragma unroll
+    for (int u = 0; u < D2; ++u) {
+      gq[u] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int k = 0; k < WV; ++k) wq[u][k] = make_uint4(0, 0, 0, 0);
+    }
+    auto fetch = [&](int j, uint4& g, uint4 (&w)[WV]) {
+      const bool ok = j * BR + c8 < n;
+      const unsigned e = eoff + (unsigned)(j * BR);
+      g = buf_load16(rG, ok ? e * 2u : OOB);
+#pragma unroll
+      for (int k = 0; k < WV; ++k) w[k] = buf_load16(rW, ok ? e * WE + 16u * k : OOB);
+    };
+    __syncthreads();
+    const float vinv = v_elem ? 0.f : vrow[row] * cf.neg_lrs;
+#pragma unroll
+    for (int u = 0; u + 2 < D2; ++u) {                             // tiles the loop does not fetch itself
+      fetch(u, gq[u], wq[u]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // round j: tail of tile j-2 from register set (j-2) % D2, then fetch tile j-2+D2 into that set
+    for (int jb = 0; jb < NR; jb += D2) {
+#pragma unroll
+      for (int u = 0; u < D2; ++u) {
+        const int su = (u + 2 * D2 - 2) % D2, j = jb + u - 2;
+        const bool ok = j >= 0 && j * BR + c8 < n && row0 + row < m;
+        const float* ca = reinterpret_cast<const float*>(Cs + ((j & 1) * 2) * C_TILE) + row * CR + c8;
+        const float* cb = ca + C_TILE / 4;
+        const float4 a0 = *reinterpret_cast<const float4*>(ca), a1 = *reinterpret_cast<const float4*>(ca + 4);
+        const float4 b0 = *reinterpret_cast<const float4*>(cb), b1 = *reinterpret_cast<const float4*>(cb + 4);
+        const float c[8] = {a0.x + b0.x, a0.y + b0.y, a0.z + b0.z, a0.w + b0.w, a1.x + b1.x, a1.y + b1.y, a1.z + b1.z, a1.w + b1.w};
+        const unsigned e = eoff + (unsigned)(j * BR);
+        RuTail<W16>::run(c, gq[su], wq[su], ok, e, rW, vst + (int64_t)row0 * n + e, v_elem, vinv, sc, cf, bound);
+        fetch(jb + u - 2 + D2, gq[su], wq[su]);
+        wg_barrier();
+      }
+    }
+  }
+}
+
+// Image of Q^T for the fused updates: per 64-column chunk [hi|lo][column j][R], 16-byte pieces of a row
+// XOR-swizzled (timg_piece); Q(a, k) = q[a * s0 + k * s1], rows r .. R-1 zero.
+__global__ __launch_bounds__(256) void qt_image_kernel(const ImgItem* __restrict__ items, Bases bs) {
+  const ImgItem it = items[blockIdx.x];
+  const int R = it.rc, n = it.K, c = it.c, rows = it.r;
+  const float* __restrict__ Q = reinterpret_cast<const float*>(resolve(it.q.ref, bs));
+  const int64_t s0 = it.q.s0, s1 = it.q.s1;
+  char* ti = bs.ws + it.off_img + (int64_t)c * timg_chunk_bytes(R);
+  const int pr = R / 8;
+  const int np2 = 2 * BK * pr;
+  for (int p = threadIdx.x; p < np2; p += 256) {
+    const int q = p % pr, j = (p / pr) % BK, hl = p / (BK * pr);
+    const int col = c * BK + j;
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int a0 = 8 * q + 2 * e;
+      const float x0 = (col < n && a0 < rows) ? Q[(int64_t)a0 * s0 + (int64_t)col * s1] : 0.f;
+      const float x1 = (col < n && a0 + 1 < rows) ? Q[(int64_t)(a0 + 1) * s0 + (int64_t)col * s1] : 0.f;
+      uint32_t h, l;
+      split_pair(x0, x1, h, l);
+      o[e] = hl ? l : h;
+    }
+    *reinterpret_cast<uint4*>(ti + ((int64_t)(hl * BK + j) * pr + timg_piece(R, j, q)) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
 // Alg. 2 stripe product: Out = A Q^T for 128 rows of A per workgroup (pass 1 of the kernel above, then a store).
 template <int RT>
 __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restrict__ items,
@@ -722,6 +993,26 @@ void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const Stripe
   if (rt == 1) hipLaunchKernelGGL((stripe_kernel<1>), grid, dim3(NT), 0, s, items, probs, b);
   else if (rt == 2) hipLaunchKernelGGL((stripe_kernel<2>), grid, dim3(NT), 0, s, items, probs, b);
   else hipLaunchKernelGGL((stripe_kernel<4>), grid, dim3(NT), 0, s, items, probs, b);
+}
+
+void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(qt_image_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
+}
+
+template <int RT>
+void launch_ru_rt(bool w16, dim3 grid, const ProjItem* items, const RuBlockDev* blocks, Bases b, StepScalars sc, hipStream_t s) {
+  if (w16) hipLaunchKernelGGL((refresh_update_kernel<RT, true>), grid, dim3(NT), 0, s, items, blocks, b, sc);
+  else hipLaunchKernelGGL((refresh_update_kernel<RT, false>), grid, dim3(NT), 0, s, items, blocks, b, sc);
+}
+
+void launch_refresh_update(int rt, bool w16, const ProjItem* items, int64_t nitems, const RuBlockDev* blocks, Bases b,
+                           StepScalars sc, hipStream_t s) {
+  if (nitems <= 0) return;
+  const dim3 grid((unsigned)nitems);
+  if (rt == 1) launch_ru_rt<1>(w16, grid, items, blocks, b, sc, s);
+  else if (rt == 2) launch_ru_rt<2>(w16, grid, items, blocks, b, sc, s);
+  else launch_ru_rt<4>(w16, grid, items, blocks, b, sc, s);
 }
 
 void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s) {
