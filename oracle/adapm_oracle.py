@@ -26,6 +26,7 @@ design notes of the repository):
 * Alg. 2 computes both gradients from the same (L, R) before either update.
 * clip(., 1) is an element-wise clamp to [-clip, clip].
 * lambda x_t is lambda W_t (pre-update W), inside the eta_t bracket.
+* global gradient-norm clipping (Sec. 5.1 set-ups) uses scale = min(1, c / (norm + 1e-6)).
 * "update frequency T": T = 1 is Alg. 1 verbatim.  For T > 1 Alg. 2 runs on
   steps with (t-1) mod T == 0 and is followed by a product-preserving re-gauge
   (R R^T = C C^T, R <- C^-1 R, L <- L C); on the other steps the arg-min of
@@ -247,15 +248,16 @@ def second_moment(blk: Block, hp: HParams, g: np.ndarray, v_prev: np.ndarray):
 def step_block(blk: Block, hp: HParams, W: np.ndarray, G: np.ndarray,
                st: Dict[str, np.ndarray], t: int, lr: float,
                refresh: str = "GD", state_dtype=np.float32,
-               want_aux: bool = False, W_alt: Optional[np.ndarray] = None):
+               want_aux: bool = False, W_alt: Optional[np.ndarray] = None, g_scale: float = 1.0):
     """One optimizer step on one block.  t is 1-based.
 
     W, G: storage arrays (float32, or uint16 bit patterns for bf16), any shape
     with rows*cols elements.  Returns (W_new storage, new state dict, aux).
     W_alt: a second parameter tensor pushed through the same last line (W enters Alg. 1
-    nowhere else); its result is returned as aux["W_alt_new"]."""
+    nowhere else); its result is returned as aux["W_alt_new"].
+    g_scale: factor of the global gradient clipping; the method then sees g_scale * G."""
     m_, n_ = blk.rows, blk.cols
-    g = load(G, blk.grad_dtype).reshape(m_, n_)
+    g = load(G, blk.grad_dtype).reshape(m_, n_) * g_scale
     w = load(W, blk.param_dtype).reshape(m_, n_)
     b1, b2 = hp.beta1, hp.beta2
     new: Dict[str, np.ndarray] = {}
@@ -318,18 +320,51 @@ def step_block(blk: Block, hp: HParams, W: np.ndarray, G: np.ndarray,
     return store(w_new, blk.param_dtype).reshape(np.shape(W)), new, aux
 
 
+def global_grad_scale(blocks: List[Block], Gs: List[np.ndarray], max_norm: float, eps: float = 1e-6):
+    """Global gradient-norm clipping of the paper's pre-training runs (Sec. 5.1, set-ups: "global
+    gradient clipping at a threshold of 1.0"): ONE factor for the whole table,
+        scale = min(1, max_norm / (||G||_2 + eps)),
+    ||G||_2 the Euclidean norm over every entry of every gradient.  The paper prints no formula; this is
+    the convention of the training code it builds on (a reading, listed in the design notes).
+    Gs are storage arrays (float32, or uint16 bit patterns for bf16).  Returns (scale, norm)."""
+    total = 0.0
+    for blk, g in zip(blocks, Gs):
+        g64 = load(g, blk.grad_dtype)
+        total += float(np.sum(g64 * g64))
+    norm = math.sqrt(total)
+    return min(1.0, float(max_norm) / (norm + eps)), norm
+
+
+def lr_cosine_warmup(t: int, peak_lr: float, min_lr: float, warmup_steps: int, total_steps: int) -> float:
+    """Learning-rate schedule of the paper's pre-training runs (Sec. 5.1, set-ups: cosine decay with
+    2000 warm-up steps): linear from 0 to peak_lr over the warm-up, then half a cosine down to min_lr at
+    total_steps, constant min_lr afterwards.  t counts steps from 1."""
+    if warmup_steps > 0 and t <= warmup_steps:
+        return peak_lr * t / warmup_steps
+    if t >= total_steps:
+        return min_lr
+    x = (t - warmup_steps) / (total_steps - warmup_steps)
+    return min_lr + 0.5 * (peak_lr - min_lr) * (1.0 + math.cos(math.pi * x))
+
+
 def step(blocks: List[Block], hp: HParams, Ws: List[np.ndarray], Gs: List[np.ndarray],
          state: List[Dict[str, np.ndarray]], t: int, lr: float, refresh: str = "GD",
-         only: Optional[List[int]] = None, Ws_alt: Optional[List[np.ndarray]] = None):
+         only: Optional[List[int]] = None, Ws_alt: Optional[List[np.ndarray]] = None,
+         grad_clip: Optional[float] = None):
     """One step over a block table (blocks are independent; `only` selects a subset).
-    With Ws_alt, also returns the alternative parameters after the same update."""
+    With Ws_alt, also returns the alternative parameters after the same update.
+    With grad_clip, every gradient of the table is first multiplied by global_grad_scale(Gs, grad_clip)
+    (the norm is over ALL gradients handed in, whatever `only` selects)."""
+    g_scale = 1.0
+    if grad_clip is not None and grad_clip > 0 and math.isfinite(grad_clip):
+        g_scale, _ = global_grad_scale(blocks, Gs, grad_clip)
     idx = range(len(blocks)) if only is None else only
     Ws = list(Ws)
     state = list(state)
     alt = list(Ws_alt) if Ws_alt is not None else None
     for i in idx:
         Ws[i], state[i], aux = step_block(blocks[i], hp, Ws[i], Gs[i], state[i], t, lr, refresh,
-                                          W_alt=None if alt is None else alt[i])
+                                          W_alt=None if alt is None else alt[i], g_scale=g_scale)
         if alt is not None:
             alt[i] = aux["W_alt_new"]
     return (Ws, state) if alt is None else (Ws, state, alt)

@@ -513,3 +513,70 @@ def test_literal_solver_stays_finite_and_tracks_on_synthetic_gradients():
         assert np.isfinite(st["L"]).all() and np.isfinite(st["R"]).all() and np.isfinite(W).all()
         ratios.append(np.linalg.norm(aux["r"]) / np.linalg.norm(aux["M"]))
     assert ratios[0] > 0.9 and ratios[-1] < 0.3
+
+
+# ---------------------------------------------------------------------------------------------------
+# Pre-step of the paper's runs (Sec. 5.1, set-ups): global gradient-norm clipping, warm-up + cosine LR
+# ---------------------------------------------------------------------------------------------------
+def test_global_grad_scale_closed_form_and_brute_force():
+    blocks = [O.Block(2, 2, grad_dtype=O.F32), O.Block(1, 1, grad_dtype=O.F32), O.Block(2, 1, grad_dtype=O.BF16)]
+    Gs = [np.array([[3.0, 0.0], [0.0, 0.0]], np.float32), np.array([[4.0]], np.float32),
+          O.f64_to_bf16_bits(np.array([[12.0], [0.0]]))]
+    scale, norm = O.global_grad_scale(blocks, Gs, 1.0)
+    assert norm == 13.0                                    # 3-4-12: sqrt(9 + 16 + 144)
+    assert scale == 1.0 / (13.0 + 1e-6)
+    assert O.global_grad_scale(blocks, Gs, 20.0)[0] == 1.0  # below the threshold: untouched
+    rng = np.random.default_rng(0)
+    blocks = [O.Block(5, 3, grad_dtype=O.F32), O.Block(7, 1, grad_dtype=O.F32)]
+    Gs = [rng.standard_normal((5, 3)).astype(np.float32), rng.standard_normal((7, 1)).astype(np.float32)]
+    tot = 0.0
+    for g in Gs:                                            # scalar loop
+        for x in g.reshape(-1):
+            tot += float(x) * float(x)
+    scale, norm = O.global_grad_scale(blocks, Gs, 0.5)
+    assert abs(norm - math.sqrt(tot)) < 1e-12 and abs(scale - 0.5 / (math.sqrt(tot) + 1e-6)) < 1e-15
+    assert scale * norm <= 0.5                              # the clipped gradient is inside the ball
+
+
+def test_step_with_global_clipping_sees_the_scaled_gradient():
+    """Clipping is linear pre-processing: a step with clipping on G equals a step without clipping on the
+    explicitly scaled gradient; a threshold above the norm changes nothing."""
+    rng = np.random.default_rng(4)
+    blocks = [O.Block(12, 10, mom_mode=O.MOM_LOWRANK, rank=3, weight_decay=0.1),
+              O.Block(6, 4, mom_mode=O.MOM_FULL, v_mode=O.V_ROWGROUP, v_group_rows=2),
+              O.Block(5, 1, mom_mode=O.MOM_NONE, lr_scale=0.75)]
+    hp = O.HParams(K=3, T=1)
+    Ws = [rng.standard_normal((b.rows, b.cols)).astype(np.float32) for b in blocks]
+    Gs = [rng.standard_normal((b.rows, b.cols)).astype(np.float32) for b in blocks]
+    st = O.init_state(blocks, hp)
+    scale, norm = O.global_grad_scale(blocks, Gs, 1.0)
+    assert norm > 1.0 and scale < 1.0
+    W1, S1 = O.step(blocks, hp, Ws, Gs, st, 1, 1e-2, grad_clip=1.0)
+    W2, S2 = Ws, st
+    W2 = list(W2); S2 = list(S2)
+    for i, b in enumerate(blocks):
+        W2[i], S2[i], _ = O.step_block(b, hp, Ws[i], Gs[i], st[i], 1, 1e-2, g_scale=scale)
+    for a, b_ in zip(W1, W2):
+        np.testing.assert_array_equal(a, b_)
+    # scaled fp32 copies of G give the same result up to the rounding of the copy
+    G3 = [(g.astype(np.float64) * scale).astype(np.float32) for g in Gs]
+    W3, _ = O.step(blocks, hp, Ws, G3, st, 1, 1e-2)
+    for a, b_ in zip(W1, W3):
+        np.testing.assert_allclose(a, b_, rtol=0, atol=2e-7)
+    W4, S4 = O.step(blocks, hp, Ws, Gs, st, 1, 1e-2, grad_clip=10.0 * norm)
+    W5, S5 = O.step(blocks, hp, Ws, Gs, st, 1, 1e-2)
+    for a, b_ in zip(W4, W5):
+        np.testing.assert_array_equal(a, b_)
+
+
+def test_lr_schedule_warmup_then_cosine():
+    peak, lo, wu, tot = 6e-4, 6e-5, 2000, 100000
+    f = lambda t: O.lr_cosine_warmup(t, peak, lo, wu, tot)
+    assert f(1) == peak / wu and f(1000) == peak / 2 and f(wu) == peak          # linear warm-up reaching the peak
+    assert f(tot) == lo and f(tot + 5) == lo                                     # floor from the last step on
+    mid = (wu + tot) // 2
+    assert abs(f(mid) - 0.5 * (peak + lo)) < 1e-12                               # half-way down at the mid-point
+    xs = [f(t) for t in range(wu, tot + 1, 997)]
+    assert all(a >= b for a, b in zip(xs, xs[1:]))                               # monotone decay
+    q = wu + (tot - wu) // 4
+    assert abs(f(q) - (lo + 0.5 * (peak - lo) * (1 + math.cos(math.pi / 4)))) < 1e-12
