@@ -85,6 +85,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-literal", action="store_true")
     ap.add_argument("--grad-sets", type=int, default=2)
+    ap.add_argument("--grad-clip", type=float, default=0.0, help="global gradient-norm clipping threshold (0 = off)")
     ap.add_argument("--rank", type=int, default=0, help="override the rank of every low-rank block (rank / T sweeps)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -113,7 +114,7 @@ def main():
 
     def make(T):
         return AdaPM(wl.blocks, make_hparams(beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, clip=wl.clip, K=wl.K, T=T),
-                     device=dev)
+                     device=dev, grad_clip=args.grad_clip)
 
     def run(opt, t0, nsteps):
         for i in range(nsteps):
@@ -210,7 +211,7 @@ def main():
         "config": {"workload": args.workload, "blocks": len(wl.blocks), "params": wl.numel, "refresh_period_T": args.T,
                    "refresh_steps_in_timed_region": n_refresh, "rank": max([b.rank for b in wl.blocks] + [0]),
                    "second_moment": "blockwise" if any(b.v_mode != "element" for b in wl.blocks) else "element",
-                   "grad_sets_rotated": len(grad_sets)},
+                   "grad_sets_rotated": len(grad_sets), "global_grad_clip": args.grad_clip},
         "device_ms_per_step": dev_ms / K,
         "achieved_algorithmic_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "algorithmic_bytes_per_step": step_bytes,

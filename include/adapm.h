@@ -125,6 +125,24 @@ adapm_status_t adapm_state_loaded(adapm_ctx* ctx);
 adapm_status_t adapm_step(adapm_ctx* ctx, void* const* params_dev, const void* const* grads_dev,
                           void* state_dev, void* workspace_dev, int64_t step, float lr, void* stream);
 
+/* Global gradient-norm clipping of the paper's pre-training runs (Sec. 5.1, set-ups: threshold 1.0),
+ * folded into the step.  After adapm_set_grad_clip(ctx, c) with c > 0, every adapm_step first sums the
+ * squares of all gradients of the table on the device (fixed order, fp64 partial sums), derives
+ *     factor = min(1, c / (||G||_2 + 1e-6))
+ * there, and uses factor * G wherever the method uses G (second moment, momentum, Alg. 2, update); the
+ * caller's gradients are not modified and nothing is read back.  c <= 0 or +inf switches it off (the
+ * default); NaN is ADAPM_EINVAL.  Costs one extra pass over the gradients. */
+adapm_status_t adapm_set_grad_clip(adapm_ctx* ctx, float max_norm);
+
+/* Norm and factor of the last clipped adapm_step that used workspace_dev (device pointer): copies two
+ * floats to the host and synchronises `stream`.  Either output may be NULL. */
+adapm_status_t adapm_last_grad_norm(adapm_ctx* ctx, const void* workspace_dev, void* stream, float* norm, float* scale);
+
+/* Learning-rate schedule of the same runs (Sec. 5.1, set-ups: cosine decay with warm-up), a host helper
+ * for the `lr` argument of adapm_step: linear from 0 to peak_lr over warmup_steps, half a cosine down to
+ * min_lr at total_steps, min_lr afterwards.  step counts from 1. */
+float adapm_lr_cosine_warmup(int64_t step, float peak_lr, float min_lr, int64_t warmup_steps, int64_t total_steps);
+
 /* Number of kernel launches the last adapm_step enqueued (0 before the first). */
 int64_t adapm_last_launch_count(const adapm_ctx* ctx);
 

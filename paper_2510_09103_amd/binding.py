@@ -42,7 +42,7 @@ class adapm_hparams_t(C.Structure):
 EXPORTS = ["adapm_init", "adapm_state_bytes", "adapm_workspace_bytes", "adapm_state_offsets",
            "adapm_state_init", "adapm_state_loaded", "adapm_step", "adapm_last_launch_count", "adapm_algorithmic_bytes",
            "adapm_algorithmic_flops", "adapm_profile_enable", "adapm_profile_read", "adapm_last_error",
-           "adapm_destroy"]
+           "adapm_set_grad_clip", "adapm_last_grad_norm", "adapm_lr_cosine_warmup", "adapm_destroy"]
 
 
 def _load() -> C.CDLL:
@@ -62,6 +62,12 @@ def _load() -> C.CDLL:
     lib.adapm_state_offsets.argtypes = [P, C.c_int64] + [C.POINTER(C.c_size_t)] * 4
     lib.adapm_state_init.restype = C.c_int
     lib.adapm_state_init.argtypes = [P, P, P]
+    lib.adapm_set_grad_clip.restype = C.c_int
+    lib.adapm_set_grad_clip.argtypes = [P, C.c_float]
+    lib.adapm_last_grad_norm.restype = C.c_int
+    lib.adapm_last_grad_norm.argtypes = [P, P, P, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    lib.adapm_lr_cosine_warmup.restype = C.c_float
+    lib.adapm_lr_cosine_warmup.argtypes = [C.c_int64, C.c_float, C.c_float, C.c_int64, C.c_int64]
     lib.adapm_state_loaded.restype = C.c_int
     lib.adapm_state_loaded.argtypes = [P]
     lib.adapm_step.restype = C.c_int
@@ -150,6 +156,21 @@ def adapm_algorithmic_bytes(ctx, refresh_step: bool) -> float:
 
 def adapm_algorithmic_flops(ctx, refresh_step: bool) -> float:
     return lib.adapm_algorithmic_flops(ctx, 1 if refresh_step else 0)
+
+
+def adapm_set_grad_clip(ctx, max_norm: float):
+    _check(lib.adapm_set_grad_clip(ctx, C.c_float(max_norm)))
+
+
+def adapm_last_grad_norm(ctx, workspace_ptr: int, stream: int = 0):
+    """(norm, factor) of the last clipped step; synchronises the stream."""
+    norm, scale = C.c_float(), C.c_float()
+    _check(lib.adapm_last_grad_norm(ctx, C.c_void_p(workspace_ptr), C.c_void_p(stream), C.byref(norm), C.byref(scale)))
+    return norm.value, scale.value
+
+
+def adapm_lr_cosine_warmup(step: int, peak_lr: float, min_lr: float, warmup_steps: int, total_steps: int) -> float:
+    return float(lib.adapm_lr_cosine_warmup(step, peak_lr, min_lr, warmup_steps, total_steps))
 
 
 def adapm_profile_enable(ctx, on: bool):

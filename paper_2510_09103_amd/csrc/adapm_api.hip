@@ -60,7 +60,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -104,11 +104,14 @@ struct adapm_ctx {
   std::vector<Layout> lay;
   size_t state_bytes = 0, ws_bytes = 0;
   int64_t off_partials = -1;
+  int64_t off_gn_partials = -1, off_gn_out = -1;   // ws: global gradient norm (partial sums; norm and factor)
+  float grad_clip = 0.f;                           // threshold of the global gradient-norm clipping; <= 0: off
 
   DevList<BlockDev> blocks;
   DevList<EwItem> ew[3];        // 0: full / no momentum; 1: low-rank, F64 path; 2: low-rank, MFMA path
   DevList<VsItem> vs[2];        // 0: every step; 1: only on steps that run Alg. 2 (fused elsewhere)
   DevList<VfItem> vf[2];
+  DevList<VsItem> gn;           // every gradient in pieces: sums of squares for the global norm
   DevList<SketchItem> sk;
   DevList<CholItem> chol[2];    // per path
   DevList<LrBlockDev> lrb;
@@ -323,8 +326,8 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, n, m});
       } else {
-        p = problem(m, r); p.A1 = G; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = P; add_problem(A, p);
-        p = problem(r, n); p.A1 = T(Lc); p.B1 = G; p.K1 = m; p.a1 = 1; p.Out = S; add_problem(A, p);
+        p = problem(m, r); p.A1 = G; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.scale_g = 1; p.Out = P; add_problem(A, p);
+        p = problem(r, n); p.A1 = T(Lc); p.B1 = G; p.K1 = m; p.a1 = 1; p.scale_g = 1; p.Out = S; add_problem(A, p);
       }
       p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Grr; add_problem(A, p);
       p = problem(r, r); p.A1 = Rp; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Gpr; add_problem(A, p);
@@ -493,7 +496,7 @@ void plan_lowrank_project_f64(adapm_ctx* c) {
     const Mat P = mat(SP_WS, 0, L.wP, r, 1, DT_F64), D = mat(SP_WS, 0, L.wLa, r, 1, DT_F64);
     const Mat C = mat(SP_WS, 0, L.wC, n, 1, DT_F32);
     GemmProblem p;
-    p = problem(m, r); p.A1 = G; p.B1 = Qt; p.K1 = n; p.a1 = 1.0; p.Out = P; add_problem(c->gemms[l_p], p);
+    p = problem(m, r); p.A1 = G; p.B1 = Qt; p.K1 = n; p.a1 = 1.0; p.scale_g = 1; p.Out = P; add_problem(c->gemms[l_p], p);
     // L_t = b1 L' + (1-b1) G Q^T;  m^c = G + b1 (L' - G Q^T) Q   (or L_t Q without the correction)
     p = problem(m, r); p.X = Ls; p.Y = P; p.Out = D;
     if (hp.bias_correction) { p.g = b1; p.d = -b1; } else { p.g = b1; p.d = 1.0 - b1; }
@@ -662,6 +665,14 @@ void build_plan(adapm_ctx* c) {
     }
   }
   if (npart > 0) { c->off_partials = (int64_t)wo; wo += align_up(8 * (size_t)npart); }
+  // global gradient norm: one partial sum per piece of every gradient, then norm and factor (two floats)
+  for (int64_t i = 0; i < nb; ++i) {
+    const int64_t numel = c->table[i].rows * c->table[i].cols;
+    for (int64_t s0 = 0; s0 < numel; s0 += VS_CHUNK)
+      c->gn.h.push_back(VsItem{s0, (int64_t)c->gn.h.size(), (int32_t)i, (int32_t)std::min<int64_t>(VS_CHUNK, numel - s0), 0, 0});
+  }
+  c->off_gn_partials = (int64_t)wo; wo += align_up(8 * c->gn.h.size());
+  c->off_gn_out = (int64_t)wo; wo += align_up(8);
   c->ws_bytes = wo;
 
   // ---- every step starts with the v statistics and the full / no-momentum blocks
@@ -693,7 +704,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   HIP_TRY(hipGetDevice(&dev));
   const size_t nb = c->table.size();
   size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
-                 bytes_of(c->tr.h) + bytes_of(c->sprob.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) +
+                 bytes_of(c->tr.h) + bytes_of(c->sprob.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) +
                  align_up(2 * nb * sizeof(void*));
   for (int i = 0; i < 6; ++i) total += bytes_of(c->ru[i].h);
   for (auto& l : c->img) total += bytes_of(l.h);
@@ -712,7 +723,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     return dst;
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
-  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->tr); PUT_LIST(c->sprob); PUT_LIST(c->rub); PUT_LIST(c->qt);
+  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->tr); PUT_LIST(c->sprob); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn);
   for (int i = 0; i < 6; ++i) PUT_LIST(c->ru[i]);
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
@@ -832,6 +843,7 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
   bs.ws = (char*)workspace_dev;
   bs.params = (void* const*)c->d_ptrs;
   bs.grads = (const void* const*)(c->d_ptrs + nb);
+  bs.gscale = nullptr;
 
   StepScalars sc;
   sc.beta1 = c->hp.beta1; sc.beta2 = c->hp.beta2; sc.eps = c->hp.eps; sc.clip = c->hp.clip;
@@ -848,7 +860,10 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
 
   double* partials = c->off_partials >= 0 ? (double*)(bs.ws + c->off_partials) : nullptr;
   int64_t launches = 0;
-  const std::vector<Op>& seq = is_refresh(c, step) ? c->seq_refresh : c->seq_project;
+  const std::vector<Op>& body = is_refresh(c, step) ? c->seq_refresh : c->seq_project;
+  std::vector<Op> seq;
+  if (c->grad_clip > 0.f && std::isfinite(c->grad_clip)) seq.push_back(Op{OP_GRADNORM, 0, 0, 0, "grad_norm"});
+  seq.insert(seq.end(), body.begin(), body.end());
   for (const Op& op : seq) {
     hipEvent_t e0 = nullptr, e1 = nullptr;
     bool skipped = false;
@@ -860,6 +875,16 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
       HIP_TRY(hipEventRecord(e0, s));
     }
     switch (op.kind) {
+      case OP_GRADNORM: {
+        // sums of squares of every gradient (unscaled), then norm and factor; every later kernel reads the factor
+        double* gp = (double*)(bs.ws + c->off_gn_partials);
+        float* out = (float*)(bs.ws + c->off_gn_out);
+        launch_vstat(c->blocks.d, c->gn.d, (int64_t)c->gn.h.size(), gp, bs, sc.beta2, s);
+        launch_gradnorm_final(gp, (int64_t)c->gn.h.size(), c->grad_clip, out, s);
+        bs.gscale = out + 1;
+        ++launches;
+        break;
+      }
       case OP_VSTAT:
         launch_vstat(c->blocks.d, c->vs[op.index].d, (int64_t)c->vs[op.index].h.size(), partials, bs, sc.beta2, s);
         break;
@@ -969,6 +994,32 @@ adapm_status_t adapm_state_loaded(adapm_ctx* c) {
   if (!c) return fail(ADAPM_EINVAL, "ctx is null");
   c->split_ws = nullptr;
   return ADAPM_OK;
+}
+
+adapm_status_t adapm_set_grad_clip(adapm_ctx* c, float max_norm) {
+  if (!c) return fail(ADAPM_EINVAL, "ctx is null");
+  if (std::isnan(max_norm)) return fail(ADAPM_EINVAL, "max_norm is NaN");
+  c->grad_clip = (max_norm > 0.f && std::isfinite(max_norm)) ? max_norm : 0.f;
+  return ADAPM_OK;
+}
+
+adapm_status_t adapm_last_grad_norm(adapm_ctx* c, const void* workspace_dev, void* stream, float* norm, float* scale) {
+  if (!c || !workspace_dev) return fail(ADAPM_EINVAL, "ctx or workspace_dev is null");
+  if (c->off_gn_out < 0) return fail(ADAPM_ESTATE, "no plan");
+  float h[2] = {0.f, 1.f};
+  hipStream_t s = (hipStream_t)stream;
+  HIP_TRY(hipMemcpyAsync(h, (const char*)workspace_dev + c->off_gn_out, sizeof h, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (norm) *norm = h[0];
+  if (scale) *scale = h[1];
+  return ADAPM_OK;
+}
+
+float adapm_lr_cosine_warmup(int64_t step, float peak_lr, float min_lr, int64_t warmup_steps, int64_t total_steps) {
+  if (warmup_steps > 0 && step <= warmup_steps) return (float)((double)peak_lr * (double)step / (double)warmup_steps);
+  if (step >= total_steps) return min_lr;
+  const double x = (double)(step - warmup_steps) / (double)(total_steps - warmup_steps);
+  return (float)((double)min_lr + 0.5 * ((double)peak_lr - (double)min_lr) * (1.0 + std::cos(M_PI * x)));
 }
 
 int64_t adapm_last_launch_count(const adapm_ctx* c) { return c ? c->last_launches : 0; }

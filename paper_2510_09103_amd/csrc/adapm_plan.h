@@ -27,7 +27,11 @@ struct Bases {
   char* ws;
   const void* const* grads;   // device array of nblocks pointers
   void* const* params;        // device array of nblocks pointers
+  const float* gscale;        // device scalar of the global gradient clipping (the method sees gscale * G); null = 1
 };
+
+// factor that the global gradient-norm clipping puts on every gradient of this step
+__device__ __forceinline__ float grad_scale(const Bases& b) { return b.gscale ? *b.gscale : 1.f; }
 
 __device__ __forceinline__ char* resolve(const Ref& r, const Bases& b) {
   switch (r.space) {
@@ -55,6 +59,8 @@ struct GemmProblem {
   Mat A1, B1, A2, B2, X, Y, Out;
   int32_t M, N, K1, K2;
   double a1, a2, g, d;
+  int32_t scale_g;   // 1: the (single) product has the gradient as an operand and takes the clipping factor
+  int32_t pad;
 };
 
 struct GemmTile {
@@ -197,6 +203,7 @@ void launch_vstat(const BlockDev* blocks, const VsItem* items, int64_t nitems, d
                   float beta2, hipStream_t s);
 void launch_vfinal(const BlockDev* blocks, const VfItem* items, int64_t nitems, const double* partials, Bases b,
                    float beta2, hipStream_t s);
+void launch_gradnorm_final(const double* partials, int64_t nparts, float max_norm, float* out, hipStream_t s);
 void launch_update(const BlockDev* blocks, const EwItem* items, int64_t nitems, Bases b, StepScalars sc,
                    hipStream_t s);
 void launch_fill_zero(void* p, size_t bytes, hipStream_t s);

@@ -97,7 +97,8 @@ __global__ __launch_bounds__(256) void vstat_kernel(const BlockDev* __restrict__
     }
   }
   for (int64_t i = a1 + lane; i < e; i += 64) { float g = load1(G, blk.grad_dtype, i); acc += g * g; }
-  double sum = wave_sum((double)acc);
+  const float gs = grad_scale(b);                 // global clipping: the method sees gs * G
+  double sum = wave_sum((double)acc) * ((double)gs * (double)gs);
   if (lane == 0) {
     if (item.direct) {
       float* v = reinterpret_cast<float*>(b.state + blk.off_v) + item.out;
@@ -121,6 +122,27 @@ __global__ __launch_bounds__(256) void vfinal_kernel(const BlockDev* __restrict_
   *v = (float)((double)beta2 * (double)*v + (1.0 - (double)beta2) * (sum / (double)blk.group_elems));
 }
 
+// Global gradient-norm clipping: partial sums of squares of every gradient (made by vstat_kernel, one per
+// piece, no scaling) -> norm and factor, summed in a fixed order.  out[0] = norm, out[1] = factor.
+__global__ __launch_bounds__(1024) void gradnorm_final_kernel(const double* __restrict__ partials, int64_t nparts,
+                                                              float max_norm, float* __restrict__ out) {
+  __shared__ double red[1024];
+  double s = 0.0;
+  for (int64_t i = threadIdx.x; i < nparts; i += 1024) s += partials[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double norm = sqrt(red[0]);
+    const double f = (double)max_norm / (norm + 1e-6);
+    out[0] = (float)norm;
+    out[1] = (float)(f < 1.0 ? f : 1.0);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // fused update
 // ---------------------------------------------------------------------------
@@ -135,6 +157,7 @@ __global__ __launch_bounds__(256) void update_kernel(const BlockDev* __restrict_
   const float* C = blk.off_C >= 0 ? reinterpret_cast<const float*>(b.ws + blk.off_C) : nullptr;
   const UpdCoef cf = make_coef(sc.lr, blk.lr_scale, blk.wd, sc.clip);
   const float ob1 = 1.f - sc.beta1, ob2 = 1.f - sc.beta2;
+  const float gs = grad_scale(b);                 // global clipping: the method sees gs * G
   const int nvec = (item.count + 7) >> 3;
   const int64_t end = item.start + item.count;
   // group index of this thread's first vector; later vectors advance by 2048 elements
@@ -150,6 +173,10 @@ __global__ __launch_bounds__(256) void update_kernel(const BlockDev* __restrict_
     if (e + 8 <= end) {
       float g[8], w[8], inv[8], mc[8];
       load8(G, blk.grad_dtype, e, g);
+      if (gs != 1.f) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) g[k] *= gs;
+      }
       load8(W, blk.param_dtype, e, w);
       if (blk.v_mode == VM_ELEMENT) {
         float vv[8];
@@ -191,7 +218,7 @@ __global__ __launch_bounds__(256) void update_kernel(const BlockDev* __restrict_
     } else {
       int64_t gk = grp, rk = rem;
       for (int64_t i = e; i < end; ++i) {
-        const float g = load1(G, blk.grad_dtype, i);
+        const float g = load1(G, blk.grad_dtype, i) * gs;
         const float w = load1(W, blk.param_dtype, i);
         float vv;
         if (blk.v_mode == VM_ELEMENT) {
@@ -256,6 +283,10 @@ void launch_vfinal(const BlockDev* blocks, const VfItem* items, int64_t nitems, 
   if (nitems <= 0) return;
   hipLaunchKernelGGL(vfinal_kernel, dim3((unsigned)((nitems + 255) / 256)), dim3(256), 0, s, blocks, items, nitems,
                      partials, b, beta2);
+}
+
+void launch_gradnorm_final(const double* partials, int64_t nparts, float max_norm, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(gradnorm_final_kernel, dim3(1), dim3(1024), 0, s, partials, nparts, max_norm, out);
 }
 
 void launch_update(const BlockDev* blocks, const EwItem* items, int64_t nitems, Bases b, StepScalars sc,

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const GemmProblem* __restri
     for (int c = 0; c < 4; ++c) acc[q][c] = 0.0;
   if (P.K1 > 0) {
     product(P.A1, P.B1, P.M, P.N, P.K1, i0, j0, bs, As, Bs, acc);
-    const double a1 = P.a1;
+    const double a1 = P.a1 * (P.scale_g ? (double)grad_scale(bs) : 1.0);   // the gradient enters clipped
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll

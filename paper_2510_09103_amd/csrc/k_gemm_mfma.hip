@@ -208,7 +208,8 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma_kernel(const GemmProblem* __
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
   // the scalar factors ride on the A operand, so both products land in the same accumulators
-  if (P.K1 > 0) product(P.A1, P.B1, (float)P.a1, P.M, P.N, P.K1, i0, j0, bs, Ah, Al, Bh, Bl, acc);
+  // a product with the gradient as an operand takes the factor of the global clipping
+  if (P.K1 > 0) product(P.A1, P.B1, (float)P.a1 * (P.scale_g ? grad_scale(bs) : 1.f), P.M, P.N, P.K1, i0, j0, bs, Ah, Al, Bh, Bl, acc);
   if (P.K2 > 0) product(P.A2, P.B2, (float)P.a2, P.M, P.N, P.K2, i0, j0, bs, Ah, Al, Bh, Bl, acc);
   const char* Xb = P.X.ref.space != SP_NONE ? resolve(P.X.ref, bs) : nullptr;
   const char* Yb = P.Y.ref.space != SP_NONE ? resolve(P.Y.ref, bs) : nullptr;

@@ -305,6 +305,10 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   const ProjItem item = items[blockIdx.x];
   if (item.lr < 0) return;
   const LrBlockDev B = lrb[item.lr];
+  // global gradient clipping: the method sees gs * G.  G stays exact bf16 in the matrix products; the factor
+  // goes on their results (P), on the sums of squares (gs^2) and on the G term of m^c.
+  const float gs = grad_scale(bs);
+  sc.cG *= gs;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool mrole = wave < 8;                       // matrix-core waves / streaming waves
@@ -342,7 +346,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   if (!mrole) {                     // a row is covered by 8 consecutive lanes
 #pragma unroll
     for (int o = 1; o < 8; o <<= 1) { ss0 += __shfl_xor(ss0, o, 64); ss1 += __shfl_xor(ss1, o, 64); }
-    if ((t512 & 7) == 0) { rsum[t512 >> 3] = ss0; rsum[64 + (t512 >> 3)] = ss1; }
+    if ((t512 & 7) == 0) { rsum[t512 >> 3] = ss0 * (gs * gs); rsum[64 + (t512 >> 3)] = ss1 * (gs * gs); }
   }
   __syncthreads();
   if (B.v_kind == 1) {             // groups of v_group_rows rows inside the stripe: finish v here
@@ -377,7 +381,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
     if (row0 + row < m && c4 < r) {
       float* lp = Lst + (int64_t)(row0 + row) * r + c4;
       const float4 pv4 = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
-      const float pv[4] = {pv4.x, pv4.y, pv4.z, pv4.w};
+      const float pv[4] = {gs * pv4.x, gs * pv4.y, gs * pv4.z, gs * pv4.w};
       const float b1 = sc.beta1, ob1 = 1.f - sc.beta1;
       if (vec4) {
         const float4 t = *reinterpret_cast<const float4*>(lp);
@@ -414,7 +418,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   lds_u8* const Ts = lds;                             // [2][TB]
   unsigned char* Cs = smem + 2 * TB;                  // [2][BM][CS] fp32
   const UpdCoef cf = make_coef(sc.lr, B.lr_scale, B.wd, sc.clip);
-  const float ob2 = 1.f - sc.beta2;
+  const float ob2 = (1.f - sc.beta2) * (gs * gs);                  // per-element v sees (gs g)^2
   const float bound = -cf.neg_lrs * cf.clip;
   constexpr int WV = W16 ? 1 : 2;                                  // 16-byte pieces of W per 8 elements
   auto fetch_gw = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
@@ -603,7 +607,7 @@ struct RuTail {
   // one 8-element vector of a row: columns col .. col+7 of the stripe
   static __device__ __forceinline__ void run(const float (&c)[8], const uint4& gq, const uint4 (&wq)[W16 ? 1 : 2],
                                              bool ok, unsigned e, __amdgpu_buffer_rsrc_t rW, float* vp, bool v_elem,
-                                             float vinv, const StepScalars& sc, const UpdCoef& cf, float bound) {
+                                             float vinv, const StepScalars& sc, const UpdCoef& cf, float bound, float gs2) {
     const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
     float g[8], mc[8], inv[8];
 #pragma unroll
@@ -617,7 +621,7 @@ struct RuTail {
         vv[0] = va.x; vv[1] = va.y; vv[2] = va.z; vv[3] = va.w;
         vv[4] = vb.x; vv[5] = vb.y; vv[6] = vb.z; vv[7] = vb.w;
       }
-      const float ob2 = 1.f - sc.beta2;
+      const float ob2 = (1.f - sc.beta2) * gs2;                    // v sees the clipped gradient
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         vv[k] = sc.beta2 * vv[k] + ob2 * g[k] * g[k];
@@ -678,6 +682,8 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
   const ProjItem item = items[blockIdx.x];
   if (item.lr < 0) return;
   const RuBlockDev B = blocks[item.lr];
+  const float gs = grad_scale(bs);                // global gradient clipping: the method sees gs * G
+  sc.cG *= gs;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool mrole = wave < 8;
@@ -827,7 +833,7 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
         const float4 b0 = *reinterpret_cast<const float4*>(cb), b1 = *reinterpret_cast<const float4*>(cb + 4);
         const float c[8] = {a0.x + b0.x, a0.y + b0.y, a0.z + b0.z, a0.w + b0.w, a1.x + b1.x, a1.y + b1.y, a1.z + b1.z, a1.w + b1.w};
         const unsigned e = eoff + (unsigned)(j * BR);
-        RuTail<W16>::run(c, gq[su], wq[su], ok, e, rW, vst + (int64_t)row0 * n + e, v_elem, vinv, sc, cf, bound);
+        RuTail<W16>::run(c, gq[su], wq[su], ok, e, rW, vst + (int64_t)row0 * n + e, v_elem, vinv, sc, cf, bound, gs * gs);
         fetch(jb + u - 2 + D2, gq[su], wq[su]);
         wg_barrier();
       }
@@ -882,6 +888,7 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   const float* Ps = reinterpret_cast<const float*>(smem);
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);
   const int r = P.r;                  // rows of Q actually present (the image is zero-padded to R)
+  const float gs = grad_scale(bs);    // global gradient clipping: A is the gradient (or its transpose)
   if (!P.transpose_out) {
     const bool vec4 = (r & 3) == 0;
 #pragma unroll
@@ -889,7 +896,8 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
       const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
       if (row0 + row < M && c4 < r) {
         float* o = Out + (int64_t)(row0 + row) * r + c4;
-        const float4 v = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
+        float4 v = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
+        v.x *= gs; v.y *= gs; v.z *= gs; v.w *= gs;
         if (vec4) *reinterpret_cast<float4*>(o) = v;
         else {
           const float x[4] = {v.x, v.y, v.z, v.w};
@@ -904,7 +912,7 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
 #pragma unroll 4
     for (int i = 0; i < (BM * R) / NT; ++i) {
       const int id = tid + NT * i, j = id % BM, a = id / BM;
-      if (row0 + j < M && a < r) Out[(int64_t)a * M + row0 + j] = Ps[j * PS + a];
+      if (row0 + j < M && a < r) Out[(int64_t)a * M + row0 + j] = gs * Ps[j * PS + a];
     }
   }
 }

@@ -27,10 +27,13 @@ def make_hparams(beta1=0.9, beta2=0.95, eps=1e-8, clip=1.0, adam_debias=0, K=5, 
 
 
 class AdaPM:
-    def __init__(self, blocks: Sequence[BlockSpec], hp: B.adapm_hparams_t, device="cuda:0", allocate=True):
+    def __init__(self, blocks: Sequence[BlockSpec], hp: B.adapm_hparams_t, device="cuda:0", allocate=True,
+                 grad_clip: float = 0.0):
         self.blocks = list(blocks)
         self.hp = hp
         self.ctx = B.adapm_init([to_c_block(b) for b in self.blocks], hp)
+        if grad_clip:
+            B.adapm_set_grad_clip(self.ctx, grad_clip)
         self.state_bytes = B.adapm_state_bytes(self.ctx)
         self.workspace_bytes = B.adapm_workspace_bytes(self.ctx)
         self.device = torch.device(device)
@@ -59,6 +62,10 @@ class AdaPM:
             self._ptr_key = key
         B.adapm_step(self.ctx, self._pp, self._gp, self.state.data_ptr(), self.workspace.data_ptr(), t, lr,
                      torch.cuda.current_stream(self.device).cuda_stream)
+
+    def last_grad_norm(self):
+        """(norm, factor) of the last step with global gradient clipping."""
+        return B.adapm_last_grad_norm(self.ctx, self.workspace.data_ptr(), torch.cuda.current_stream(self.device).cuda_stream)
 
     # views into the flat state buffer (fp32), for tests and checkpoints
     def state_view(self, i: int):

@@ -74,7 +74,7 @@ def compare_params(got: np.ndarray, ref: np.ndarray, tol: float, tol_bf16: float
 class Pair:
     """The library and the oracle stepping side by side on one workload."""
 
-    def __init__(self, wl: WL.Workload, hp_kwargs=None, device="cuda:0", grad_scale=1.0):
+    def __init__(self, wl: WL.Workload, hp_kwargs=None, device="cuda:0", grad_scale=1.0, grad_clip=None):
         from paper_2510_09103_amd.optimizer import AdaPM, make_hparams
         hp_kwargs = dict(hp_kwargs or {})
         self.wl = wl
@@ -83,7 +83,8 @@ class Pair:
         self.hp_c = make_hparams(**base)
         ok = {k: v for k, v in base.items() if k != "contraction"}
         self.hp_o = O.HParams(**ok) if "seed" in ok else O.HParams(**ok, seed=0x5EED)
-        self.opt = AdaPM(wl.blocks, self.hp_c, device=device)
+        self.grad_clip = grad_clip
+        self.opt = AdaPM(wl.blocks, self.hp_c, device=device, grad_clip=grad_clip or 0.0)
         self.blocks_o = [oracle_block(b) for b in wl.blocks]
         self.state_o = O.init_state(self.blocks_o, self.hp_o)
         self.params = WL.initial_params(wl, device=device)
@@ -99,7 +100,12 @@ class Pair:
         self.opt.step(self.params, grads, self.t, lr)
         G_o = [to_np(g) for g in grads]
         self.W_o, self.state_o, forced = O.step(self.blocks_o, self.hp_o, self.W_o, G_o, self.state_o, self.t, lr,
-                                                only=oracle_only, Ws_alt=W_before)
+                                                only=oracle_only, Ws_alt=W_before, grad_clip=self.grad_clip)
+        if self.grad_clip:
+            # the norm and the factor the library derived on the device against the oracle's
+            norm, scale = self.opt.last_grad_norm()
+            s_o, n_o = O.global_grad_scale(self.blocks_o, G_o, self.grad_clip)
+            assert abs(norm - n_o) <= 1e-6 * n_o and abs(scale - s_o) <= 1e-6 * s_o, (norm, n_o, scale, s_o)
         # single-step check from identical parameters: bf16 results at most ONE ulp apart
         idx = range(len(self.wl.blocks)) if oracle_only is None else oracle_only
         for i in idx:

@@ -195,3 +195,22 @@ def test_gpt2_1p5b_state_and_traffic_figures():
     assert B.adapm_algorithmic_flops(ctx, False) == pytest.approx(4 * lr_mnr, rel=1e-12)
     assert abs(4 * lr_mnr / 1e12 - 0.755) < 0.001
     B.adapm_destroy(ctx)
+
+
+def test_lr_schedule_helper_matches_the_oracle():
+    peak, lo, wu, tot = 6e-4, 6e-5, 2000, 100000
+    for t in [1, 7, 1000, 2000, 2001, 30000, 51000, 99999, 100000, 123456]:
+        want = O.lr_cosine_warmup(t, peak, lo, wu, tot)
+        got = B.adapm_lr_cosine_warmup(t, peak, lo, wu, tot)
+        assert abs(got - want) <= 2e-7 * peak, (t, got, want)
+
+
+def test_grad_clip_setter_validates():
+    wl = WL.tiny_block()
+    ctx = B.adapm_init([to_c_block(b) for b in wl.blocks], make_hparams())
+    B.adapm_set_grad_clip(ctx, 1.0)
+    B.adapm_set_grad_clip(ctx, 0.0)
+    B.adapm_set_grad_clip(ctx, float("inf"))
+    with pytest.raises(B.AdapmError):
+        B.adapm_set_grad_clip(ctx, float("nan"))
+    B.adapm_destroy(ctx)

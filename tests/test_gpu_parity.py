@@ -129,6 +129,31 @@ def test_paper_partition_layer(shape, mini):
     run(WL.subset(full, names), 5, dict(T=3), tol_state=TOL16, tol_param=TOL16, check_every=2)
 
 
+@pytest.mark.parametrize("hp", [dict(T=1), dict(T=3)])
+def test_global_gradient_clipping_on_the_exact_path(hp):
+    """Sec. 5.1 set-ups: global gradient-norm clipping folded into the step (every regime, every kind of v)."""
+    hp = dict(hp, contraction=B.ADAPM_CONTRACT_F64)
+    pair, _ = run(mixed_table(), 6, hp, tol_state=TOL32, tol_param=TOL32, check_every=2, grad_clip=1.0)
+    assert pair.opt.last_grad_norm()[1] < 1.0              # the clipping was active
+
+
+@pytest.mark.parametrize("hp", [dict(T=1), dict(T=3), dict(T=2, bias_correction=0)])
+def test_global_gradient_clipping_on_the_mfma_path(hp):
+    hp = dict(hp, contraction=B.ADAPM_CONTRACT_BF16X2)
+    pair, _ = run(ragged_bf16_table(), 6, hp, tol_state=TOL16, tol_param=TOL16, check_every=2, grad_clip=0.5)
+    assert pair.opt.last_grad_norm()[1] < 1.0
+    run(odd_rank_table(), 4, hp, tol_state=TOL16, tol_param=TOL16, check_every=2, grad_clip=0.5)
+
+
+def test_global_gradient_clipping_above_the_norm_changes_nothing():
+    wl = ragged_bf16_table()
+    a, _ = run(wl, 3, dict(T=2, contraction=B.ADAPM_CONTRACT_BF16X2), tol_state=TOL16, tol_param=TOL16, grad_clip=1e9)
+    b, _ = run(wl, 3, dict(T=2, contraction=B.ADAPM_CONTRACT_BF16X2), tol_state=TOL16, tol_param=TOL16)
+    assert a.opt.last_grad_norm()[1] == 1.0
+    for x, y in zip(a.params, b.params):
+        assert torch.equal(x, y)
+
+
 def test_literal_zero_start_stays_zero_on_gpu():
     wl = WL.subset(WL.tiny_block(), ["attn.q"])
     pair, _ = run(wl, 3, dict(seed=0))
