@@ -19,6 +19,36 @@ __device__ __forceinline__ double load_el(const char* base, int dtype, int64_t i
   return reinterpret_cast<const double*>(base)[idx];
 }
 
+// Four elements of an operand tile per thread.  Every load is issued unconditionally on a clamped (always
+// valid) index and masked afterwards: a load inside its own bounds check would wait for the previous one.
+template <int DT>
+__device__ __forceinline__ void fetch4_t(const char* base, const int64_t (&idx)[4], const bool (&ok)[4], double (&x)[4]) {
+  if (DT == DT_F32) {
+    float r[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) r[p] = reinterpret_cast<const float*>(base)[ok[p] ? idx[p] : 0];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) x[p] = ok[p] ? (double)r[p] : 0.0;
+  } else if (DT == DT_BF16) {
+    uint16_t r[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) r[p] = reinterpret_cast<const uint16_t*>(base)[ok[p] ? idx[p] : 0];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) x[p] = ok[p] ? (double)__uint_as_float(((uint32_t)r[p]) << 16) : 0.0;
+  } else {
+    double r[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) r[p] = reinterpret_cast<const double*>(base)[ok[p] ? idx[p] : 0];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) x[p] = ok[p] ? r[p] : 0.0;
+  }
+}
+__device__ __forceinline__ void fetch4(const char* base, int dtype, const int64_t (&idx)[4], const bool (&ok)[4], double (&x)[4]) {
+  if (dtype == DT_F32) fetch4_t<DT_F32>(base, idx, ok, x);
+  else if (dtype == DT_BF16) fetch4_t<DT_BF16>(base, idx, ok, x);
+  else fetch4_t<DT_F64>(base, idx, ok, x);
+}
+
 __device__ __forceinline__ void product(const Mat& A, const Mat& B, int M, int N, int K, int i0, int j0,
                                         const Bases& bs, double (*As)[TM + PAD], double (*Bs)[TN + PAD],
                                         double acc[4][4]) {
@@ -26,22 +56,36 @@ __device__ __forceinline__ void product(const Mat& A, const Mat& B, int M, int N
   const char* Bb = resolve(B.ref, bs);
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const bool a_kfast = (A.s1 == 1), b_jfast = (B.s1 == 1);
-  for (int k0 = 0; k0 < K; k0 += TK) {
+  int ia[4], ka[4], jb[4], kb[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int idx = tid + p * 256;
+    if (a_kfast) { ka[p] = idx & 15; ia[p] = idx >> 4; } else { ia[p] = idx & 63; ka[p] = idx >> 6; }
+    if (b_jfast) { jb[p] = idx & 63; kb[p] = idx >> 6; } else { kb[p] = idx & 15; jb[p] = idx >> 4; }
+  }
+  auto fetch = [&](int k0, double (&xa)[4], double (&xb)[4]) {
+    int64_t ix[4];
+    bool ok[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      const int idx = tid + p * 256;
-      int i, k;
-      if (a_kfast) { k = idx & 15; i = idx >> 4; } else { i = idx & 63; k = idx >> 6; }
-      double x = 0.0;
-      if (i0 + i < M && k0 + k < K) x = load_el(Ab, A.dtype, (int64_t)(i0 + i) * A.s0 + (int64_t)(k0 + k) * A.s1);
-      As[k][i] = x;
-      int j, kb;
-      if (b_jfast) { j = idx & 63; kb = idx >> 6; } else { kb = idx & 15; j = idx >> 4; }
-      double y = 0.0;
-      if (j0 + j < N && k0 + kb < K) y = load_el(Bb, B.dtype, (int64_t)(k0 + kb) * B.s0 + (int64_t)(j0 + j) * B.s1);
-      Bs[kb][j] = y;
+      ok[p] = i0 + ia[p] < M && k0 + ka[p] < K;
+      ix[p] = (int64_t)(i0 + ia[p]) * A.s0 + (int64_t)(k0 + ka[p]) * A.s1;
     }
+    fetch4(Ab, A.dtype, ix, ok, xa);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      ok[p] = j0 + jb[p] < N && k0 + kb[p] < K;
+      ix[p] = (int64_t)(k0 + kb[p]) * B.s0 + (int64_t)(j0 + jb[p]) * B.s1;
+    }
+    fetch4(Bb, B.dtype, ix, ok, xb);
+  };
+  double xa[4], xb[4];
+  fetch(0, xa, xb);
+  for (int k0 = 0; k0 < K; k0 += TK) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) { As[ka[p]][ia[p]] = xa[p]; Bs[kb[p]][jb[p]] = xb[p]; }
     __syncthreads();
+    if (k0 + TK < K) fetch(k0 + TK, xa, xb);       // the next chunk travels while this one is multiplied
 #pragma unroll
     for (int kk = 0; kk < TK; ++kk) {
       double a[4], b[4];
@@ -93,17 +137,24 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const GemmProblem* __restri
   const char* Xb = P.X.ref.space != SP_NONE ? resolve(P.X.ref, bs) : nullptr;
   const char* Yb = P.Y.ref.space != SP_NONE ? resolve(P.Y.ref, bs) : nullptr;
   char* Ob = resolve(P.Out.ref, bs);
+  // X and Y are read unconditionally on clamped indices (independent loads); the bounds check guards the store
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int i = i0 + ty * 4 + q;
-    if (i >= P.M) continue;
+    const int ic = i < P.M ? i : 0;
+    double xv[4] = {0.0, 0.0, 0.0, 0.0}, yv[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const int j = j0 + tx * 4 + c;
-      if (j >= P.N) continue;
-      double val = acc[q][c];
-      if (Xb) val = fma(P.g, load_el(Xb, P.X.dtype, (int64_t)i * P.X.s0 + (int64_t)j * P.X.s1), val);
-      if (Yb) val = fma(P.d, load_el(Yb, P.Y.dtype, (int64_t)i * P.Y.s0 + (int64_t)j * P.Y.s1), val);
+      const int jc = j < P.N ? j : 0;
+      if (Xb) xv[c] = load_el(Xb, P.X.dtype, (int64_t)ic * P.X.s0 + (int64_t)jc * P.X.s1);
+      if (Yb) yv[c] = load_el(Yb, P.Y.dtype, (int64_t)ic * P.Y.s0 + (int64_t)jc * P.Y.s1);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int j = j0 + tx * 4 + c;
+      if (i >= P.M || j >= P.N) continue;
+      const double val = fma(P.d, yv[c], fma(P.g, xv[c], acc[q][c]));
       const int64_t o = (int64_t)i * P.Out.s0 + (int64_t)j * P.Out.s1;
       if (P.Out.dtype == DT_F64) reinterpret_cast<double*>(Ob)[o] = val;
       else reinterpret_cast<float*>(Ob)[o] = (float)val;
