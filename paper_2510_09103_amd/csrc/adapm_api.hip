@@ -55,12 +55,13 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wG64 = -1, wCinv = -1, wC = -1;
   int64_t wQf = -1, wTimg = -1;                             // ws: bf16 (hi, lo) images of Q and Q^T
   int64_t wGt = -1, wIr = -1, wIl = -1;                     // ws: G^T (bf16) and the fragment images of R, L^T during Alg. 2
+  int64_t wIr0 = -1, wIl0 = -1;                             // ws: the same images of R_{t-1}, L_{t-1}^T (first iteration; Gram matrices)
   int64_t wT1 = -1, wT2 = -1;                               // ws: images of R_{t-1}^T and R_t^T for the fused update after Alg. 2
   int64_t nv = 0;
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -121,6 +122,7 @@ struct adapm_ctx {
   DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
   std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T
   std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
+  std::vector<DevList<GramItem>> gram;  //   ... per GD iteration: the four r x r Gram-type products, from the images
   DevList<RuBlockDev> rub;              // fused update after Alg. 2 (MFMA path): blocks, images of R^T, stripes
   DevList<ImgItem> qt;
   DevList<ProjItem> ru[6];              //   (rank class 32 / 64 / 128) x (fp32 / bf16 parameters)
@@ -279,7 +281,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   constexpr int NXCD = 8;
   struct StripeWork { int prob; int64_t M, K; };
   std::vector<std::vector<StripeWork>> swork(fast ? 3 * n_eff : 0);
-  if (fast) { c->img.resize(n_eff); c->sit.resize(3 * n_eff); }
+  if (fast) { c->img.resize(n_eff); c->sit.resize(3 * n_eff); c->gram.resize(n_eff); }
   const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list(fast) : -1;
   const int l_epi = new_list(fast);
   const int l_gram = hp.refresh_period_T > 1 ? new_list(false) : -1;
@@ -314,25 +316,34 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
             for (int tj = 0; tj < (n + 63) / 64; ++tj) c->tr.h.push_back(TrItem{(int32_t)i, m, n, ti, tj, 0, L.wGt});
         Mat LcT = T(Lc);
         const int rc = rank_class(r);
-        for (int ch = 0; ch < (n + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{Rc, r, n, ch, rc, L.wIr});
-        for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, rc, L.wIl});
+        // the images of the first iteration are those of (R_{t-1}, L_{t-1}^T) and are kept for the Gram matrices
+        const int64_t iR = e == 0 ? L.wIr0 : L.wIr, iL = e == 0 ? L.wIl0 : L.wIl;
+        for (int ch = 0; ch < (n + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{Rc, r, n, ch, rc, iR});
+        for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, rc, iL});
+        // R R^T, R' R^T (contraction over n) and L^T L, L^T L' (over m), longest contraction first
+        c->gram[e].h.push_back(GramItem{iR, iR, L.wGrr, n, r, rc, 0});
+        c->gram[e].h.push_back(GramItem{L.wIr0, iR, L.wGpr, n, r, rc, 0});
+        c->gram[e].h.push_back(GramItem{iL, iL, L.wGll, m, r, rc, 0});
+        c->gram[e].h.push_back(GramItem{iL, L.wIl0, L.wGlp, m, r, rc, 0});
         const int cls = rc == 32 ? 0 : (rc == 64 ? 1 : 2);
         StripeProb sp;
         memset(&sp, 0, sizeof sp);
-        sp.a = G.ref; sp.M = m; sp.K = n; sp.r = r; sp.rc = rc; sp.transpose_out = 0; sp.off_img = L.wIr; sp.off_out = L.wP;
+        sp.a = G.ref; sp.M = m; sp.K = n; sp.r = r; sp.rc = rc; sp.transpose_out = 0; sp.off_img = iR; sp.off_out = L.wP;
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
-        sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = L.wIl; sp.off_out = L.wS;
+        sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = iL; sp.off_out = L.wS;
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, n, m});
       } else {
         p = problem(m, r); p.A1 = G; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.scale_g = 1; p.Out = P; add_problem(A, p);
         p = problem(r, n); p.A1 = T(Lc); p.B1 = G; p.K1 = m; p.a1 = 1; p.scale_g = 1; p.Out = S; add_problem(A, p);
       }
-      p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Grr; add_problem(A, p);
-      p = problem(r, r); p.A1 = Rp; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Gpr; add_problem(A, p);
-      p = problem(r, r); p.A1 = T(Lc); p.B1 = Lc; p.K1 = m; p.a1 = 1; p.Out = Gll; add_problem(A, p);
-      p = problem(r, r); p.A1 = T(Lc); p.B1 = Lp; p.K1 = m; p.a1 = 1; p.Out = Glp; add_problem(A, p);
+      if (!(fast && stripe_ok(b))) {
+        p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Grr; add_problem(A, p);
+        p = problem(r, r); p.A1 = Rp; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.Out = Gpr; add_problem(A, p);
+        p = problem(r, r); p.A1 = T(Lc); p.B1 = Lc; p.K1 = m; p.a1 = 1; p.Out = Gll; add_problem(A, p);
+        p = problem(r, r); p.A1 = T(Lc); p.B1 = Lp; p.K1 = m; p.a1 = 1; p.Out = Glp; add_problem(A, p);
+      }
       GemmList& Bl = c->gemms[listB[e]];
       p = problem(m, r);
       p.A1 = Lc; p.B1 = Grr; p.K1 = r; p.a1 = -eta;
@@ -421,6 +432,8 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       static const char* names[3] = {"alg2_stripe_products_r32", "alg2_stripe_products_r64", "alg2_stripe_products_r128"};
       for (int cls = 0; cls < 3; ++cls)
         if (!c->sit[3 * e + cls].h.empty()) seq.push_back(Op{OP_STRIPE, 3 * e + cls, 0, 0, names[cls]});
+      std::stable_sort(c->gram[e].h.begin(), c->gram[e].h.end(), [](const GramItem& a, const GramItem& b) { return a.K > b.K; });
+      seq.push_back(Op{OP_GRAM, e, 0, 0, "alg2_gram_products"});
     }
     if (c->gemms[listA[e]].tiles.empty()) { seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"}); continue; }
     seq.push_back(Op{gk, listA[e], 0, 0, fast ? "alg2_products_mfma" : "alg2_products_f64"});
@@ -605,6 +618,8 @@ void build_plan(adapm_ctx* c) {
         L.wGt = walloc(2 * m * n);
         L.wIr = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
         L.wIl = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
+        L.wIr0 = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
+        L.wIl0 = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
       }
       if (L.path == PATH_FAST && hp.refresh_period_T > 1) {
         L.wQf = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
@@ -709,6 +724,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   for (int i = 0; i < 6; ++i) total += bytes_of(c->ru[i].h);
   for (auto& l : c->img) total += bytes_of(l.h);
   for (auto& l : c->sit) total += bytes_of(l.h);
+  for (auto& l : c->gram) total += bytes_of(l.h);
   for (int i = 0; i < 3; ++i) total += bytes_of(c->ew[i].h);
   for (int i = 0; i < 6; ++i) total += bytes_of(c->proj[i].h);
   for (int i = 0; i < 2; ++i) total += bytes_of(c->vs[i].h) + bytes_of(c->vf[i].h) + bytes_of(c->chol[i].h);
@@ -727,6 +743,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   for (int i = 0; i < 6; ++i) PUT_LIST(c->ru[i]);
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
+  for (auto& l : c->gram) PUT_LIST(l);
   for (int i = 0; i < 3; ++i) PUT_LIST(c->ew[i]);
   for (int i = 0; i < 6; ++i) PUT_LIST(c->proj[i]);
   for (int i = 0; i < 2; ++i) { PUT_LIST(c->vs[i]); PUT_LIST(c->vf[i]); PUT_LIST(c->chol[i]); }
@@ -924,6 +941,9 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         break;
       case OP_STRIPE:
         launch_stripe(1 << (op.index % 3), c->sit[op.index].d, (int64_t)c->sit[op.index].h.size(), c->sprob.d, bs, s);
+        break;
+      case OP_GRAM:
+        launch_gram(c->gram[op.index].d, (int64_t)c->gram[op.index].h.size(), bs, s);
         break;
       case OP_QTIMG:
         launch_qt_image(c->qt.d, (int64_t)c->qt.h.size(), bs, s);

@@ -159,6 +159,11 @@ struct ImgItem {           // one workgroup: one 64-column chunk of the fragment
   int32_t r, K, c, rc;     // rows of Q, columns, chunk, rank class of the image (rows r .. rc-1 are zero)
   int64_t off_img;
 };
+struct GramItem {          // one workgroup: Out (r x r, row stride r) = X Y^T from the fragment images of X, Y (r x K)
+  int64_t off_x, off_y;    // workspace: images (rank class rc)
+  int64_t off_out;         // workspace: fp32
+  int32_t K, r, rc, pad;
+};
 struct TrItem {            // one workgroup: one 64 x 64 tile of the bf16 transpose G (m x n) -> G^T (n x m)
   int32_t block, m, n, ti, tj, pad;
   int64_t off_out;         // workspace
@@ -215,6 +220,7 @@ void launch_proj(int rt, bool w16, const ProjItem* items, int64_t nitems, const 
 void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s);
 void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s);
 void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
+void launch_gram(const GramItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_refresh_update(int rt, bool w16, const ProjItem* items, int64_t nitems, const RuBlockDev* blocks, Bases b,
                            StepScalars sc, hipStream_t s);

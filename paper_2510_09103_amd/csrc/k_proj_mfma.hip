@@ -942,6 +942,72 @@ __global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict
   }
 }
 
+// r x r Gram-type products of Alg. 2 (R R^T, R' R^T, L^T L, L^T L') straight from the fragment images: a lane's
+// 16 bytes of an image hold 8 consecutive k of one row, which is the A-operand layout for rows of X and
+// equally the B-operand layout for columns of Y^T.  One workgroup per product; wave w owns column tile w of
+// the result (all row tiles); fragments come from global memory (the images sit in L2), one k-step ahead.
+template <int RT>
+__device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs) {
+  constexpr int R = 32 * RT;
+  constexpr int QF = qf_chunk_bytes(R);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
+  if (wave >= RT) return;
+  const char* __restrict__ X = bs.ws + it.off_x;
+  const char* __restrict__ Y = bs.ws + it.off_y;
+  const int nsteps = ((it.K + BK - 1) / BK) * (BK / 16);           // k-steps of 16; the images are zero-padded
+  // fragment (k-step s, tile t, hi|lo): chunk s / 4, kk = s % 4
+  auto frag = [&](const char* img, int s, int t, int hl) {
+    const uint4 q = *reinterpret_cast<const uint4*>(img + (int64_t)(s >> 2) * QF + ((((s & 3) * RT + t) * 2 + hl) * 64 + lane) * 16);
+    return as_frag(q);
+  };
+  f32x16 acc[RT];
+#pragma unroll
+  for (int t = 0; t < RT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+  bf16x8 xh[RT], xl[RT], yh, yl;
+#pragma unroll
+  for (int t = 0; t < RT; ++t) { xh[t] = frag(X, 0, t, 0); xl[t] = frag(X, 0, t, 1); }
+  yh = frag(Y, 0, wave, 0);
+  yl = frag(Y, 0, wave, 1);
+  for (int s = 0; s < nsteps; ++s) {
+    bf16x8 nxh[RT], nxl[RT], nyh, nyl;
+    const int sn = s + 1 < nsteps ? s + 1 : s;                       // the last step re-reads itself (in bounds)
+#pragma unroll
+    for (int t = 0; t < RT; ++t) { nxh[t] = frag(X, sn, t, 0); nxl[t] = frag(X, sn, t, 1); }
+    nyh = frag(Y, sn, wave, 0);
+    nyl = frag(Y, sn, wave, 1);
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[t], yh, acc[t], 0, 0, 0);
+      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[t], yh, acc[t], 0, 0, 0);
+      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[t], yl, acc[t], 0, 0, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < RT; ++t) { xh[t] = nxh[t]; xl[t] = nxl[t]; }
+    yh = nyh;
+    yl = nyl;
+  }
+  float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + it.off_out);
+  const int r = it.r, col = 32 * wave + l32;
+#pragma unroll
+  for (int t = 0; t < RT; ++t)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int row = 32 * t + 8 * q + 4 * lh + p;
+        if (row < r && col < r) Out[(int64_t)row * r + col] = acc[t][4 * q + p];
+      }
+}
+
+__global__ __launch_bounds__(256) void gram_kernel(const GramItem* __restrict__ items, Bases bs) {
+  const GramItem it = items[blockIdx.x];
+  if (it.rc == 32) gram_body<1>(it, bs);
+  else if (it.rc == 64) gram_body<2>(it, bs);
+  else gram_body<4>(it, bs);
+}
+
 // bf16 transpose through LDS, 64 x 64 tiles; needs m % 8 == 0 and n % 8 == 0 (16-byte vectors both ways)
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const TrItem* __restrict__ items, Bases bs) {
   __shared__ uint16_t tile[64][66];
@@ -1001,6 +1067,11 @@ void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const Stripe
   if (rt == 1) hipLaunchKernelGGL((stripe_kernel<1>), grid, dim3(NT), 0, s, items, probs, b);
   else if (rt == 2) hipLaunchKernelGGL((stripe_kernel<2>), grid, dim3(NT), 0, s, items, probs, b);
   else hipLaunchKernelGGL((stripe_kernel<4>), grid, dim3(NT), 0, s, items, probs, b);
+}
+
+void launch_gram(const GramItem* items, int64_t nitems, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(gram_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
 }
 
 void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s) {
