@@ -206,7 +206,9 @@ def main():
         "value": wl.numel / (ms_per_step * 1e-3), "unit": "params/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 arithmetic; bf16 params/grads, fp32 state; bf16 MFMA with hi+lo operand pairs",
+        "dtype": "f32",
+        "precision_note": "fp32 arithmetic and state; bf16 parameters and gradients; contractions on bf16 MFMA with every "
+                          "fp32 operand as a (hi, lo) bf16 pair, fp32 accumulation",
         "data": "synthetic",
         "config": {"workload": args.workload, "blocks": len(wl.blocks), "params": wl.numel, "refresh_period_T": args.T,
                    "refresh_steps_in_timed_region": n_refresh, "rank": max([b.rank for b in wl.blocks] + [0]),
