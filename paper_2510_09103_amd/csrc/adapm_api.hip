@@ -109,7 +109,7 @@ struct adapm_ctx {
   float grad_clip = 0.f;                           // threshold of the global gradient-norm clipping; <= 0: off
 
   DevList<BlockDev> blocks;
-  DevList<EwItem> ew[3];        // 0: full / no momentum; 1: low-rank, F64 path; 2: low-rank, MFMA path
+  DevList<EwItem> ew[2];        // 0: full / no momentum; 1: low-rank, F64 path (the MFMA path updates in its fused kernels)
   DevList<VsItem> vs[2];        // 0: every step; 1: only on steps that run Alg. 2 (fused elsewhere)
   DevList<VfItem> vf[2];
   DevList<VsItem> gn;           // every gradient in pieces: sums of squares for the global norm
@@ -283,7 +283,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   std::vector<std::vector<StripeWork>> swork(fast ? 3 * n_eff : 0);
   if (fast) { c->img.resize(n_eff); c->sit.resize(3 * n_eff); c->gram.resize(n_eff); }
   const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list(fast) : -1;
-  const int l_epi = new_list(fast);
+  const int l_epi = fast ? -1 : new_list(false);      // m x n term of eq. 3-4 (the MFMA path never forms it)
   const int l_gram = hp.refresh_period_T > 1 ? new_list(false) : -1;
   const int l_fin = (hp.refresh_period_T > 1 || n_eff > 0) ? new_list(fast && hp.refresh_period_T <= 1) : -1;
   for (int64_t i = 0; i < nb; ++i) {
@@ -725,7 +725,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   for (auto& l : c->img) total += bytes_of(l.h);
   for (auto& l : c->sit) total += bytes_of(l.h);
   for (auto& l : c->gram) total += bytes_of(l.h);
-  for (int i = 0; i < 3; ++i) total += bytes_of(c->ew[i].h);
+  for (int i = 0; i < 2; ++i) total += bytes_of(c->ew[i].h);
   for (int i = 0; i < 6; ++i) total += bytes_of(c->proj[i].h);
   for (int i = 0; i < 2; ++i) total += bytes_of(c->vs[i].h) + bytes_of(c->vf[i].h) + bytes_of(c->chol[i].h);
   for (auto& g : c->gemms) total += bytes_of(g.probs) + bytes_of(g.tiles);
@@ -744,7 +744,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
   for (auto& l : c->gram) PUT_LIST(l);
-  for (int i = 0; i < 3; ++i) PUT_LIST(c->ew[i]);
+  for (int i = 0; i < 2; ++i) PUT_LIST(c->ew[i]);
   for (int i = 0; i < 6; ++i) PUT_LIST(c->proj[i]);
   for (int i = 0; i < 2; ++i) { PUT_LIST(c->vs[i]); PUT_LIST(c->vf[i]); PUT_LIST(c->chol[i]); }
 #undef PUT_LIST

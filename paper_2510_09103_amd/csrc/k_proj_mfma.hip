@@ -1,23 +1,29 @@
-// Fused low-rank step with R held (refresh period T > 1, steps between two runs of Alg. 2).
+// Stripe kernels of the low-rank blocks on the MFMA path.  All of them give one workgroup (16 waves) a
+// stripe of 128 rows of one block: waves 0-7 feed the matrix cores, waves 8-15 stream G and W and do the
+// element-wise work; the two groups hand tiles to each other through multi-buffered LDS with one
+// barrier per tile, and the bf16 (hi, lo) images of the factors arrive by direct global -> LDS copies.
 //
-// With orthonormal rows Q = R the arg-min of Alg. 1 over L alone is a projection:
-//   P   = G Q^T                                  (m x r)
-//   L_t = beta1 L_{t-1} + (1-beta1) P            (least-squares fit of m_t = (1-beta1) G + beta1 L_{t-1} Q)
-//   m^c = G + beta1 (L_{t-1} - P) Q              (eq. 3-4 with r_t = L_t Q - m_t)
-//   W  <- W - lr (clip(m^c / (sqrt(v) + eps)) + lambda W)     (Alg. 1 last line)
-// One workgroup (16 waves) owns a stripe of 128 rows of one block and makes two passes over it.  Waves
-// 0-7 feed the matrix cores, waves 8-15 stream G and W and do the element-wise work; the two groups
-// hand tiles to each other through double-buffered LDS with one barrier per 64-column chunk:
-//   pass 1: the streaming waves put chunk c of G into LDS (row sums of G^2 for the blockwise second
-//           moment ride along) while the matrix-core waves accumulate P on chunk c-1; the Q operand
-//           arrives already laid out as MFMA fragments, copied global -> LDS without touching registers;
-//   pass 2: the matrix-core waves build tile j of D Q (D = beta1 (L_{t-1} - P), held in registers as
-//           A fragments; Q^T arrives as a ready-made, bank-swizzled LDS image) while the streaming
-//           waves apply the update of tile j-1 to W and prefetch G, W of the next tiles.
-// Matrix work uses v_mfma_f32_32x32x16_bf16.  G is bf16 (exact); every fp32 operand (Q, D) is
+//  proj_kernel            step with R held (refresh period T > 1, between two runs of Alg. 2).  With
+//                         orthonormal rows Q = R the arg-min of Alg. 1 over L alone is a projection:
+//                           P   = G Q^T                              (m x r)
+//                           L_t = beta1 L_{t-1} + (1-beta1) P        (least-squares fit of m_t)
+//                           m^c = G + beta1 (L_{t-1} - P) Q          (eq. 3-4 with r_t = L_t Q - m_t)
+//                           W  <- W - lr (clip(m^c / (sqrt(v) + eps)) + lambda W)    (Alg. 1 last line)
+//                         pass 1: the streaming waves put chunk c of G into LDS (row sums of G^2 for the
+//                         blockwise second moment ride along) while the matrix-core waves accumulate P on
+//                         chunk c-2 from the fragment image of Q; pass 2: the matrix-core waves build
+//                         tile j of D Q (D = beta1 (L_{t-1} - P) held in registers as A-fragments, Q^T
+//                         from a bank-swizzled LDS image) while the streaming waves apply the update of
+//                         tile j-2 to W and prefetch G, W of the next tiles.
+//  stripe_kernel          pass 1 alone, followed by a store: the products G R^T and (G^T L)^T of Alg. 2.
+//  refresh_update_kernel  pass 2 alone with two (factor, image) pairs: the update of a step that ran Alg. 2,
+//                         m^c = G + beta1/(1-beta1) (L_{t-1} R_{t-1} - L_t R_t), never storing the m x n term.
+//  gram_kernel, qimage_kernel, qf_image_kernel, qt_image_kernel, transpose_bf16_kernel: the r x r products of
+//                         Alg. 2 from the images, the images themselves, the transposed copy of G.
+//
+// Matrix work uses v_mfma_f32_32x32x16_bf16.  G is bf16 (exact); every fp32 operand (factors, D) is
 // carried as a (hi, lo) pair of bf16 values, products hi*hi + lo*hi + hi*lo accumulated in fp32
-// (relative operand error 2^-17).  The two images of Q are written by qimage_kernel after each run
-// of Alg. 2.
+// (relative operand error 2^-17).
 #include "adapm_plan.h"
 #include "ew_math.h"
 
