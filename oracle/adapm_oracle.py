@@ -75,6 +75,7 @@ class HParams:
     K: int = 5                  # App. B
     T: int = 1                  # 1 = Alg. 1 verbatim
     bias_correction: int = 1    # eq. 4; 0 = ablation of Sec. 5.1.2
+    normalise: int = 0          # 1 = scale-normalised step sizes in Alg. 2 (an option beyond the paper)
     seed: int = 0x5EED
 
 
@@ -187,12 +188,21 @@ def gd_step_sizes(K: int) -> List[float]:
     return [0.5 * (1.0 + math.cos(math.pi * k / K)) for k in range(1, K + 1)]
 
 
-def refresh_gd(M: np.ndarray, L: np.ndarray, R: np.ndarray, K: int):
+def refresh_gd(M: np.ndarray, L: np.ndarray, R: np.ndarray, K: int, normalise: bool = False):
     """Alg. 2: K simultaneous gradient steps on l(L,R) with the printed gradients
-    dl/dL = (L R - M) R^T,  dl/dR = L^T (L R - M)."""
+    dl/dL = (L R - M) R^T,  dl/dR = L^T (L R - M).
+
+    normalise (an option beyond the paper; Alg. 2 as printed takes eta_k as is, which diverges once the
+    gradients' largest singular value passes a few units and stalls when it is small): every iteration
+    divides its step size by nu = max(||R R^T||_F, ||L^T L||_F), an upper bound of the curvature of l in
+    either factor, so that the iteration is invariant under (L, R, M) -> (sqrt(c) L, sqrt(c) R, c M)."""
     L = L.copy()
     R = R.copy()
     for eta in gd_step_sizes(K):
+        if normalise:
+            nu = max(float(np.linalg.norm(R @ R.T)), float(np.linalg.norm(L.T @ L)))
+            if nu > 0.0:
+                eta = eta / nu
         E = L @ R - M
         dL = E @ R.T
         dR = L.T @ E
@@ -281,7 +291,7 @@ def step_block(blk: Block, hp: HParams, W: np.ndarray, G: np.ndarray,
         M = (1.0 - b1) * g + b1 * A                      # Alg. 1: m_t
         if is_refresh_step(t, hp.T):
             if refresh == "GD":
-                L, R = refresh_gd(M, Lp, Rp, hp.K)         # Alg. 2
+                L, R = refresh_gd(M, Lp, Rp, hp.K, normalise=bool(hp.normalise))     # Alg. 2
             elif refresh == "EXACT":
                 L, R = refresh_exact(M, blk.rank)
             else:

@@ -580,3 +580,48 @@ def test_lr_schedule_warmup_then_cosine():
     assert all(a >= b for a, b in zip(xs, xs[1:]))                               # monotone decay
     q = wu + (tot - wu) // 4
     assert abs(f(q) - (lo + 0.5 * (peak - lo) * (1 + math.cos(math.pi / 4)))) < 1e-12
+
+
+# ---------------------------------------------------------------------------------------------------
+# Scale-normalised Alg. 2 (an option beyond the paper)
+# ---------------------------------------------------------------------------------------------------
+def test_normalised_alg2_is_scale_invariant_and_literal_alg2_is_not():
+    rng = np.random.default_rng(11)
+    m_, n_, r = 14, 11, 3
+    M = rng.standard_normal((m_, r)) @ rng.standard_normal((r, n_)) + 0.05 * rng.standard_normal((m_, n_))
+    L0 = 0.3 * rng.standard_normal((m_, r))
+    R0 = 0.3 * rng.standard_normal((r, n_))
+    L1, R1 = O.refresh_gd(M, L0, R0, 5, normalise=True)
+    for c in (1e-4, 37.0, 1e4):
+        Lc, Rc = O.refresh_gd(c * M, math.sqrt(c) * L0, math.sqrt(c) * R0, 5, normalise=True)
+        np.testing.assert_allclose(Lc, math.sqrt(c) * L1, rtol=1e-10, atol=0)
+        np.testing.assert_allclose(Rc, math.sqrt(c) * R1, rtol=1e-10, atol=0)
+    # the printed iteration does not have this property: at c = 37 it blows up, at c = 1e-4 it barely moves
+    La, Ra = O.refresh_gd(M, L0, R0, 5)
+    with np.errstate(over="ignore", invalid="ignore"):
+        Lb, Rb = O.refresh_gd(37.0 * M, math.sqrt(37.0) * L0, math.sqrt(37.0) * R0, 5)
+    assert not np.allclose(Lb @ Rb, 37.0 * (La @ Ra), rtol=1e-3)
+    Ls, Rs = O.refresh_gd(1e-4 * M, 1e-2 * L0, 1e-2 * R0, 5)
+    moved_literal = np.linalg.norm(Ls - 1e-2 * L0) / np.linalg.norm(1e-2 * L0)
+    moved_normalised = np.linalg.norm(L1 - L0) / np.linalg.norm(L0)
+    assert moved_literal < 0.02 * moved_normalised
+
+
+def test_normalised_alg2_descends_at_any_scale_and_reduces_to_the_literal_one():
+    rng = np.random.default_rng(12)
+    m_, n_, r = 20, 16, 4
+    M = rng.standard_normal((m_, r)) @ rng.standard_normal((r, n_))
+    for c in (1e-3, 1.0, 1e3):
+        L, R = np.zeros((m_, r)), math.sqrt(c) * rng.standard_normal((r, n_)) / math.sqrt(n_)
+        errs = [np.linalg.norm(L @ R - c * M)]
+        for _ in range(12):
+            L, R = O.refresh_gd(c * M, L, R, 5, normalise=True)
+            errs.append(np.linalg.norm(L @ R - c * M))
+        assert all(b <= a * (1 + 1e-12) for a, b in zip(errs, errs[1:]))          # monotone
+        assert errs[-1] < 0.2 * errs[0]                                            # and it gets somewhere
+    # normaliser 1: rank 1, unit row, L = 0  =>  the first iteration is the printed one
+    R0 = np.zeros((1, n_)); R0[0, 3] = 1.0
+    La, Ra = O.refresh_gd(M, np.zeros((m_, 1)), R0, 2)
+    Lb, Rb = O.refresh_gd(M, np.zeros((m_, 1)), R0, 2, normalise=True)
+    np.testing.assert_array_equal(La, Lb)
+    np.testing.assert_array_equal(Ra, Rb)
