@@ -79,6 +79,10 @@ typedef struct {
                                  of R; on other steps L is the least-squares fit with R held. */
   int32_t bias_correction;    /* 1 = eq. 4; 0 = ablation of Sec. 5.1.2 (use L_t R_t as the momentum) */
   int32_t contraction;        /* adapm_contract_t */
+  int32_t refresh_normalise;  /* 0 = Alg. 2 as printed.  1 (an option beyond the paper): every iteration of Alg. 2
+                                 divides its step size by max(||R R^T||_F, ||L^T L||_F), which makes the
+                                 iteration invariant under a rescaling of the gradients (as printed it
+                                 diverges for large and stalls for small gradients) */
   uint64_t seed;              /* seeded start R_0 of the low-rank factors; 0 = literal all-zero start */
 } adapm_hparams_t;
 

@@ -36,7 +36,8 @@ class adapm_hparams_t(C.Structure):
     _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("clip", C.c_float),
                 ("adam_debias", C.c_int32), ("refresh_iters_K", C.c_int32),
                 ("refresh_period_T", C.c_int32), ("bias_correction", C.c_int32),
-                ("contraction", C.c_int32), ("seed", C.c_uint64)]
+                ("contraction", C.c_int32), ("refresh_normalise", C.c_int32),
+                ("seed", C.c_uint64)]
 
 
 EXPORTS = ["adapm_init", "adapm_state_bytes", "adapm_workspace_bytes", "adapm_state_offsets",

@@ -56,12 +56,13 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wQf = -1, wTimg = -1;                             // ws: bf16 (hi, lo) images of Q and Q^T
   int64_t wGt = -1, wIr = -1, wIl = -1;                     // ws: G^T (bf16) and the fragment images of R, L^T during Alg. 2
   int64_t wIr0 = -1, wIl0 = -1;                             // ws: the same images of R_{t-1}, L_{t-1}^T (first iteration; Gram matrices)
+  int64_t wNu = -1;                                         // ws: normaliser of the optional scale-normalised Alg. 2 (one double)
   int64_t wT1 = -1, wT2 = -1;                               // ws: images of R_{t-1}^T and R_t^T for the fused update after Alg. 2
   int64_t nv = 0;
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -123,6 +124,7 @@ struct adapm_ctx {
   std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T
   std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
   std::vector<DevList<GramItem>> gram;  //   ... per GD iteration: the four r x r Gram-type products, from the images
+  std::vector<DevList<GnormItem>> gnorm; // optional scale-normalised Alg. 2: per (path, GD iteration) the normalisers
   DevList<RuBlockDev> rub;              // fused update after Alg. 2 (MFMA path): blocks, images of R^T, stripes
   DevList<ImgItem> qt;
   DevList<ProjItem> ru[6];              //   (rank class 32 / 64 / 128) x (fp32 / bf16 parameters)
@@ -189,6 +191,7 @@ adapm_status_t validate(const adapm_block_t* t, int64_t n, const adapm_hparams_t
   if (hp->refresh_period_T < 1) return fail(ADAPM_EINVAL, "refresh_period_T must be >= 1");
   if (hp->adam_debias != 0 && hp->adam_debias != 1) return fail(ADAPM_EINVAL, "adam_debias must be 0 or 1");
   if (hp->bias_correction != 0 && hp->bias_correction != 1) return fail(ADAPM_EINVAL, "bias_correction must be 0 or 1");
+  if (hp->refresh_normalise != 0 && hp->refresh_normalise != 1) return fail(ADAPM_EINVAL, "refresh_normalise must be 0 or 1");
   if (hp->contraction < ADAPM_CONTRACT_AUTO || hp->contraction > ADAPM_CONTRACT_BF16X2)
     return fail(ADAPM_EINVAL, "unknown contraction mode %d", hp->contraction);
   for (int64_t i = 0; i < n; ++i) {
@@ -242,6 +245,7 @@ GemmProblem problem(int M, int N) {
   memset(&p, 0, sizeof p);
   p.A1 = p.B1 = p.A2 = p.B2 = p.X = p.Y = p.Out = none_mat();
   p.M = M; p.N = N;
+  p.off_s = -1;
   return p;
 }
 
@@ -277,6 +281,8 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   };
   std::vector<int> listA(n_eff), listB(n_eff);
   for (int e = 0; e < n_eff; ++e) { listA[e] = new_list(fast); listB[e] = new_list(fast); }
+  const int gnorm0 = (int)c->gnorm.size();          // this path's normaliser lists, one per iteration
+  if (hp.refresh_normalise) c->gnorm.resize(gnorm0 + n_eff);
   // MFMA path: per GD iteration the images of (R, L^T) and, per rank class, the stripe problems
   constexpr int NXCD = 8;
   struct StripeWork { int prob; int64_t M, K; };
@@ -345,15 +351,18 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         p = problem(r, r); p.A1 = T(Lc); p.B1 = Lp; p.K1 = m; p.a1 = 1; p.Out = Glp; add_problem(A, p);
       }
       GemmList& Bl = c->gemms[listB[e]];
+      // optional: both updates of this iteration take eta / max(||R R^T||_F, ||L^T L||_F), a device scalar
+      const int64_t off_s = hp.refresh_normalise ? L.wNu : -1;
+      if (hp.refresh_normalise) c->gnorm[gnorm0 + e].h.push_back(GnormItem{L.wGrr, L.wGll, L.wNu, r, idt});
       p = problem(m, r);
       p.A1 = Lc; p.B1 = Grr; p.K1 = r; p.a1 = -eta;
       p.A2 = Lp; p.B2 = Gpr; p.K2 = r; p.a2 = eta * b1;
-      p.X = Lc; p.g = 1.0; p.Y = P; p.d = eta * (1.0 - b1); p.Out = Ln;
+      p.X = Lc; p.g = 1.0; p.Y = P; p.d = eta * (1.0 - b1); p.Out = Ln; p.off_s = off_s;
       add_problem(Bl, p);
       p = problem(r, n);
       p.A1 = Gll; p.B1 = Rc; p.K1 = r; p.a1 = -eta;
       p.A2 = Glp; p.B2 = Rp; p.K2 = r; p.a2 = eta * b1;
-      p.X = Rc; p.g = 1.0; p.Y = S; p.d = eta * (1.0 - b1); p.Out = Rn;
+      p.X = Rc; p.g = 1.0; p.Y = S; p.d = eta * (1.0 - b1); p.Out = Rn; p.off_s = off_s;
       add_problem(Bl, p);
       Lc = Ln; Rc = Rn;
     }
@@ -435,8 +444,9 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       std::stable_sort(c->gram[e].h.begin(), c->gram[e].h.end(), [](const GramItem& a, const GramItem& b) { return a.K > b.K; });
       seq.push_back(Op{OP_GRAM, e, 0, 0, "alg2_gram_products"});
     }
-    if (c->gemms[listA[e]].tiles.empty()) { seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"}); continue; }
-    seq.push_back(Op{gk, listA[e], 0, 0, fast ? "alg2_products_mfma" : "alg2_products_f64"});
+    if (!c->gemms[listA[e]].tiles.empty())
+      seq.push_back(Op{gk, listA[e], 0, 0, fast ? "alg2_products_mfma" : "alg2_products_f64"});
+    if (hp.refresh_normalise) seq.push_back(Op{OP_GNORM, gnorm0 + e, 0, 0, "alg2_step_normaliser"});
     seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"});
   }
   if (l_pre >= 0) seq.push_back(Op{gk, l_pre, 0, 0, "copy_factors"});
@@ -608,6 +618,7 @@ void build_plan(adapm_ctx* c) {
       L.wGrr = walloc(es * r * r); L.wGpr = walloc(es * r * r);
       L.wGll = walloc(es * r * r); L.wGlp = walloc(es * r * r);
       L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
+      L.wNu = walloc(8);
       if (L.path == PATH_FAST) {
         L.wT1 = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
         L.wT2 = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
@@ -725,6 +736,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   for (auto& l : c->img) total += bytes_of(l.h);
   for (auto& l : c->sit) total += bytes_of(l.h);
   for (auto& l : c->gram) total += bytes_of(l.h);
+  for (auto& l : c->gnorm) total += bytes_of(l.h);
   for (int i = 0; i < 2; ++i) total += bytes_of(c->ew[i].h);
   for (int i = 0; i < 6; ++i) total += bytes_of(c->proj[i].h);
   for (int i = 0; i < 2; ++i) total += bytes_of(c->vs[i].h) + bytes_of(c->vf[i].h) + bytes_of(c->chol[i].h);
@@ -744,6 +756,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
   for (auto& l : c->gram) PUT_LIST(l);
+  for (auto& l : c->gnorm) PUT_LIST(l);
   for (int i = 0; i < 2; ++i) PUT_LIST(c->ew[i]);
   for (int i = 0; i < 6; ++i) PUT_LIST(c->proj[i]);
   for (int i = 0; i < 2; ++i) { PUT_LIST(c->vs[i]); PUT_LIST(c->vf[i]); PUT_LIST(c->chol[i]); }
@@ -941,6 +954,9 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         break;
       case OP_STRIPE:
         launch_stripe(1 << (op.index % 3), c->sit[op.index].d, (int64_t)c->sit[op.index].h.size(), c->sprob.d, bs, s);
+        break;
+      case OP_GNORM:
+        launch_gram_norm(c->gnorm[op.index].d, (int64_t)c->gnorm[op.index].h.size(), bs, s);
         break;
       case OP_GRAM:
         launch_gram(c->gram[op.index].d, (int64_t)c->gram[op.index].h.size(), bs, s);

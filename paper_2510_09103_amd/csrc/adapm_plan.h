@@ -61,6 +61,7 @@ struct GemmProblem {
   double a1, a2, g, d;
   int32_t scale_g;   // 1: the (single) product has the gradient as an operand and takes the clipping factor
   int32_t pad;
+  int64_t off_s;     // >= 0: workspace offset of a device scalar s (double); then Out = g X + s (a1 A1 B1 + a2 A2 B2 + d Y)
 };
 
 struct GemmTile {
@@ -164,6 +165,11 @@ struct GramItem {          // one workgroup: Out (r x r, row stride r) = X Y^T f
   int64_t off_out;         // workspace: fp32
   int32_t K, r, rc, pad;
 };
+struct GnormItem {         // one workgroup: s = 1 / max(||A||_F, ||B||_F) for two r x r matrices (1 if both vanish)
+  int64_t off_a, off_b;    // workspace
+  int64_t off_out;         // workspace, one double
+  int32_t r, dtype;        // DT_F32 or DT_F64
+};
 struct TrItem {            // one workgroup: one 64 x 64 tile of the bf16 transpose G (m x n) -> G^T (n x m)
   int32_t block, m, n, ti, tj, pad;
   int64_t off_out;         // workspace
@@ -208,6 +214,7 @@ void launch_vstat(const BlockDev* blocks, const VsItem* items, int64_t nitems, d
                   float beta2, hipStream_t s);
 void launch_vfinal(const BlockDev* blocks, const VfItem* items, int64_t nitems, const double* partials, Bases b,
                    float beta2, hipStream_t s);
+void launch_gram_norm(const GnormItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gradnorm_final(const double* partials, int64_t nparts, float max_norm, float* out, hipStream_t s);
 void launch_update(const BlockDev* blocks, const EwItem* items, int64_t nitems, Bases b, StepScalars sc,
                    hipStream_t s);

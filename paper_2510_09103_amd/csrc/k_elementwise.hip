@@ -143,6 +143,38 @@ __global__ __launch_bounds__(1024) void gradnorm_final_kernel(const double* __re
   }
 }
 
+// Normaliser of the optional scale-normalised Alg. 2: s = 1 / max(||R R^T||_F, ||L^T L||_F) from the two Gram
+// matrices of the iteration (fp64 sums in a fixed order).
+__global__ __launch_bounds__(256) void gram_norm_kernel(const GnormItem* __restrict__ items, Bases b) {
+  __shared__ double red[2][256];
+  const GnormItem it = items[blockIdx.x];
+  const int n = it.r * it.r;
+  double sa = 0.0, sb = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) {
+    double x, y;
+    if (it.dtype == DT_F64) {
+      x = reinterpret_cast<const double*>(b.ws + it.off_a)[i];
+      y = reinterpret_cast<const double*>(b.ws + it.off_b)[i];
+    } else {
+      x = (double)reinterpret_cast<const float*>(b.ws + it.off_a)[i];
+      y = (double)reinterpret_cast<const float*>(b.ws + it.off_b)[i];
+    }
+    sa += x * x;
+    sb += y * y;
+  }
+  red[0][threadIdx.x] = sa;
+  red[1][threadIdx.x] = sb;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) { red[0][threadIdx.x] += red[0][threadIdx.x + w]; red[1][threadIdx.x] += red[1][threadIdx.x + w]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double nu = sqrt(red[0][0] > red[1][0] ? red[0][0] : red[1][0]);
+    *reinterpret_cast<double*>(b.ws + it.off_out) = nu > 0.0 ? 1.0 / nu : 1.0;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // fused update
 // ---------------------------------------------------------------------------
@@ -283,6 +315,11 @@ void launch_vfinal(const BlockDev* blocks, const VfItem* items, int64_t nitems, 
   if (nitems <= 0) return;
   hipLaunchKernelGGL(vfinal_kernel, dim3((unsigned)((nitems + 255) / 256)), dim3(256), 0, s, blocks, items, nitems,
                      partials, b, beta2);
+}
+
+void launch_gram_norm(const GnormItem* items, int64_t nitems, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(gram_norm_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
 }
 
 void launch_gradnorm_final(const double* partials, int64_t nparts, float max_norm, float* out, hipStream_t s) {

@@ -137,6 +137,8 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const GemmProblem* __restri
   const char* Xb = P.X.ref.space != SP_NONE ? resolve(P.X.ref, bs) : nullptr;
   const char* Yb = P.Y.ref.space != SP_NONE ? resolve(P.Y.ref, bs) : nullptr;
   char* Ob = resolve(P.Out.ref, bs);
+  // optional device scalar on everything but X (normalised step of Alg. 2)
+  const double step_scale = P.off_s >= 0 ? *reinterpret_cast<const double*>(bs.ws + P.off_s) : 1.0;
   // X and Y are read unconditionally on clamped indices (independent loads); the bounds check guards the store
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
@@ -154,7 +156,8 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const GemmProblem* __restri
     for (int c = 0; c < 4; ++c) {
       const int j = j0 + tx * 4 + c;
       if (i >= P.M || j >= P.N) continue;
-      const double val = fma(P.d, yv[c], fma(P.g, xv[c], acc[q][c]));
+      const double val = P.off_s >= 0 ? fma(P.g, xv[c], step_scale * fma(P.d, yv[c], acc[q][c]))
+                                      : fma(P.d, yv[c], fma(P.g, xv[c], acc[q][c]));
       const int64_t o = (int64_t)i * P.Out.s0 + (int64_t)j * P.Out.s1;
       if (P.Out.dtype == DT_F64) reinterpret_cast<double*>(Ob)[o] = val;
       else reinterpret_cast<float*>(Ob)[o] = (float)val;

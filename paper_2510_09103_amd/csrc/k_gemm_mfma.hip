@@ -215,6 +215,9 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma_kernel(const GemmProblem* __
   const char* Yb = P.Y.ref.space != SP_NONE ? resolve(P.Y.ref, bs) : nullptr;
   float* Ob = reinterpret_cast<float*>(resolve(P.Out.ref, bs));
   const float g = (float)P.g, d = (float)P.d;
+  // optional device scalar on everything but X (normalised step of Alg. 2)
+  const bool scaled = P.off_s >= 0;
+  const float step_scale = scaled ? (float)*reinterpret_cast<const double*>(bs.ws + P.off_s) : 1.f;
   // X and Y are read unconditionally on clamped indices (16 independent loads at a time) and the
   // bounds check is applied to the store only
 #pragma unroll
@@ -235,7 +238,8 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma_kernel(const GemmProblem* __
       for (int e = 0; e < 16; ++e) {
         const int i = i0 + 64 * wm + 32 * tm + 8 * (e >> 2) + 4 * lh + (e & 3);
         if (i < P.M && j < P.N)
-          Ob[(int64_t)i * P.Out.s0 + (int64_t)j * P.Out.s1] = acc[tm][tn][e] + g * xv[e] + d * yv[e];
+          Ob[(int64_t)i * P.Out.s0 + (int64_t)j * P.Out.s1] =
+              scaled ? g * xv[e] + step_scale * (acc[tm][tn][e] + d * yv[e]) : acc[tm][tn][e] + g * xv[e] + d * yv[e];
       }
     }
 }

@@ -758,12 +758,16 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
     for (int ks = 0; ks < 2 * RT; ++ks) toff[ks] = (unsigned)(l32 * R * 2 + timg_piece(R, l32, 2 * ks + lh) * 16);
     const int coff = (32 * wr + 4 * lh) * CR + l32;
     const char* img[2] = {bs.ws + B.off_img1, bs.ws + B.off_img2};
+    // a product with coefficient 0 (no bias correction: a1 = 0) has no image: it is neither copied nor
+    // multiplied (0 x stale bits could be NaN), its partial tile is written as zeros
+    const bool live[2] = {B.a1 != 0.f, B.a2 != 0.f};
     for (int j = 0; j < NR; ++j) {
       // round j: start the copies of tile j (hi and lo halves of both products: 4 pieces of TH bytes shared
       // by the eight waves), build tile j-1 from what landed in the last round
       if (j < nr) {
         for (int k = mw; k < 4 * TH / 1024; k += 8) {
           const int q = k / (TH / 1024), piece = k % (TH / 1024);     // q = 2 * product + (lo half)
+          if (!live[q >> 1]) continue;
           const char* src = img[q >> 1] + (int64_t)(j >> 1) * T64 + (q & 1) * (BK * R * 2) + (j & 1) * TH + piece * 1024;
           __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + lane * 16),
                                            (__attribute__((address_space(3))) void*)(lds + (j & 1) * TBUF + q * TH + piece * 1024),
@@ -775,19 +779,21 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
         f32x16 c;
 #pragma unroll
         for (int i = 0; i < 16; ++i) c[i] = 0.f;
+        if (live[prod]) {
 #pragma unroll
-        for (int ks = 0; ks < 2 * RT; ks += 2) {
-          bf16x8 bh0 = lds_frag_raw(th + toff[ks]);
-          bf16x8 bl0 = lds_frag_raw(tl + toff[ks]);
-          bf16x8 bh1 = lds_frag_raw(th + toff[ks + 1]);
-          bf16x8 bl1 = lds_frag_raw(tl + toff[ks + 1]);
-          lds_wait(bh0, bl0, bh1, bl1);
-          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bh0, c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks], bh0, c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bl0, c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks + 1], bh1, c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks + 1], bh1, c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks + 1], bl1, c, 0, 0, 0);
+          for (int ks = 0; ks < 2 * RT; ks += 2) {
+            bf16x8 bh0 = lds_frag_raw(th + toff[ks]);
+            bf16x8 bl0 = lds_frag_raw(tl + toff[ks]);
+            bf16x8 bh1 = lds_frag_raw(th + toff[ks + 1]);
+            bf16x8 bl1 = lds_frag_raw(tl + toff[ks + 1]);
+            lds_wait(bh0, bl0, bh1, bl1);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bh0, c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks], bh0, c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks], bl0, c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks + 1], bh1, c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dl[ks + 1], bh1, c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dh[ks + 1], bl1, c, 0, 0, 0);
+          }
         }
         lds_f32* cs = (lds_f32*)(lds + 2 * TBUF + (((j - 1) & 1) * 2 + prod) * C_TILE);
 #pragma unroll

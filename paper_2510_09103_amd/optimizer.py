@@ -21,9 +21,9 @@ def to_c_block(b: BlockSpec) -> B.adapm_block_t:
 
 
 def make_hparams(beta1=0.9, beta2=0.95, eps=1e-8, clip=1.0, adam_debias=0, K=5, T=1, bias_correction=1,
-                 contraction=B.ADAPM_CONTRACT_AUTO, seed=0x5EED) -> B.adapm_hparams_t:
+                 contraction=B.ADAPM_CONTRACT_AUTO, seed=0x5EED, normalise=0) -> B.adapm_hparams_t:
     return B.adapm_hparams_t(beta1, beta2, eps, clip if math.isfinite(clip) else float("inf"), adam_debias, K, T,
-                             bias_correction, contraction, seed)
+                             bias_correction, contraction, normalise, seed)
 
 
 class AdaPM:

@@ -85,6 +85,9 @@ class Pair:
         self.hp_o = O.HParams(**ok) if "seed" in ok else O.HParams(**ok, seed=0x5EED)
         self.grad_clip = grad_clip
         self.opt = AdaPM(wl.blocks, self.hp_c, device=device, grad_clip=grad_clip or 0.0)
+        # the workspace is scratch: poison it (every byte 0xFF = NaN in bf16, fp32 and fp64) so that anything read
+        # before it was written in the same step shows up whatever the allocator handed out
+        self.opt.workspace.fill_(255)
         self.blocks_o = [oracle_block(b) for b in wl.blocks]
         self.state_o = O.init_state(self.blocks_o, self.hp_o)
         self.params = WL.initial_params(wl, device=device)

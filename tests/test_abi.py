@@ -52,7 +52,8 @@ def test_init_rejects_bad_table_entries(bad):
 
 
 @pytest.mark.parametrize("bad", [dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1.0), dict(clip=0.0), dict(K=0),
-                                 dict(T=0), dict(adam_debias=2), dict(bias_correction=7), dict(contraction=9)])
+                                 dict(T=0), dict(adam_debias=2), dict(bias_correction=7), dict(contraction=9),
+                                 dict(normalise=2)])
 def test_init_rejects_bad_hparams(bad):
     with pytest.raises(B.AdapmError) as e:
         B.adapm_init([blk()], make_hparams(**bad))

@@ -154,6 +154,22 @@ def test_global_gradient_clipping_above_the_norm_changes_nothing():
         assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("hp", [dict(T=1), dict(T=3)])
+def test_scale_normalised_alg2_on_the_exact_path(hp):
+    """The optional normalised step sizes of Alg. 2 (beyond the paper), every regime, also at a gradient scale where
+    the printed iteration overflows."""
+    hp = dict(hp, contraction=B.ADAPM_CONTRACT_F64, normalise=1)
+    run(mixed_table(), 6, hp, tol_state=TOL32, tol_param=TOL32, check_every=2)
+    run(mixed_table(), 4, hp, tol_state=TOL32, tol_param=TOL32, check_every=2, grad_scale=40.0)
+
+
+@pytest.mark.parametrize("hp", [dict(T=1), dict(T=3), dict(T=2, bias_correction=0)])
+def test_scale_normalised_alg2_on_the_mfma_path(hp):
+    hp = dict(hp, contraction=B.ADAPM_CONTRACT_BF16X2, normalise=1)
+    run(ragged_bf16_table(), 6, hp, tol_state=TOL16, tol_param=TOL16, check_every=2)
+    run(odd_rank_table(), 4, hp, tol_state=TOL16, tol_param=TOL16, check_every=2, grad_scale=0.01)
+
+
 def test_literal_zero_start_stays_zero_on_gpu():
     wl = WL.subset(WL.tiny_block(), ["attn.q"])
     pair, _ = run(wl, 3, dict(seed=0))
