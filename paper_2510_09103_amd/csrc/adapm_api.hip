@@ -62,7 +62,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM, OP_UPDATE_GROUPED };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -113,6 +113,7 @@ struct adapm_ctx {
   DevList<EwItem> ew[2];        // 0: full / no momentum; 1: low-rank, F64 path (the MFMA path updates in its fused kernels)
   DevList<VsItem> vs[2];        // 0: every step; 1: only on steps that run Alg. 2 (fused elsewhere)
   DevList<VfItem> vf[2];
+  DevList<GrpItem> grp;         // full / no momentum blocks whose v groups fit a wavefront: statistic + update fused
   DevList<VsItem> gn;           // every gradient in pieces: sums of squares for the global norm
   DevList<SketchItem> sk;
   DevList<CholItem> chol[2];    // per path
@@ -658,6 +659,15 @@ void build_plan(adapm_ctx* c) {
     d.mom_mode = b.mom_mode; d.v_mode = b.v_mode;
     d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
     c->blocks.h.push_back(d);
+    // full / no momentum blocks with a blockwise v whose groups fit a wavefront's registers: one fused kernel
+    const bool grouped = L.path == PATH_NONE && b.v_mode != ADAPM_V_ELEMENT && d.group_elems <= GRP_MAX_ELEMS &&
+                         d.group_elems % 8 == 0 && b.grad_dtype == ADAPM_BF16 && b.param_dtype == ADAPM_BF16;
+    if (grouped) {
+      const int64_t per = std::max<int64_t>(4, 32768 / d.group_elems);      // groups per workgroup (4 waves)
+      for (int64_t g0 = 0; g0 < L.nv; g0 += per)
+        c->grp.h.push_back(GrpItem{g0, (int32_t)i, (int32_t)std::min<int64_t>(per, L.nv - g0)});
+      continue;
+    }
     // low-rank blocks on the MFMA path are updated by the fused stripe kernels, not by the element-wise kernel
     if (L.path != PATH_FAST) {
       auto& ew = c->ew[L.path == PATH_NONE ? 0 : 1].h;
@@ -711,6 +721,7 @@ void build_plan(adapm_ctx* c) {
       if (!c->vf[1].h.empty()) seq.push_back(Op{OP_VFINAL, 1, 0, 0, "v_statistics_fold"});
     }
     if (!c->ew[0].h.empty()) seq.push_back(Op{OP_UPDATE, 0, 0, 0, "update_full"});
+    if (!c->grp.h.empty()) seq.push_back(Op{OP_UPDATE_GROUPED, 0, 0, 0, "update_full_grouped"});
   }
   if (c->n_lowrank == 0) return;
   plan_lowrank_refresh(c, false);
@@ -730,7 +741,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   HIP_TRY(hipGetDevice(&dev));
   const size_t nb = c->table.size();
   size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
-                 bytes_of(c->tr.h) + bytes_of(c->sprob.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) +
+                 bytes_of(c->tr.h) + bytes_of(c->sprob.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) + bytes_of(c->grp.h) +
                  align_up(2 * nb * sizeof(void*));
   for (int i = 0; i < 6; ++i) total += bytes_of(c->ru[i].h);
   for (auto& l : c->img) total += bytes_of(l.h);
@@ -751,7 +762,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     return dst;
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
-  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->tr); PUT_LIST(c->sprob); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn);
+  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->tr); PUT_LIST(c->sprob); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn); PUT_LIST(c->grp);
   for (int i = 0; i < 6; ++i) PUT_LIST(c->ru[i]);
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
@@ -954,6 +965,9 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         break;
       case OP_STRIPE:
         launch_stripe(1 << (op.index % 3), c->sit[op.index].d, (int64_t)c->sit[op.index].h.size(), c->sprob.d, bs, s);
+        break;
+      case OP_UPDATE_GROUPED:
+        launch_update_grouped(c->blocks.d, c->grp.d, (int64_t)c->grp.h.size(), bs, sc, s);
         break;
       case OP_GNORM:
         launch_gram_norm(c->gnorm[op.index].d, (int64_t)c->gnorm[op.index].h.size(), bs, s);

@@ -165,6 +165,12 @@ struct GramItem {          // one workgroup: Out (r x r, row stride r) = X Y^T f
   int64_t off_out;         // workspace: fp32
   int32_t K, r, rc, pad;
 };
+struct GrpItem {           // one workgroup of the grouped update: groups g0 .. g0 + ngroups - 1 of a block's blockwise v
+  int64_t g0;
+  int32_t block;
+  int32_t ngroups;
+};
+constexpr int GRP_MAX_ELEMS = 2048;   // a wavefront holds one whole group of v in registers: 64 lanes x 4 vectors x 8
 struct GnormItem {         // one workgroup: s = 1 / max(||A||_F, ||B||_F) for two r x r matrices (1 if both vanish)
   int64_t off_a, off_b;    // workspace
   int64_t off_out;         // workspace, one double
@@ -215,6 +221,8 @@ void launch_vstat(const BlockDev* blocks, const VsItem* items, int64_t nitems, d
 void launch_vfinal(const BlockDev* blocks, const VfItem* items, int64_t nitems, const double* partials, Bases b,
                    float beta2, hipStream_t s);
 void launch_gram_norm(const GnormItem* items, int64_t nitems, Bases b, hipStream_t s);
+void launch_update_grouped(const BlockDev* blocks, const GrpItem* items, int64_t nitems, Bases b, StepScalars sc,
+                           hipStream_t s);
 void launch_gradnorm_final(const double* partials, int64_t nparts, float max_norm, float* out, hipStream_t s);
 void launch_update(const BlockDev* blocks, const EwItem* items, int64_t nitems, Bases b, StepScalars sc,
                    hipStream_t s);

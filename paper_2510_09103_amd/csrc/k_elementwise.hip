@@ -143,6 +143,76 @@ __global__ __launch_bounds__(1024) void gradnorm_final_kernel(const double* __re
   }
 }
 
+// Full / no momentum blocks with a blockwise second moment whose groups fit a wavefront's registers
+// (bf16 G and W, at most GRP_MAX_ELEMS elements, a multiple of 8: e.g. one v per 1600-element row of an embedding):
+// statistic and update in one pass.  A wave reads its group of G once, reduces sum G^2 (fp32 per lane, fp64
+// across lanes, the same arithmetic as vstat_kernel), updates v_g and then W (and m) with G still in registers.
+__global__ __launch_bounds__(256) void update_grouped_kernel(const BlockDev* __restrict__ blocks,
+                                                             const GrpItem* __restrict__ items, Bases b, StepScalars sc) {
+  const GrpItem item = items[blockIdx.x];
+  const BlockDev blk = blocks[item.block];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const char* G = (const char*)b.grads[item.block];
+  char* W = (char*)b.params[item.block];
+  float* m = blk.off_m >= 0 ? reinterpret_cast<float*>(b.state + blk.off_m) : nullptr;
+  float* v = reinterpret_cast<float*>(b.state + blk.off_v);
+  const UpdCoef cf = make_coef(sc.lr, blk.lr_scale, blk.wd, sc.clip);
+  const float ob1 = 1.f - sc.beta1;
+  const float gs = grad_scale(b);                 // global clipping: the method sees gs * G
+  const int ge = (int)blk.group_elems, nvec = ge >> 3;
+  for (int64_t g = item.g0 + wave; g < item.g0 + item.ngroups; g += 4) {
+    const int64_t base = g * ge;
+    // G, W and m of the whole group are requested together, as raw vectors on clamped (always valid) indices, and
+    // converted afterwards (W and m do not depend on v): one memory latency per group.  bf16 G and W only.
+    uint4 gq[4], wq[4];
+    float4 ma[4], mb[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int iv = lane + 64 * k;
+      const int64_t e0 = base + (int64_t)(iv < nvec ? iv : nvec - 1) * 8;
+      gq[k] = *reinterpret_cast<const uint4*>(G + e0 * 2);
+      wq[k] = *reinterpret_cast<const uint4*>(W + e0 * 2);
+      if (m) {
+        ma[k] = *reinterpret_cast<const float4*>(m + e0);
+        mb[k] = *reinterpret_cast<const float4*>(m + e0 + 4);
+      }
+    }
+    float acc = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (lane + 64 * k < nvec) acc += dot2_sq(gq[k].w, dot2_sq(gq[k].z, dot2_sq(gq[k].y, dot2_sq(gq[k].x, 0.f))));
+    const double sum = wave_sum((double)acc) * ((double)gs * (double)gs);
+    const float vn = (float)((double)sc.beta2 * (double)v[g] + (1.0 - (double)sc.beta2) * (sum / (double)ge));
+    if (lane == 0) v[g] = vn;
+    const float inv = inv_denom_exact(vn, sc.inv_debias_v, sc.inv_debias_m, sc.eps);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int iv = lane + 64 * k;
+      if (iv < nvec) {
+        const int64_t e0 = base + (int64_t)iv * 8;
+        const uint32_t gw[4] = {gq[k].x, gq[k].y, gq[k].z, gq[k].w}, ww[4] = {wq[k].x, wq[k].y, wq[k].z, wq[k].w};
+        float mc[8], w[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          mc[2 * e] = gs * __uint_as_float(gw[e] << 16);
+          mc[2 * e + 1] = gs * __uint_as_float(gw[e] & 0xffff0000u);
+          w[2 * e] = __uint_as_float(ww[e] << 16);
+          w[2 * e + 1] = __uint_as_float(ww[e] & 0xffff0000u);
+        }
+        if (m) {                                  // full momentum, eq. 5
+          const float mo[8] = {ma[k].x, ma[k].y, ma[k].z, ma[k].w, mb[k].x, mb[k].y, mb[k].z, mb[k].w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) mc[e] = ob1 * mc[e] + sc.beta1 * mo[e];
+          store8((char*)m, DT_F32, e0, mc);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = apply_update(w[e], mc[e], inv, cf);
+        store8(W, DT_BF16, e0, w);
+      }
+    }
+  }
+}
+
 // Normaliser of the optional scale-normalised Alg. 2: s = 1 / max(||R R^T||_F, ||L^T L||_F) from the two Gram
 // matrices of the iteration (fp64 sums in a fixed order).
 __global__ __launch_bounds__(256) void gram_norm_kernel(const GnormItem* __restrict__ items, Bases b) {
@@ -315,6 +385,12 @@ void launch_vfinal(const BlockDev* blocks, const VfItem* items, int64_t nitems, 
   if (nitems <= 0) return;
   hipLaunchKernelGGL(vfinal_kernel, dim3((unsigned)((nitems + 255) / 256)), dim3(256), 0, s, blocks, items, nitems,
                      partials, b, beta2);
+}
+
+void launch_update_grouped(const BlockDev* blocks, const GrpItem* items, int64_t nitems, Bases b, StepScalars sc,
+                           hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(update_grouped_kernel, dim3((unsigned)nitems), dim3(256), 0, s, blocks, items, b, sc);
 }
 
 void launch_gram_norm(const GnormItem* items, int64_t nitems, Bases b, hipStream_t s) {
