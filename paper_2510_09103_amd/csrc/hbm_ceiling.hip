@@ -7,6 +7,8 @@
 //   rmw       : one pass over G plus a read-modify-write pass over W of the same shape (the update)
 //   read + rmw: pass 1 over G, then pass 2 over G together with the read-modify-write of W -- the
 //               traffic of the fused held-R kernel without its arithmetic
+//   ... back  : the same with the second pass walking the stripe from its last column to its first, so that
+//               what pass 1 read last is read again first
 // Every access is in bounds by construction (rows is a multiple of ROWS, rowbytes of 128).
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -21,7 +23,7 @@
     }                                                                                \
   } while (0)
 
-template <int ROWS, int PASSES, bool RMW>
+template <int ROWS, int PASSES, bool RMW, bool REV>
 __global__ __launch_bounds__(512) void walk(const uint4* __restrict__ g, uint4* __restrict__ w, float* out, int rowbytes) {
   constexpr int RPS = 64;   // 512 threads = 64 rows x 8 vectors of 16 bytes
   constexpr int K = ROWS / RPS;
@@ -30,7 +32,8 @@ __global__ __launch_bounds__(512) void walk(const uint4* __restrict__ g, uint4* 
   const int steps = rowbytes / 128;
   unsigned acc = 0;
   for (int p = 0; p < PASSES; ++p)
-    for (int s = 0; s < steps; ++s) {
+    for (int s_ = 0; s_ < steps; ++s_) {
+      const int s = (REV && p == PASSES - 1) ? steps - 1 - s_ : s_;   // the last pass may walk the stripe backwards
       uint4 q[K];
 #pragma unroll
       for (int k = 0; k < K; ++k) q[k] = g[((row0 + r + k * RPS) * rowbytes + (size_t)s * 128) / 16 + v];
@@ -48,16 +51,16 @@ __global__ __launch_bounds__(512) void walk(const uint4* __restrict__ g, uint4* 
   if (acc == 0x12345678u) out[0] = 1.f;   // keeps the loads alive
 }
 
-template <int ROWS, int PASSES, bool RMW>
+template <int ROWS, int PASSES, bool RMW, bool REV = false>
 void run(const char* name, const uint4* g, uint4* w, float* out, int rows, int rowbytes) {
   hipEvent_t a, b;
   CK(hipEventCreate(&a));
   CK(hipEventCreate(&b));
   const dim3 grid(rows / ROWS);
-  for (int i = 0; i < 2; ++i) hipLaunchKernelGGL((walk<ROWS, PASSES, RMW>), grid, dim3(512), 0, 0, g, w, out, rowbytes);
+  for (int i = 0; i < 2; ++i) hipLaunchKernelGGL((walk<ROWS, PASSES, RMW, REV>), grid, dim3(512), 0, 0, g, w, out, rowbytes);
   CK(hipEventRecord(a));
   const int N = 10;
-  for (int i = 0; i < N; ++i) hipLaunchKernelGGL((walk<ROWS, PASSES, RMW>), grid, dim3(512), 0, 0, g, w, out, rowbytes);
+  for (int i = 0; i < N; ++i) hipLaunchKernelGGL((walk<ROWS, PASSES, RMW, REV>), grid, dim3(512), 0, 0, g, w, out, rowbytes);
   CK(hipEventRecord(b));
   CK(hipEventSynchronize(b));
   CK(hipGetLastError());
@@ -66,7 +69,7 @@ void run(const char* name, const uint4* g, uint4* w, float* out, int rows, int r
   ms /= N;
   const double mat = (double)rows * rowbytes;
   const double bytes = mat * (PASSES + (RMW ? 2 : 0));
-  printf("  %-11s rows/workgroup %3d  %7.3f ms  %5.2f TB/s requested\n", name, ROWS, ms, bytes / ms / 1e9);
+  printf("  %-13s rows/workgroup %3d  %7.3f ms  %5.2f TB/s requested\n", name, ROWS, ms, bytes / ms / 1e9);
   fflush(stdout);
   CK(hipEventDestroy(a));
   CK(hipEventDestroy(b));
@@ -90,6 +93,8 @@ int main() {
     run<64, 2, true>("read + rmw", g, w, out, rows, rowbytes);
     run<128, 2, true>("read + rmw", g, w, out, rows, rowbytes);
     run<256, 2, true>("read + rmw", g, w, out, rows, rowbytes);
+    run<128, 2, false, true>("read x2 back", g, w, out, rows, rowbytes);
+    run<128, 2, true, true>("read+rmw back", g, w, out, rows, rowbytes);
     CK(hipFree(g));
     CK(hipFree(w));
     CK(hipFree(out));

@@ -427,11 +427,14 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   const float ob2 = (1.f - sc.beta2) * (gs * gs);                  // per-element v sees (gs g)^2
   const float bound = -cf.neg_lrs * cf.clip;
   constexpr int WV = W16 ? 1 : 2;                                  // 16-byte pieces of W per 8 elements
+  // Pass 2 walks the stripe from its last 64-column chunk to its first: tile j of the loops is chunk nc-1-j,
+  // so what pass 1 read last is asked for again first and part of the second read of G is served by the caches.
   auto fetch_gw = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
-    const bool ok = j * BK + c8 < n;
+    const int pj = nc - 1 - j;
+    const bool ok = (unsigned)pj < (unsigned)nc && pj * BK + c8 < n;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const unsigned e = eoff[i] + (unsigned)(j * BK);
+      const unsigned e = eoff[i] + (unsigned)(pj * BK);
       gq[i] = buf_load16(rG, ok ? e * 2u : OOB);
 #pragma unroll
       for (int k = 0; k < WV; ++k) wq[i][k] = buf_load16(rW, ok ? e * WE + 16u * k : OOB);
@@ -440,11 +443,12 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   // tile j < 0 or at / beyond nc: every store falls outside the buffer and is dropped
   auto tail = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
     const float* cs = reinterpret_cast<const float*>(Cs + (j & 1) * C_TILE);
-    const bool ok = j >= 0 && j * BK + c8 < n;
+    const int pj = nc - 1 - j;
+    const bool ok = (unsigned)pj < (unsigned)nc && pj * BK + c8 < n;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int row = (t512 >> 3) + 64 * i;
-      const unsigned e = eoff[i] + (unsigned)(j * BK);
+      const unsigned e = eoff[i] + (unsigned)(pj * BK);
       const uint32_t gw[4] = {gq[i].x, gq[i].y, gq[i].z, gq[i].w};
       float g[8], mc[8], inv[8];
 #pragma unroll
@@ -520,7 +524,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
     // round j: start the copy of image j, build tile j-1 from the image that landed in the last round
     for (int j = 0; j < NR2; ++j) {
       p2_round<RT>(lds_addr(Ts) + ((j - 1) & 1) * TB, Ts + (j & 1) * TB, (lds_f32*)(lds + 2 * TB + ((j - 1) & 1) * C_TILE),
-                   Timg + (int64_t)j * TB, j < nc, j >= 1 && j <= nc, dh, dl, toff, coff, mw, lane);
+                   Timg + (int64_t)(j < nc ? nc - 1 - j : 0) * TB, j < nc, j >= 1 && j <= nc, dh, dl, toff, coff, mw, lane);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // image j has landed
       wg_barrier();
     }
