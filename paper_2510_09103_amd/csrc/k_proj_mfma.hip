@@ -100,6 +100,15 @@ __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c, bf16x8
 __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c)::"memory");
 }
+// the same, leaving the newest KEEP LDS requests of this wave in flight
+template <int KEEP>
+__device__ __forceinline__ void lds_wait_keep(bf16x8& a, bf16x8& b, bf16x8& c, bf16x8& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(KEEP) : "memory");
+}
+template <int KEEP>
+__device__ __forceinline__ void lds_wait_keep(bf16x8& a, bf16x8& b, bf16x8& c) {
+  asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(KEEP) : "memory");
+}
 
 // Barrier of the role loops: LDS traffic of this wave is complete, global loads / copies stay in flight
 // (__syncthreads() would also drain every outstanding global access, and with it the prefetches).
@@ -124,21 +133,35 @@ __device__ __forceinline__ void p1_round(unsigned qs, unsigned gs, lds_u8* dst, 
     const int l32 = lane & 31, lh = lane >> 5;
     const unsigned qa = qs + (unsigned)((my_rt * 2 * 64 + lane) * 16);
     const unsigned ga = gs + (unsigned)(((32 * my_mt0 + l32) * GS + 8 * lh) * 2);
+    // the fragments of k-step kk+1 are requested before the products of k-step kk are issued, so the wave's
+    // LDS latency hides behind its own matrix work (LDS results return in order: the wait leaves the newer
+    // requests in flight)
+    constexpr int NK = BK / 16, NF = 2 + TPW;
+    bf16x8 bh[2], bl[2], a0[2], a1[2];
+    bh[0] = lds_frag_raw(qa);
+    bl[0] = lds_frag_raw(qa + 1024);
+    a0[0] = lds_frag_raw(ga);
+    if (TPW == 2) a1[0] = lds_frag_raw(ga + 32 * GS * 2);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 bh = lds_frag_raw(qa + kk * RT * 2048);
-      bf16x8 bl = lds_frag_raw(qa + kk * RT * 2048 + 1024);
-      bf16x8 a0 = lds_frag_raw(ga + kk * 32);
-      if (TPW == 2) {
-        bf16x8 a1 = lds_frag_raw(ga + kk * 32 + 32 * GS * 2);
-        lds_wait(bh, bl, a0, a1);
-        acc[TPW - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bh, acc[TPW - 1], 0, 0, 0);
-        acc[TPW - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bl, acc[TPW - 1], 0, 0, 0);
-      } else {
-        lds_wait(bh, bl, a0);
+    for (int kk = 0; kk < NK; ++kk) {
+      const int c = kk & 1, nx = c ^ 1;
+      if (kk + 1 < NK) {
+        bh[nx] = lds_frag_raw(qa + (kk + 1) * RT * 2048);
+        bl[nx] = lds_frag_raw(qa + (kk + 1) * RT * 2048 + 1024);
+        a0[nx] = lds_frag_raw(ga + (kk + 1) * 32);
+        if (TPW == 2) a1[nx] = lds_frag_raw(ga + (kk + 1) * 32 + 32 * GS * 2);
       }
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bh, acc[0], 0, 0, 0);
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bl, acc[0], 0, 0, 0);
+      if (TPW == 2) {
+        if (kk + 1 < NK) lds_wait_keep<NF>(bh[c], bl[c], a0[c], a1[c]); else lds_wait(bh[c], bl[c], a0[c], a1[c]);
+        acc[TPW - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[c], bh[c], acc[TPW - 1], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[c], bh[c], acc[0], 0, 0, 0);
+        acc[TPW - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[c], bl[c], acc[TPW - 1], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[c], bl[c], acc[0], 0, 0, 0);
+      } else {
+        if (kk + 1 < NK) lds_wait_keep<NF>(bh[c], bl[c], a0[c]); else lds_wait(bh[c], bl[c], a0[c]);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[c], bh[c], acc[0], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[c], bl[c], acc[0], 0, 0, 0);
+      }
     }
   }
 }
