@@ -54,7 +54,7 @@ typedef enum { ADAPM_V_ELEMENT = 0, ADAPM_V_ROWGROUP = 1, ADAPM_V_WHOLE = 2 } ad
  *            as a (hi, lo) pair of bf16 values (relative operand error 2^-17);
  *            requires bf16 gradients.  Implemented for rank <= 128 (a block runs in
  *            the kernels of the next rank class 32 / 64 / 128, its factors padded
- *            with zeros on chip) and cols % 8 == 0; any other block silently uses F64;
+ *            with zeros on chip) and cols >= 8; any other block silently uses F64;
  *  AUTO    - per block: F64 when the block's parameters are fp32, else BF16X2. */
 typedef enum { ADAPM_CONTRACT_AUTO = 0, ADAPM_CONTRACT_F64 = 1, ADAPM_CONTRACT_BF16X2 = 2 } adapm_contract_t;
 

@@ -162,7 +162,9 @@ int64_t group_elems(const adapm_block_t& b) {
 }
 int esize(int32_t dt) { return dt == ADAPM_BF16 ? 2 : 4; }
 
-// BF16X2 needs bf16 gradients, a rank of 32, 64 or 128 and 16-byte aligned rows; other blocks use F64.
+// BF16X2 needs bf16 gradients and a rank of at most 128; other blocks use F64.  The number of columns is free:
+// the fused kernels read 8-element vectors at whatever alignment the rows have and finish a row's last
+// cols mod 8 columns element by element.
 // rank class the MFMA kernels are compiled for (the bf16 images of the factors are zero-padded to it); 0 = none
 int rank_class(int r) { return r <= 32 ? 32 : (r <= 64 ? 64 : (r <= 128 ? 128 : 0)); }
 
@@ -170,13 +172,13 @@ int path_of(const adapm_block_t& b, const adapm_hparams_t& hp) {
   if (b.mom_mode != ADAPM_MOM_LOWRANK) return PATH_NONE;
   const bool want = hp.contraction == ADAPM_CONTRACT_BF16X2 ||
                     (hp.contraction == ADAPM_CONTRACT_AUTO && b.param_dtype == ADAPM_BF16);
-  const bool can = b.grad_dtype == ADAPM_BF16 && rank_class(b.rank) != 0 && b.cols % 8 == 0 &&
+  const bool can = b.grad_dtype == ADAPM_BF16 && rank_class(b.rank) != 0 && b.cols >= 8 &&
                    b.cols <= (1 << 21);   // 128 rows of a stripe stay inside one 32-bit buffer range
   return (want && can) ? PATH_FAST : PATH_F64;
 }
 // Alg. 2 on the MFMA path: the two products that stream G (G R^T and L^T G) run as stripe products when
-// the transposed copy of G also has 16-byte rows and fits the kernel's 32-bit buffer ranges
-bool stripe_ok(const adapm_block_t& b) { return b.rows % 8 == 0 && b.rows <= (1 << 21); }
+// G and its transposed copy both have 16-byte rows and the copy fits the kernel's 32-bit buffer ranges
+bool stripe_ok(const adapm_block_t& b) { return b.rows % 8 == 0 && b.cols % 8 == 0 && b.rows <= (1 << 21); }
 // v of a block on the MFMA path can be finished inside the 128-row stripe of the fused kernel
 bool v_fusable(const adapm_block_t& b) {
   return b.v_mode == ADAPM_V_ROWGROUP && b.v_group_rows <= 128 && 128 % b.v_group_rows == 0;
@@ -381,7 +383,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       else { d.v_kind = 2; d.v_group_rows = b.v_mode == ADAPM_V_WHOLE ? (int32_t)b.rows : b.v_group_rows; }
       d.param_dtype = b.param_dtype; d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
       d.a1 = hp.bias_correction ? 1.f : 0.f; d.a2 = hp.bias_correction ? -1.f : 1.f;
-      d.l1 = Lp.ref; d.l2 = Lc.ref; d.off_img1 = L.wT1; d.off_img2 = L.wT2; d.off_v = L.sv;
+      d.l1 = Lp.ref; d.l2 = Lc.ref; d.q1 = Rp.ref; d.q2 = Rc.ref; d.off_img1 = L.wT1; d.off_img2 = L.wT2; d.off_v = L.sv;
       c->rub.h.push_back(d);
       for (int ch = 0; ch < (n + 63) / 64; ++ch) {
         if (hp.bias_correction) c->qt.h.push_back(ImgItem{Rp, r, n, ch, d.rc, L.wT1});

@@ -33,6 +33,11 @@ struct Bases {
 // factor that the global gradient-norm clipping puts on every gradient of this step
 __device__ __forceinline__ float grad_scale(const Bases& b) { return b.gscale ? *b.gscale : 1.f; }
 
+// 16-byte vectors at the alignment of their elements: rows of G, W, R and v start wherever the number of
+// columns puts them (the hardware serves global and buffer accesses at any byte alignment)
+struct __attribute__((packed, aligned(2))) u32x4_a2 { uint32_t x, y, z, w; };
+struct __attribute__((packed, aligned(4))) f32x4_a4 { float x, y, z, w; };
+
 __device__ __forceinline__ char* resolve(const Ref& r, const Bases& b) {
   switch (r.space) {
     case SP_STATE: return b.state + r.off;
@@ -192,6 +197,7 @@ struct RuBlockDev {
   int32_t param_dtype;
   float lr_scale, wd, a1, a2;
   Ref l1, l2;              // fp32, m x r, row stride r
+  Ref q1, q2;              // fp32, r x n, row stride n (read for a row's last n mod 8 columns only)
   int64_t off_img1, off_img2;   // workspace: images of Q1^T, Q2^T (layout of the held-R kernel's second image)
   int64_t off_v;           // state
 };

@@ -57,13 +57,13 @@ __device__ __forceinline__ void fetch(const char* base, int dtype, int64_t su, i
       const int64_t idx = (int64_t)gu * su + gk;
       if (gu < U && gk + 8 <= K) {
         if (dtype == DT_BF16) {
-          const uint4 q = *reinterpret_cast<const uint4*>(base + idx * 2);
+          const u32x4_a2 q = *reinterpret_cast<const u32x4_a2*>(base + idx * 2);
           const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) { st.x[8 * h + 2 * i] = __uint_as_float(w[i] << 16); st.x[8 * h + 2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u); }
         } else {
-          const float4 a = *reinterpret_cast<const float4*>(base + idx * 4);
-          const float4 b = *reinterpret_cast<const float4*>(base + idx * 4 + 16);
+          const f32x4_a4 a = *reinterpret_cast<const f32x4_a4*>(base + idx * 4);
+          const f32x4_a4 b = *reinterpret_cast<const f32x4_a4*>(base + idx * 4 + 16);
           st.x[8 * h + 0] = a.x; st.x[8 * h + 1] = a.y; st.x[8 * h + 2] = a.z; st.x[8 * h + 3] = a.w;
           st.x[8 * h + 4] = b.x; st.x[8 * h + 5] = b.y; st.x[8 * h + 6] = b.z; st.x[8 * h + 7] = b.w;
         }

@@ -214,19 +214,20 @@ struct Pass1 {
   static constexpr int D1 = 4;                            // chunks of A in flight per streaming thread
 };
 
-// P = A Q^T for the 128 rows of A behind the range-checked buffer rG (bf16, n columns, row stride n),
-// Q given as its fragment image Qf.  Leaves P in LDS at smem as [BM][R + 4] fp32 (the caller has to
+// P = A Q^T for the 128 rows of A behind the range-checked buffer rG (bf16, row stride n; columns 0 .. nv-1,
+// nv a multiple of 8, are covered: rows need not start on 16-byte boundaries, a row's last n mod 8 columns
+// are the caller's business), Q given as its fragment image Qf.  Leaves P in LDS at smem as [BM][R + 4] fp32 (the caller has to
 // __syncthreads() before reading it) and returns, in the streaming waves, this thread's sums of
 // squares of its two rows of A (rows t512/8 and 64 + t512/8, columns 8 (t512 % 8) .. of every chunk).
 template <int RT>
-__device__ __forceinline__ void stripe_pass1(unsigned char* smem, __amdgpu_buffer_rsrc_t rG, int n,
+__device__ __forceinline__ void stripe_pass1(unsigned char* smem, __amdgpu_buffer_rsrc_t rG, int n, int nv,
                                              const char* __restrict__ Qf, float& ss0, float& ss1) {
   constexpr int QF = Pass1<RT>::QF, G_TILE = Pass1<RT>::G_TILE, NB1 = Pass1<RT>::NB1, PS = Pass1<RT>::PS, D1 = Pass1<RT>::D1;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool mrole = wave < 8;
   const int mw = wave & 7, t512 = tid & 511, l32 = lane & 31, lh = lane >> 5;
-  const int nc = (n + BK - 1) / BK;
+  const int nc = (nv + BK - 1) / BK;
   const int c8 = (t512 & 7) * 8;
   const unsigned eoff[2] = {(unsigned)((t512 >> 3) * n + c8), (unsigned)((64 + (t512 >> 3)) * n + c8)};
   const int NR1 = (nc + 1 + D1) / D1 * D1;             // rounds: nc + 2, rounded up to the prefetch depth
@@ -246,7 +247,7 @@ __device__ __forceinline__ void stripe_pass1(unsigned char* smem, __amdgpu_buffe
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
   ss0 = 0.f; ss1 = 0.f;
   auto fetch_g = [&](int c, uint4 (&dst)[2]) {
-    const bool ok = c * BK + c8 < n;
+    const bool ok = c * BK + c8 < nv;
 #pragma unroll
     for (int i = 0; i < 2; ++i) dst[i] = buf_load16(rG, ok ? (eoff[i] + (unsigned)(c * BK)) * 2u : OOB);
   };
@@ -330,6 +331,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
   __shared__ float vrow[BM];
   __shared__ float rsum[BM];
+  __shared__ float ctail[BM * 8];                         // (D Q) of a row's last n mod 8 columns
 
   const ProjItem item = items[blockIdx.x];
   if (item.lr < 0) return;
@@ -345,7 +347,12 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   const int t512 = tid & 511;                        // thread index within the role
   const int l32 = lane & 31, lh = lane >> 5;
   const int m = B.m, n = B.n, row0 = item.row0;
-  const int nc = (n + BK - 1) / BK;
+  // Rows of G and W need not start on 16-byte boundaries (n need not be a multiple of 8): the 8-element vectors
+  // of the two passes cover columns 0 .. n8-1 of every row at whatever alignment they have; the last
+  // n mod 8 columns of the rows are done element by element beside the passes (rank-(n mod 8) correction of P,
+  // their share of D Q, their update).
+  const int n8 = n & ~7, nt = n - n8;
+  const int nc = (n8 + BK - 1) / BK;
   const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(bs.grads[B.block]);
   char* __restrict__ W = reinterpret_cast<char*>(bs.params[B.block]);
   float* __restrict__ Lst = reinterpret_cast<float*>(bs.state + B.off_L);
@@ -367,7 +374,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
 
   // ------------------------------------------------------------------ pass 1: P = G Q^T, left in LDS
   float ss0, ss1;                                    // streaming thread: sums of g^2 of rows t512/8 and 64 + t512/8
-  stripe_pass1<RT>(smem, rG, n, Qf, ss0, ss1);
+  stripe_pass1<RT>(smem, rG, n, n8, Qf, ss0, ss1);
   lds_u8* const lds = (lds_u8*)smem;
 
   // ------------------------------------------------------------------ second moment of the stripe, P to LDS
@@ -378,6 +385,43 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
     if ((t512 & 7) == 0) { rsum[t512 >> 3] = ss0 * (gs * gs); rsum[64 + (t512 >> 3)] = ss1 * (gs * gs); }
   }
   __syncthreads();
+  // the last n mod 8 columns: their G and Q (fp32, exact) staged beside P, then P += G_tail Q_tail^T and the
+  // rows' sums of squares
+  constexpr int TAIL_OFF = (P_BYTES > D_BYTES ? P_BYTES : D_BYTES);
+  static_assert(TAIL_OFF % 16 == 0 && TAIL_OFF + (BM + R) * 8 * 4 <= SMEM, "tail staging fits beside P and D");
+  float* const gtail = reinterpret_cast<float*>(smem + TAIL_OFF);   // [BM][8]
+  float* const qtail = gtail + BM * 8;                              // [R][8]
+  if (nt > 0) {
+    const float* __restrict__ Qst = reinterpret_cast<const float*>(bs.state + B.off_Q);   // r x n
+    for (int id = tid; id < (BM + R) * 8; id += NT) {
+      const int c = id & 7;
+      float x = 0.f;
+      if (id < BM * 8) {
+        const int row = id >> 3;
+        if (c < nt && row0 + row < m) x = bf16lo((uint32_t)G[(int64_t)(row0 + row) * n + n8 + c]);
+      } else {
+        const int k = (id >> 3) - BM;
+        if (c < nt && k < B.r) x = Qst[(int64_t)k * n + n8 + c];
+      }
+      gtail[id] = x;
+    }
+    __syncthreads();
+    float* Pw = reinterpret_cast<float*>(smem);
+    for (int id = tid; id < BM * R; id += NT) {
+      const int row = id / R, k = id % R;
+      float acc = 0.f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc = fmaf(gtail[row * 8 + c], qtail[k * 8 + c], acc);
+      Pw[row * PS + k] += acc;
+    }
+    if (tid < BM) {
+      float q = 0.f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) q = fmaf(gtail[tid * 8 + c], gtail[tid * 8 + c], q);
+      rsum[tid] += q * (gs * gs);
+    }
+    __syncthreads();
+  }
   if (B.v_kind == 1) {             // groups of v_group_rows rows inside the stripe: finish v here
     const int g = B.v_group_rows;
     if (tid < BM / g) {
@@ -441,6 +485,14 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
     *reinterpret_cast<uint2*>(Dl + row * DS + c4) = dlv[i];
   }
   __syncthreads();
+  if (nt > 0) {                    // (D Q) of the last n mod 8 columns, kept until the end of pass 2
+    static_assert(BM * 8 == NT, "one tail element per thread");
+    const int row = tid >> 3, c = tid & 7;
+    float acc = 0.f;
+    for (int k = 0; k < R; ++k)
+      acc = fmaf(bf16lo((uint32_t)Dh[row * DS + k]) + bf16lo((uint32_t)Dl[row * DS + k]), qtail[k * 8 + c], acc);
+    ctail[tid] = acc;
+  }
   // ------------------------------------------------------------------ pass 2: C = D Q, update W
   // Matrix-core waves build tile j of D Q (Q^T image j came by direct-to-LDS copy during tile j-1) while
   // the streaming waves run the element-wise tail of tile j-1 and prefetch G, W.  One barrier per tile.
@@ -454,7 +506,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   // so what pass 1 read last is asked for again first and part of the second read of G is served by the caches.
   auto fetch_gw = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
     const int pj = nc - 1 - j;
-    const bool ok = (unsigned)pj < (unsigned)nc && pj * BK + c8 < n;
+    const bool ok = (unsigned)pj < (unsigned)nc && pj * BK + c8 < n8;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const unsigned e = eoff[i] + (unsigned)(pj * BK);
@@ -467,7 +519,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   auto tail = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
     const float* cs = reinterpret_cast<const float*>(Cs + (j & 1) * C_TILE);
     const int pj = nc - 1 - j;
-    const bool ok = (unsigned)pj < (unsigned)nc && pj * BK + c8 < n;
+    const bool ok = (unsigned)pj < (unsigned)nc && pj * BK + c8 < n8;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int row = (t512 >> 3) + 64 * i;
@@ -488,10 +540,10 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
       }
       if (B.v_kind == 0) {          // per-element second moment
         float vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        float4* vp = reinterpret_cast<float4*>(vst + (int64_t)row0 * n + e);
+        f32x4_a4* vp = reinterpret_cast<f32x4_a4*>(vst + (int64_t)row0 * n + e);
         const bool live = ok && row0 + row < m;
         if (live) {
-          const float4 va = vp[0], vb = vp[1];
+          const f32x4_a4 va = vp[0], vb = vp[1];
           vv[0] = va.x; vv[1] = va.y; vv[2] = va.z; vv[3] = va.w;
           vv[4] = vb.x; vv[5] = vb.y; vv[6] = vb.z; vv[7] = vb.w;
         }
@@ -501,8 +553,8 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
           inv[k] = inv_denom_fast(vv[k], sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);   // -lr folded in
         }
         if (live) {
-          vp[0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
-          vp[1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
+          vp[0] = f32x4_a4{vv[0], vv[1], vv[2], vv[3]};
+          vp[1] = f32x4_a4{vv[4], vv[5], vv[6], vv[7]};
         }
       } else {
         const float x = vrow[row] * cf.neg_lrs;                     // -lr folded into the inverse denominator
@@ -580,6 +632,30 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
       }
     }
   }
+  // ------------------------------------------------------------------ the last n mod 8 columns, one element per thread
+  if (nt > 0) {
+    const int row = tid >> 3, c = tid & 7;
+    if (c < nt && row0 + row < m) {
+      const int64_t e = (int64_t)(row0 + row) * n + n8 + c;
+      const float g = bf16lo((uint32_t)G[e]);
+      const float mc = fmaf(sc.cC, ctail[tid], sc.cG == 1.f ? g : sc.cG * g);
+      float inv;
+      if (B.v_kind == 0) {
+        const float vv = sc.beta2 * vst[e] + ob2 * g * g;
+        vst[e] = vv;
+        inv = inv_denom_fast(vv, sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);
+      } else {
+        inv = vrow[row] * cf.neg_lrs;
+      }
+      if (W16) {
+        uint16_t* wp = reinterpret_cast<uint16_t*>(W) + e;
+        *wp = (uint16_t)pack_bf16x2(apply_update_scaled(bf16lo((uint32_t)*wp), mc, inv, bound, cf.decay), 0.f);
+      } else {
+        float* wp = reinterpret_cast<float*>(W) + e;
+        *wp = apply_update_scaled(*wp, mc, inv, bound, cf.decay);
+      }
+    }
+  }
 }
 
 // After Alg. 2: R (r x n fp32, state) -> the two bf16 (hi, lo) images used by proj_kernel, in the workspace.
@@ -650,7 +726,7 @@ struct RuTail {
     if (v_elem) {                   // per-element second moment
       float vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       if (ok) {
-        const float4 va = reinterpret_cast<const float4*>(vp)[0], vb = reinterpret_cast<const float4*>(vp)[1];
+        const f32x4_a4 va = reinterpret_cast<const f32x4_a4*>(vp)[0], vb = reinterpret_cast<const f32x4_a4*>(vp)[1];
         vv[0] = va.x; vv[1] = va.y; vv[2] = va.z; vv[3] = va.w;
         vv[4] = vb.x; vv[5] = vb.y; vv[6] = vb.z; vv[7] = vb.w;
       }
@@ -661,8 +737,8 @@ struct RuTail {
         inv[k] = inv_denom_fast(vv[k], sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);   // -lr folded in
       }
       if (ok) {
-        reinterpret_cast<float4*>(vp)[0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
-        reinterpret_cast<float4*>(vp)[1] = make_float4(vv[4], vv[5], vv[6], vv[7]);
+        reinterpret_cast<f32x4_a4*>(vp)[0] = f32x4_a4{vv[0], vv[1], vv[2], vv[3]};
+        reinterpret_cast<f32x4_a4*>(vp)[1] = f32x4_a4{vv[4], vv[5], vv[6], vv[7]};
       }
     } else {
 #pragma unroll
@@ -711,6 +787,7 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
   constexpr int D2 = 4;                           // tiles of G and W in flight per streaming thread
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
   __shared__ float vrow[BM];
+  __shared__ float ctail[BM * 8];                 // a1 L1 Q1 + a2 L2 Q2 of a row's last n mod 8 columns
 
   const ProjItem item = items[blockIdx.x];
   if (item.lr < 0) return;
@@ -722,7 +799,10 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
   const bool mrole = wave < 8;
   const int mw = wave & 7, t512 = tid & 511, l32 = lane & 31, lh = lane >> 5;
   const int m = B.m, n = B.n, r = B.r, row0 = item.row0;
-  const int nr = (n + BR - 1) / BR;               // 32-column tiles
+  // 8-element vectors cover columns 0 .. n8-1 of every row at whatever alignment the rows have; the last
+  // n mod 8 columns are done element by element (as in the held-R kernel)
+  const int n8 = n & ~7, nt = n - n8;
+  const int nr = (n8 + BR - 1) / BR;              // 32-column tiles
   const int NR = (nr + 1 + D2) / D2 * D2;         // rounds: nr + 2, rounded up to the prefetch depth
   const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(bs.grads[B.block]);
   char* __restrict__ W = reinterpret_cast<char*>(bs.params[B.block]);
@@ -765,6 +845,23 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
     }
   }
   __syncthreads();
+  if (nt > 0) {                    // the factors are staged: their product with the last columns of Q1, Q2
+    static_assert(BM * 8 == NT, "one tail element per thread");
+    const int row = tid >> 3, c = tid & 7;
+    float acc = 0.f;
+    if (c < nt) {
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        if ((p == 0 ? B.a1 : B.a2) == 0.f) continue;
+        const float* __restrict__ Qp = reinterpret_cast<const float*>(resolve(p == 0 ? B.q1 : B.q2, bs)) + n8 + c;
+        const uint16_t* Dh = reinterpret_cast<const uint16_t*>(smem + (2 * p) * D_ONE) + row * DS;
+        const uint16_t* Dl = reinterpret_cast<const uint16_t*>(smem + (2 * p + 1) * D_ONE) + row * DS;
+        for (int k = 0; k < r; ++k)
+          acc = fmaf(bf16lo((uint32_t)Dh[k]) + bf16lo((uint32_t)Dl[k]), Qp[(int64_t)k * n], acc);
+      }
+    }
+    ctail[tid] = acc;
+  }
 
   unsigned char* Cs = smem + 2 * TBUF;            // [2 buffers][2 products][BM][CR] fp32
   const UpdCoef cf = make_coef(sc.lr, B.lr_scale, B.wd, sc.clip);
@@ -847,7 +944,7 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
       for (int k = 0; k < WV; ++k) wq[u][k] = make_uint4(0, 0, 0, 0);
     }
     auto fetch = [&](int j, uint4& g, uint4 (&w)[WV]) {
-      const bool ok = j * BR + c8 < n;
+      const bool ok = j * BR + c8 < n8;
       const unsigned e = eoff + (unsigned)(j * BR);
       g = buf_load16(rG, ok ? e * 2u : OOB);
 #pragma unroll
@@ -865,7 +962,7 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
 #pragma unroll
       for (int u = 0; u < D2; ++u) {
         const int su = (u + 2 * D2 - 2) % D2, j = jb + u - 2;
-        const bool ok = j >= 0 && j * BR + c8 < n && row0 + row < m;
+        const bool ok = j >= 0 && j * BR + c8 < n8 && row0 + row < m;
         const float* ca = reinterpret_cast<const float*>(Cs + ((j & 1) * 2) * C_TILE) + row * CR + c8;
         const float* cb = ca + C_TILE / 4;
         const float4 a0 = *reinterpret_cast<const float4*>(ca), a1 = *reinterpret_cast<const float4*>(ca + 4);
@@ -875,6 +972,29 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
         RuTail<W16>::run(c, gq[su], wq[su], ok, e, rW, vst + (int64_t)row0 * n + e, v_elem, vinv, sc, cf, bound, gs * gs);
         fetch(jb + u - 2 + D2, gq[su], wq[su]);
         wg_barrier();
+      }
+    }
+  }
+  if (nt > 0) {                    // the last n mod 8 columns, one element per thread
+    const int row = tid >> 3, c = tid & 7;
+    if (c < nt && row0 + row < m) {
+      const int64_t e = (int64_t)(row0 + row) * n + n8 + c;
+      const float g = bf16lo((uint32_t)G[e]);
+      const float mc = fmaf(sc.cC, ctail[tid], sc.cG * g);
+      float inv;
+      if (B.v_kind == 0) {
+        const float vv = sc.beta2 * vst[e] + (1.f - sc.beta2) * (gs * gs) * g * g;
+        vst[e] = vv;
+        inv = inv_denom_fast(vv, sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);
+      } else {
+        inv = vrow[row] * cf.neg_lrs;
+      }
+      if (W16) {
+        uint16_t* wp = reinterpret_cast<uint16_t*>(W) + e;
+        *wp = (uint16_t)pack_bf16x2(apply_update_scaled(bf16lo((uint32_t)*wp), mc, inv, bound, cf.decay), 0.f);
+      } else {
+        float* wp = reinterpret_cast<float*>(W) + e;
+        *wp = apply_update_scaled(*wp, mc, inv, bound, cf.decay);
       }
     }
   }
@@ -922,7 +1042,7 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   const unsigned rows_valid = (unsigned)(M - row0 < BM ? M - row0 : BM);
   const __amdgpu_buffer_rsrc_t rA = make_rsrc(A + (int64_t)row0 * K, rows_valid * (unsigned)K * 2u);
   float ss0, ss1;
-  stripe_pass1<RT>(smem, rA, K, bs.ws + P.off_img, ss0, ss1);
+  stripe_pass1<RT>(smem, rA, K, K, bs.ws + P.off_img, ss0, ss1);
   __syncthreads();
   const float* Ps = reinterpret_cast<const float*>(smem);
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);

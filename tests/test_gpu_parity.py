@@ -77,7 +77,7 @@ def test_mixed_table_all_modes(hp):
 
 def ragged_bf16_table():
     """bf16 blocks on the MFMA path whose sizes are not multiples of the 64-row stripes, the
-    64-column chunks or the 128 x 128 GEMM tiles; every rank class; every kind of v."""
+    64-column chunks, the 128 x 128 GEMM tiles or the 8-element vectors; every rank class; every kind of v."""
     mk = BlockSpec
     return WL.Workload("ragged_bf16", (
         mk("r32_cols1000", 200, 1000, "bf16", "bf16", "lowrank", 32, "rowgroup", 1, 1.0, 0.1),
@@ -85,6 +85,12 @@ def ragged_bf16_table():
         mk("r128_rows130", 130, 264, "bf16", "bf16", "lowrank", 128, "rowgroup", 65, 1.0, 0.1),
         mk("r32_f32params", 70, 72, "f32", "bf16", "lowrank", 32, "whole", 1, 1.0, 0.0),
         mk("r64_heads16", 192, 320, "bf16", "bf16", "lowrank", 64, "rowgroup", 16, 1.0, 0.1, 16),
+        # columns that are not a multiple of 8: rows of G, W and v start at any 2-byte (4-byte) alignment and the
+        # last cols mod 8 columns of every row are done element by element
+        mk("r32_cols1001", 200, 1001, "bf16", "bf16", "lowrank", 32, "rowgroup", 1, 1.0, 0.1),
+        mk("r64_cols77_elem", 96, 77, "bf16", "bf16", "lowrank", 64, "element", 1, 1.0, 0.1),
+        mk("r128_cols333_f32params", 136, 333, "f32", "bf16", "lowrank", 128, "element", 1, 1.0, 0.0),
+        mk("r32_cols70_whole", 130, 70, "bf16", "bf16", "lowrank", 20, "whole", 1, 1.0, 0.1),
     ), steps=6, seed=5, signal_rank=40)
 
 
