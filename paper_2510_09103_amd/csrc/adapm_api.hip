@@ -118,7 +118,7 @@ struct adapm_ctx {
   DevList<SketchItem> sk;
   DevList<CholItem> chol[2];    // per path
   DevList<LrBlockDev> lrb;
-  DevList<ProjItem> proj[6];    // (rank 32 / 64 / 128) x (fp32 / bf16 parameters)
+  DevList<ProjItem> proj[12];   // (rank 32 / 64 / 128) x (fp32 / bf16 parameters) x (blockwise / per-element v)
   DevList<QsItem> qs;
   DevList<TrItem> tr;                   // Alg. 2, MFMA path: transposed copies of G
   DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
@@ -566,12 +566,15 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
   // hands in a different workspace); steps with R held reuse them
   c->seq_refresh.push_back(Op{OP_QSPLIT, 0, 0, 0, "split_Q"});
   seq.push_back(Op{OP_QSPLIT, 1, 0, 0, "split_Q"});
-  for (int cls = 0; cls < 6; ++cls) {       // (rank 32 / 64 / 128) x (fp32 / bf16 parameters)
-    const int rank = 32 << (cls >> 1);
+  for (int cls = 0; cls < 12; ++cls) {      // (rank 32 / 64 / 128) x (fp32 / bf16 parameters) x (blockwise / per-element v)
+    const int rank = 32 << ((cls >> 1) % 3);
     const int pdt = (cls & 1) ? ADAPM_BF16 : ADAPM_F32;
+    const bool vel = cls >= 6;
     std::vector<int64_t> ids;
     for (int64_t i = 0; i < nb; ++i)
-      if (lr_of[i] >= 0 && rank_class(c->table[i].rank) == rank && c->table[i].param_dtype == pdt) ids.push_back(i);
+      if (lr_of[i] >= 0 && rank_class(c->table[i].rank) == rank && c->table[i].param_dtype == pdt &&
+          (c->table[i].v_mode == ADAPM_V_ELEMENT) == vel)
+        ids.push_back(i);
     if (ids.empty()) continue;
     // longest rows first; whole blocks dealt to the least loaded XCD
     std::stable_sort(ids.begin(), ids.end(), [&](int64_t a, int64_t b) {
@@ -592,7 +595,8 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
     for (auto& v : per) longest = std::max(longest, v.size());
     for (size_t q = 0; q < longest; ++q)
       for (int x = 0; x < NXCD; ++x) c->proj[cls].h.push_back(q < per[x].size() ? per[x][q] : ProjItem{-1, 0});
-    seq.push_back(Op{OP_PROJ, cls, 0, 0, (cls >> 1) == 0 ? "fused_project_r32" : ((cls >> 1) == 1 ? "fused_project_r64" : "fused_project_r128")});
+    static const char* names[3] = {"fused_project_r32", "fused_project_r64", "fused_project_r128"};
+    seq.push_back(Op{OP_PROJ, cls, 0, 0, names[(cls >> 1) % 3]});
   }
 }
 
@@ -751,7 +755,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   for (auto& l : c->gram) total += bytes_of(l.h);
   for (auto& l : c->gnorm) total += bytes_of(l.h);
   for (int i = 0; i < 2; ++i) total += bytes_of(c->ew[i].h);
-  for (int i = 0; i < 6; ++i) total += bytes_of(c->proj[i].h);
+  for (int i = 0; i < 12; ++i) total += bytes_of(c->proj[i].h);
   for (int i = 0; i < 2; ++i) total += bytes_of(c->vs[i].h) + bytes_of(c->vf[i].h) + bytes_of(c->chol[i].h);
   for (auto& g : c->gemms) total += bytes_of(g.probs) + bytes_of(g.tiles);
   HIP_TRY(hipMalloc((void**)&c->arena, total));
@@ -771,7 +775,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   for (auto& l : c->gram) PUT_LIST(l);
   for (auto& l : c->gnorm) PUT_LIST(l);
   for (int i = 0; i < 2; ++i) PUT_LIST(c->ew[i]);
-  for (int i = 0; i < 6; ++i) PUT_LIST(c->proj[i]);
+  for (int i = 0; i < 12; ++i) PUT_LIST(c->proj[i]);
   for (int i = 0; i < 2; ++i) { PUT_LIST(c->vs[i]); PUT_LIST(c->vf[i]); PUT_LIST(c->chol[i]); }
 #undef PUT_LIST
   for (auto& g : c->gemms) {
@@ -991,8 +995,8 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         StepScalars x = sc;
         x.cG = c->hp.bias_correction ? 1.f : 0.f;
         x.cC = 1.f;
-        launch_proj(1 << (op.index >> 1), (op.index & 1) != 0, c->proj[op.index].d, (int64_t)c->proj[op.index].h.size(),
-                    c->lrb.d, bs, x, s);
+        launch_proj(1 << ((op.index >> 1) % 3), (op.index & 1) != 0, op.index >= 6, c->proj[op.index].d,
+                    (int64_t)c->proj[op.index].h.size(), c->lrb.d, bs, x, s);
         break;
       }
     }

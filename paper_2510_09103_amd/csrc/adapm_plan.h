@@ -236,7 +236,7 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 void launch_sketch(const SketchItem* items, int64_t nitems, char* state, hipStream_t s);
 void launch_chol(const CholItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gemm_mfma(const GemmProblem* probs, const GemmTile* tiles, int64_t ntiles, Bases b, hipStream_t s);
-void launch_proj(int rt, bool w16, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
+void launch_proj(int rt, bool w16, bool vel, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
                  StepScalars sc, hipStream_t s);
 void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s);
 void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s);

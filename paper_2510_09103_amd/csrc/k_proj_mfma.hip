@@ -313,7 +313,7 @@ __device__ __forceinline__ void stripe_pass1(unsigned char* smem, __amdgpu_buffe
   }
 }
 
-template <int RT, bool W16>
+template <int RT, bool W16, bool VEL>
 __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict__ items,
                                                      const LrBlockDev* __restrict__ lrb, Bases bs, StepScalars sc) {
   constexpr int R = 32 * RT;
@@ -365,11 +365,14 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   const unsigned rows_valid = (unsigned)(m - row0 < BM ? m - row0 : BM);
   const __amdgpu_buffer_rsrc_t rG = make_rsrc(G + (int64_t)row0 * n, rows_valid * (unsigned)n * 2u);
   const __amdgpu_buffer_rsrc_t rW = make_rsrc(W + (int64_t)row0 * n * WE, rows_valid * (unsigned)n * WE);
+  // VEL (every block of the launch has a per-element second moment): the stripe's rows of v as a third
+  // range-checked buffer, prefetched with G and W
+  const __amdgpu_buffer_rsrc_t rV = make_rsrc(vst + (VEL ? (int64_t)row0 * n : 0), VEL ? rows_valid * (unsigned)n * 4u : 0u);
   const int c8 = (t512 & 7) * 8;
   const unsigned eoff[2] = {(unsigned)((t512 >> 3) * n + c8), (unsigned)((64 + (t512 >> 3)) * n + c8)};
   // rounds of pass 2: nc + 2, rounded up to the prefetch depth of the streaming waves (their loop is
   // unrolled by the depth so that every register set has a fixed name)
-  constexpr int D2 = W16 ? 3 : 2;                    // tiles of G and W in flight per thread
+  constexpr int D2 = (W16 && !VEL) ? 3 : 2;          // tiles of G and W (and v) in flight per thread
   const int NR2 = (nc + 1 + D2) / D2 * D2;
 
   // ------------------------------------------------------------------ pass 1: P = G Q^T, left in LDS
@@ -504,7 +507,8 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   constexpr int WV = W16 ? 1 : 2;                                  // 16-byte pieces of W per 8 elements
   // Pass 2 walks the stripe from its last 64-column chunk to its first: tile j of the loops is chunk nc-1-j,
   // so what pass 1 read last is asked for again first and part of the second read of G is served by the caches.
-  auto fetch_gw = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
+  constexpr int VV = VEL ? 2 : 1;                                  // 16-byte pieces of v per 8 elements (VEL only)
+  auto fetch_gw = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV], uint4 (&vq)[2][VV]) {
     const int pj = nc - 1 - j;
     const bool ok = (unsigned)pj < (unsigned)nc && pj * BK + c8 < n8;
 #pragma unroll
@@ -513,10 +517,14 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
       gq[i] = buf_load16(rG, ok ? e * 2u : OOB);
 #pragma unroll
       for (int k = 0; k < WV; ++k) wq[i][k] = buf_load16(rW, ok ? e * WE + 16u * k : OOB);
+      if (VEL) {
+#pragma unroll
+        for (int k = 0; k < VV; ++k) vq[i][k] = buf_load16(rV, ok ? e * 4u + 16u * k : OOB);
+      }
     }
   };
   // tile j < 0 or at / beyond nc: every store falls outside the buffer and is dropped
-  auto tail = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV]) {
+  auto tail = [&](int j, uint4 (&gq)[2], uint4 (&wq)[2][WV], uint4 (&vq)[2][VV]) {
     const float* cs = reinterpret_cast<const float*>(Cs + (j & 1) * C_TILE);
     const int pj = nc - 1 - j;
     const bool ok = (unsigned)pj < (unsigned)nc && pj * BK + c8 < n8;
@@ -538,24 +546,17 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
 #pragma unroll
         for (int k = 0; k < 8; ++k) mc[k] = fmaf(sc.cC, cc[k], sc.cG * g[k]);
       }
-      if (B.v_kind == 0) {          // per-element second moment
-        float vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        f32x4_a4* vp = reinterpret_cast<f32x4_a4*>(vst + (int64_t)row0 * n + e);
-        const bool live = ok && row0 + row < m;
-        if (live) {
-          const f32x4_a4 va = vp[0], vb = vp[1];
-          vv[0] = va.x; vv[1] = va.y; vv[2] = va.z; vv[3] = va.w;
-          vv[4] = vb.x; vv[5] = vb.y; vv[6] = vb.z; vv[7] = vb.w;
-        }
+      if (VEL) {                    // per-element second moment, its old values prefetched with G and W
+        const uint32_t vw[8] = {vq[i][0].x, vq[i][0].y, vq[i][0].z, vq[i][0].w,
+                                vq[i][VV - 1].x, vq[i][VV - 1].y, vq[i][VV - 1].z, vq[i][VV - 1].w};
+        float vv[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          vv[k] = sc.beta2 * vv[k] + ob2 * g[k] * g[k];
+          vv[k] = sc.beta2 * __uint_as_float(vw[k]) + ob2 * g[k] * g[k];
           inv[k] = inv_denom_fast(vv[k], sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);   // -lr folded in
         }
-        if (live) {
-          vp[0] = f32x4_a4{vv[0], vv[1], vv[2], vv[3]};
-          vp[1] = f32x4_a4{vv[4], vv[5], vv[6], vv[7]};
-        }
+        buf_store16(rV, ok ? e * 4u : OOB, make_uint4(__float_as_uint(vv[0]), __float_as_uint(vv[1]), __float_as_uint(vv[2]), __float_as_uint(vv[3])));
+        buf_store16(rV, ok ? e * 4u + 16u : OOB, make_uint4(__float_as_uint(vv[4]), __float_as_uint(vv[5]), __float_as_uint(vv[6]), __float_as_uint(vv[7])));
       } else {
         const float x = vrow[row] * cf.neg_lrs;                     // -lr folded into the inverse denominator
 #pragma unroll
@@ -604,7 +605,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
       wg_barrier();
     }
   } else {
-    uint4 gq[D2][2], wq[D2][2][WV];                                // G / W vectors of D2 tiles in flight
+    uint4 gq[D2][2], wq[D2][2][WV], vq[D2][2][VV];                 // G / W (/ v) vectors of D2 tiles in flight
 #pragma unroll
     for (int u = 0; u < D2; ++u)
 #pragma unroll
@@ -612,11 +613,13 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
         gq[u][i] = make_uint4(0, 0, 0, 0);
 #pragma unroll
         for (int k = 0; k < WV; ++k) wq[u][i][k] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int k = 0; k < VV; ++k) vq[u][i][k] = make_uint4(0, 0, 0, 0);
       }
     __syncthreads();
 #pragma unroll
     for (int u = 0; u + 2 < D2; ++u) {                             // tiles the loop does not fetch itself
-      fetch_gw(u, gq[u], wq[u]);
+      fetch_gw(u, gq[u], wq[u], vq[u]);
       __builtin_amdgcn_sched_barrier(0);
     }
     // round j: tail of tile j-2 (built in the last round) from register set (j-2) % D2, then fetch tile
@@ -626,8 +629,8 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
 #pragma unroll
       for (int u = 0; u < D2; ++u) {
         const int su = (u + 2 * D2 - 2) % D2;
-        tail(jb + u - 2, gq[su], wq[su]);
-        fetch_gw(jb + u - 2 + D2, gq[su], wq[su]);
+        tail(jb + u - 2, gq[su], wq[su], vq[su]);
+        fetch_gw(jb + u - 2 + D2, gq[su], wq[su], vq[su]);
         wg_barrier();
       }
     }
@@ -640,7 +643,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
       const float g = bf16lo((uint32_t)G[e]);
       const float mc = fmaf(sc.cC, ctail[tid], sc.cG == 1.f ? g : sc.cG * g);
       float inv;
-      if (B.v_kind == 0) {
+      if (VEL) {
         const float vv = sc.beta2 * vst[e] + ob2 * g * g;
         vst[e] = vv;
         inv = inv_denom_fast(vv, sc.inv_debias_v, sc.inv_debias_m * cf.neg_lrs, sc.eps);
@@ -1200,10 +1203,12 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const TrItem* __res
 }
 
 template <int RT>
-void launch_proj_rt(bool w16, dim3 grid, const ProjItem* items, const LrBlockDev* lrb, Bases b, StepScalars sc,
+void launch_proj_rt(bool w16, bool vel, dim3 grid, const ProjItem* items, const LrBlockDev* lrb, Bases b, StepScalars sc,
                     hipStream_t s) {
-  if (w16) hipLaunchKernelGGL((proj_kernel<RT, true>), grid, dim3(NT), 0, s, items, lrb, b, sc);
-  else hipLaunchKernelGGL((proj_kernel<RT, false>), grid, dim3(NT), 0, s, items, lrb, b, sc);
+  if (w16 && vel) hipLaunchKernelGGL((proj_kernel<RT, true, true>), grid, dim3(NT), 0, s, items, lrb, b, sc);
+  else if (w16) hipLaunchKernelGGL((proj_kernel<RT, true, false>), grid, dim3(NT), 0, s, items, lrb, b, sc);
+  else if (vel) hipLaunchKernelGGL((proj_kernel<RT, false, true>), grid, dim3(NT), 0, s, items, lrb, b, sc);
+  else hipLaunchKernelGGL((proj_kernel<RT, false, false>), grid, dim3(NT), 0, s, items, lrb, b, sc);
 }
 
 }  // namespace
@@ -1211,13 +1216,14 @@ void launch_proj_rt(bool w16, dim3 grid, const ProjItem* items, const LrBlockDev
 size_t proj_qf_bytes(int r, int n) { return (size_t)((n + BK - 1) / BK) * qf_chunk_bytes(r); }
 size_t proj_timg_bytes(int r, int n) { return (size_t)((n + BK - 1) / BK) * timg_chunk_bytes(r); }
 
-void launch_proj(int rt, bool w16, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
+// vel: every block of the list keeps a per-element second moment (v_kind 0); otherwise none does
+void launch_proj(int rt, bool w16, bool vel, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
                  StepScalars sc, hipStream_t s) {
   if (nitems <= 0) return;
   const dim3 grid((unsigned)nitems);
-  if (rt == 1) launch_proj_rt<1>(w16, grid, items, lrb, b, sc, s);
-  else if (rt == 2) launch_proj_rt<2>(w16, grid, items, lrb, b, sc, s);
-  else launch_proj_rt<4>(w16, grid, items, lrb, b, sc, s);
+  if (rt == 1) launch_proj_rt<1>(w16, vel, grid, items, lrb, b, sc, s);
+  else if (rt == 2) launch_proj_rt<2>(w16, vel, grid, items, lrb, b, sc, s);
+  else launch_proj_rt<4>(w16, vel, grid, items, lrb, b, sc, s);
 }
 
 void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s) {
