@@ -147,6 +147,11 @@ adapm_status_t adapm_last_grad_norm(adapm_ctx* ctx, const void* workspace_dev, v
  * min_lr at total_steps, min_lr afterwards.  step counts from 1. */
 float adapm_lr_cosine_warmup(int64_t step, float peak_lr, float min_lr, int64_t warmup_steps, int64_t total_steps);
 
+/* Arithmetic the planner chose for the contractions of a block (see adapm_contract_t):
+ * ADAPM_CONTRACT_F64 or ADAPM_CONTRACT_BF16X2 for a low-rank block, -1 for a block without
+ * low-rank momentum or an index out of range. */
+int32_t adapm_block_contraction(const adapm_ctx* ctx, int64_t block);
+
 /* Number of kernel launches the last adapm_step enqueued (0 before the first). */
 int64_t adapm_last_launch_count(const adapm_ctx* ctx);
 

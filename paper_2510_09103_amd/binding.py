@@ -41,7 +41,8 @@ class adapm_hparams_t(C.Structure):
 
 
 EXPORTS = ["adapm_init", "adapm_state_bytes", "adapm_workspace_bytes", "adapm_state_offsets",
-           "adapm_state_init", "adapm_state_loaded", "adapm_step", "adapm_last_launch_count", "adapm_algorithmic_bytes",
+           "adapm_state_init", "adapm_state_loaded", "adapm_step", "adapm_block_contraction", "adapm_last_launch_count",
+           "adapm_algorithmic_bytes",
            "adapm_algorithmic_flops", "adapm_profile_enable", "adapm_profile_read", "adapm_last_error",
            "adapm_set_grad_clip", "adapm_last_grad_norm", "adapm_lr_cosine_warmup", "adapm_destroy"]
 
@@ -73,6 +74,8 @@ def _load() -> C.CDLL:
     lib.adapm_state_loaded.argtypes = [P]
     lib.adapm_step.restype = C.c_int
     lib.adapm_step.argtypes = [P, C.POINTER(P), C.POINTER(P), P, P, C.c_int64, C.c_float, P]
+    lib.adapm_block_contraction.restype = C.c_int32
+    lib.adapm_block_contraction.argtypes = [P, C.c_int64]
     lib.adapm_last_launch_count.restype = C.c_int64
     lib.adapm_last_launch_count.argtypes = [P]
     lib.adapm_algorithmic_bytes.restype = C.c_double
@@ -145,6 +148,10 @@ def adapm_step(ctx, params_ptrs, grads_ptrs, state_ptr: int, workspace_ptr: int,
     """params_ptrs / grads_ptrs: ctypes arrays of c_void_p (see ptr_array)."""
     _check(lib.adapm_step(ctx, params_ptrs, grads_ptrs, C.c_void_p(state_ptr), C.c_void_p(workspace_ptr),
                           step, lr, C.c_void_p(stream)))
+
+
+def adapm_block_contraction(ctx, block: int) -> int:
+    return lib.adapm_block_contraction(ctx, block)
 
 
 def adapm_last_launch_count(ctx) -> int:

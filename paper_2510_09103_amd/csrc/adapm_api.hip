@@ -1078,6 +1078,12 @@ float adapm_lr_cosine_warmup(int64_t step, float peak_lr, float min_lr, int64_t 
   return (float)((double)min_lr + 0.5 * ((double)peak_lr - (double)min_lr) * (1.0 + std::cos(M_PI * x)));
 }
 
+int32_t adapm_block_contraction(const adapm_ctx* c, int64_t block) {
+  if (!c || block < 0 || block >= (int64_t)c->lay.size()) return -1;
+  const int path = c->lay[block].path;
+  return path == PATH_FAST ? ADAPM_CONTRACT_BF16X2 : (path == PATH_F64 ? ADAPM_CONTRACT_F64 : -1);
+}
+
 int64_t adapm_last_launch_count(const adapm_ctx* c) { return c ? c->last_launches : 0; }
 
 double adapm_algorithmic_bytes(const adapm_ctx* c, int32_t refresh_step) {

@@ -77,6 +77,33 @@ def test_bf16x2_contraction_needs_bf16_gradients():
         B.adapm_init([blk(grad_dtype=B.ADAPM_F32)], make_hparams(contraction=B.ADAPM_CONTRACT_BF16X2))
 
 
+def test_planner_choice_of_contraction_per_block():
+    """AUTO: fp64 contraction for fp32 parameters, split-bf16 MFMA for bf16 parameters with bf16 gradients and
+    rank <= 128, whatever the number of columns (>= 8); everything else falls back to fp64."""
+    BF, F32 = B.ADAPM_BF16, B.ADAPM_F32
+    table = [
+        blk(rows=2048, cols=5461, rank=128, param_dtype=BF, grad_dtype=BF),     # odd column count: still MFMA
+        blk(rows=1600, cols=1600, rank=80, param_dtype=BF, grad_dtype=BF),      # rank between the classes
+        blk(rows=512, cols=512, rank=32, param_dtype=F32, grad_dtype=BF),       # fp32 parameters
+        blk(rows=512, cols=512, rank=32, param_dtype=BF, grad_dtype=F32),       # fp32 gradients
+        blk(rows=512, cols=512, rank=200, param_dtype=BF, grad_dtype=BF),       # rank above the largest class
+        blk(rows=64, cols=6, rank=2, param_dtype=BF, grad_dtype=BF),            # fewer than 8 columns
+        blk(rows=64, cols=64, param_dtype=BF, grad_dtype=BF, mom_mode=B.ADAPM_MOM_FULL, rank=0),
+    ]
+    ctx = B.adapm_init(table, make_hparams())
+    got = [B.adapm_block_contraction(ctx, i) for i in range(len(table))]
+    X, D = B.ADAPM_CONTRACT_BF16X2, B.ADAPM_CONTRACT_F64
+    assert got == [X, X, D, D, D, D, -1]
+    assert B.adapm_block_contraction(ctx, len(table)) == -1 and B.adapm_block_contraction(ctx, -1) == -1
+    B.adapm_destroy(ctx)
+    forced = B.adapm_init(table[:3], make_hparams(contraction=B.ADAPM_CONTRACT_BF16X2))
+    assert [B.adapm_block_contraction(forced, i) for i in range(3)] == [X, X, X]
+    B.adapm_destroy(forced)
+    exact = B.adapm_init(table[:3], make_hparams(contraction=B.ADAPM_CONTRACT_F64))
+    assert [B.adapm_block_contraction(exact, i) for i in range(3)] == [D, D, D]
+    B.adapm_destroy(exact)
+
+
 def test_step_argument_checks_do_not_need_a_device():
     ctx = B.adapm_init([blk()], make_hparams())
     pp, gp = B.ptr_array([256]), B.ptr_array([512])
