@@ -39,7 +39,7 @@ def block_bytes(b, refresh):
     return tot
 
 
-def cpu_baseline(wl, T, lr, nlayers=4, held_steps=3):
+def cpu_baseline(wl, T, lr, nlayers=6, held_steps=3):
     """The oracle, as it stands, on the first transformer layers of the workload (blocks are independent):
     one step that runs Alg. 2 and a few steps with R held, combined with the same T weighting.  Sized to
     10 - 30 s of CPU work at the GPT-2-1.5B shape."""
