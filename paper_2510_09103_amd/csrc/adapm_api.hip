@@ -141,7 +141,9 @@ struct adapm_ctx {
   hipEvent_t stage_free = nullptr;
   int64_t last_launches = 0;
   int n_lowrank = 0;
-  const void* split_ws = nullptr;       // workspace that holds valid bf16 copies of Q (T > 1, MFMA path)
+  const void* split_ws = nullptr;       // workspace that holds valid bf16 copies of Q (T > 1, MFMA path) ...
+  const void* split_state = nullptr;    // ... made from the R of this state buffer
+  std::vector<std::pair<std::string, std::pair<double, int64_t>>> prof_agg;   // folded timings (adapm_profile_read)
 
   bool profiling = false;
   std::vector<ProfRec> prof;
@@ -959,9 +961,10 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         break;
       case OP_QSPLIT:
         // index 1: only needed if the copies in the workspace are not the ones written last
-        if (op.index == 1 && c->split_ws == workspace_dev) { skipped = true; break; }
+        if (op.index == 1 && c->split_ws == workspace_dev && c->split_state == state_dev) { skipped = true; break; }
         launch_qimage(c->qs.d, (int64_t)c->qs.h.size(), c->lrb.d, bs, s);
         c->split_ws = workspace_dev;
+        c->split_state = state_dev;
         break;
       case OP_TRANSPOSE:
         launch_transpose_bf16(c->tr.d, (int64_t)c->tr.h.size(), bs, s);
@@ -1024,7 +1027,7 @@ int64_t adapm_profile_read(adapm_ctx* c, int64_t index, char* name, size_t name_
                            int64_t* launches) {
   if (!c) return 0;
   // fold the finished event pairs into per-label totals (the caller has synchronised the stream)
-  static thread_local std::vector<std::pair<std::string, std::pair<double, int64_t>>> agg;
+  auto& agg = c->prof_agg;
   if (index == 0) {
     agg.clear();
     for (const ProfRec& r : c->prof) {

@@ -293,6 +293,37 @@ def test_restoring_a_state_into_a_live_optimizer():
         assert torch.equal(x, y)
 
 
+def test_one_context_serving_two_state_buffers():
+    """The derived copies of R in the workspace belong to one state buffer: a context that steps two replicas
+    (two state buffers, one workspace) in turn must rebuild them whenever the state buffer changes."""
+    from paper_2510_09103_amd.optimizer import AdaPM, make_hparams
+    wl = WL.subset(WL.gpt2_350m(), ["h0.attn.q", "h0.mlp.fc"])
+    hp = make_hparams(beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, clip=wl.clip, K=wl.K, T=4)
+    stream = WL.GradientStream(wl, device="cuda:0")
+    grads = [[g.clone() for g in stream.next()] for _ in range(6)]
+    seqs = [grads, grads[::-1]]                      # the two replicas see different gradients
+    want = []
+    for k in (0, 1):                                 # each replica with a context of its own
+        opt = AdaPM(wl.blocks, hp)
+        params = WL.initial_params(wl, device="cuda:0")
+        for t in range(1, 7):
+            opt.step(params, seqs[k][t - 1], t, wl.lr)
+        torch.cuda.synchronize()
+        want.append((params, opt.state.clone()))
+    shared = AdaPM(wl.blocks, hp)
+    states = [shared.state, shared.state.clone()]    # the seeded start is the same for both
+    params = [WL.initial_params(wl, device="cuda:0"), WL.initial_params(wl, device="cuda:0")]
+    for t in range(1, 7):
+        for k in (0, 1):
+            shared.state = states[k]
+            shared.step(params[k], seqs[k][t - 1], t, wl.lr)
+    torch.cuda.synchronize()
+    for k in (0, 1):
+        for x, y in zip(params[k], want[k][0]):
+            assert torch.equal(x, y), f"replica {k}"
+        assert torch.equal(states[k], want[k][1]), f"replica {k}"
+
+
 def test_step_rejects_bad_arguments_on_device():
     wl = WL.subset(WL.tiny_block(), ["norm1"])
     pair = Pair(wl)
