@@ -102,8 +102,9 @@ size_t adapm_state_bytes(const adapm_ctx* ctx);
 /* Size of the caller-allocated scratch buffer used inside adapm_step (previous
  * factors, thin products, Gram matrices, partial sums).  With refresh_period_T > 1 the
  * library also keeps bf16 copies of R there between two runs of Alg. 2: pass the same,
- * unmodified buffer on consecutive steps (a different pointer is detected and the copies
- * are rebuilt; overwriting the contents between steps is not). */
+ * unmodified buffer on consecutive steps (a different workspace or state pointer is detected
+ * and the copies are rebuilt from that state; overwriting the contents of either buffer
+ * between steps is not, see adapm_state_loaded). */
 size_t adapm_workspace_bytes(const adapm_ctx* ctx);
 
 /* Byte offsets into the state buffer of block `block`'s sub-buffers; an absent
