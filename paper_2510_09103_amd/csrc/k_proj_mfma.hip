@@ -1106,50 +1106,66 @@ __global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict
 
 // r x r Gram-type products of Alg. 2 (R R^T, R' R^T, L^T L, L^T L') straight from the fragment images: a lane's
 // 16 bytes of an image hold 8 consecutive k of one row, which is the A-operand layout for rows of X and
-// equally the B-operand layout for columns of Y^T.  One workgroup per product; wave w owns column tile w of
-// the result (all row tiles); fragments come from global memory (the images sit in L2), one k-step ahead.
+// equally the B-operand layout for columns of Y^T.  One workgroup (4 waves) per product; the 64-column chunks of
+// the two images are copied global -> LDS without registers, two buffers deep, so that every image byte is read
+// from L2 once per product (read per wave, the launch was bound by L2 bandwidth); wave w owns column tile w of
+// the result (all row tiles).
 template <int RT>
-__device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs) {
+__device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, unsigned char* smem) {
   constexpr int R = 32 * RT;
   constexpr int QF = qf_chunk_bytes(R);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
-  if (wave >= RT) return;
+  const int lane = threadIdx.x & 63, l32 = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const char* __restrict__ X = bs.ws + it.off_x;
   const char* __restrict__ Y = bs.ws + it.off_y;
-  const int nsteps = ((it.K + BK - 1) / BK) * (BK / 16);           // k-steps of 16; the images are zero-padded
-  // fragment (k-step s, tile t, hi|lo): chunk s / 4, kk = s % 4
-  auto frag = [&](const char* img, int s, int t, int hl) {
-    const uint4 q = *reinterpret_cast<const uint4*>(img + (int64_t)(s >> 2) * QF + ((((s & 3) * RT + t) * 2 + hl) * 64 + lane) * 16);
-    return as_frag(q);
+  const bool same = it.off_x == it.off_y;
+  const int nch = (it.K + BK - 1) / BK;                               // the images are zero-padded to whole chunks
+  lds_u8* const lds = (lds_u8*)smem;                                  // [2 buffers][X | Y][QF]
+  auto copy = [&](int c, int buf) {
+    for (int k = wave; k < QF / 1024; k += 4) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(X + (int64_t)c * QF + k * 1024 + lane * 16),
+                                       (__attribute__((address_space(3))) void*)(lds + (buf * 2) * QF + k * 1024), 16, 0, 0);
+      if (!same)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Y + (int64_t)c * QF + k * 1024 + lane * 16),
+                                         (__attribute__((address_space(3))) void*)(lds + (buf * 2 + 1) * QF + k * 1024), 16, 0, 0);
+    }
   };
   f32x16 acc[RT];
 #pragma unroll
   for (int t = 0; t < RT; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
-  bf16x8 xh[RT], xl[RT], yh, yl;
+  copy(0, 0);
+  for (int c = 0; c < nch; ++c) {
+    // chunk c has landed (every wave waits for its own copies, the barrier collects them) and everybody is done
+    // with the buffer chunk c+1 goes to; its copy runs while chunk c is multiplied
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wg_barrier();
+    if (c + 1 < nch) copy(c + 1, (c + 1) & 1);
+    if (wave < RT) {
+      const unsigned xs = lds_addr(lds) + ((c & 1) * 2) * QF, ys = same ? xs : xs + QF;
 #pragma unroll
-  for (int t = 0; t < RT; ++t) { xh[t] = frag(X, 0, t, 0); xl[t] = frag(X, 0, t, 1); }
-  yh = frag(Y, 0, wave, 0);
-  yl = frag(Y, 0, wave, 1);
-  for (int s = 0; s < nsteps; ++s) {
-    bf16x8 nxh[RT], nxl[RT], nyh, nyl;
-    const int sn = s + 1 < nsteps ? s + 1 : s;                       // the last step re-reads itself (in bounds)
+      for (int kk = 0; kk < BK / 16; ++kk) {
+        bf16x8 xh[RT], xl[RT];
 #pragma unroll
-    for (int t = 0; t < RT; ++t) { nxh[t] = frag(X, sn, t, 0); nxl[t] = frag(X, sn, t, 1); }
-    nyh = frag(Y, sn, wave, 0);
-    nyl = frag(Y, sn, wave, 1);
+        for (int t = 0; t < RT; ++t) {
+          xh[t] = lds_frag_raw(xs + (((kk * RT + t) * 2) * 64 + lane) * 16);
+          xl[t] = lds_frag_raw(xs + (((kk * RT + t) * 2 + 1) * 64 + lane) * 16);
+        }
+        bf16x8 yh = lds_frag_raw(ys + (((kk * RT + wave) * 2) * 64 + lane) * 16);
+        bf16x8 yl = lds_frag_raw(ys + (((kk * RT + wave) * 2 + 1) * 64 + lane) * 16);
 #pragma unroll
-    for (int t = 0; t < RT; ++t) {
-      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[t], yh, acc[t], 0, 0, 0);
-      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[t], yh, acc[t], 0, 0, 0);
-      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[t], yl, acc[t], 0, 0, 0);
+        for (int t = 0; t < RT; ++t) lds_wait(xh[t], xl[t], yh, yl);
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[t], yh, acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[t], yh, acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[t], yl, acc[t], 0, 0, 0);
+        }
+      }
     }
-#pragma unroll
-    for (int t = 0; t < RT; ++t) { xh[t] = nxh[t]; xl[t] = nxl[t]; }
-    yh = nyh;
-    yl = nyl;
   }
+  if (wave >= RT) return;
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + it.off_out);
   const int r = it.r, col = 32 * wave + l32;
 #pragma unroll
@@ -1164,10 +1180,11 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs) {
 }
 
 __global__ __launch_bounds__(256) void gram_kernel(const GramItem* __restrict__ items, Bases bs) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * qf_chunk_bytes(128)];
   const GramItem it = items[blockIdx.x];
-  if (it.rc == 32) gram_body<1>(it, bs);
-  else if (it.rc == 64) gram_body<2>(it, bs);
-  else gram_body<4>(it, bs);
+  if (it.rc == 32) gram_body<1>(it, bs, smem);
+  else if (it.rc == 64) gram_body<2>(it, bs, smem);
+  else gram_body<4>(it, bs, smem);
 }
 
 // bf16 transpose through LDS, 64 x 64 tiles; needs m % 8 == 0 and n % 8 == 0 (16-byte vectors both ways)
