@@ -430,7 +430,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
     for (const StripeWork& sw : v) {
       int x = 0;
       for (int k = 1; k < NXCD; ++k) if (load[k] < load[x]) x = k;
-      for (int64_t r0 = 0; r0 < sw.M; r0 += 128) per[x].push_back(StripeItem{sw.prob, (int32_t)r0});
+      for (int64_t r0 = 0; r0 < sw.M; r0 += 256) per[x].push_back(StripeItem{sw.prob, (int32_t)r0});   // two stripes per workgroup
       load[x] += (double)sw.M * sw.K;
     }
     size_t longest = 0;

@@ -100,6 +100,9 @@ __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c, bf16x8
 __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c)::"memory");
 }
+__device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b)::"memory");
+}
 // the same, leaving the newest KEEP LDS requests of this wave in flight
 template <int KEEP>
 __device__ __forceinline__ void lds_wait_keep(bf16x8& a, bf16x8& b, bf16x8& c, bf16x8& d) {
@@ -301,6 +304,125 @@ __device__ __forceinline__ void stripe_pass1(unsigned char* smem, __amdgpu_buffe
   }
   __syncthreads();
   if (p1_active) {
+    float* Ps = reinterpret_cast<float*>(smem);
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+      const int col = 32 * my_rt + l32;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) Ps[(32 * (my_mt0 + t) + 8 * q + 4 * lh + p) * PS + col] = acc[t][4 * q + p];
+    }
+  }
+}
+
+// Pass 1 over TWO stripes (256 rows) at once: every chunk of the fragment image of Q that is copied into LDS
+// serves both, which halves the image traffic per row of A (the copies, 32 KB per 64 columns, cost more than a
+// quarter of the pass at 128 rows).  Two buffers of the image and of the A tile: round cc copies fragments cc
+// and stages chunk cc of A while chunk cc-1 is multiplied; the copy has to land within its round.
+template <int RT>
+struct Pass1x2 {
+  static constexpr int R = 32 * RT;
+  static constexpr int ROWS = 2 * BM;
+  static constexpr int PS = R + 4;                        // LDS row stride of P (floats)
+  static constexpr int QF = qf_chunk_bytes(R);
+  static constexpr int G_TILE = ROWS * GS * 2;
+  static constexpr int BYTES = 2 * QF + 2 * G_TILE;       // LDS during the pass
+  static constexpr int P_BYTES = ROWS * PS * 4;           // LDS holding P afterwards
+  static constexpr int D1 = 4;                            // chunks of A in flight per streaming thread
+};
+
+// As stripe_pass1, for the 256 rows behind rG: leaves P in LDS at smem as [256][R + 4] fp32 (the caller has to
+// __syncthreads() before reading it); ss[i] = this streaming thread's sum of squares of row t512/8 + 64 i.
+template <int RT>
+__device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_buffer_rsrc_t rG, int n, int nv,
+                                                const char* __restrict__ Qf, float (&ss)[4]) {
+  constexpr int QF = Pass1x2<RT>::QF, G_TILE = Pass1x2<RT>::G_TILE, PS = Pass1x2<RT>::PS, D1 = Pass1x2<RT>::D1;
+  constexpr int TPW = RT;                                 // 8 row tiles x RT rank tiles over 8 waves
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool mrole = wave < 8;
+  const int mw = wave & 7, t512 = tid & 511, l32 = lane & 31, lh = lane >> 5;
+  const int nc = (nv + BK - 1) / BK;
+  const int c8 = (t512 & 7) * 8;
+  unsigned eoff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) eoff[i] = (unsigned)(((t512 >> 3) + 64 * i) * n + c8);
+  const int NR1 = (nc + D1) / D1 * D1;                    // rounds: nc + 1, rounded up to the prefetch depth
+  lds_u8* const lds = (lds_u8*)smem;
+  lds_u8* const Qs = lds;                                 // [2][QF]
+  unsigned char* Gs = smem + 2 * QF;                      // [2][256][GS] bf16
+  const int my_rt = mw % RT;                              // rank tile
+  const int my_mt0 = (mw / RT) * TPW;                     // first of this wave's TPW row tiles
+  f32x16 acc[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) ss[i] = 0.f;
+  auto fetch_g = [&](int c, uint4 (&dst)[4]) {
+    const bool ok = c * BK + c8 < nv;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dst[i] = buf_load16(rG, ok ? (eoff[i] + (unsigned)(c * BK)) * 2u : OOB);
+  };
+  auto stage_g = [&](int buf, uint4 (&src)[4]) {
+    uint16_t* gs = reinterpret_cast<uint16_t*>(Gs + buf * G_TILE);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = (t512 >> 3) + 64 * i;
+      const uint4 q = src[i];
+      *reinterpret_cast<uint4*>(gs + row * GS + c8) = q;
+      ss[i] += dot2_sq(q.w, dot2_sq(q.z, dot2_sq(q.y, dot2_sq(q.x, 0.f))));
+    }
+  };
+  if (mrole) {
+    for (int cc = 0; cc < NR1; ++cc) {
+      if (cc < nc) dma_copy(Qf + (int64_t)cc * QF, Qs + (cc & 1) * QF, QF, mw, lane);
+      if (cc >= 1 && cc <= nc) {
+        const int b = (cc - 1) & 1;
+        const unsigned qa = lds_addr(Qs) + b * QF + (unsigned)((my_rt * 2 * 64 + lane) * 16);
+        const unsigned ga = lds_addr(Qs) + 2 * QF + b * G_TILE + (unsigned)(((32 * my_mt0 + l32) * GS + 8 * lh) * 2);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+          bf16x8 bh = lds_frag_raw(qa + kk * RT * 2048);
+          bf16x8 bl = lds_frag_raw(qa + kk * RT * 2048 + 1024);
+          bf16x8 a[TPW];
+#pragma unroll
+          for (int t = 0; t < TPW; ++t) a[t] = lds_frag_raw(ga + kk * 32 + t * 32 * GS * 2);
+          if (TPW == 1) lds_wait(bh, bl, a[0]);
+          else {
+            lds_wait(bh, bl, a[0], a[1]);
+            if (TPW == 4) lds_wait(a[TPW - 2], a[TPW - 1]);
+          }
+#pragma unroll
+          for (int t = 0; t < TPW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], bh, acc[t], 0, 0, 0);
+#pragma unroll
+          for (int t = 0; t < TPW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], bl, acc[t], 0, 0, 0);
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // fragments cc have landed
+      wg_barrier();
+    }
+  } else {
+    uint4 gq[D1][4];
+#pragma unroll
+    for (int u = 0; u < D1; ++u) {
+      fetch_g(u, gq[u]);
+      __builtin_amdgcn_sched_barrier(0);   // keep issue order = use order, or the loop's first wait drains everything
+    }
+    static_assert(D1 % 2 == 0, "the A tile buffer of round cb + u is u % 2");
+    for (int cb = 0; cb < NR1; cb += D1) {   // chunks at or beyond nc read zeros into a tile nobody multiplies
+#pragma unroll
+      for (int u = 0; u < D1; ++u) {
+        stage_g(u & 1, gq[u]);
+        fetch_g(cb + u + D1, gq[u]);
+        wg_barrier();
+      }
+    }
+  }
+  __syncthreads();
+  if (mrole) {
     float* Ps = reinterpret_cast<float*>(smem);
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
@@ -1034,18 +1156,18 @@ __global__ __launch_bounds__(256) void qt_image_kernel(const ImgItem* __restrict
 template <int RT>
 __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restrict__ items,
                                                        const StripeProb* __restrict__ probs, Bases bs) {
-  constexpr int R = 32 * RT, PS = Pass1<RT>::PS;
-  constexpr int SMEM = Pass1<RT>::BYTES > Pass1<RT>::P_BYTES ? Pass1<RT>::BYTES : Pass1<RT>::P_BYTES;
+  constexpr int R = 32 * RT, PS = Pass1x2<RT>::PS, ROWS = Pass1x2<RT>::ROWS;
+  constexpr int SMEM = Pass1x2<RT>::BYTES > Pass1x2<RT>::P_BYTES ? Pass1x2<RT>::BYTES : Pass1x2<RT>::P_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
   const StripeItem item = items[blockIdx.x];
   if (item.prob < 0) return;
   const StripeProb P = probs[item.prob];
   const int M = P.M, K = P.K, row0 = item.row0, tid = threadIdx.x;
   const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(resolve(P.a, bs));
-  const unsigned rows_valid = (unsigned)(M - row0 < BM ? M - row0 : BM);
+  const unsigned rows_valid = (unsigned)(M - row0 < ROWS ? M - row0 : ROWS);
   const __amdgpu_buffer_rsrc_t rA = make_rsrc(A + (int64_t)row0 * K, rows_valid * (unsigned)K * 2u);
-  float ss0, ss1;
-  stripe_pass1<RT>(smem, rA, K, K, bs.ws + P.off_img, ss0, ss1);
+  float ss[4];
+  stripe_pass1_x2<RT>(smem, rA, K, K, bs.ws + P.off_img, ss);
   __syncthreads();
   const float* Ps = reinterpret_cast<const float*>(smem);
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);
@@ -1054,7 +1176,7 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   if (!P.transpose_out) {
     const bool vec4 = (r & 3) == 0;
 #pragma unroll
-    for (int i = 0; i < (BM * R / 4) / NT; ++i) {
+    for (int i = 0; i < (ROWS * R / 4) / NT; ++i) {
       const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
       if (row0 + row < M && c4 < r) {
         float* o = Out + (int64_t)(row0 + row) * r + c4;
@@ -1072,8 +1194,8 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   } else {
     // Out[a][row0 + j] = P[j][a]: lanes run along j, so the global stores are contiguous
 #pragma unroll 4
-    for (int i = 0; i < (BM * R) / NT; ++i) {
-      const int id = tid + NT * i, j = id % BM, a = id / BM;
+    for (int i = 0; i < (ROWS * R) / NT; ++i) {
+      const int id = tid + NT * i, j = id % ROWS, a = id / ROWS;
       if (row0 + j < M && a < r) Out[(int64_t)a * M + row0 + j] = gs * Ps[j * PS + a];
     }
   }
