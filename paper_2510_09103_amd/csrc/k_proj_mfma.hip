@@ -14,12 +14,16 @@
 //                         chunk c-2 from the fragment image of Q; pass 2: the matrix-core waves build
 //                         tile j of D Q (D = beta1 (L_{t-1} - P) held in registers as A-fragments, Q^T
 //                         from a bank-swizzled LDS image) while the streaming waves apply the update of
-//                         tile j-2 to W and prefetch G, W of the next tiles.
-//  stripe_kernel          pass 1 alone, followed by a store: the products G R^T and (G^T L)^T of Alg. 2.
+//                         tile j-2 to W and prefetch G, W (and a per-element v) of the next tiles.  Rows
+//                         may start at any 2-byte alignment: vectors cover the columns up to the last
+//                         multiple of 8, the remaining columns are done element by element.
+//  stripe_kernel          pass 1 alone on two stripes (256 rows) that share every copied chunk of the
+//                         image, followed by a store: the products G R^T and (G^T L)^T of Alg. 2.
 //  refresh_update_kernel  pass 2 alone with two (factor, image) pairs: the update of a step that ran Alg. 2,
 //                         m^c = G + beta1/(1-beta1) (L_{t-1} R_{t-1} - L_t R_t), never storing the m x n term.
 //  gram_kernel, qimage_kernel, qf_image_kernel, qt_image_kernel, transpose_bf16_kernel: the r x r products of
-//                         Alg. 2 from the images, the images themselves, the transposed copy of G.
+//                         Alg. 2 from the images (chunks shared through LDS), the images themselves, the
+//                         transposed copy of G.
 //
 // Matrix work uses v_mfma_f32_32x32x16_bf16.  G is bf16 (exact); every fp32 operand (factors, D) is
 // carried as a (hi, lo) pair of bf16 values, products hi*hi + lo*hi + hi*lo accumulated in fp32
