@@ -293,6 +293,29 @@ def test_restoring_a_state_into_a_live_optimizer():
         assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("hp", [dict(T=1), dict(T=3)])
+def test_degenerate_inputs_zero_gradients_and_zero_step_size(hp):
+    """Two degenerate inputs on both contraction paths.  (i) Gradients that are exactly zero from the first step
+    on: v stays 0, every momentum stays 0, only the decoupled decay moves W.  (ii) lr = 0: the state advances,
+    the parameters must not change by a single bit."""
+    wl = WL.Workload("degenerate", ragged_bf16_table().blocks[:3] + WL.subset(WL.tiny_block(), ["attn.q", "norm1"]).blocks,
+                     steps=4, seed=3, signal_rank=16)
+    pair, _ = run(wl, 4, hp, tol_state=TOL16, tol_param=TOL16, grad_scale=0.0)
+    for i in range(len(wl.blocks)):
+        sv = pair.opt.state_view(i)
+        assert float(sv["v"].abs().max()) == 0.0
+        if "L" in sv:
+            assert float(sv["L"].abs().max()) == 0.0
+    frozen = Pair(wl, hp)
+    before = [p.clone() for p in frozen.params]
+    for _ in range(3):
+        frozen.step(lr=0.0)
+    torch.cuda.synchronize()
+    for a, b in zip(before, frozen.params):
+        assert torch.equal(a, b)
+    frozen.compare(TOL16, TOL16)
+
+
 def test_one_context_serving_two_state_buffers():
     """The derived copies of R in the workspace belong to one state buffer: a context that steps two replicas
     (two state buffers, one workspace) in turn must rebuild them whenever the state buffer changes."""
