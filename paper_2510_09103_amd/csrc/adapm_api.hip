@@ -236,13 +236,15 @@ uint64_t mix64(uint64_t z) {
 }
 
 // output tile edge: 64 for the fp64 kernel, 128 for the MFMA kernel
-void add_problem(GemmList& gl, const GemmProblem& p, int tile = 0) {
+// lower_only: a symmetric result of which only the tiles on and below the diagonal are read afterwards
+void add_problem(GemmList& gl, const GemmProblem& p, int tile = 0, bool lower_only = false) {
   if (tile) gl.tile = tile;
   gl.probs.push_back(p);
   const uint32_t id = (uint32_t)gl.probs.size() - 1;
   const int T = gl.tile;
   for (int ti = 0; ti < (p.M + T - 1) / T; ++ti)
-    for (int tj = 0; tj < (p.N + T - 1) / T; ++tj) gl.tiles.push_back(GemmTile{id, (uint16_t)ti, (uint16_t)tj});
+    for (int tj = 0; tj < (p.N + T - 1) / T; ++tj)
+      if (!lower_only || tj <= ti) gl.tiles.push_back(GemmTile{id, (uint16_t)ti, (uint16_t)tj});
 }
 
 GemmProblem problem(int M, int N) {
@@ -408,7 +410,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       // product-preserving orthonormalisation of R, always in fp64
       const Mat G64 = mat(SP_WS, 0, L.wG64, r, 1, DT_F64), Cinv = mat(SP_WS, 0, L.wCinv, r, 1, DT_F64);
       p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1.0; p.Out = G64;
-      add_problem(c->gemms[l_gram], p);
+      add_problem(c->gemms[l_gram], p, 0, true);      // the Cholesky factorisation reads the lower triangle only
       c->chol[fast ? 1 : 0].h.push_back(CholItem{L.wG64, L.wCinv, r, 0});
       p = problem(r, n); p.A1 = Cinv; p.B1 = Rc; p.K1 = r; p.a1 = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
       p = problem(m, r); p.A1 = Lc; p.B1 = G64; p.K1 = r; p.a1 = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
