@@ -412,8 +412,9 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1.0; p.Out = G64;
       add_problem(c->gemms[l_gram], p, 0, true);      // the Cholesky factorisation reads the lower triangle only
       c->chol[fast ? 1 : 0].h.push_back(CholItem{L.wG64, L.wCinv, r, 0});
-      p = problem(r, n); p.A1 = Cinv; p.B1 = Rc; p.K1 = r; p.a1 = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
-      p = problem(m, r); p.A1 = Lc; p.B1 = G64; p.K1 = r; p.a1 = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
+      // C^-1 and C are lower triangular
+      p = problem(r, n); p.A1 = Cinv; p.B1 = Rc; p.K1 = r; p.a1 = 1.0; p.tri = 1; p.Out = Rp; add_problem(c->gemms[l_fin], p);
+      p = problem(m, r); p.A1 = Lc; p.B1 = G64; p.K1 = r; p.a1 = 1.0; p.tri = 2; p.Out = Lp; add_problem(c->gemms[l_fin], p);
     } else if (n_eff > 0) {
       p = problem(m, r); p.X = Lc; p.g = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
       p = problem(r, n); p.X = Rc; p.g = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);

@@ -65,7 +65,7 @@ struct GemmProblem {
   int32_t M, N, K1, K2;
   double a1, a2, g, d;
   int32_t scale_g;   // 1: the (single) product has the gradient as an operand and takes the clipping factor
-  int32_t pad;
+  int32_t tri;       // fp64 kernel: 1 = A1 is lower triangular, 2 = B1 is lower triangular (zero part of the contraction skipped)
   int64_t off_s;     // >= 0: workspace offset of a device scalar s (double); then Out = g X + s (a1 A1 B1 + a2 A2 B2 + d Y)
 };
 

@@ -49,7 +49,8 @@ __device__ __forceinline__ void fetch4(const char* base, int dtype, const int64_
   else fetch4_t<DT_F64>(base, idx, ok, x);
 }
 
-__device__ __forceinline__ void product(const Mat& A, const Mat& B, int M, int N, int K, int i0, int j0,
+// contraction over k in [kbeg, K)
+__device__ __forceinline__ void product(const Mat& A, const Mat& B, int M, int N, int kbeg, int K, int i0, int j0,
                                         const Bases& bs, double (*As)[TM + PAD], double (*Bs)[TN + PAD],
                                         double acc[4][4]) {
   const char* Ab = resolve(A.ref, bs);
@@ -80,8 +81,8 @@ __device__ __forceinline__ void product(const Mat& A, const Mat& B, int M, int N
     fetch4(Bb, B.dtype, ix, ok, xb);
   };
   double xa[4], xb[4];
-  fetch(0, xa, xb);
-  for (int k0 = 0; k0 < K; k0 += TK) {
+  fetch(kbeg, xa, xb);
+  for (int k0 = kbeg; k0 < K; k0 += TK) {
 #pragma unroll
     for (int p = 0; p < 4; ++p) { As[ka[p]][ia[p]] = xa[p]; Bs[kb[p]][jb[p]] = xb[p]; }
     __syncthreads();
@@ -114,7 +115,11 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const GemmProblem* __restri
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[q][c] = 0.0;
   if (P.K1 > 0) {
-    product(P.A1, P.B1, P.M, P.N, P.K1, i0, j0, bs, As, Bs, acc);
+    // a lower-triangular operand of the first product (tri = 1: A1, tri = 2: B1) leaves part of the contraction
+    // identically zero for this tile: rows i0 .. i0+63 of A1 end at column i0+63, columns j0 .. of B1 start at row j0
+    const int ke = P.tri == 1 ? (P.K1 < i0 + TM ? P.K1 : i0 + TM) : P.K1;
+    const int kb = P.tri == 2 ? (j0 / TK) * TK : 0;
+    product(P.A1, P.B1, P.M, P.N, kb, ke, i0, j0, bs, As, Bs, acc);
     const double a1 = P.a1 * (P.scale_g ? (double)grad_scale(bs) : 1.0);   // the gradient enters clipped
 #pragma unroll
     for (int q = 0; q < 4; ++q)
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(256) void gemm64_kernel(const GemmProblem* __restri
     for (int q = 0; q < 4; ++q)
 #pragma unroll
       for (int c = 0; c < 4; ++c) acc2[q][c] = 0.0;
-    product(P.A2, P.B2, P.M, P.N, P.K2, i0, j0, bs, As, Bs, acc2);
+    product(P.A2, P.B2, P.M, P.N, 0, P.K2, i0, j0, bs, As, Bs, acc2);
     const double a2 = P.a2;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
