@@ -787,50 +787,92 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Images of a factor Q(a, k) = q[a * s0 + k * s1] (fp32, rows x K, rows <= R): one workgroup builds one
+// 64-column chunk.  The chunk is read once, along whichever index is contiguous in memory, into an LDS tile
+// (every load on a clamped index, masked afterwards); each 16-byte piece of an image is then cut from the tile
+// and written with its (hi, lo) partner by one thread.
+constexpr int QT_LD = BK + 1;                      // LDS row stride of the tile (floats)
+
+template <int R>
+__device__ __forceinline__ void q_tile_load(float* tile, const float* __restrict__ Q, int64_t s0, int64_t s1,
+                                            int rows, int K, int c) {
+  const int k0 = c * BK;
+  if (s1 == 1) {                                   // rows of Q are contiguous: lanes run along k
+    for (int id = threadIdx.x; id < R * BK; id += 256) {
+      const int a = id / BK, k = id % BK;
+      const bool ok = a < rows && k0 + k < K;
+      const float x = Q[ok ? (int64_t)a * s0 + (k0 + k) : 0];
+      tile[a * QT_LD + k] = ok ? x : 0.f;
+    }
+  } else {                                         // columns are contiguous (a transposed view): lanes run along a
+    for (int id = threadIdx.x; id < R * BK; id += 256) {
+      const int k = id / R, a = id % R;
+      const bool ok = a < rows && k0 + k < K;
+      const float x = Q[ok ? (int64_t)a * s0 + (int64_t)(k0 + k) * s1 : 0];
+      tile[a * QT_LD + k] = ok ? x : 0.f;
+    }
+  }
+}
+
+// pass-1 fragment image of the chunk: [k-step][r-tile][hi|lo][lane][8]; lane l holds Q[32 tile + l%32][16 kk + 8 (l/32) .. +7]
+template <int R>
+__device__ __forceinline__ void q_tile_fragments(const float* tile, char* qf) {
+  constexpr int RT = R / 32;
+  constexpr int np = (BK / 16) * RT * 64;          // (hi, lo) pairs of pieces
+  for (int p = threadIdx.x; p < np; p += 256) {
+    const int lane = p & 63, rest = p >> 6, tl = rest % RT, kk = rest / RT;
+    const float* src = tile + (32 * tl + (lane & 31)) * QT_LD + kk * 16 + 8 * (lane >> 5);
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split_pair(src[2 * e], src[2 * e + 1], h[e], l[e]);
+    char* dst = qf + ((int64_t)((kk * RT + tl) * 2) * 64 + lane) * 16;
+    *reinterpret_cast<uint4*>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+    *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(l[0], l[1], l[2], l[3]);
+  }
+}
+
+// pass-2 image of the chunk: [hi|lo][column j][R]; logical piece q (8 consecutive rows of Q) of column j sits at
+// physical piece timg_piece(R, j, q)
+template <int R>
+__device__ __forceinline__ void q_tile_transposed(const float* tile, char* ti) {
+  constexpr int pr = R / 8;
+  for (int p = threadIdx.x; p < BK * pr; p += 256) {
+    const int q = p % pr, j = p / pr;
+    const float* src = tile + (8 * q) * QT_LD + j;
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split_pair(src[(2 * e) * QT_LD], src[(2 * e + 1) * QT_LD], h[e], l[e]);
+    char* dst = ti + ((int64_t)j * pr + timg_piece(R, j, q)) * 16;
+    *reinterpret_cast<uint4*>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+    *reinterpret_cast<uint4*>(dst + (int64_t)BK * pr * 16) = make_uint4(l[0], l[1], l[2], l[3]);
+  }
+}
+
 // After Alg. 2: R (r x n fp32, state) -> the two bf16 (hi, lo) images used by proj_kernel, in the workspace.
 // One workgroup per (block, 64-column chunk); a thread writes 16-byte pieces.
+template <int R>
+__device__ __forceinline__ void q_images(float* tile, const float* __restrict__ Q, int64_t s0, int64_t s1, int rows, int K, int c,
+                                         char* qf, char* ti) {
+  q_tile_load<R>(tile, Q, s0, s1, rows, K, c);
+  __syncthreads();
+  if (qf) q_tile_fragments<R>(tile, qf + (int64_t)c * qf_chunk_bytes(R));
+  if (ti) q_tile_transposed<R>(tile, ti + (int64_t)c * timg_chunk_bytes(R));
+}
+__device__ __forceinline__ void q_images_rc(int rc, float* tile, const float* __restrict__ Q, int64_t s0, int64_t s1, int rows,
+                                            int K, int c, char* qf, char* ti) {
+  if (rc == 32) q_images<32>(tile, Q, s0, s1, rows, K, c, qf, ti);
+  else if (rc == 64) q_images<64>(tile, Q, s0, s1, rows, K, c, qf, ti);
+  else q_images<128>(tile, Q, s0, s1, rows, K, c, qf, ti);
+}
+
 __global__ __launch_bounds__(256) void qimage_kernel(const QsItem* __restrict__ items,
                                                      const LrBlockDev* __restrict__ lrb, Bases bs) {
+  __shared__ float tile[128 * QT_LD];
   const QsItem it = items[blockIdx.x];
-  const LrBlockDev B = lrb[it.lr];
-  const int n = B.n, R = B.rc, RT = R / 32, c = it.c, rows = B.r;      // rows rows .. R-1 of both images are zero
-  const float* __restrict__ Q = reinterpret_cast<const float*>(bs.state + B.off_Q);
-  char* qf = bs.ws + B.off_Qf + (int64_t)c * qf_chunk_bytes(R);
-  char* ti = bs.ws + B.off_Timg + (int64_t)c * timg_chunk_bytes(R);
-  // pass-1 fragments: piece p = ((kk * RT + tile) * 2 + hl) * 64 + lane
-  const int np1 = (BK / 16) * RT * 2 * 64;
-  for (int p = threadIdx.x; p < np1; p += 256) {
-    const int lane = p & 63, hl = (p >> 6) & 1, rest = p >> 7, tile = rest % RT, kk = rest / RT;
-    const int a = 32 * tile + (lane & 31), k = c * BK + kk * 16 + 8 * (lane >> 5);
-    uint32_t o[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float x0 = (a < rows && k + 2 * e < n) ? Q[(int64_t)a * n + k + 2 * e] : 0.f;
-      const float x1 = (a < rows && k + 2 * e + 1 < n) ? Q[(int64_t)a * n + k + 2 * e + 1] : 0.f;
-      uint32_t h, l;
-      split_pair(x0, x1, h, l);
-      o[e] = hl ? l : h;
-    }
-    *reinterpret_cast<uint4*>(qf + (int64_t)p * 16) = make_uint4(o[0], o[1], o[2], o[3]);
-  }
-  // pass-2 image: logical piece q (8 consecutive r) of row j of half hl sits at physical piece timg_piece(R, j, q)
-  const int pr = R / 8;
-  const int np2 = 2 * BK * pr;
-  for (int p = threadIdx.x; p < np2; p += 256) {
-    const int q = p % pr, j = (p / pr) % BK, hl = p / (BK * pr);
-    const int col = c * BK + j;
-    uint32_t o[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int a0 = 8 * q + 2 * e;
-      const float x0 = (col < n && a0 < rows) ? Q[(int64_t)a0 * n + col] : 0.f;
-      const float x1 = (col < n && a0 + 1 < rows) ? Q[(int64_t)(a0 + 1) * n + col] : 0.f;
-      uint32_t h, l;
-      split_pair(x0, x1, h, l);
-      o[e] = hl ? l : h;
-    }
-    *reinterpret_cast<uint4*>(ti + ((int64_t)(hl * BK + j) * pr + timg_piece(R, j, q)) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
-  }
+  const LrBlockDev B = lrb[it.lr];                                      // rows r .. rc-1 of both images are zero
+  q_images_rc(B.rc, tile, reinterpret_cast<const float*>(bs.state + B.off_Q), B.n, 1, B.r, B.n, it.c, bs.ws + B.off_Qf,
+              bs.ws + B.off_Timg);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1132,28 +1174,10 @@ __global__ __launch_bounds__(NT, 1) void refresh_update_kernel(const ProjItem* _
 // Image of Q^T for the fused updates: per 64-column chunk [hi|lo][column j][R], 16-byte pieces of a row
 // XOR-swizzled (timg_piece); Q(a, k) = q[a * s0 + k * s1], rows r .. R-1 zero.
 __global__ __launch_bounds__(256) void qt_image_kernel(const ImgItem* __restrict__ items, Bases bs) {
+  __shared__ float tile[128 * QT_LD];
   const ImgItem it = items[blockIdx.x];
-  const int R = it.rc, n = it.K, c = it.c, rows = it.r;
-  const float* __restrict__ Q = reinterpret_cast<const float*>(resolve(it.q.ref, bs));
-  const int64_t s0 = it.q.s0, s1 = it.q.s1;
-  char* ti = bs.ws + it.off_img + (int64_t)c * timg_chunk_bytes(R);
-  const int pr = R / 8;
-  const int np2 = 2 * BK * pr;
-  for (int p = threadIdx.x; p < np2; p += 256) {
-    const int q = p % pr, j = (p / pr) % BK, hl = p / (BK * pr);
-    const int col = c * BK + j;
-    uint32_t o[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int a0 = 8 * q + 2 * e;
-      const float x0 = (col < n && a0 < rows) ? Q[(int64_t)a0 * s0 + (int64_t)col * s1] : 0.f;
-      const float x1 = (col < n && a0 + 1 < rows) ? Q[(int64_t)(a0 + 1) * s0 + (int64_t)col * s1] : 0.f;
-      uint32_t h, l;
-      split_pair(x0, x1, h, l);
-      o[e] = hl ? l : h;
-    }
-    *reinterpret_cast<uint4*>(ti + ((int64_t)(hl * BK + j) * pr + timg_piece(R, j, q)) * 16) = make_uint4(o[0], o[1], o[2], o[3]);
-  }
+  q_images_rc(it.rc, tile, reinterpret_cast<const float*>(resolve(it.q.ref, bs)), it.q.s0, it.q.s1, it.r, it.K, it.c, nullptr,
+              bs.ws + it.off_img);
 }
 
 // Alg. 2 stripe product: Out = A Q^T for 128 rows of A per workgroup (pass 1 of the kernel above, then a store).
