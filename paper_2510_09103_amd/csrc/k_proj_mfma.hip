@@ -1241,13 +1241,27 @@ __global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict
   for (int p = threadIdx.x; p < np; p += 256) {
     const int lane = p & 63, rest = p >> 6, tile = rest % RT, kk = rest / RT;
     const int a = 32 * tile + (lane & 31), k = c * BK + kk * 16 + 8 * (lane >> 5);
+    // the lane's 8 values: every load on a clamped (valid) index, masked afterwards; whole 16-byte vectors where
+    // the rows of Q are contiguous and aligned
+    float x[8];
+    const bool rowok = a < rows;
+    const float* qa = Q + (int64_t)(rowok ? a : 0) * s0;
+    if (s1 == 1 && (s0 & 3) == 0 && (K & 3) == 0) {
+      const float4 u = *reinterpret_cast<const float4*>(qa + (k < K ? k : 0));
+      const float4 v = *reinterpret_cast<const float4*>(qa + (k + 4 < K ? k + 4 : 0));
+      const bool ou = rowok && k < K, ov = rowok && k + 4 < K;
+      x[0] = ou ? u.x : 0.f; x[1] = ou ? u.y : 0.f; x[2] = ou ? u.z : 0.f; x[3] = ou ? u.w : 0.f;
+      x[4] = ov ? v.x : 0.f; x[5] = ov ? v.y : 0.f; x[6] = ov ? v.z : 0.f; x[7] = ov ? v.w : 0.f;
+    } else {
+      float raw[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) raw[e] = qa[(int64_t)(k + e < K ? k + e : 0) * s1];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = (rowok && k + e < K) ? raw[e] : 0.f;
+    }
     uint32_t h[4], l[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float x0 = (a < rows && k + 2 * e < K) ? Q[(int64_t)a * s0 + (int64_t)(k + 2 * e) * s1] : 0.f;
-      const float x1 = (a < rows && k + 2 * e + 1 < K) ? Q[(int64_t)a * s0 + (int64_t)(k + 2 * e + 1) * s1] : 0.f;
-      split_pair(x0, x1, h[e], l[e]);
-    }
+    for (int e = 0; e < 4; ++e) split_pair(x[2 * e], x[2 * e + 1], h[e], l[e]);
     char* dst = qf + ((int64_t)((kk * RT + tile) * 2) * 64 + lane) * 16;
     *reinterpret_cast<uint4*>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
     *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(l[0], l[1], l[2], l[3]);
