@@ -576,6 +576,17 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
   const int r = B.r;
   const bool vec4 = (r & 3) == 0;
   uint2 dhv[LV], dlv[LV];
+  // the thread's vectors of L_{t-1} are requested together, on clamped (valid) addresses, before any of them is
+  // replaced: a load behind the previous vector's store would wait for it (four latencies per stripe)
+  float4 lraw[LV];
+  if (vec4) {
+#pragma unroll
+    for (int i = 0; i < LV; ++i) {
+      const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
+      const bool ok = row0 + row < m && c4 < r;
+      lraw[i] = *reinterpret_cast<const float4*>(Lst + (ok ? (int64_t)(row0 + row) * r + c4 : 0));
+    }
+  }
 #pragma unroll
   for (int i = 0; i < LV; ++i) {
     const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
@@ -586,7 +597,7 @@ __global__ __launch_bounds__(NT, 1) void proj_kernel(const ProjItem* __restrict_
       const float pv[4] = {gs * pv4.x, gs * pv4.y, gs * pv4.z, gs * pv4.w};
       const float b1 = sc.beta1, ob1 = 1.f - sc.beta1;
       if (vec4) {
-        const float4 t = *reinterpret_cast<const float4*>(lp);
+        const float4 t = lraw[i];
         lprev[0] = t.x; lprev[1] = t.y; lprev[2] = t.z; lprev[3] = t.w;
         *reinterpret_cast<float4*>(lp) = make_float4(b1 * lprev[0] + ob1 * pv[0], b1 * lprev[1] + ob1 * pv[1],
                                                      b1 * lprev[2] + ob1 * pv[2], b1 * lprev[3] + ob1 * pv[3]);
