@@ -218,7 +218,7 @@ struct Pass1 {
   static constexpr int NB1 = 3;                           // buffers: a chunk is consumed two rounds after its copy starts
   static constexpr int BYTES = NB1 * QF + NB1 * G_TILE;   // LDS during the pass
   static constexpr int P_BYTES = BM * PS * 4;             // LDS holding P afterwards
-  static constexpr int D1 = 4;                            // chunks of A in flight per streaming thread
+  static constexpr int D1 = 3;                            // chunks of A in flight per streaming thread
 };
 
 // P = A Q^T for the 128 rows of A behind the range-checked buffer rG (bf16, row stride n; columns 0 .. nv-1,
