@@ -333,7 +333,7 @@ struct Pass1x2 {
   static constexpr int G_TILE = ROWS * GS * 2;
   static constexpr int BYTES = 2 * QF + 2 * G_TILE;       // LDS during the pass
   static constexpr int P_BYTES = ROWS * PS * 4;           // LDS holding P afterwards
-  static constexpr int D1 = 4;                            // chunks of A in flight per streaming thread
+  static constexpr int D1 = 2;                            // chunks of A in flight per streaming thread
 };
 
 // As stripe_pass1, for the 256 rows behind rG: leaves P in LDS at smem as [256][R + 4] fp32 (the caller has to
