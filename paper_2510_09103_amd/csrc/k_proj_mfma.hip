@@ -1281,23 +1281,24 @@ __global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict
 
 // r x r Gram-type products of Alg. 2 (R R^T, R' R^T, L^T L, L^T L') straight from the fragment images: a lane's
 // 16 bytes of an image hold 8 consecutive k of one row, which is the A-operand layout for rows of X and
-// equally the B-operand layout for columns of Y^T.  One workgroup (4 waves) per product; the 64-column chunks of
+// equally the B-operand layout for columns of Y^T.  One workgroup (8 waves) per product; the 64-column chunks of
 // the two images are copied global -> LDS without registers, two buffers deep, so that every image byte is read
-// from L2 once per product (read per wave, the launch was bound by L2 bandwidth); wave w owns column tile w of
-// the result (all row tiles).
+// from L2 once per product (read per wave, the launch was bound by L2 bandwidth); wave w owns column tile w % 4 of
+// the result (all row tiles) and half w / 4 of the k-steps of every chunk.
 template <int RT>
 __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, unsigned char* smem) {
   constexpr int R = 32 * RT;
   constexpr int QF = qf_chunk_bytes(R);
   const int lane = threadIdx.x & 63, l32 = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int cw = wave & 3, kh = wave >> 2;                            // column tile of the result; half of the k-steps of a chunk
   const char* __restrict__ X = bs.ws + it.off_x;
   const char* __restrict__ Y = bs.ws + it.off_y;
   const bool same = it.off_x == it.off_y;
   const int nch = (it.K + BK - 1) / BK;                               // the images are zero-padded to whole chunks
   lds_u8* const lds = (lds_u8*)smem;                                  // [2 buffers][X | Y][QF]
   auto copy = [&](int c, int buf) {
-    for (int k = wave; k < QF / 1024; k += 4) {
+    for (int k = wave; k < QF / 1024; k += 8) {
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(X + (int64_t)c * QF + k * 1024 + lane * 16),
                                        (__attribute__((address_space(3))) void*)(lds + (buf * 2) * QF + k * 1024), 16, 0, 0);
       if (!same)
@@ -1317,18 +1318,19 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     wg_barrier();
     if (c + 1 < nch) copy(c + 1, (c + 1) & 1);
-    if (wave < RT) {
+    if (cw < RT) {
       const unsigned xs = lds_addr(lds) + ((c & 1) * 2) * QF, ys = same ? xs : xs + QF;
 #pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
+      for (int q = 0; q < BK / 32; ++q) {
+        const int kk = (BK / 32) * kh + q;
         bf16x8 xh[RT], xl[RT];
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
           xh[t] = lds_frag_raw(xs + (((kk * RT + t) * 2) * 64 + lane) * 16);
           xl[t] = lds_frag_raw(xs + (((kk * RT + t) * 2 + 1) * 64 + lane) * 16);
         }
-        bf16x8 yh = lds_frag_raw(ys + (((kk * RT + wave) * 2) * 64 + lane) * 16);
-        bf16x8 yl = lds_frag_raw(ys + (((kk * RT + wave) * 2 + 1) * 64 + lane) * 16);
+        bf16x8 yh = lds_frag_raw(ys + (((kk * RT + cw) * 2) * 64 + lane) * 16);
+        bf16x8 yl = lds_frag_raw(ys + (((kk * RT + cw) * 2 + 1) * 64 + lane) * 16);
 #pragma unroll
         for (int t = 0; t < RT; ++t) lds_wait(xh[t], xl[t], yh, yl);
 #pragma unroll
@@ -1340,9 +1342,19 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
       }
     }
   }
-  if (wave >= RT) return;
+  // the two halves of the k-steps are added through LDS (the image buffers are free now), in a fixed order
+  __syncthreads();
+  float* part = reinterpret_cast<float*>(smem) + (cw * RT * 16) * 64;  // [column tile][row tile][16][lane]
+  if (kh == 1 && cw < RT) {
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) part[(t * 16 + i) * 64 + lane] = acc[t][i];
+  }
+  __syncthreads();
+  if (kh != 0 || cw >= RT) return;
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + it.off_out);
-  const int r = it.r, col = 32 * wave + l32;
+  const int r = it.r, col = 32 * cw + l32;
 #pragma unroll
   for (int t = 0; t < RT; ++t)
 #pragma unroll
@@ -1350,11 +1362,11 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const int row = 32 * t + 8 * q + 4 * lh + p;
-        if (row < r && col < r) Out[(int64_t)row * r + col] = acc[t][4 * q + p];
+        if (row < r && col < r) Out[(int64_t)row * r + col] = acc[t][4 * q + p] + part[(t * 16 + 4 * q + p) * 64 + lane];
       }
 }
 
-__global__ __launch_bounds__(256) void gram_kernel(const GramItem* __restrict__ items, Bases bs) {
+__global__ __launch_bounds__(512) void gram_kernel(const GramItem* __restrict__ items, Bases bs) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * qf_chunk_bytes(128)];
   const GramItem it = items[blockIdx.x];
   if (it.rc == 32) gram_body<1>(it, bs, smem);
@@ -1428,7 +1440,7 @@ void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const Stripe
 
 void launch_gram(const GramItem* items, int64_t nitems, Bases b, hipStream_t s) {
   if (nitems <= 0) return;
-  hipLaunchKernelGGL(gram_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
+  hipLaunchKernelGGL(gram_kernel, dim3((unsigned)nitems), dim3(512), 0, s, items, b);
 }
 
 void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s) {
