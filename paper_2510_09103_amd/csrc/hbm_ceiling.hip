@@ -23,25 +23,26 @@
     }                                                                                \
   } while (0)
 
-template <int ROWS, int PASSES, bool RMW, bool REV>
+// SEG: 16-byte vectors per row and step (8 = the 128-byte row pieces of the fused kernels)
+template <int ROWS, int PASSES, bool RMW, bool REV, int SEG>
 __global__ __launch_bounds__(512) void walk(const uint4* __restrict__ g, uint4* __restrict__ w, float* out, int rowbytes) {
-  constexpr int RPS = 64;   // 512 threads = 64 rows x 8 vectors of 16 bytes
+  constexpr int RPS = 512 / SEG;   // 512 threads = RPS rows x SEG vectors of 16 bytes
   constexpr int K = ROWS / RPS;
   const size_t row0 = (size_t)blockIdx.x * ROWS;
-  const int r = threadIdx.x >> 3, v = threadIdx.x & 7;
-  const int steps = rowbytes / 128;
+  const int r = threadIdx.x / SEG, v = threadIdx.x % SEG;
+  const int steps = rowbytes / (16 * SEG);
   unsigned acc = 0;
   for (int p = 0; p < PASSES; ++p)
     for (int s_ = 0; s_ < steps; ++s_) {
       const int s = (REV && p == PASSES - 1) ? steps - 1 - s_ : s_;   // the last pass may walk the stripe backwards
       uint4 q[K];
 #pragma unroll
-      for (int k = 0; k < K; ++k) q[k] = g[((row0 + r + k * RPS) * rowbytes + (size_t)s * 128) / 16 + v];
+      for (int k = 0; k < K; ++k) q[k] = g[((row0 + r + k * RPS) * rowbytes + (size_t)s * (16 * SEG)) / 16 + v];
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         acc += q[k].x ^ q[k].y ^ q[k].z ^ q[k].w;
         if (RMW && p == PASSES - 1) {
-          const size_t idx = ((row0 + r + k * RPS) * rowbytes + (size_t)s * 128) / 16 + v;
+          const size_t idx = ((row0 + r + k * RPS) * rowbytes + (size_t)s * (16 * SEG)) / 16 + v;
           uint4 x = w[idx];
           x.x += q[k].x;
           w[idx] = x;
@@ -51,16 +52,16 @@ __global__ __launch_bounds__(512) void walk(const uint4* __restrict__ g, uint4* 
   if (acc == 0x12345678u) out[0] = 1.f;   // keeps the loads alive
 }
 
-template <int ROWS, int PASSES, bool RMW, bool REV = false>
+template <int ROWS, int PASSES, bool RMW, bool REV = false, int SEG = 8>
 void run(const char* name, const uint4* g, uint4* w, float* out, int rows, int rowbytes) {
   hipEvent_t a, b;
   CK(hipEventCreate(&a));
   CK(hipEventCreate(&b));
   const dim3 grid(rows / ROWS);
-  for (int i = 0; i < 2; ++i) hipLaunchKernelGGL((walk<ROWS, PASSES, RMW, REV>), grid, dim3(512), 0, 0, g, w, out, rowbytes);
+  for (int i = 0; i < 2; ++i) hipLaunchKernelGGL((walk<ROWS, PASSES, RMW, REV, SEG>), grid, dim3(512), 0, 0, g, w, out, rowbytes);
   CK(hipEventRecord(a));
   const int N = 10;
-  for (int i = 0; i < N; ++i) hipLaunchKernelGGL((walk<ROWS, PASSES, RMW, REV>), grid, dim3(512), 0, 0, g, w, out, rowbytes);
+  for (int i = 0; i < N; ++i) hipLaunchKernelGGL((walk<ROWS, PASSES, RMW, REV, SEG>), grid, dim3(512), 0, 0, g, w, out, rowbytes);
   CK(hipEventRecord(b));
   CK(hipEventSynchronize(b));
   CK(hipGetLastError());
@@ -95,6 +96,12 @@ int main() {
     run<256, 2, true>("read + rmw", g, w, out, rows, rowbytes);
     run<128, 2, false, true>("read x2 back", g, w, out, rows, rowbytes);
     run<128, 2, true, true>("read+rmw back", g, w, out, rows, rowbytes);
+    run<128, 1, false, false, 16>("read 256B", g, w, out, rows, rowbytes);
+    run<128, 1, false, false, 32>("read 512B", g, w, out, rows, rowbytes);
+    run<128, 1, true, false, 16>("rmw 256B", g, w, out, rows, rowbytes);
+    run<128, 1, true, false, 32>("rmw 512B", g, w, out, rows, rowbytes);
+    run<128, 2, true, true, 16>("r+rmw bk 256B", g, w, out, rows, rowbytes);
+    run<128, 2, true, true, 32>("r+rmw bk 512B", g, w, out, rows, rowbytes);
     CK(hipFree(g));
     CK(hipFree(w));
     CK(hipFree(out));
