@@ -96,7 +96,7 @@ adapm_status_t adapm_init(adapm_ctx** out, const adapm_block_t* table, int64_t n
 
 /* Size of the caller-allocated optimizer state: per block, in table order,
  * [L (rows x rank) | R (rank x cols)] or [m (rows x cols)] or nothing, then v;
- * fp32, each sub-buffer 256-byte aligned (Alg. 1 line 1).  0 if ctx is NULL. */
+ * fp32, each sub-buffer 256-byte aligned (Alg. 1, initialisation).  0 if ctx is NULL. */
 size_t adapm_state_bytes(const adapm_ctx* ctx);
 
 /* Size of the caller-allocated scratch buffer used inside adapm_step (previous
@@ -112,7 +112,7 @@ size_t adapm_workspace_bytes(const adapm_ctx* ctx);
 adapm_status_t adapm_state_offsets(const adapm_ctx* ctx, int64_t block, size_t* L, size_t* R,
                                    size_t* m, size_t* v);
 
-/* Zero the state and write the seeded R_0 (Alg. 1 line 1 with L_0 R_0 = 0).
+/* Zero the state and write the seeded R_0 (Alg. 1, initialisation, with L_0 R_0 = 0).
  * Asynchronous on `stream` (a hipStream_t, or NULL for the default stream). */
 adapm_status_t adapm_state_init(adapm_ctx* ctx, void* state_dev, void* stream);
 

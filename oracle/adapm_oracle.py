@@ -21,7 +21,7 @@ their storage type.  bf16 tensors travel as uint16 bit patterns.
 Readings taken where the paper is silent or inconsistent (each is listed in the
 design notes of the repository):
 * cold start: L_0 = 0 and R_0 = a seeded uniform sketch (so L_0 R_0 = 0 as
-  Alg. 1 line 1 and the proof of Thm. 2 need, but Alg. 2 can leave zero);
+  the initialisation of Alg. 1 and the proof of Thm. 2 need, but Alg. 2 can leave zero);
   seed = 0 gives the literal all-zero start.
 * Alg. 2 computes both gradients from the same (L, R) before either update.
 * clip(., 1) is an element-wise clamp to [-clip, clip].
@@ -29,8 +29,8 @@ design notes of the repository):
 * global gradient-norm clipping (Sec. 5.1 set-ups) uses scale = min(1, c / (norm + 1e-6)).
 * "update frequency T": T = 1 is Alg. 1 verbatim.  For T > 1 Alg. 2 runs on
   steps with (t-1) mod T == 0 and is followed by a product-preserving re-gauge
-  (R R^T = C C^T, R <- C^-1 R, L <- L C); on the other steps the arg-min of
-  Alg. 1 line 5 is taken over L with R held, i.e. the least-squares solution.
+  (R R^T = C C^T, R <- C^-1 R, L <- L C); on the other steps the arg min
+  of Alg. 1 is taken over L with R held, i.e. the least-squares solution.
 
 Parity pins for every function here live in tests/test_oracle_pins.py.  The
 T > 1 step is a reading, pinned only by the normal equations ("parity unpinned"
@@ -119,7 +119,7 @@ def store(x: np.ndarray, dtype: int) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
-# cold start (reading of Alg. 1 line 1)
+# cold start (reading of the initialisation of Alg. 1)
 # ----------------------------------------------------------------------------
 _M64 = (1 << 64) - 1
 
@@ -167,7 +167,7 @@ def num_v(blk: Block) -> int:
 
 
 def init_state(blocks: List[Block], hp: HParams, dtype=np.float32) -> List[Dict[str, np.ndarray]]:
-    """Alg. 1 line 1 with the cold-start reading above; m^f_0 = 0 (eq. 5)."""
+    """Initialisation of Alg. 1 with the cold-start reading above; m^f_0 = 0 (eq. 5)."""
     out = []
     for i, b in enumerate(blocks):
         st: Dict[str, np.ndarray] = {"v": np.zeros(num_v(b), dtype=dtype)}
@@ -382,7 +382,7 @@ def step(blocks: List[Block], hp: HParams, Ws: List[np.ndarray], Gs: List[np.nda
 
 def state_bytes_closed_form(blocks: List[Block]) -> int:
     """Optimizer-state size in fp32 with no padding: L, R for low-rank blocks
-    (Alg. 1 line 1), m for full-momentum blocks, one v per group."""
+    (Alg. 1, initialisation), m for full-momentum blocks, one v per group."""
     tot = 0
     for b in blocks:
         if b.mom_mode == MOM_LOWRANK:

@@ -1,5 +1,5 @@
 """Host-side tests of the C-ABI library: it loads, exports what the header declares,
-validates its arguments, and lays the state out as Alg. 1 line 1 prescribes.  No GPU."""
+validates its arguments, and lays the state out as the initialisation of Alg. 1 prescribes.  No GPU."""
 import ctypes as C
 import math
 import os
