@@ -57,6 +57,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wGt = -1, wIr = -1, wIl = -1;                     // ws: G^T (bf16) and the fragment images of R, L^T during Alg. 2
   int64_t wIr0 = -1, wIl0 = -1;                             // ws: the same images of R_{t-1}, L_{t-1}^T (first iteration; Gram matrices)
   int64_t wNu = -1;                                         // ws: normaliser of the optional scale-normalised Alg. 2 (one double)
+  int64_t wB[4] = {-1, -1, -1, -1};                         // ws: fragment images of R R^T, R' R^T, L^T L, L^T L' (transposed as the fused GD step needs them)
   int64_t wT1 = -1, wT2 = -1;                               // ws: images of R_{t-1}^T and R_t^T for the fused update after Alg. 2
   int64_t nv = 0;
   int path = PATH_NONE;
@@ -122,7 +123,7 @@ struct adapm_ctx {
   DevList<QsItem> qs;
   DevList<TrItem> tr;                   // Alg. 2, MFMA path: transposed copies of G
   DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
-  std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T
+  std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T; behind those, per GD iteration, the images of the Gram-type products
   std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
   std::vector<DevList<GramItem>> gram;  //   ... per GD iteration: the four r x r Gram-type products, from the images
   std::vector<DevList<GnormItem>> gnorm; // optional scale-normalised Alg. 2: per (path, GD iteration) the normalisers
@@ -294,7 +295,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   constexpr int NXCD = 8;
   struct StripeWork { int prob; int64_t M, K; };
   std::vector<std::vector<StripeWork>> swork(fast ? 3 * n_eff : 0);
-  if (fast) { c->img.resize(n_eff); c->sit.resize(3 * n_eff); c->gram.resize(n_eff); }
+  if (fast) { c->img.resize(2 * n_eff); c->sit.resize(3 * n_eff); c->gram.resize(n_eff); }
   const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list(fast) : -1;
   const int l_epi = fast ? -1 : new_list(false);      // m x n term of eq. 3-4 (the MFMA path never forms it)
   const int l_gram = hp.refresh_period_T > 1 ? new_list(false) : -1;
@@ -338,13 +339,25 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         c->gram[e].h.push_back(GramItem{L.wIr0, iR, L.wGpr, n, r, rc, 0});
         c->gram[e].h.push_back(GramItem{iL, iL, L.wGll, m, r, rc, 0});
         c->gram[e].h.push_back(GramItem{iL, L.wIl0, L.wGlp, m, r, rc, 0});
+        // the GD step rides on the stripes: L_new = L + s (-eta L (R R^T) + eta b1 L' (R' R^T) + eta (1-b1) G R^T) on the
+        // rows of a stripe of G, R_new likewise on the columns of R behind a stripe of G^T.  The r x r matrices enter
+        // as images with row a, column k = B[k][a]: (R R^T)^T and (R' R^T)^T for L; L^T L and L^T L' for R^T.
+        const Mat gsrc[4] = {mat(SP_WS, 0, L.wGrr, 1, r, DT_F32), mat(SP_WS, 0, L.wGpr, 1, r, DT_F32),
+                             mat(SP_WS, 0, L.wGll, r, 1, DT_F32), mat(SP_WS, 0, L.wGlp, r, 1, DT_F32)};
+        for (int k = 0; k < 4; ++k)
+          for (int ch = 0; ch < (r + 63) / 64; ++ch) c->img[n_eff + e].h.push_back(ImgItem{gsrc[k], r, r, ch, rc, L.wB[k]});
         const int cls = rc == 32 ? 0 : (rc == 64 ? 1 : 2);
         StripeProb sp;
         memset(&sp, 0, sizeof sp);
-        sp.a = G.ref; sp.M = m; sp.K = n; sp.r = r; sp.rc = rc; sp.transpose_out = 0; sp.off_img = iR; sp.off_out = L.wP;
+        sp.M = m; sp.K = n; sp.r = r; sp.rc = rc;
+        sp.upd = 1; sp.off_s = hp.refresh_normalise ? L.wNu : -1;
+        sp.c1 = (float)-eta; sp.c2 = (float)(eta * b1); sp.cp = (float)(eta * (1.0 - b1));
+        sp.a = G.ref; sp.transpose_out = 0; sp.off_img = iR;
+        sp.x_cur = Lc.ref; sp.x_prev = Lp.ref; sp.off_b1 = L.wB[0]; sp.off_b2 = L.wB[1]; sp.off_out = Ln.ref.off;
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
-        sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = iL; sp.off_out = L.wS;
+        sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = iL;
+        sp.x_cur = Rc.ref; sp.x_prev = Rp.ref; sp.off_b1 = L.wB[2]; sp.off_b2 = L.wB[3]; sp.off_out = Rn.ref.off;
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, n, m});
       } else {
@@ -361,16 +374,18 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       // optional: both updates of this iteration take eta / max(||R R^T||_F, ||L^T L||_F), a device scalar
       const int64_t off_s = hp.refresh_normalise ? L.wNu : -1;
       if (hp.refresh_normalise) c->gnorm[gnorm0 + e].h.push_back(GnormItem{L.wGrr, L.wGll, L.wNu, r, idt});
-      p = problem(m, r);
-      p.A1 = Lc; p.B1 = Grr; p.K1 = r; p.a1 = -eta;
-      p.A2 = Lp; p.B2 = Gpr; p.K2 = r; p.a2 = eta * b1;
-      p.X = Lc; p.g = 1.0; p.Y = P; p.d = eta * (1.0 - b1); p.Out = Ln; p.off_s = off_s;
-      add_problem(Bl, p);
-      p = problem(r, n);
-      p.A1 = Gll; p.B1 = Rc; p.K1 = r; p.a1 = -eta;
-      p.A2 = Glp; p.B2 = Rp; p.K2 = r; p.a2 = eta * b1;
-      p.X = Rc; p.g = 1.0; p.Y = S; p.d = eta * (1.0 - b1); p.Out = Rn; p.off_s = off_s;
-      add_problem(Bl, p);
+      if (!(fast && stripe_ok(b))) {
+        p = problem(m, r);
+        p.A1 = Lc; p.B1 = Grr; p.K1 = r; p.a1 = -eta;
+        p.A2 = Lp; p.B2 = Gpr; p.K2 = r; p.a2 = eta * b1;
+        p.X = Lc; p.g = 1.0; p.Y = P; p.d = eta * (1.0 - b1); p.Out = Ln; p.off_s = off_s;
+        add_problem(Bl, p);
+        p = problem(r, n);
+        p.A1 = Gll; p.B1 = Rc; p.K1 = r; p.a1 = -eta;
+        p.A2 = Glp; p.B2 = Rp; p.K2 = r; p.a2 = eta * b1;
+        p.X = Rc; p.g = 1.0; p.Y = S; p.d = eta * (1.0 - b1); p.Out = Rn; p.off_s = off_s;
+        add_problem(Bl, p);
+      }
       Lc = Ln; Rc = Rn;
     }
     if (l_pre >= 0) {      // no effective iteration but an in-place re-gauge ahead: work on a copy
@@ -444,18 +459,24 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   std::vector<Op>& seq = c->seq_refresh;
   if (fast && !c->tr.h.empty()) seq.push_back(Op{OP_TRANSPOSE, 0, 0, 0, "transpose_G"});
   for (int e = 0; e < n_eff; ++e) {
-    if (fast && !c->img[e].h.empty()) {
+    const bool stripes = fast && !c->img[e].h.empty();
+    if (stripes) {
       seq.push_back(Op{OP_QFIMG, e, 0, 0, "alg2_factor_images"});
-      static const char* names[3] = {"alg2_stripe_products_r32", "alg2_stripe_products_r64", "alg2_stripe_products_r128"};
-      for (int cls = 0; cls < 3; ++cls)
-        if (!c->sit[3 * e + cls].h.empty()) seq.push_back(Op{OP_STRIPE, 3 * e + cls, 0, 0, names[cls]});
       std::stable_sort(c->gram[e].h.begin(), c->gram[e].h.end(), [](const GramItem& a, const GramItem& b) { return a.K > b.K; });
       seq.push_back(Op{OP_GRAM, e, 0, 0, "alg2_gram_products"});
     }
     if (!c->gemms[listA[e]].tiles.empty())
       seq.push_back(Op{gk, listA[e], 0, 0, fast ? "alg2_products_mfma" : "alg2_products_f64"});
     if (hp.refresh_normalise) seq.push_back(Op{OP_GNORM, gnorm0 + e, 0, 0, "alg2_step_normaliser"});
-    seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"});
+    if (stripes) {
+      // both streaming products of the iteration and, behind each stripe, the GD step on the factor rows it covers
+      seq.push_back(Op{OP_QFIMG, n_eff + e, 0, 0, "alg2_gram_images"});
+      static const char* names[3] = {"alg2_stripe_step_r32", "alg2_stripe_step_r64", "alg2_stripe_step_r128"};
+      for (int cls = 0; cls < 3; ++cls)
+        if (!c->sit[3 * e + cls].h.empty()) seq.push_back(Op{OP_STRIPE, 3 * e + cls, 0, 0, names[cls]});
+    }
+    if (!c->gemms[listB[e]].tiles.empty())
+      seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"});
   }
   if (l_pre >= 0) seq.push_back(Op{gk, l_pre, 0, 0, "copy_factors"});
   const float cG = hp.bias_correction ? 1.f : 0.f;
@@ -643,6 +664,7 @@ void build_plan(adapm_ctx* c) {
         L.wIl = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
         L.wIr0 = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
         L.wIl0 = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
+        for (int k = 0; k < 4; ++k) L.wB[k] = walloc(proj_qf_bytes(rank_class((int)r), (int)r));
       }
       if (L.path == PATH_FAST && hp.refresh_period_T > 1) {
         L.wQf = walloc(proj_qf_bytes(rank_class((int)r), (int)n));

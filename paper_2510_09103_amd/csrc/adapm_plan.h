@@ -152,9 +152,16 @@ struct StripeProb {
   Ref a;                   // A: M x K bf16, row-major, row stride K
   int32_t M, K, r;         // r: rows of Q actually present
   int32_t transpose_out;   // 0: Out is M x r (row stride r); 1: Out is r x M (row stride M)
-  int32_t rc, pad;         // rank class of the image: 32, 64 or 128 >= r
+  int32_t rc, upd;         // rank class of the image: 32, 64 or 128 >= r; upd: the factor update of Alg. 2 follows
   int64_t off_img;         // workspace: fragment image of Q
   int64_t off_out;         // workspace: fp32 result
+  // upd != 0: Out = X + s (c1 X B1 + c2 X' B2 + cp A Q^T), the GD step of Alg. 2 on the factor X (X' = the factor of
+  // the previous step), all three in the layout of Out; B1, B2 = r x r matrices given as fragment images of their
+  // transposes (image row a, column k = B[k][a]); s = the double at workspace offset off_s (1 if off_s < 0)
+  Ref x_cur, x_prev;
+  int64_t off_b1, off_b2;
+  int64_t off_s;
+  float c1, c2, cp, pad;
 };
 struct StripeItem {        // one workgroup: 128 rows of A; prob < 0 = padding
   int32_t prob;

@@ -18,7 +18,10 @@
 //                         may start at any 2-byte alignment: vectors cover the columns up to the last
 //                         multiple of 8, the remaining columns are done element by element.
 //  stripe_kernel          pass 1 alone on two stripes (256 rows) that share every copied chunk of the
-//                         image, followed by a store: the products G R^T and (G^T L)^T of Alg. 2.
+//                         image: the products G R^T and (G^T L)^T of Alg. 2, each continued by the thin
+//                         products of the GD step on the factor rows behind the stripe (L (R R^T),
+//                         L' (R' R^T) for L; the same with L^T L, L^T L' for R^T), so that the new factor
+//                         is stored and the m x r / r x n products never leave the accumulators.
 //  refresh_update_kernel  pass 2 alone with two (factor, image) pairs: the update of a step that ran Alg. 2,
 //                         m^c = G + beta1/(1-beta1) (L_{t-1} R_{t-1} - L_t R_t), never storing the m x n term.
 //  gram_kernel, qimage_kernel, qf_image_kernel, qt_image_kernel, transpose_bf16_kernel: the r x r products of
@@ -336,11 +339,26 @@ struct Pass1x2 {
   static constexpr int D1 = 2;                            // chunks of A in flight per streaming thread
 };
 
+// Thin products appended to the stripe product (the GD step of Alg. 2 on one factor): P <- cp P + c1 X B1 + c2 X' B2
+// for the 256 x r pieces X, X' of the factor and its predecessor that belong to the stripe's rows.
+struct StripeTail {
+  const float* xc;                   // X(j, a) = xc[j * sj + a * sa], j = row of the stripe; null: no tail
+  const float* xp;                   // X' likewise
+  int64_t sj, sa;
+  int rows, r;                       // rows of the stripe that exist; columns of X
+  const char* img1;                  // fragment images of B1^T, B2^T (r x r, rank class of the stripe product)
+  const char* img2;
+  float c1, c2, cp;
+};
+
 // As stripe_pass1, for the 256 rows behind rG: leaves P in LDS at smem as [256][R + 4] fp32 (the caller has to
 // __syncthreads() before reading it); ss[i] = this streaming thread's sum of squares of row t512/8 + 64 i.
+// With a tail, the thin products run as further rounds of the same pipeline: the streaming waves scale a 64-column
+// chunk of X by its coefficient and stage it as two bf16 tiles (hi, lo), the matrix-core waves copy the matching
+// chunk of the coefficient image and multiply hi * (hi, lo) + lo * hi onto the accumulators that hold P.
 template <int RT>
 __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_buffer_rsrc_t rG, int n, int nv,
-                                                const char* __restrict__ Qf, float (&ss)[4]) {
+                                                const char* __restrict__ Qf, float (&ss)[4], const StripeTail& tl) {
   constexpr int QF = Pass1x2<RT>::QF, G_TILE = Pass1x2<RT>::G_TILE, PS = Pass1x2<RT>::PS, D1 = Pass1x2<RT>::D1;
   constexpr int TPW = RT;                                 // 8 row tiles x RT rank tiles over 8 waves
   const int tid = threadIdx.x, lane = tid & 63;
@@ -358,11 +376,6 @@ __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_bu
   unsigned char* Gs = smem + 2 * QF;                      // [2][256][GS] bf16
   const int my_rt = mw % RT;                              // rank tile
   const int my_mt0 = (mw / RT) * TPW;                     // first of this wave's TPW row tiles
-  f32x16 acc[TPW];
-#pragma unroll
-  for (int t = 0; t < TPW; ++t)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 #pragma unroll
   for (int i = 0; i < 4; ++i) ss[i] = 0.f;
   auto fetch_g = [&](int c, uint4 (&dst)[4]) {
@@ -380,6 +393,11 @@ __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_bu
       ss[i] += dot2_sq(q.w, dot2_sq(q.z, dot2_sq(q.y, dot2_sq(q.x, 0.f))));
     }
   };
+  f32x16 acc[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
   if (mrole) {
     for (int cc = 0; cc < NR1; ++cc) {
       if (cc < nc) dma_copy(Qf + (int64_t)cc * QF, Qs + (cc & 1) * QF, QF, mw, lane);
@@ -421,6 +439,107 @@ __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_bu
       for (int u = 0; u < D1; ++u) {
         stage_g(u & 1, gq[u]);
         fetch_g(cb + u + D1, gq[u]);
+        wg_barrier();
+      }
+    }
+  }
+  if (tl.xc) {
+    // Every round above ended with a barrier behind its reads, so both tile buffers and both image buffers are free.
+    // Chunk q = (matrix, 64 columns of X): barrier A = tiles staged and image landed, barrier B = both read.  The
+    // tail moves about as many bytes per stripe as a short stripe product does and runs at that rate; deeper
+    // prefetching of its operands (measured) gains nothing.
+    const int nk2 = (tl.r + BK - 1) / BK, nq = 2 * nk2;
+    if (mrole) {
+      dma_copy(tl.img1, Qs, QF, mw, lane);
+#pragma unroll
+      for (int t = 0; t < TPW; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] *= tl.cp;
+      const unsigned g_hi = lds_addr(Qs) + 2 * QF + (unsigned)(((32 * my_mt0 + l32) * GS + 8 * lh) * 2);
+      const unsigned g_lo = g_hi + G_TILE;
+      for (int q = 0; q < nq; ++q) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        wg_barrier();
+        if (q + 1 < nq)
+          dma_copy((q + 1 < nk2 ? tl.img1 + (int64_t)(q + 1) * QF : tl.img2 + (int64_t)(q + 1 - nk2) * QF),
+                   Qs + ((q + 1) & 1) * QF, QF, mw, lane);
+        const unsigned qa = lds_addr(Qs) + (q & 1) * QF + (unsigned)((my_rt * 2 * 64 + lane) * 16);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+          bf16x8 bh = lds_frag_raw(qa + kk * RT * 2048);
+          bf16x8 bl = lds_frag_raw(qa + kk * RT * 2048 + 1024);
+          bf16x8 a[TPW];
+#pragma unroll
+          for (int t = 0; t < TPW; ++t) a[t] = lds_frag_raw(g_hi + kk * 32 + t * 32 * GS * 2);
+          if (TPW == 1) lds_wait(bh, bl, a[0]);
+          else {
+            lds_wait(bh, bl, a[0], a[1]);
+            if (TPW == 4) lds_wait(a[TPW - 2], a[TPW - 1]);
+          }
+#pragma unroll
+          for (int t = 0; t < TPW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], bh, acc[t], 0, 0, 0);
+#pragma unroll
+          for (int t = 0; t < TPW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], bl, acc[t], 0, 0, 0);
+#pragma unroll
+          for (int t = 0; t < TPW; ++t) a[t] = lds_frag_raw(g_lo + kk * 32 + t * 32 * GS * 2);
+          if (TPW == 1) lds_wait(bh, a[0]);
+          else {
+            lds_wait(bh, a[0], a[1]);
+            if (TPW == 4) lds_wait(a[TPW - 2], a[TPW - 1]);
+          }
+#pragma unroll
+          for (int t = 0; t < TPW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t], bh, acc[t], 0, 0, 0);
+        }
+        wg_barrier();
+      }
+    } else {
+      // this thread's slots: rows t512 / 8 + 64 i, columns c8 .. c8 + 7 of the chunk.  Range-checked loads on 32-bit
+      // offsets: a slot outside the piece of X reads zeros or a neighbouring element of X, and is masked when staged
+      const bool vec = tl.sa == 1 && (tl.r & 3) == 0 && (tl.sj & 3) == 0;
+      const unsigned xbytes = (unsigned)(((int64_t)(tl.rows - 1) * tl.sj + (int64_t)(tl.r - 1) * tl.sa + 1) * 4);
+      const __amdgpu_buffer_rsrc_t rXc = make_rsrc(tl.xc, xbytes), rXp = make_rsrc(tl.xp, xbytes);
+      const unsigned sj4 = (unsigned)tl.sj * 4u, sa4 = (unsigned)tl.sa * 4u;
+      float raw[4][8];
+      auto fetch_x = [&](int q) {
+        const __amdgpu_buffer_rsrc_t rX = q < nk2 ? rXc : rXp;
+        const unsigned k0 = (unsigned)((q < nk2 ? q : q - nk2) * BK + c8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned at = (unsigned)((t512 >> 3) + 64 * i) * sj4 + k0 * sa4;
+          if (vec) {
+            const uint4 u = buf_load16(rX, at), v = buf_load16(rX, at + 16u);
+            raw[i][0] = __uint_as_float(u.x); raw[i][1] = __uint_as_float(u.y);
+            raw[i][2] = __uint_as_float(u.z); raw[i][3] = __uint_as_float(u.w);
+            raw[i][4] = __uint_as_float(v.x); raw[i][5] = __uint_as_float(v.y);
+            raw[i][6] = __uint_as_float(v.z); raw[i][7] = __uint_as_float(v.w);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              raw[i][e] = __uint_as_float((unsigned)__builtin_amdgcn_raw_buffer_load_b32(rX, (int)(at + (unsigned)e * sa4), 0, 0));
+          }
+        }
+      };
+      fetch_x(0);
+      uint16_t* const t_hi = reinterpret_cast<uint16_t*>(Gs);
+      uint16_t* const t_lo = reinterpret_cast<uint16_t*>(Gs + G_TILE);
+      for (int q = 0; q < nq; ++q) {
+        const float cf = q < nk2 ? tl.c1 : tl.c2;
+        const int k0 = (q < nk2 ? q : q - nk2) * BK + c8;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = (t512 >> 3) + 64 * i;
+          uint32_t h[4], l[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float x0 = (row < tl.rows && k0 + 2 * e < tl.r) ? cf * raw[i][2 * e] : 0.f;
+            const float x1 = (row < tl.rows && k0 + 2 * e + 1 < tl.r) ? cf * raw[i][2 * e + 1] : 0.f;
+            split_pair(x0, x1, h[e], l[e]);
+          }
+          *reinterpret_cast<uint4*>(t_hi + row * GS + c8) = make_uint4(h[0], h[1], h[2], h[3]);
+          *reinterpret_cast<uint4*>(t_lo + row * GS + c8) = make_uint4(l[0], l[1], l[2], l[3]);
+        }
+        wg_barrier();
+        if (q + 1 < nq) fetch_x(q + 1);
         wg_barrier();
       }
     }
@@ -1191,7 +1310,8 @@ __global__ __launch_bounds__(256) void qt_image_kernel(const ImgItem* __restrict
               bs.ws + it.off_img);
 }
 
-// Alg. 2 stripe product: Out = A Q^T for 128 rows of A per workgroup (pass 1 of the kernel above, then a store).
+// Alg. 2 stripe product: Out = A Q^T for 256 rows of A per workgroup (pass 1 of the kernel above, then a store), or
+// the whole GD step on the factor behind those rows (the stripe product continued by the thin products, then a store).
 template <int RT>
 __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restrict__ items,
                                                        const StripeProb* __restrict__ probs, Bases bs) {
@@ -1206,27 +1326,50 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   const unsigned rows_valid = (unsigned)(M - row0 < ROWS ? M - row0 : ROWS);
   const __amdgpu_buffer_rsrc_t rA = make_rsrc(A + (int64_t)row0 * K, rows_valid * (unsigned)K * 2u);
   float ss[4];
-  stripe_pass1_x2<RT>(smem, rA, K, K, bs.ws + P.off_img, ss);
+  const int r = P.r;                  // rows of Q actually present (the image is zero-padded to R)
+  float gs = grad_scale(bs);          // global gradient clipping: A is the gradient (or its transpose)
+  // fused GD step of Alg. 2: the factor X in the layout of Out; its coefficients take the step normaliser, the one of
+  // the stripe product also the gradient scale (the store below then adds X instead of scaling)
+  StripeTail tl = {};
+  const float* __restrict__ Xc = nullptr;
+  if (P.upd) {
+    const float s = P.off_s >= 0 ? (float)*reinterpret_cast<const double*>(bs.ws + P.off_s) : 1.f;
+    Xc = reinterpret_cast<const float*>(resolve(P.x_cur, bs));
+    const float* Xp = reinterpret_cast<const float*>(resolve(P.x_prev, bs));
+    tl.sj = P.transpose_out ? 1 : r;
+    tl.sa = P.transpose_out ? M : 1;
+    tl.xc = Xc + (int64_t)row0 * tl.sj;
+    tl.xp = Xp + (int64_t)row0 * tl.sj;
+    tl.rows = (int)rows_valid; tl.r = r;
+    tl.img1 = bs.ws + P.off_b1; tl.img2 = bs.ws + P.off_b2;
+    tl.c1 = s * P.c1; tl.c2 = s * P.c2; tl.cp = s * gs * P.cp;
+    gs = 1.f;
+  }
+  stripe_pass1_x2<RT>(smem, rA, K, K, bs.ws + P.off_img, ss, tl);
   __syncthreads();
   const float* Ps = reinterpret_cast<const float*>(smem);
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);
-  const int r = P.r;                  // rows of Q actually present (the image is zero-padded to R)
-  const float gs = grad_scale(bs);    // global gradient clipping: A is the gradient (or its transpose)
   if (!P.transpose_out) {
     const bool vec4 = (r & 3) == 0;
 #pragma unroll
     for (int i = 0; i < (ROWS * R / 4) / NT; ++i) {
       const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
       if (row0 + row < M && c4 < r) {
-        float* o = Out + (int64_t)(row0 + row) * r + c4;
+        const int64_t at = (int64_t)(row0 + row) * r + c4;
+        float* o = Out + at;
         float4 v = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
         v.x *= gs; v.y *= gs; v.z *= gs; v.w *= gs;
-        if (vec4) *reinterpret_cast<float4*>(o) = v;
-        else {
+        if (vec4) {
+          if (Xc) {
+            const float4 x = *reinterpret_cast<const float4*>(Xc + at);
+            v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
+          }
+          *reinterpret_cast<float4*>(o) = v;
+        } else {
           const float x[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            if (c4 + e < r) o[e] = x[e];
+            if (c4 + e < r) o[e] = Xc ? Xc[at + e] + x[e] : x[e];
         }
       }
     }
@@ -1235,7 +1378,11 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
 #pragma unroll 4
     for (int i = 0; i < (ROWS * R) / NT; ++i) {
       const int id = tid + NT * i, j = id % ROWS, a = id / ROWS;
-      if (row0 + j < M && a < r) Out[(int64_t)a * M + row0 + j] = gs * Ps[j * PS + a];
+      if (row0 + j < M && a < r) {
+        const int64_t at = (int64_t)a * M + row0 + j;
+        const float v = gs * Ps[j * PS + a];
+        Out[at] = Xc ? Xc[at] + v : v;
+      }
     }
   }
 }
