@@ -647,7 +647,8 @@ void build_plan(adapm_ctx* c) {
       const size_t es = L.path == PATH_FAST ? 4 : 8;
       L.wLa = walloc(es * m * r); L.wRa = walloc(es * r * n);
       L.wLb = walloc(es * m * r); L.wRb = walloc(es * r * n);
-      L.wP = walloc(es * m * r); L.wS = walloc(es * r * n);
+      // G R^T and L^T G: blocks whose GD step rides on the stripe products never store them
+      if (!(L.path == PATH_FAST && stripe_ok(b))) { L.wP = walloc(es * m * r); L.wS = walloc(es * r * n); }
       L.wGrr = walloc(es * r * r); L.wGpr = walloc(es * r * r);
       L.wGll = walloc(es * r * r); L.wGlp = walloc(es * r * r);
       L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
