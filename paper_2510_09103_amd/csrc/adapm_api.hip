@@ -54,7 +54,8 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wP = -1, wS = -1, wGrr = -1, wGpr = -1, wGll = -1, wGlp = -1;
   int64_t wG64 = -1, wCinv = -1, wC = -1;
   int64_t wQf = -1, wTimg = -1;                             // ws: bf16 (hi, lo) images of Q and Q^T
-  int64_t wGt = -1, wIr = -1, wIl = -1;                     // ws: G^T (bf16) and the fragment images of R, L^T during Alg. 2
+  int64_t wGt = -1, wIr = -1, wIl = -1;                     // ws: G^T (bf16) and the fragment images of R, L^T during Alg. 2 ...
+  int64_t wIr2 = -1, wIl2 = -1;                             // ws: ... written by the stripes of one GD iteration for the next, hence two sets
   int64_t wIr0 = -1, wIl0 = -1;                             // ws: the same images of R_{t-1}, L_{t-1}^T (first iteration; Gram matrices)
   int64_t wNu = -1;                                         // ws: normaliser of the optional scale-normalised Alg. 2 (one double)
   int64_t wB[4] = {-1, -1, -1, -1};                         // ws: fragment images of R R^T, R' R^T, L^T L, L^T L' (transposed as the fused GD step needs them)
@@ -330,10 +331,16 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
             for (int tj = 0; tj < (n + 63) / 64; ++tj) c->tr.h.push_back(TrItem{(int32_t)i, m, n, ti, tj, 0, L.wGt});
         Mat LcT = T(Lc);
         const int rc = rank_class(r);
-        // the images of the first iteration are those of (R_{t-1}, L_{t-1}^T) and are kept for the Gram matrices
-        const int64_t iR = e == 0 ? L.wIr0 : L.wIr, iL = e == 0 ? L.wIl0 : L.wIl;
-        for (int ch = 0; ch < (n + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{Rc, r, n, ch, rc, iR});
-        for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, rc, iL});
+        // the images of the first iteration are those of (R_{t-1}, L_{t-1}^T), made by the image kernel and kept for
+        // the Gram matrices; the stripes of every iteration write the images of the factors they produce
+        auto img_r = [&](int it) { return it == 0 ? L.wIr0 : ((it & 1) ? L.wIr : L.wIr2); };
+        auto img_l = [&](int it) { return it == 0 ? L.wIl0 : ((it & 1) ? L.wIl : L.wIl2); };
+        const int64_t iR = img_r(e), iL = img_l(e);
+        const int64_t iRn = e + 1 < n_eff ? img_r(e + 1) : -1, iLn = e + 1 < n_eff ? img_l(e + 1) : -1;
+        if (e == 0) {
+          for (int ch = 0; ch < (n + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{Rc, r, n, ch, rc, iR});
+          for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, rc, iL});
+        }
         // R R^T, R' R^T (contraction over n) and L^T L, L^T L' (over m), longest contraction first
         c->gram[e].h.push_back(GramItem{iR, iR, L.wGrr, n, r, rc, 0});
         c->gram[e].h.push_back(GramItem{L.wIr0, iR, L.wGpr, n, r, rc, 0});
@@ -354,10 +361,12 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         sp.c1 = (float)-eta; sp.c2 = (float)(eta * b1); sp.cp = (float)(eta * (1.0 - b1));
         sp.a = G.ref; sp.transpose_out = 0; sp.off_img = iR;
         sp.x_cur = Lc.ref; sp.x_prev = Lp.ref; sp.off_b1 = L.wB[0]; sp.off_b2 = L.wB[1]; sp.off_out = Ln.ref.off;
+        sp.off_next = iLn;
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
         sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = iL;
         sp.x_cur = Rc.ref; sp.x_prev = Rp.ref; sp.off_b1 = L.wB[2]; sp.off_b2 = L.wB[3]; sp.off_out = Rn.ref.off;
+        sp.off_next = iRn;
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, n, m});
       } else {
@@ -459,9 +468,9 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   std::vector<Op>& seq = c->seq_refresh;
   if (fast && !c->tr.h.empty()) seq.push_back(Op{OP_TRANSPOSE, 0, 0, 0, "transpose_G"});
   for (int e = 0; e < n_eff; ++e) {
-    const bool stripes = fast && !c->img[e].h.empty();
+    const bool stripes = fast && !c->gram[e].h.empty();
     if (stripes) {
-      seq.push_back(Op{OP_QFIMG, e, 0, 0, "alg2_factor_images"});
+      if (!c->img[e].h.empty()) seq.push_back(Op{OP_QFIMG, e, 0, 0, "alg2_factor_images"});
       std::stable_sort(c->gram[e].h.begin(), c->gram[e].h.end(), [](const GramItem& a, const GramItem& b) { return a.K > b.K; });
       seq.push_back(Op{OP_GRAM, e, 0, 0, "alg2_gram_products"});
     }
@@ -663,6 +672,8 @@ void build_plan(adapm_ctx* c) {
         L.wGt = walloc(2 * m * n);
         L.wIr = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
         L.wIl = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
+        L.wIr2 = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
+        L.wIl2 = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
         L.wIr0 = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
         L.wIl0 = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
         for (int k = 0; k < 4; ++k) L.wB[k] = walloc(proj_qf_bytes(rank_class((int)r), (int)r));

@@ -161,6 +161,7 @@ struct StripeProb {
   Ref x_cur, x_prev;
   int64_t off_b1, off_b2;
   int64_t off_s;
+  int64_t off_next;        // >= 0: workspace offset where the fragment image of the new factor goes (its chunks run along M)
   float c1, c2, cp, pad;
 };
 struct StripeItem {        // one workgroup: 128 rows of A; prob < 0 = padding

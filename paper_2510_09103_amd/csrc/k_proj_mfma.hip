@@ -1347,42 +1347,75 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   }
   stripe_pass1_x2<RT>(smem, rA, K, K, bs.ws + P.off_img, ss, tl);
   __syncthreads();
-  const float* Ps = reinterpret_cast<const float*>(smem);
+  float* Ps = reinterpret_cast<float*>(smem);
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);
+  // with the GD step, the new factor values (zeros outside the factor) go back into P for the image below
+  const bool emit = P.upd && P.off_next >= 0;
   if (!P.transpose_out) {
     const bool vec4 = (r & 3) == 0;
 #pragma unroll
     for (int i = 0; i < (ROWS * R / 4) / NT; ++i) {
       const int id = tid + NT * i, row = id / (R / 4), c4 = (id % (R / 4)) * 4;
+      float4 v = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
+      float x[4] = {v.x * gs, v.y * gs, v.z * gs, v.w * gs};
       if (row0 + row < M && c4 < r) {
         const int64_t at = (int64_t)(row0 + row) * r + c4;
         float* o = Out + at;
-        float4 v = *reinterpret_cast<const float4*>(Ps + row * PS + c4);
-        v.x *= gs; v.y *= gs; v.z *= gs; v.w *= gs;
         if (vec4) {
           if (Xc) {
-            const float4 x = *reinterpret_cast<const float4*>(Xc + at);
-            v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
+            const float4 xc = *reinterpret_cast<const float4*>(Xc + at);
+            x[0] += xc.x; x[1] += xc.y; x[2] += xc.z; x[3] += xc.w;
           }
-          *reinterpret_cast<float4*>(o) = v;
+          *reinterpret_cast<float4*>(o) = make_float4(x[0], x[1], x[2], x[3]);
         } else {
-          const float x[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (c4 + e < r) o[e] = Xc ? Xc[at + e] + x[e] : x[e];
+          for (int e = 0; e < 4; ++e) {
+            if (c4 + e < r) {
+              if (Xc) x[e] += Xc[at + e];
+              o[e] = x[e];
+            } else {
+              x[e] = 0.f;
+            }
+          }
         }
+      } else {
+        x[0] = x[1] = x[2] = x[3] = 0.f;
       }
+      if (emit) *reinterpret_cast<float4*>(Ps + row * PS + c4) = make_float4(x[0], x[1], x[2], x[3]);
     }
   } else {
     // Out[a][row0 + j] = P[j][a]: lanes run along j, so the global stores are contiguous
 #pragma unroll 4
     for (int i = 0; i < (ROWS * R) / NT; ++i) {
       const int id = tid + NT * i, j = id % ROWS, a = id / ROWS;
+      float v = gs * Ps[j * PS + a];
       if (row0 + j < M && a < r) {
         const int64_t at = (int64_t)a * M + row0 + j;
-        const float v = gs * Ps[j * PS + a];
-        Out[at] = Xc ? Xc[at] + v : v;
+        if (Xc) v += Xc[at];
+        Out[at] = v;
+      } else {
+        v = 0.f;
       }
+      if (emit) Ps[j * PS + a] = v;
+    }
+  }
+  if (emit) {
+    // fragment image of the new factor for the next GD iteration (the layout qf_image_kernel writes): the stripe's
+    // rows are the image's contraction index, four 64-wide chunks; lane l of a piece holds rows 16 kk + 8 (l / 32) .. + 7
+    // of the chunk at factor column 32 tile + l % 32
+    __syncthreads();
+    constexpr int QF = qf_chunk_bytes(R);
+    char* const img = bs.ws + P.off_next + (int64_t)(row0 / BK) * QF;
+    for (int p = tid; p < (ROWS / BK) * (BK / 16) * RT * 64; p += NT) {
+      const int lane = p & 63, rest = p >> 6, tile = rest % RT, kk = (rest / RT) % (BK / 16), cq = rest / (RT * (BK / 16));
+      if (row0 + BK * cq >= M) continue;          // the image ends with the chunk that holds row M - 1
+      const float* src = Ps + (BK * cq + 16 * kk + 8 * (lane >> 5)) * PS + 32 * tile + (lane & 31);
+      uint32_t h[4], l[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) split_pair(src[(2 * e) * PS], src[(2 * e + 1) * PS], h[e], l[e]);
+      char* dst = img + (int64_t)cq * QF + ((int64_t)((kk * RT + tile) * 2) * 64 + lane) * 16;
+      *reinterpret_cast<uint4*>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+      *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(l[0], l[1], l[2], l[3]);
     }
   }
 }
