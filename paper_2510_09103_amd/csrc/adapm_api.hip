@@ -360,11 +360,13 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         sp.upd = 1; sp.off_s = hp.refresh_normalise ? L.wNu : -1;
         sp.c1 = (float)-eta; sp.c2 = (float)(eta * b1); sp.cp = (float)(eta * (1.0 - b1));
         sp.a = G.ref; sp.transpose_out = 0; sp.off_img = iR;
+        if (e == 0 && v_fusable(b)) { sp.v_rows = b.v_group_rows; sp.off_v = L.sv; sp.beta2 = hp.beta2; }
         sp.x_cur = Lc.ref; sp.x_prev = Lp.ref; sp.off_b1 = L.wB[0]; sp.off_b2 = L.wB[1]; sp.off_out = Ln.ref.off;
         sp.off_next = iLn;
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
         sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = iL;
+        sp.v_rows = 0;
         sp.x_cur = Rc.ref; sp.x_prev = Rp.ref; sp.off_b1 = L.wB[2]; sp.off_b2 = L.wB[3]; sp.off_out = Rn.ref.off;
         sp.off_next = iRn;
         c->sprob.h.push_back(sp);
@@ -720,10 +722,13 @@ void build_plan(adapm_ctx* c) {
         ew.push_back(EwItem{s, (int32_t)i, (int32_t)std::min<int64_t>(EW_CHUNK, d.numel - s)});
     }
     if (b.v_mode != ADAPM_V_ELEMENT) {
-      // on the MFMA path with T > 1 the fused kernel finishes fusable groups itself on steps with R held
+      // on the MFMA path with T > 1 the fused kernel finishes fusable groups itself on steps with R held (list 1: only
+      // steps that run Alg. 2), and where Alg. 2 streams G in stripes its first GD iteration does so (no list at all)
       const int which = (L.path == PATH_FAST && hp.refresh_period_T > 1 && v_fusable(b)) ? 1 : 0;
+      const bool in_stripes = L.path == PATH_FAST && v_fusable(b) && stripe_ok(b) &&
+                              !effective_step_sizes(hp.refresh_iters_K).empty() && (which == 1 || hp.refresh_period_T == 1);
       const int64_t ge = d.group_elems;
-      for (int64_t g = 0; g < L.nv; ++g) {
+      for (int64_t g = 0; g < (in_stripes ? 0 : L.nv); ++g) {
         if (ge <= VS_CHUNK) {
           c->vs[which].h.push_back(VsItem{g * ge, g, (int32_t)i, (int32_t)ge, 1, 0});
         } else {

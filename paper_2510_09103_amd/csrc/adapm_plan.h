@@ -162,7 +162,12 @@ struct StripeProb {
   int64_t off_b1, off_b2;
   int64_t off_s;
   int64_t off_next;        // >= 0: workspace offset where the fragment image of the new factor goes (its chunks run along M)
-  float c1, c2, cp, pad;
+  float c1, c2, cp;
+  // v_rows > 0 (A is the gradient itself): the blockwise second moment of the block is finished here,
+  // v_g <- beta2 v_g + (1 - beta2) mean of g^2 over the v_rows rows of group g (state offset off_v, one float per group)
+  float beta2;
+  int64_t off_v;
+  int32_t v_rows, pad2;
 };
 struct StripeItem {        // one workgroup: 128 rows of A; prob < 0 = padding
   int32_t prob;

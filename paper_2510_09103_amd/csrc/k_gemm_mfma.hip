@@ -21,12 +21,6 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 constexpr int TM = 128, TN = 128, TK = 32;
 constexpr int LS = TK + 8;                     // LDS row stride in bf16 elements (80 bytes)
 
-__device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-
 union Frag {
   bf16x8 v;
   uint4 q;

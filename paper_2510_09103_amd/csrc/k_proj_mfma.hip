@@ -47,15 +47,6 @@ constexpr int GS = BK + 8; // LDS row stride of the G tile (elements): 16-byte f
 constexpr int CS = BK + 8; // LDS row stride of the fp32 C tile
 constexpr int NT = 1024;   // threads: waves 0-7 feed the matrix cores, waves 8-15 stream G, W and do the element-wise work
 
-union Frag {
-  bf16x8 v;
-  uint4 q;
-};
-__device__ __forceinline__ bf16x8 as_frag(const uint4& q) {
-  Frag f;
-  f.q = q;
-  return f.v;
-}
 // Range-checked buffer access: a lane whose offset is at or beyond the descriptor's size reads zeros /
 // writes nothing, so ragged edges need no branches and the compiler can count outstanding loads.
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -352,13 +343,13 @@ struct StripeTail {
 };
 
 // As stripe_pass1, for the 256 rows behind rG: leaves P in LDS at smem as [256][R + 4] fp32 (the caller has to
-// __syncthreads() before reading it); ss[i] = this streaming thread's sum of squares of row t512/8 + 64 i.
+// __syncthreads() before reading it); rsum (LDS, 256 floats, or null) receives the sums of squares of the rows.
 // With a tail, the thin products run as further rounds of the same pipeline: the streaming waves scale a 64-column
 // chunk of X by its coefficient and stage it as two bf16 tiles (hi, lo), the matrix-core waves copy the matching
 // chunk of the coefficient image and multiply hi * (hi, lo) + lo * hi onto the accumulators that hold P.
 template <int RT>
 __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_buffer_rsrc_t rG, int n, int nv,
-                                                const char* __restrict__ Qf, float (&ss)[4], const StripeTail& tl) {
+                                                const char* __restrict__ Qf, float* rsum, const StripeTail& tl) {
   constexpr int QF = Pass1x2<RT>::QF, G_TILE = Pass1x2<RT>::G_TILE, PS = Pass1x2<RT>::PS, D1 = Pass1x2<RT>::D1;
   constexpr int TPW = RT;                                 // 8 row tiles x RT rank tiles over 8 waves
   const int tid = threadIdx.x, lane = tid & 63;
@@ -376,8 +367,7 @@ __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_bu
   unsigned char* Gs = smem + 2 * QF;                      // [2][256][GS] bf16
   const int my_rt = mw % RT;                              // rank tile
   const int my_mt0 = (mw / RT) * TPW;                     // first of this wave's TPW row tiles
-#pragma unroll
-  for (int i = 0; i < 4; ++i) ss[i] = 0.f;
+  float ss[4] = {0.f, 0.f, 0.f, 0.f};   // this streaming thread's sums of squares of rows t512 / 8 + 64 i
   auto fetch_g = [&](int c, uint4 (&dst)[4]) {
     const bool ok = c * BK + c8 < nv;
 #pragma unroll
@@ -440,6 +430,14 @@ __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_bu
         stage_g(u & 1, gq[u]);
         fetch_g(cb + u + D1, gq[u]);
         wg_barrier();
+      }
+    }
+    if (rsum) {                               // a row is covered by 8 consecutive lanes
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) ss[i] += __shfl_xor(ss[i], o, 64);
+        if ((t512 & 7) == 0) rsum[(t512 >> 3) + 64 * i] = ss[i];
       }
     }
   }
@@ -1325,9 +1323,10 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(resolve(P.a, bs));
   const unsigned rows_valid = (unsigned)(M - row0 < ROWS ? M - row0 : ROWS);
   const __amdgpu_buffer_rsrc_t rA = make_rsrc(A + (int64_t)row0 * K, rows_valid * (unsigned)K * 2u);
-  float ss[4];
+  __shared__ float rsum[ROWS];        // sums of squares of the stripe's rows (second moment)
   const int r = P.r;                  // rows of Q actually present (the image is zero-padded to R)
   float gs = grad_scale(bs);          // global gradient clipping: A is the gradient (or its transpose)
+  const float gs2 = gs * gs;
   // fused GD step of Alg. 2: the factor X in the layout of Out; its coefficients take the step normaliser, the one of
   // the stripe product also the gradient scale (the store below then adds X instead of scaling)
   StripeTail tl = {};
@@ -1345,8 +1344,17 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
     tl.c1 = s * P.c1; tl.c2 = s * P.c2; tl.cp = s * gs * P.cp;
     gs = 1.f;
   }
-  stripe_pass1_x2<RT>(smem, rA, K, K, bs.ws + P.off_img, ss, tl);
+  stripe_pass1_x2<RT>(smem, rA, K, K, bs.ws + P.off_img, P.v_rows > 0 ? rsum : nullptr, tl);
   __syncthreads();
+  if (P.v_rows > 0) {               // groups of v_rows rows inside the stripe (v_rows divides 128)
+    const int g = P.v_rows;
+    if (tid < ROWS / g && row0 + tid * g < M) {
+      double s = 0.0;
+      for (int i = 0; i < g; ++i) s += (double)rsum[tid * g + i];
+      float* vp = reinterpret_cast<float*>(bs.state + P.off_v) + (row0 + tid * g) / g;
+      *vp = (float)((double)P.beta2 * (double)*vp + (1.0 - (double)P.beta2) * ((double)gs2 * s / ((double)g * (double)K)));
+    }
+  }
   float* Ps = reinterpret_cast<float*>(smem);
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);
   // with the GD step, the new factor values (zeros outside the factor) go back into P for the image below
