@@ -124,6 +124,41 @@ def test_ranks_between_the_classes_on_the_mfma_path(hp):
     run(odd_rank_table(), 6, hp, tol_state=TOL16, tol_param=TOL16, check_every=2)
 
 
+def random_table(rng, case):
+    """A few low-rank bf16-gradient blocks with random sizes (mostly multiples of 8, which Alg. 2 takes as stripe
+    products with the GD step riding on them; otherwise any size), ranks on and between the class and vector
+    boundaries, every kind of second moment."""
+    blocks = []
+    for b in range(rng.randint(2, 4)):
+        if rng.random() < 0.7:
+            m, n = 8 * rng.randint(2, 90), 8 * rng.randint(2, 90)
+        else:
+            m, n = rng.randint(9, 500), rng.randint(9, 500)
+        r = min(rng.choice([1, 3, 4, 7, 8, 16, 20, 31, 32, 33, 48, 51, 64, 65, 80, 100, 127, 128]), m, n)
+        vm = rng.choice(["element", "rowgroup", "rowgroup", "whole"])
+        g = rng.choice([d for d in (1, 2, 3, 4, 5, 8, 16, 32, 64, 128) if m % d == 0]) if vm == "rowgroup" else 1
+        pd = rng.choice(["bf16", "bf16", "f32"])
+        blocks.append(BlockSpec(f"c{case}b{b}_{m}x{n}_r{r}_{vm}{g}_{pd}", m, n, pd, "bf16", "lowrank", r, vm, g, 1.0,
+                                rng.choice([0.0, 0.1])))
+    return WL.Workload(f"random{case}", tuple(blocks), steps=5, seed=100 + case, signal_rank=24)
+
+
+@pytest.mark.parametrize("seed", [2, 3])
+def test_random_tables_on_the_mfma_path(seed):
+    import random
+    rng = random.Random(seed)
+    for case in range(10):
+        wl = random_table(rng, case)
+        hp = dict(T=rng.choice([1, 1, 2, 3]), K=rng.choice([2, 3, 5, 5]), contraction=B.ADAPM_CONTRACT_BF16X2)
+        if rng.random() < 0.25:
+            hp["normalise"] = 1
+        if rng.random() < 0.2:
+            hp["bias_correction"] = 0
+        clip = rng.choice([None, None, 0.5])
+        print([b.name for b in wl.blocks], hp, clip, flush=True)
+        run(wl, 5, hp, tol_state=TOL16, tol_param=TOL16, grad_clip=clip)
+
+
 @pytest.mark.parametrize("shape,mini", [("gpt2_1p5b", False), ("gpt2_1p5b", True), ("llama_350m", False), ("llama_350m", True)])
 def test_paper_partition_layer(shape, mini):
     """One layer (plus an embedding-like block) of the paper's own partition (Sec. 4.1): no momentum at
