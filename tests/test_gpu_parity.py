@@ -159,6 +159,36 @@ def test_random_tables_on_the_mfma_path(seed):
         run(wl, 5, hp, tol_state=TOL16, tol_param=TOL16, grad_clip=clip)
 
 
+def test_random_tables_of_every_regime_on_the_exact_path():
+    """Random sizes (vectors included), regimes, dtypes, second-moment kinds and flags at the fp32 tolerance."""
+    import random
+    rng = random.Random(1)
+    for case in range(12):
+        blocks = []
+        for b in range(rng.randint(2, 5)):
+            mom = rng.choice(["none", "full", "full", "lowrank", "lowrank"])
+            m, n = (rng.randint(1, 3000), 1) if rng.random() < 0.2 else (rng.randint(1, 400), rng.randint(1, 400))
+            if mom == "lowrank" and (m < 2 or n < 2):
+                mom = "full"
+            r = max(1, min(rng.choice([1, 2, 5, 8, 16, 33, 64]), m, n)) if mom == "lowrank" else 0
+            vm = rng.choice(["element", "rowgroup", "rowgroup", "whole"])
+            g = rng.choice([d for d in (1, 2, 3, 4, 5, 7, 8, 16, 25, 32, 64, 100, 128) if m % d == 0]) if vm == "rowgroup" else 1
+            pd, gd = rng.choice(["bf16", "f32"]), rng.choice(["bf16", "f32"])
+            blocks.append(BlockSpec(f"c{case}b{b}_{mom}_{m}x{n}_r{r}_{vm}{g}_{pd}{gd}", m, n, pd, gd, mom, r, vm, g,
+                                    0.75 if mom == "none" else 1.0, rng.choice([0.0, 0.1])))
+        hp = dict(T=rng.choice([1, 1, 2, 3]), K=rng.choice([1, 2, 3, 5, 5]), contraction=B.ADAPM_CONTRACT_F64)
+        if rng.random() < 0.25:
+            hp["normalise"] = 1
+        if rng.random() < 0.2:
+            hp["bias_correction"] = 0
+        if rng.random() < 0.2:
+            hp.update(adam_debias=1, clip=float("inf"))
+        clip = rng.choice([None, None, 0.5])
+        wl = WL.Workload(f"random_exact{case}", tuple(blocks), steps=5, seed=200 + case, signal_rank=24)
+        print([b.name for b in wl.blocks], hp, clip, flush=True)
+        run(wl, 5, hp, tol_state=TOL32, tol_param=TOL32, grad_clip=clip)
+
+
 @pytest.mark.parametrize("shape,mini", [("gpt2_1p5b", False), ("gpt2_1p5b", True), ("llama_350m", False), ("llama_350m", True)])
 def test_paper_partition_layer(shape, mini):
     """One layer (plus an embedding-like block) of the paper's own partition (Sec. 4.1): no momentum at
