@@ -126,7 +126,7 @@ struct adapm_ctx {
   DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
   std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T; behind those, per GD iteration, the images of the Gram-type products
   std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
-  std::vector<DevList<GramItem>> gram;  //   ... per GD iteration: the four r x r Gram-type products, from the images
+  std::vector<DevList<GramItem>> gram;  //   ... per GD iteration: the four r x r Gram-type products, from the images, in pairs that share one
   std::vector<DevList<GnormItem>> gnorm; // optional scale-normalised Alg. 2: per (path, GD iteration) the normalisers
   DevList<RuBlockDev> rub;              // fused update after Alg. 2 (MFMA path): blocks, images of R^T, stripes
   DevList<ImgItem> qt;
@@ -341,11 +341,9 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
           for (int ch = 0; ch < (n + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{Rc, r, n, ch, rc, iR});
           for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, rc, iL});
         }
-        // R R^T, R' R^T (contraction over n) and L^T L, L^T L' (over m), longest contraction first
-        c->gram[e].h.push_back(GramItem{iR, iR, L.wGrr, n, r, rc, 0});
-        c->gram[e].h.push_back(GramItem{L.wIr0, iR, L.wGpr, n, r, rc, 0});
-        c->gram[e].h.push_back(GramItem{iL, iL, L.wGll, m, r, rc, 0});
-        c->gram[e].h.push_back(GramItem{iL, L.wIl0, L.wGlp, m, r, rc, 0});
+        // R' R^T with R R^T (contraction over n) and L^T L' with L^T L (over m); longest contraction first
+        c->gram[e].h.push_back(GramItem{L.wIr0, iR, L.wGpr, L.wGrr, n, r, rc, 0});   // R' R^T and R R^T
+        c->gram[e].h.push_back(GramItem{L.wIl0, iL, L.wGlp, L.wGll, m, r, rc, 1});   // (L'^T L)^T = L^T L' and L^T L
         // the GD step rides on the stripes: L_new = L + s (-eta L (R R^T) + eta b1 L' (R' R^T) + eta (1-b1) G R^T) on the
         // rows of a stripe of G, R_new likewise on the columns of R behind a stripe of G^T.  The r x r matrices enter
         // as images with row a, column k = B[k][a]: (R R^T)^T and (R' R^T)^T for L; L^T L and L^T L' for R^T.

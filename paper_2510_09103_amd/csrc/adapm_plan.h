@@ -178,10 +178,10 @@ struct ImgItem {           // one workgroup: one 64-column chunk of the fragment
   int32_t r, K, c, rc;     // rows of Q, columns, chunk, rank class of the image (rows r .. rc-1 are zero)
   int64_t off_img;
 };
-struct GramItem {          // one workgroup: Out (r x r, row stride r) = X Y^T from the fragment images of X, Y (r x K)
-  int64_t off_x, off_y;    // workspace: images (rank class rc)
-  int64_t off_out;         // workspace: fp32
-  int32_t K, r, rc, pad;
+struct GramItem {          // one workgroup: Out_xs = X S^T (stored transposed if transpose_xs) and Out_ss = S S^T, both r x r
+  int64_t off_x, off_s;    // with row stride r, from the fragment images of X, S (r x K); workspace: images (rank class rc)
+  int64_t off_out_xs, off_out_ss;   // workspace: fp32
+  int32_t K, r, rc, transpose_xs;
 };
 struct GrpItem {           // one workgroup of the grouped update: groups g0 .. g0 + ngroups - 1 of a block's blockwise v
   int64_t g0;

@@ -1467,38 +1467,40 @@ __global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict
   }
 }
 
-// r x r Gram-type products of Alg. 2 (R R^T, R' R^T, L^T L, L^T L') straight from the fragment images: a lane's
-// 16 bytes of an image hold 8 consecutive k of one row, which is the A-operand layout for rows of X and
-// equally the B-operand layout for columns of Y^T.  One workgroup (8 waves) per product; the 64-column chunks of
-// the two images are copied global -> LDS without registers, two buffers deep, so that every image byte is read
-// from L2 once per product (read per wave, the launch was bound by L2 bandwidth); wave w owns column tile w % 4 of
-// the result (all row tiles) and half w / 4 of the k-steps of every chunk.
+// r x r Gram-type products of Alg. 2 straight from the fragment images: a lane's 16 bytes of an image hold 8
+// consecutive k of one row, which is the A-operand layout for rows of X and equally the B-operand layout for columns
+// of S^T.  One workgroup (8 waves) per pair of products that share an image: X S^T and S S^T, i.e. (R' R^T, R R^T)
+// with X = R', S = R and ((L^T L')^T, L^T L) with X = L'^T, S = L^T.  The 64-column chunks of the two images are
+// copied global -> LDS without registers, two buffers deep, so that every image byte is read from L2 once per pair
+// (read per wave, or once per product, the launch was bound by L2 bandwidth); wave w owns column tile w % 4 of both
+// results (all row tiles) and half w / 4 of the k-steps of every chunk.  In the first GD iteration X = S and one
+// product serves both outputs.
 template <int RT>
 __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, unsigned char* smem) {
   constexpr int R = 32 * RT;
   constexpr int QF = qf_chunk_bytes(R);
   const int lane = threadIdx.x & 63, l32 = lane & 31, lh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int cw = wave & 3, kh = wave >> 2;                            // column tile of the result; half of the k-steps of a chunk
+  const int cw = wave & 3, kh = wave >> 2;                            // column tile of the results; half of the k-steps of a chunk
   const char* __restrict__ X = bs.ws + it.off_x;
-  const char* __restrict__ Y = bs.ws + it.off_y;
-  const bool same = it.off_x == it.off_y;
+  const char* __restrict__ S = bs.ws + it.off_s;
+  const bool same = it.off_x == it.off_s;
   const int nch = (it.K + BK - 1) / BK;                               // the images are zero-padded to whole chunks
-  lds_u8* const lds = (lds_u8*)smem;                                  // [2 buffers][X | Y][QF]
+  lds_u8* const lds = (lds_u8*)smem;                                  // [2 buffers][S | X][QF]
   auto copy = [&](int c, int buf) {
     for (int k = wave; k < QF / 1024; k += 8) {
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(X + (int64_t)c * QF + k * 1024 + lane * 16),
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(S + (int64_t)c * QF + k * 1024 + lane * 16),
                                        (__attribute__((address_space(3))) void*)(lds + (buf * 2) * QF + k * 1024), 16, 0, 0);
       if (!same)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Y + (int64_t)c * QF + k * 1024 + lane * 16),
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(X + (int64_t)c * QF + k * 1024 + lane * 16),
                                          (__attribute__((address_space(3))) void*)(lds + (buf * 2 + 1) * QF + k * 1024), 16, 0, 0);
     }
   };
-  f32x16 acc[RT];
+  f32x16 ass[RT], axs[RT];
 #pragma unroll
   for (int t = 0; t < RT; ++t)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+    for (int i = 0; i < 16; ++i) ass[t][i] = axs[t][i] = 0.f;
   copy(0, 0);
   for (int c = 0; c < nch; ++c) {
     // chunk c has landed (every wave waits for its own copies, the barrier collects them) and everybody is done
@@ -1507,41 +1509,61 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
     wg_barrier();
     if (c + 1 < nch) copy(c + 1, (c + 1) & 1);
     if (cw < RT) {
-      const unsigned xs = lds_addr(lds) + ((c & 1) * 2) * QF, ys = same ? xs : xs + QF;
+      const unsigned ss = lds_addr(lds) + ((c & 1) * 2) * QF, xs = ss + QF;
 #pragma unroll
       for (int q = 0; q < BK / 32; ++q) {
         const int kk = (BK / 32) * kh + q;
-        bf16x8 xh[RT], xl[RT];
+        bf16x8 ah[RT], al[RT];
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-          xh[t] = lds_frag_raw(xs + (((kk * RT + t) * 2) * 64 + lane) * 16);
-          xl[t] = lds_frag_raw(xs + (((kk * RT + t) * 2 + 1) * 64 + lane) * 16);
+          ah[t] = lds_frag_raw(ss + (((kk * RT + t) * 2) * 64 + lane) * 16);
+          al[t] = lds_frag_raw(ss + (((kk * RT + t) * 2 + 1) * 64 + lane) * 16);
         }
-        bf16x8 yh = lds_frag_raw(ys + (((kk * RT + cw) * 2) * 64 + lane) * 16);
-        bf16x8 yl = lds_frag_raw(ys + (((kk * RT + cw) * 2 + 1) * 64 + lane) * 16);
+        bf16x8 bh = lds_frag_raw(ss + (((kk * RT + cw) * 2) * 64 + lane) * 16);
+        bf16x8 bl = lds_frag_raw(ss + (((kk * RT + cw) * 2 + 1) * 64 + lane) * 16);
 #pragma unroll
-        for (int t = 0; t < RT; ++t) lds_wait(xh[t], xl[t], yh, yl);
+        for (int t = 0; t < RT; ++t) lds_wait(ah[t], al[t], bh, bl);
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[t], yh, acc[t], 0, 0, 0);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[t], yh, acc[t], 0, 0, 0);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[t], yl, acc[t], 0, 0, 0);
+          ass[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bh, ass[t], 0, 0, 0);
+          ass[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[t], bh, ass[t], 0, 0, 0);
+          ass[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bl, ass[t], 0, 0, 0);
+        }
+        if (!same) {
+#pragma unroll
+          for (int t = 0; t < RT; ++t) {
+            ah[t] = lds_frag_raw(xs + (((kk * RT + t) * 2) * 64 + lane) * 16);
+            al[t] = lds_frag_raw(xs + (((kk * RT + t) * 2 + 1) * 64 + lane) * 16);
+          }
+#pragma unroll
+          for (int t = 0; t < RT; ++t) lds_wait(ah[t], al[t], bh, bl);
+#pragma unroll
+          for (int t = 0; t < RT; ++t) {
+            axs[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bh, axs[t], 0, 0, 0);
+            axs[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[t], bh, axs[t], 0, 0, 0);
+            axs[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bl, axs[t], 0, 0, 0);
+          }
         }
       }
     }
   }
   // the two halves of the k-steps are added through LDS (the image buffers are free now), in a fixed order
   __syncthreads();
-  float* part = reinterpret_cast<float*>(smem) + (cw * RT * 16) * 64;  // [column tile][row tile][16][lane]
+  float* part = reinterpret_cast<float*>(smem) + (cw * RT * 16) * 64;  // [product][column tile][row tile][16][lane]
+  float* part2 = part + 4 * RT * 16 * 64;
   if (kh == 1 && cw < RT) {
 #pragma unroll
     for (int t = 0; t < RT; ++t)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) part[(t * 16 + i) * 64 + lane] = acc[t][i];
+      for (int i = 0; i < 16; ++i) {
+        part[(t * 16 + i) * 64 + lane] = ass[t][i];
+        if (!same) part2[(t * 16 + i) * 64 + lane] = axs[t][i];
+      }
   }
   __syncthreads();
   if (kh != 0 || cw >= RT) return;
-  float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + it.off_out);
+  float* __restrict__ Oss = reinterpret_cast<float*>(bs.ws + it.off_out_ss);
+  float* __restrict__ Oxs = reinterpret_cast<float*>(bs.ws + it.off_out_xs);
   const int r = it.r, col = 32 * cw + l32;
 #pragma unroll
   for (int t = 0; t < RT; ++t)
@@ -1550,7 +1572,12 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const int row = 32 * t + 8 * q + 4 * lh + p;
-        if (row < r && col < r) Out[(int64_t)row * r + col] = acc[t][4 * q + p] + part[(t * 16 + 4 * q + p) * 64 + lane];
+        if (row < r && col < r) {
+          const float vss = ass[t][4 * q + p] + part[(t * 16 + 4 * q + p) * 64 + lane];
+          const float vxs = same ? vss : axs[t][4 * q + p] + part2[(t * 16 + 4 * q + p) * 64 + lane];
+          Oss[(int64_t)row * r + col] = vss;
+          Oxs[it.transpose_xs ? (int64_t)col * r + row : (int64_t)row * r + col] = vxs;
+        }
       }
 }
 
