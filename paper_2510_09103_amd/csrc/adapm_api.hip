@@ -360,13 +360,14 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         sp.a = G.ref; sp.transpose_out = 0; sp.off_img = iR;
         if (e == 0 && v_fusable(b)) { sp.v_rows = b.v_group_rows; sp.off_v = L.sv; sp.beta2 = hp.beta2; }
         sp.x_cur = Lc.ref; sp.x_prev = Lp.ref; sp.off_b1 = L.wB[0]; sp.off_b2 = L.wB[1]; sp.off_out = Ln.ref.off;
-        sp.off_next = iLn;
+        sp.off_next = iLn; sp.off_timg = -1;
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
         sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = iL;
         sp.v_rows = 0;
         sp.x_cur = Rc.ref; sp.x_prev = Rp.ref; sp.off_b1 = L.wB[2]; sp.off_b2 = L.wB[3]; sp.off_out = Rn.ref.off;
         sp.off_next = iRn;
+        sp.off_timg = e + 1 == n_eff ? L.wT2 : -1;     // the last iteration leaves the image of R_t^T for the fused update
         c->sprob.h.push_back(sp);
         swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, n, m});
       } else {
@@ -415,7 +416,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       c->rub.h.push_back(d);
       for (int ch = 0; ch < (n + 63) / 64; ++ch) {
         if (hp.bias_correction) c->qt.h.push_back(ImgItem{Rp, r, n, ch, d.rc, L.wT1});
-        c->qt.h.push_back(ImgItem{Rc, r, n, ch, d.rc, L.wT2});
+        if (!(stripe_ok(b) && n_eff > 0)) c->qt.h.push_back(ImgItem{Rc, r, n, ch, d.rc, L.wT2});   // else: written by the stripes
       }
     } else {
       // m x n low-rank term of m^c (eq. 4): C = L'R' - L R, or L R without the correction
@@ -492,7 +493,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   const float cC = hp.bias_correction ? (float)(b1 / (1.0 - b1)) : 1.f;
   if (fast) {
     // stripes of the fused update, per (rank class, parameter type), whole blocks dealt to XCDs
-    seq.push_back(Op{OP_QTIMG, 0, 0, 0, "update_factor_images"});
+    if (!c->qt.h.empty()) seq.push_back(Op{OP_QTIMG, 0, 0, 0, "update_factor_images"});
     for (int cls = 0; cls < 6; ++cls) {
       const int rank = 32 << (cls >> 1);
       const int pdt = (cls & 1) ? ADAPM_BF16 : ADAPM_F32;

@@ -1358,7 +1358,7 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   float* Ps = reinterpret_cast<float*>(smem);
   float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);
   // with the GD step, the new factor values (zeros outside the factor) go back into P for the image below
-  const bool emit = P.upd && P.off_next >= 0;
+  const bool emit_f = P.upd && P.off_next >= 0, emit_t = P.upd && P.off_timg >= 0, emit = emit_f || emit_t;
   if (!P.transpose_out) {
     const bool vec4 = (r & 3) == 0;
 #pragma unroll
@@ -1407,11 +1407,28 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
       if (emit) Ps[j * PS + a] = v;
     }
   }
-  if (emit) {
+  if (emit) __syncthreads();
+  if (emit_t) {
+    // image of the new factor's transpose for the fused update (the layout qt_image_kernel writes): one row of R
+    // values per stripe row, its 16-byte pieces swizzled with the row's index inside the 64-row chunk
+    constexpr int pr = R / 8, T64 = timg_chunk_bytes(R);
+    for (int p = tid; p < ROWS * pr; p += NT) {
+      const int q = p % pr, j = p / pr;
+      if (row0 + (j & ~(BK - 1)) >= M) continue;   // the image ends with the chunk that holds row M - 1
+      const float4 u = *reinterpret_cast<const float4*>(Ps + j * PS + 8 * q), v = *reinterpret_cast<const float4*>(Ps + j * PS + 8 * q + 4);
+      uint32_t h[4], l[4];
+      split_pair(u.x, u.y, h[0], l[0]); split_pair(u.z, u.w, h[1], l[1]);
+      split_pair(v.x, v.y, h[2], l[2]); split_pair(v.z, v.w, h[3], l[3]);
+      const int jc = j & (BK - 1);
+      char* dst = bs.ws + P.off_timg + (int64_t)((row0 + j) / BK) * T64 + ((int64_t)jc * pr + timg_piece(R, jc, q)) * 16;
+      *reinterpret_cast<uint4*>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+      *reinterpret_cast<uint4*>(dst + (int64_t)BK * pr * 16) = make_uint4(l[0], l[1], l[2], l[3]);
+    }
+  }
+  if (emit_f) {
     // fragment image of the new factor for the next GD iteration (the layout qf_image_kernel writes): the stripe's
     // rows are the image's contraction index, four 64-wide chunks; lane l of a piece holds rows 16 kk + 8 (l / 32) .. + 7
     // of the chunk at factor column 32 tile + l % 32
-    __syncthreads();
     constexpr int QF = qf_chunk_bytes(R);
     char* const img = bs.ws + P.off_next + (int64_t)(row0 / BK) * QF;
     for (int p = tid; p < (ROWS / BK) * (BK / 16) * RT * 64; p += NT) {
