@@ -96,6 +96,8 @@ int main() {
     run<256, 2, true>("read + rmw", g, w, out, rows, rowbytes);
     run<128, 2, false, true>("read x2 back", g, w, out, rows, rowbytes);
     run<128, 2, true, true>("read+rmw back", g, w, out, rows, rowbytes);
+    run<128, 1, false, false, 4>("read 64B", g, w, out, rows, rowbytes);
+    run<128, 1, true, false, 4>("rmw 64B", g, w, out, rows, rowbytes);
     run<128, 1, false, false, 16>("read 256B", g, w, out, rows, rowbytes);
     run<128, 1, false, false, 32>("read 512B", g, w, out, rows, rowbytes);
     run<128, 1, true, false, 16>("rmw 256B", g, w, out, rows, rowbytes);
