@@ -340,6 +340,7 @@ struct StripeTail {
   const char* img1;                  // fragment images of B1^T, B2^T (r x r, rank class of the stripe product)
   const char* img2;
   float c1, c2, cp;
+  int nmat;                          // 2, or 1: only the first thin product (X' = X and B2 = B1 folded into c1)
 };
 
 // As stripe_pass1, for the 256 rows behind rG: leaves P in LDS at smem as [256][R + 4] fp32 (the caller has to
@@ -446,7 +447,7 @@ __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_bu
     // Chunk q = (matrix, 64 columns of X): barrier A = tiles staged and image landed, barrier B = both read.  The
     // tail moves about as many bytes per stripe as a short stripe product does and runs at that rate; deeper
     // prefetching of its operands (measured) gains nothing.
-    const int nk2 = (tl.r + BK - 1) / BK, nq = 2 * nk2;
+    const int nk2 = (tl.r + BK - 1) / BK, nq = tl.nmat * nk2;
     if (mrole) {
       dma_copy(tl.img1, Qs, QF, mw, lane);
 #pragma unroll
@@ -1342,6 +1343,10 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
     tl.rows = (int)rows_valid; tl.r = r;
     tl.img1 = bs.ws + P.off_b1; tl.img2 = bs.ws + P.off_b2;
     tl.c1 = s * P.c1; tl.c2 = s * P.c2; tl.cp = s * gs * P.cp;
+    tl.nmat = 2;
+    // first GD iteration: the factor is still the one of the previous step and the two r x r matrices are one and the
+    // same product (the Gram kernel writes it to both places), so the two thin products fold into one
+    if (P.x_cur.space == P.x_prev.space && P.x_cur.off == P.x_prev.off) { tl.c1 += tl.c2; tl.nmat = 1; }
     gs = 1.f;
   }
   stripe_pass1_x2<RT>(smem, rA, K, K, bs.ws + P.off_img, P.v_rows > 0 ? rsum : nullptr, tl);
