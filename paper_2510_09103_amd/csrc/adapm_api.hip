@@ -124,7 +124,7 @@ struct adapm_ctx {
   DevList<QsItem> qs;
   DevList<TrItem> tr;                   // Alg. 2, MFMA path: transposed copies of G
   DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
-  std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T; behind those, per GD iteration, the images of the Gram-type products
+  std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T (only the first iteration has any: the stripes write the later ones)
   std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
   std::vector<DevList<GramItem>> gram;  //   ... per GD iteration: the four r x r Gram-type products, from the images, in pairs that share one
   std::vector<DevList<GnormItem>> gnorm; // optional scale-normalised Alg. 2: per (path, GD iteration) the normalisers
@@ -296,7 +296,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   constexpr int NXCD = 8;
   struct StripeWork { int prob; int64_t M, K; };
   std::vector<std::vector<StripeWork>> swork(fast ? 3 * n_eff : 0);
-  if (fast) { c->img.resize(2 * n_eff); c->sit.resize(3 * n_eff); c->gram.resize(n_eff); }
+  if (fast) { c->img.resize(n_eff); c->sit.resize(3 * n_eff); c->gram.resize(n_eff); }
   const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list(fast) : -1;
   const int l_epi = fast ? -1 : new_list(false);      // m x n term of eq. 3-4 (the MFMA path never forms it)
   const int l_gram = hp.refresh_period_T > 1 ? new_list(false) : -1;
@@ -342,15 +342,13 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
           for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, rc, iL});
         }
         // R' R^T with R R^T (contraction over n) and L^T L' with L^T L (over m); longest contraction first
-        c->gram[e].h.push_back(GramItem{L.wIr0, iR, L.wGpr, L.wGrr, n, r, rc, 0});   // R' R^T and R R^T
-        c->gram[e].h.push_back(GramItem{L.wIl0, iL, L.wGlp, L.wGll, m, r, rc, 1});   // (L'^T L)^T = L^T L' and L^T L
+        // ... each with the fragment images of its two results, which the GD step on the stripes multiplies by: image
+        // row a, column k = B[k][a] with B = R' R^T, R R^T for L and B = (L^T L')^T, L^T L for R^T
+        c->gram[e].h.push_back(GramItem{L.wIr0, iR, L.wGpr, L.wGrr, L.wB[1], L.wB[0], n, r, rc, 0});   // R' R^T and R R^T
+        c->gram[e].h.push_back(GramItem{L.wIl0, iL, L.wGlp, L.wGll, L.wB[3], L.wB[2], m, r, rc, 1});   // (L'^T L)^T = L^T L' and L^T L
         // the GD step rides on the stripes: L_new = L + s (-eta L (R R^T) + eta b1 L' (R' R^T) + eta (1-b1) G R^T) on the
         // rows of a stripe of G, R_new likewise on the columns of R behind a stripe of G^T.  The r x r matrices enter
         // as images with row a, column k = B[k][a]: (R R^T)^T and (R' R^T)^T for L; L^T L and L^T L' for R^T.
-        const Mat gsrc[4] = {mat(SP_WS, 0, L.wGrr, 1, r, DT_F32), mat(SP_WS, 0, L.wGpr, 1, r, DT_F32),
-                             mat(SP_WS, 0, L.wGll, r, 1, DT_F32), mat(SP_WS, 0, L.wGlp, r, 1, DT_F32)};
-        for (int k = 0; k < 4; ++k)
-          for (int ch = 0; ch < (r + 63) / 64; ++ch) c->img[n_eff + e].h.push_back(ImgItem{gsrc[k], r, r, ch, rc, L.wB[k]});
         const int cls = rc == 32 ? 0 : (rc == 64 ? 1 : 2);
         StripeProb sp;
         memset(&sp, 0, sizeof sp);
@@ -480,7 +478,6 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
     if (hp.refresh_normalise) seq.push_back(Op{OP_GNORM, gnorm0 + e, 0, 0, "alg2_step_normaliser"});
     if (stripes) {
       // both streaming products of the iteration and, behind each stripe, the GD step on the factor rows it covers
-      seq.push_back(Op{OP_QFIMG, n_eff + e, 0, 0, "alg2_gram_images"});
       static const char* names[3] = {"alg2_stripe_step_r32", "alg2_stripe_step_r64", "alg2_stripe_step_r128"};
       for (int cls = 0; cls < 3; ++cls)
         if (!c->sit[3 * e + cls].h.empty()) seq.push_back(Op{OP_STRIPE, 3 * e + cls, 0, 0, names[cls]});

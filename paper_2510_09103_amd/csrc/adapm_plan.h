@@ -183,6 +183,8 @@ struct ImgItem {           // one workgroup: one 64-column chunk of the fragment
 struct GramItem {          // one workgroup: Out_xs = X S^T (stored transposed if transpose_xs) and Out_ss = S S^T, both r x r
   int64_t off_x, off_s;    // with row stride r, from the fragment images of X, S (r x K); workspace: images (rank class rc)
   int64_t off_out_xs, off_out_ss;   // workspace: fp32
+  int64_t off_img_xs, off_img_ss;   // workspace: fragment images of the two results as the GD step on the stripes reads them
+                                    // (image row a, column k = result[k][a]; S S^T is symmetric up to rounding); < 0: none
   int32_t K, r, rc, transpose_xs;
 };
 struct GrpItem {           // one workgroup of the grouped update: groups g0 .. g0 + ngroups - 1 of a block's blockwise v

@@ -1596,24 +1596,59 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
       }
   }
   __syncthreads();
-  if (kh != 0 || cw >= RT) return;
-  float* __restrict__ Oss = reinterpret_cast<float*>(bs.ws + it.off_out_ss);
-  float* __restrict__ Oxs = reinterpret_cast<float*>(bs.ws + it.off_out_xs);
-  const int r = it.r, col = 32 * cw + l32;
+  const bool owner = kh == 0 && cw < RT;
+  if (owner) {
 #pragma unroll
-  for (int t = 0; t < RT; ++t)
+    for (int t = 0; t < RT; ++t)
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int row = 32 * t + 8 * q + 4 * lh + p;
-        if (row < r && col < r) {
-          const float vss = ass[t][4 * q + p] + part[(t * 16 + 4 * q + p) * 64 + lane];
-          const float vxs = same ? vss : axs[t][4 * q + p] + part2[(t * 16 + 4 * q + p) * 64 + lane];
-          Oss[(int64_t)row * r + col] = vss;
-          Oxs[it.transpose_xs ? (int64_t)col * r + row : (int64_t)row * r + col] = vxs;
-        }
+      for (int i = 0; i < 16; ++i) {
+        ass[t][i] += part[(t * 16 + i) * 64 + lane];
+        axs[t][i] = same ? ass[t][i] : axs[t][i] + part2[(t * 16 + i) * 64 + lane];
       }
+  }
+  __syncthreads();                                                     // the partial sums are read: LDS takes the results
+  float* const Mss = reinterpret_cast<float*>(smem);                   // [R][R] each; rows and columns beyond r are zero
+  float* const Mxs = Mss + R * R;                                      // (the images of the factors are zero-padded)
+  if (owner) {
+    float* __restrict__ Oss = reinterpret_cast<float*>(bs.ws + it.off_out_ss);
+    float* __restrict__ Oxs = reinterpret_cast<float*>(bs.ws + it.off_out_xs);
+    const int r = it.r, col = 32 * cw + l32;
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int row = 32 * t + 8 * q + 4 * lh + p;
+          const float vss = ass[t][4 * q + p], vxs = axs[t][4 * q + p];
+          Mss[row * R + col] = vss;
+          Mxs[row * R + col] = vxs;
+          if (row < r && col < r) {
+            Oss[(int64_t)row * r + col] = vss;
+            Oxs[it.transpose_xs ? (int64_t)col * r + row : (int64_t)row * r + col] = vxs;
+          }
+        }
+  }
+  if (it.off_img_ss < 0) return;
+  __syncthreads();
+  // fragment images of the two results for the GD step on the stripes (the layout qf_image_kernel writes), 64-wide
+  // chunks of the contraction index k: lane l of a piece holds result[64 c + 16 kk + 8 (l / 32) .. + 7][32 tile + l % 32]
+  const int nk2 = (it.r + BK - 1) / BK;
+  for (int p = threadIdx.x; p < 2 * nk2 * (BK / 16) * RT * 64; p += 512) {
+    const int ln = p & 63, rest = p >> 6, tile = rest % RT, kk = (rest / RT) % (BK / 16), kc = (rest / (RT * (BK / 16))) % nk2;
+    const int which = rest / (RT * (BK / 16) * nk2);
+    const float* M = (which ? Mxs : Mss) + 32 * tile + (ln & 31);
+    const int k0 = BK * kc + 16 * kk + 8 * (ln >> 5);
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = k0 + e < R ? M[(k0 + e) * R] : 0.f;
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split_pair(x[2 * e], x[2 * e + 1], h[e], l[e]);
+    char* dst = bs.ws + (which ? it.off_img_xs : it.off_img_ss) + (int64_t)kc * QF + ((int64_t)((kk * RT + tile) * 2) * 64 + ln) * 16;
+    *reinterpret_cast<uint4*>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+    *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(l[0], l[1], l[2], l[3]);
+  }
 }
 
 __global__ __launch_bounds__(512) void gram_kernel(const GramItem* __restrict__ items, Bases bs) {
