@@ -295,8 +295,8 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   // MFMA path: per GD iteration the images of (R, L^T) and, per rank class, the stripe problems
   constexpr int NXCD = 8;
   struct StripeWork { int prob; int64_t M, K; };
-  std::vector<std::vector<StripeWork>> swork(fast ? 3 * n_eff : 0);
-  if (fast) { c->img.resize(n_eff); c->sit.resize(3 * n_eff); c->gram.resize(n_eff); }
+  std::vector<std::vector<StripeWork>> swork(fast ? 6 * n_eff : 0);   // per GD iteration: (rank class, G / G^T)
+  if (fast) { c->img.resize(n_eff); c->sit.resize(6 * n_eff); c->gram.resize(n_eff); }
   const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list(fast) : -1;
   const int l_epi = fast ? -1 : new_list(false);      // m x n term of eq. 3-4 (the MFMA path never forms it)
   const int l_gram = hp.refresh_period_T > 1 ? new_list(false) : -1;
@@ -325,10 +325,8 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       //   (L R - m_t) R^T = L (R R^T) - (1-b1) G R^T - b1 L' (R' R^T)
       //   L^T (L R - m_t) = (L^T L) R - (1-b1) L^T G - b1 (L^T L') R'
       if (fast && stripe_ok(b)) {
-        // P = G R^T and S = L^T G = (G^T L)^T as stripe products on images of the current factors
-        if (e == 0)
-          for (int ti = 0; ti < (m + 63) / 64; ++ti)
-            for (int tj = 0; tj < (n + 63) / 64; ++tj) c->tr.h.push_back(TrItem{(int32_t)i, m, n, ti, tj, 0, L.wGt});
+        // P = G R^T and S = L^T G = (G^T L)^T as stripe products on images of the current factors; the stripes of
+        // G^T are 256 columns of G, read with transposing LDS reads
         Mat LcT = T(Lc);
         const int rc = rank_class(r);
         // the images of the first iteration are those of (R_{t-1}, L_{t-1}^T), made by the image kernel and kept for
@@ -360,14 +358,14 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         sp.x_cur = Lc.ref; sp.x_prev = Lp.ref; sp.off_b1 = L.wB[0]; sp.off_b2 = L.wB[1]; sp.off_out = Ln.ref.off;
         sp.off_next = iLn; sp.off_timg = -1;
         c->sprob.h.push_back(sp);
-        swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
-        sp.a = Ref{SP_WS, 0, L.wGt}; sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = iL;
+        swork[6 * e + 2 * cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
+        sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = iL;
         sp.v_rows = 0;
         sp.x_cur = Rc.ref; sp.x_prev = Rp.ref; sp.off_b1 = L.wB[2]; sp.off_b2 = L.wB[3]; sp.off_out = Rn.ref.off;
         sp.off_next = iRn;
         sp.off_timg = e + 1 == n_eff ? L.wT2 : -1;     // the last iteration leaves the image of R_t^T for the fused update
         c->sprob.h.push_back(sp);
-        swork[3 * e + cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, n, m});
+        swork[6 * e + 2 * cls + 1].push_back(StripeWork{(int)c->sprob.h.size() - 1, n, m});
       } else {
         p = problem(m, r); p.A1 = G; p.B1 = T(Rc); p.K1 = n; p.a1 = 1; p.scale_g = 1; p.Out = P; add_problem(A, p);
         p = problem(r, n); p.A1 = T(Lc); p.B1 = G; p.K1 = m; p.a1 = 1; p.scale_g = 1; p.Out = S; add_problem(A, p);
@@ -478,9 +476,10 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
     if (hp.refresh_normalise) seq.push_back(Op{OP_GNORM, gnorm0 + e, 0, 0, "alg2_step_normaliser"});
     if (stripes) {
       // both streaming products of the iteration and, behind each stripe, the GD step on the factor rows it covers
-      static const char* names[3] = {"alg2_stripe_step_r32", "alg2_stripe_step_r64", "alg2_stripe_step_r128"};
-      for (int cls = 0; cls < 3; ++cls)
-        if (!c->sit[3 * e + cls].h.empty()) seq.push_back(Op{OP_STRIPE, 3 * e + cls, 0, 0, names[cls]});
+      static const char* names[6] = {"alg2_stripe_step_L_r32", "alg2_stripe_step_R_r32", "alg2_stripe_step_L_r64",
+                                     "alg2_stripe_step_R_r64", "alg2_stripe_step_L_r128", "alg2_stripe_step_R_r128"};
+      for (int k = 0; k < 6; ++k)
+        if (!c->sit[6 * e + k].h.empty()) seq.push_back(Op{OP_STRIPE, 6 * e + k, 0, 0, names[k]});
     }
     if (!c->gemms[listB[e]].tiles.empty())
       seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"});
@@ -667,7 +666,6 @@ void build_plan(adapm_ctx* c) {
         L.wC = walloc(4 * m * n);
       }
       if (L.path == PATH_FAST && stripe_ok(b)) {
-        L.wGt = walloc(2 * m * n);
         L.wIr = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
         L.wIl = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
         L.wIr2 = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
@@ -1011,7 +1009,7 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         launch_qf_image(c->img[op.index].d, (int64_t)c->img[op.index].h.size(), bs, s);
         break;
       case OP_STRIPE:
-        launch_stripe(1 << (op.index % 3), c->sit[op.index].d, (int64_t)c->sit[op.index].h.size(), c->sprob.d, bs, s);
+        launch_stripe(1 << ((op.index % 6) >> 1), (op.index & 1) != 0, c->sit[op.index].d, (int64_t)c->sit[op.index].h.size(), c->sprob.d, bs, s);
         break;
       case OP_UPDATE_GROUPED:
         launch_update_grouped(c->blocks.d, c->grp.d, (int64_t)c->grp.h.size(), bs, sc, s);

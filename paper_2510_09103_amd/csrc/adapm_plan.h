@@ -149,7 +149,7 @@ struct QsItem {            // one workgroup: one 64-column chunk of Q
 // given as a bf16 (hi, lo) fragment image.  Used for G R^T (A = G) and, on the transposed copy of G,
 // for (L^T G)^T = G^T L (A = G^T, Q = L^T), whose result is written back transposed.
 struct StripeProb {
-  Ref a;                   // A: M x K bf16, row-major, row stride K
+  Ref a;                   // A: M x K bf16, row-major, row stride K; with transpose_out: A^T (K x M, row stride M) instead
   int32_t M, K, r;         // r: rows of Q actually present
   int32_t transpose_out;   // 0: Out is M x r (row stride r); 1: Out is r x M (row stride M)
   int32_t rc, upd;         // rank class of the image: 32, 64 or 128 >= r; upd: the factor update of Alg. 2 follows
@@ -256,7 +256,7 @@ void launch_gemm_mfma(const GemmProblem* probs, const GemmTile* tiles, int64_t n
 void launch_proj(int rt, bool w16, bool vel, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
                  StepScalars sc, hipStream_t s);
 void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s);
-void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s);
+void launch_stripe(int rt, bool tra, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s);
 void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gram(const GramItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);

@@ -101,6 +101,17 @@ __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b, bf16x8& c) {
 __device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b)::"memory");
 }
+// LDS transpose read (gfx950): within each block of 16 lanes, lane i receives element i % 4 of the 8 bytes that
+// lanes i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12 of the block address.  With lane s of a block pointing at row
+// k0 + s / 4, columns n0 + 4 (s % 4) .. + 3 of a row-major bf16 tile, lane i gets column n0 + i of rows k0 .. k0 + 3:
+// an operand fragment along the tile's rows, read from a tile stored along its columns.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x2 lds_tr16_raw(unsigned addr) {
+  u32x2 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+__device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b)::"memory"); }
 // the same, leaving the newest KEEP LDS requests of this wave in flight
 template <int KEEP>
 __device__ __forceinline__ void lds_wait_keep(bf16x8& a, bf16x8& b, bf16x8& c, bf16x8& d) {
@@ -348,20 +359,38 @@ struct StripeTail {
 // With a tail, the thin products run as further rounds of the same pipeline: the streaming waves scale a 64-column
 // chunk of X by its coefficient and stage it as two bf16 tiles (hi, lo), the matrix-core waves copy the matching
 // chunk of the coefficient image and multiply hi * (hi, lo) + lo * hi onto the accumulators that hold P.
-template <int RT>
-__device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_buffer_rsrc_t rG, int n, int nv,
-                                                const char* __restrict__ Qf, float* rsum, const StripeTail& tl) {
+// TRA = false: A is the 256 x K stripe behind rG (row stride n = K elements).  TRA = true: the stripe is 256 columns
+// of a K x ld row-major matrix (base points at the stripe's first column): the stripe product of the transposed
+// matrix without a transposed copy.  A chunk is then 64 rows of that matrix, staged as it lies in memory (512
+// contiguous bytes per row), and the matrix-core waves take their fragments with transpose reads.
+struct StripeSrc {
+  __amdgpu_buffer_rsrc_t rG;         // TRA = false
+  int n, nv;
+  const uint16_t* base;              // TRA = true
+  int64_t ld;
+  int K, width;                      // rows of the matrix; columns of the stripe that exist
+};
+constexpr int TS = 4 * BK + 32;      // LDS row stride (elements) of a transposed-read tile: rows 64 bytes apart in bank space
+
+template <int RT, bool TRA>
+__device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, const StripeSrc& src, const char* __restrict__ Qf,
+                                                float* rsum, const StripeTail& tl) {
   constexpr int QF = Pass1x2<RT>::QF, G_TILE = Pass1x2<RT>::G_TILE, PS = Pass1x2<RT>::PS, D1 = Pass1x2<RT>::D1;
+  static_assert(BK * TS * 2 <= G_TILE, "a transposed-read tile fits the tile buffer");
   constexpr int TPW = RT;                                 // 8 row tiles x RT rank tiles over 8 waves
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool mrole = wave < 8;
   const int mw = wave & 7, t512 = tid & 511, l32 = lane & 31, lh = lane >> 5;
-  const int nc = (nv + BK - 1) / BK;
+  const __amdgpu_buffer_rsrc_t rG = src.rG;
+  const int n = src.n, nv = src.nv;
+  const int nc = ((TRA ? src.K : nv) + BK - 1) / BK;
   const int c8 = (t512 & 7) * 8;
   unsigned eoff[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) eoff[i] = (unsigned)(((t512 >> 3) + 64 * i) * n + c8);
+  // TRA: this thread's vectors of a chunk: rows t512 / 32 + 16 i, columns 8 (t512 % 32) .. + 7 of the stripe
+  const int tj = (t512 & 31) * 8, tr = t512 >> 5;
   const int NR1 = (nc + D1) / D1 * D1;                    // rounds: nc + 1, rounded up to the prefetch depth
   lds_u8* const lds = (lds_u8*)smem;
   lds_u8* const Qs = lds;                                 // [2][QF]
@@ -370,18 +399,32 @@ __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_bu
   const int my_mt0 = (mw / RT) * TPW;                     // first of this wave's TPW row tiles
   float ss[4] = {0.f, 0.f, 0.f, 0.f};   // this streaming thread's sums of squares of rows t512 / 8 + 64 i
   auto fetch_g = [&](int c, uint4 (&dst)[4]) {
-    const bool ok = c * BK + c8 < nv;
+    if (TRA) {
+      // the chunk's own range: rows at or beyond K read zeros; 32-bit offsets stay below 64 rows of the matrix
+      const int rows = src.K - c * BK < BK ? src.K - c * BK : BK;
+      const __amdgpu_buffer_rsrc_t rc = make_rsrc(src.base + (int64_t)c * BK * src.ld,
+                                                  rows > 0 ? (unsigned)(((int64_t)(rows - 1) * src.ld + src.width) * 2) : 0u);
+      const bool ok = tj < src.width;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) dst[i] = buf_load16(rG, ok ? (eoff[i] + (unsigned)(c * BK)) * 2u : OOB);
+      for (int i = 0; i < 4; ++i) dst[i] = buf_load16(rc, ok ? (unsigned)((tr + 16 * i) * (int)src.ld + tj) * 2u : OOB);
+    } else {
+      const bool ok = c * BK + c8 < nv;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) dst[i] = buf_load16(rG, ok ? (eoff[i] + (unsigned)(c * BK)) * 2u : OOB);
+    }
   };
-  auto stage_g = [&](int buf, uint4 (&src)[4]) {
+  auto stage_g = [&](int buf, uint4 (&q4)[4]) {
     uint16_t* gs = reinterpret_cast<uint16_t*>(Gs + buf * G_TILE);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = (t512 >> 3) + 64 * i;
-      const uint4 q = src[i];
-      *reinterpret_cast<uint4*>(gs + row * GS + c8) = q;
-      ss[i] += dot2_sq(q.w, dot2_sq(q.z, dot2_sq(q.y, dot2_sq(q.x, 0.f))));
+      const uint4 q = q4[i];
+      if (TRA) {
+        *reinterpret_cast<uint4*>(gs + (tr + 16 * i) * TS + tj) = q;
+      } else {
+        const int row = (t512 >> 3) + 64 * i;
+        *reinterpret_cast<uint4*>(gs + row * GS + c8) = q;
+        ss[i] += dot2_sq(q.w, dot2_sq(q.z, dot2_sq(q.y, dot2_sq(q.x, 0.f))));
+      }
     }
   };
   f32x16 acc[TPW];
@@ -396,13 +439,34 @@ __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, __amdgpu_bu
         const int b = (cc - 1) & 1;
         const unsigned qa = lds_addr(Qs) + b * QF + (unsigned)((my_rt * 2 * 64 + lane) * 16);
         const unsigned ga = lds_addr(Qs) + 2 * QF + b * G_TILE + (unsigned)(((32 * my_mt0 + l32) * GS + 8 * lh) * 2);
+        // TRA: lane s of a 16-lane block addresses row 8 (lane / 32) + s / 4 (+ 4 for the second read) of the k-step,
+        // columns 32 tile + 16 (lane / 16 % 2) + 4 (s % 4) .. + 3; it receives column 32 tile + lane % 32
+        const unsigned gt = lds_addr(Qs) + 2 * QF + b * G_TILE +
+                            (unsigned)(((8 * lh + ((lane & 15) >> 2)) * TS + 32 * my_mt0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
           bf16x8 bh = lds_frag_raw(qa + kk * RT * 2048);
           bf16x8 bl = lds_frag_raw(qa + kk * RT * 2048 + 1024);
           bf16x8 a[TPW];
+          if (TRA) {
+            // the halves of a fragment are put together only behind the wait that names them
+            u32x2 lo[TPW], hi[TPW];
 #pragma unroll
-          for (int t = 0; t < TPW; ++t) a[t] = lds_frag_raw(ga + kk * 32 + t * 32 * GS * 2);
+            for (int t = 0; t < TPW; ++t) {
+              lo[t] = lds_tr16_raw(gt + (unsigned)((16 * kk * TS + 32 * t) * 2));
+              hi[t] = lds_tr16_raw(gt + (unsigned)(((16 * kk + 4) * TS + 32 * t) * 2));
+            }
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) lds_wait(lo[t], hi[t]);
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+              const u32x4 both = {lo[t].x, lo[t].y, hi[t].x, hi[t].y};
+              a[t] = __builtin_bit_cast(bf16x8, both);
+            }
+          } else {
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) a[t] = lds_frag_raw(ga + kk * 32 + t * 32 * GS * 2);
+          }
           if (TPW == 1) lds_wait(bh, bl, a[0]);
           else {
             lds_wait(bh, bl, a[0], a[1]);
@@ -1324,7 +1388,9 @@ __global__ __launch_bounds__(256) void qt_image_kernel(const ImgItem* __restrict
 
 // Alg. 2 stripe product: Out = A Q^T for 256 rows of A per workgroup (pass 1 of the kernel above, then a store), or
 // the whole GD step on the factor behind those rows (the stripe product continued by the thin products, then a store).
-template <int RT>
+// TRA: the stripes of a transposed_out problem are 256 columns of its matrix A^T (K x M, row-major: the gradient
+// itself where A = G^T), read with transposing LDS reads instead of from a transposed copy.
+template <int RT, bool TRA>
 __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restrict__ items,
                                                        const StripeProb* __restrict__ probs, Bases bs) {
   constexpr int R = 32 * RT, PS = Pass1x2<RT>::PS, ROWS = Pass1x2<RT>::ROWS;
@@ -1336,7 +1402,13 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   const int M = P.M, K = P.K, row0 = item.row0, tid = threadIdx.x;
   const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(resolve(P.a, bs));
   const unsigned rows_valid = (unsigned)(M - row0 < ROWS ? M - row0 : ROWS);
-  const __amdgpu_buffer_rsrc_t rA = make_rsrc(A + (int64_t)row0 * K, rows_valid * (unsigned)K * 2u);
+  StripeSrc src = {};
+  if (TRA) {
+    src.base = A + row0; src.ld = M; src.K = K; src.width = (int)rows_valid;
+  } else {
+    src.rG = make_rsrc(A + (int64_t)row0 * K, rows_valid * (unsigned)K * 2u);
+    src.n = K; src.nv = K;
+  }
   __shared__ float rsum[ROWS];        // sums of squares of the stripe's rows (second moment)
   const int r = P.r;                  // rows of Q actually present (the image is zero-padded to R)
   float gs = grad_scale(bs);          // global gradient clipping: A is the gradient (or its transpose)
@@ -1362,7 +1434,7 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
     if (P.x_cur.space == P.x_prev.space && P.x_cur.off == P.x_prev.off) { tl.c1 += tl.c2; tl.nmat = 1; }
     gs = 1.f;
   }
-  stripe_pass1_x2<RT>(smem, rA, K, K, bs.ws + P.off_img, P.v_rows > 0 ? rsum : nullptr, tl);
+  stripe_pass1_x2<RT, TRA>(smem, src, bs.ws + P.off_img, (!TRA && P.v_rows > 0) ? rsum : nullptr, tl);
   __syncthreads();
   if (P.v_rows > 0) {               // groups of v_rows rows inside the stripe (v_rows divides 128)
     const int g = P.v_rows;
@@ -1715,12 +1787,18 @@ void launch_proj(int rt, bool w16, bool vel, const ProjItem* items, int64_t nite
   else launch_proj_rt<4>(w16, vel, grid, items, lrb, b, sc, s);
 }
 
-void launch_stripe(int rt, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s) {
+void launch_stripe(int rt, bool tra, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s) {
   if (nitems <= 0) return;
   const dim3 grid((unsigned)nitems);
-  if (rt == 1) hipLaunchKernelGGL((stripe_kernel<1>), grid, dim3(NT), 0, s, items, probs, b);
-  else if (rt == 2) hipLaunchKernelGGL((stripe_kernel<2>), grid, dim3(NT), 0, s, items, probs, b);
-  else hipLaunchKernelGGL((stripe_kernel<4>), grid, dim3(NT), 0, s, items, probs, b);
+  if (tra) {
+    if (rt == 1) hipLaunchKernelGGL((stripe_kernel<1, true>), grid, dim3(NT), 0, s, items, probs, b);
+    else if (rt == 2) hipLaunchKernelGGL((stripe_kernel<2, true>), grid, dim3(NT), 0, s, items, probs, b);
+    else hipLaunchKernelGGL((stripe_kernel<4, true>), grid, dim3(NT), 0, s, items, probs, b);
+  } else {
+    if (rt == 1) hipLaunchKernelGGL((stripe_kernel<1, false>), grid, dim3(NT), 0, s, items, probs, b);
+    else if (rt == 2) hipLaunchKernelGGL((stripe_kernel<2, false>), grid, dim3(NT), 0, s, items, probs, b);
+    else hipLaunchKernelGGL((stripe_kernel<4, false>), grid, dim3(NT), 0, s, items, probs, b);
+  }
 }
 
 void launch_gram(const GramItem* items, int64_t nitems, Bases b, hipStream_t s) {
