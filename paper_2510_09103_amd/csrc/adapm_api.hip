@@ -54,7 +54,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wP = -1, wS = -1, wGrr = -1, wGpr = -1, wGll = -1, wGlp = -1;
   int64_t wG64 = -1, wCinv = -1, wC = -1;
   int64_t wQf = -1, wTimg = -1;                             // ws: bf16 (hi, lo) images of Q and Q^T
-  int64_t wGt = -1, wIr = -1, wIl = -1;                     // ws: G^T (bf16) and the fragment images of R, L^T during Alg. 2 ...
+  int64_t wIr = -1, wIl = -1;                               // ws: the fragment images of R, L^T during Alg. 2 ...
   int64_t wIr2 = -1, wIl2 = -1;                             // ws: ... written by the stripes of one GD iteration for the next, hence two sets
   int64_t wIr0 = -1, wIl0 = -1;                             // ws: the same images of R_{t-1}, L_{t-1}^T (first iteration; Gram matrices)
   int64_t wNu = -1;                                         // ws: normaliser of the optional scale-normalised Alg. 2 (one double)
@@ -64,7 +64,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_TRANSPOSE, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM, OP_UPDATE_GROUPED };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM, OP_UPDATE_GROUPED };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -122,7 +122,6 @@ struct adapm_ctx {
   DevList<LrBlockDev> lrb;
   DevList<ProjItem> proj[12];   // (rank 32 / 64 / 128) x (fp32 / bf16 parameters) x (blockwise / per-element v)
   DevList<QsItem> qs;
-  DevList<TrItem> tr;                   // Alg. 2, MFMA path: transposed copies of G
   DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
   std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T (only the first iteration has any: the stripes write the later ones)
   std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
@@ -180,9 +179,9 @@ int path_of(const adapm_block_t& b, const adapm_hparams_t& hp) {
                    b.cols <= (1 << 21);   // 128 rows of a stripe stay inside one 32-bit buffer range
   return (want && can) ? PATH_FAST : PATH_F64;
 }
-// Alg. 2 on the MFMA path: the two products that stream G (G R^T and L^T G) run as stripe products when
-// G and its transposed copy both have 16-byte rows and the copy fits the kernel's 32-bit buffer ranges
-bool stripe_ok(const adapm_block_t& b) { return b.rows % 8 == 0 && b.cols % 8 == 0 && b.rows <= (1 << 21); }
+// Alg. 2 on the MFMA path: the two products that stream G (G R^T and L^T G) run as stripe products when the rows
+// of G are whole 16-byte vectors (both read G itself: stripes of rows, and stripes of columns in chunks of 64 rows)
+bool stripe_ok(const adapm_block_t& b) { return b.cols % 8 == 0; }
 // v of a block on the MFMA path can be finished inside the 128-row stripe of the fused kernel
 bool v_fusable(const adapm_block_t& b) {
   return b.v_mode == ADAPM_V_ROWGROUP && b.v_group_rows <= 128 && 128 % b.v_group_rows == 0;
@@ -463,7 +462,6 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       for (int x = 0; x < NXCD; ++x) c->sit[w].h.push_back(q < per[x].size() ? per[x][q] : StripeItem{-1, 0});
   }
   std::vector<Op>& seq = c->seq_refresh;
-  if (fast && !c->tr.h.empty()) seq.push_back(Op{OP_TRANSPOSE, 0, 0, 0, "transpose_G"});
   for (int e = 0; e < n_eff; ++e) {
     const bool stripes = fast && !c->gram[e].h.empty();
     if (stripes) {
@@ -785,7 +783,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   HIP_TRY(hipGetDevice(&dev));
   const size_t nb = c->table.size();
   size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
-                 bytes_of(c->tr.h) + bytes_of(c->sprob.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) + bytes_of(c->grp.h) +
+                 bytes_of(c->sprob.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) + bytes_of(c->grp.h) +
                  align_up(2 * nb * sizeof(void*));
   for (int i = 0; i < 6; ++i) total += bytes_of(c->ru[i].h);
   for (auto& l : c->img) total += bytes_of(l.h);
@@ -806,7 +804,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     return dst;
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
-  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->tr); PUT_LIST(c->sprob); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn); PUT_LIST(c->grp);
+  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->sprob); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn); PUT_LIST(c->grp);
   for (int i = 0; i < 6; ++i) PUT_LIST(c->ru[i]);
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
@@ -1001,9 +999,6 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         launch_qimage(c->qs.d, (int64_t)c->qs.h.size(), c->lrb.d, bs, s);
         c->split_ws = workspace_dev;
         c->split_state = state_dev;
-        break;
-      case OP_TRANSPOSE:
-        launch_transpose_bf16(c->tr.d, (int64_t)c->tr.h.size(), bs, s);
         break;
       case OP_QFIMG:
         launch_qf_image(c->img[op.index].d, (int64_t)c->img[op.index].h.size(), bs, s);

@@ -198,10 +198,6 @@ struct GnormItem {         // one workgroup: s = 1 / max(||A||_F, ||B||_F) for t
   int64_t off_out;         // workspace, one double
   int32_t r, dtype;        // DT_F32 or DT_F64
 };
-struct TrItem {            // one workgroup: one 64 x 64 tile of the bf16 transpose G (m x n) -> G^T (n x m)
-  int32_t block, m, n, ti, tj, pad;
-  int64_t off_out;         // workspace
-};
 
 // Fused update of a step that ran Alg. 2 (MFMA path): m^c = cG G + cC (a1 L1 Q1 + a2 L2 Q2) tile by tile, never
 // stored; (L1, Q1) = (L_{t-1}, R_{t-1}), (L2, Q2) = (L_t, R_t), (a1, a2) = (1, -1) with the bias correction of
@@ -262,7 +258,6 @@ void launch_gram(const GramItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_refresh_update(int rt, bool w16, const ProjItem* items, int64_t nitems, const RuBlockDev* blocks, Bases b,
                            StepScalars sc, hipStream_t s);
-void launch_transpose_bf16(const TrItem* items, int64_t nitems, Bases b, hipStream_t s);
 size_t proj_qf_bytes(int r, int n);     // sizes of the two images of Q kept for the fused step
 size_t proj_timg_bytes(int r, int n);
 

@@ -18,15 +18,16 @@
 //                         may start at any 2-byte alignment: vectors cover the columns up to the last
 //                         multiple of 8, the remaining columns are done element by element.
 //  stripe_kernel          pass 1 alone on two stripes (256 rows) that share every copied chunk of the
-//                         image: the products G R^T and (G^T L)^T of Alg. 2, each continued by the thin
+//                         image: the products G R^T and (G^T L)^T of Alg. 2 (the stripes of G^T are 256
+//                         columns of G, staged as they lie in memory and read with the transposing LDS
+//                         reads of gfx950), each continued by the thin
 //                         products of the GD step on the factor rows behind the stripe (L (R R^T),
 //                         L' (R' R^T) for L; the same with L^T L, L^T L' for R^T), so that the new factor
 //                         is stored and the m x r / r x n products never leave the accumulators.
 //  refresh_update_kernel  pass 2 alone with two (factor, image) pairs: the update of a step that ran Alg. 2,
 //                         m^c = G + beta1/(1-beta1) (L_{t-1} R_{t-1} - L_t R_t), never storing the m x n term.
-//  gram_kernel, qimage_kernel, qf_image_kernel, qt_image_kernel, transpose_bf16_kernel: the r x r products of
-//                         Alg. 2 from the images (chunks shared through LDS), the images themselves, the
-//                         transposed copy of G.
+//  gram_kernel, qimage_kernel, qf_image_kernel, qt_image_kernel: the r x r products of Alg. 2 from the
+//                         images (chunks shared through LDS, results also as images), the images themselves.
 //
 // Matrix work uses v_mfma_f32_32x32x16_bf16.  G is bf16 (exact); every fp32 operand (factors, D) is
 // carried as a (hi, lo) pair of bf16 values, products hi*hi + lo*hi + hi*lo accumulated in fp32
@@ -1731,38 +1732,6 @@ __global__ __launch_bounds__(512) void gram_kernel(const GramItem* __restrict__ 
   else gram_body<4>(it, bs, smem);
 }
 
-// bf16 transpose through LDS, 64 x 64 tiles; needs m % 8 == 0 and n % 8 == 0 (16-byte vectors both ways)
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const TrItem* __restrict__ items, Bases bs) {
-  __shared__ uint16_t tile[64][66];
-  const TrItem it = items[blockIdx.x];
-  const int m = it.m, n = it.n, i0 = it.ti * 64, j0 = it.tj * 64, t = threadIdx.x;
-  const uint16_t* __restrict__ G = reinterpret_cast<const uint16_t*>(bs.grads[it.block]);
-  uint16_t* __restrict__ Gt = reinterpret_cast<uint16_t*>(bs.ws + it.off_out);
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int r = (t >> 3) + 32 * h, c8 = (t & 7) * 8;
-    uint4 q = make_uint4(0, 0, 0, 0);
-    if (i0 + r < m && j0 + c8 < n) q = *reinterpret_cast<const uint4*>(G + (int64_t)(i0 + r) * n + j0 + c8);
-    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      tile[r][c8 + 2 * e] = (uint16_t)(w[e] & 0xffffu);
-      tile[r][c8 + 2 * e + 1] = (uint16_t)(w[e] >> 16);
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int j = (t >> 3) + 32 * h, r8 = (t & 7) * 8;
-    if (j0 + j < n && i0 + r8 < m) {
-      uint32_t w[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[r8 + 2 * e][j] | ((uint32_t)tile[r8 + 2 * e + 1][j] << 16);
-      *reinterpret_cast<uint4*>(Gt + (int64_t)(j0 + j) * m + i0 + r8) = make_uint4(w[0], w[1], w[2], w[3]);
-    }
-  }
-}
-
 template <int RT>
 void launch_proj_rt(bool w16, bool vel, dim3 grid, const ProjItem* items, const LrBlockDev* lrb, Bases b, StepScalars sc,
                     hipStream_t s) {
@@ -1829,11 +1798,6 @@ void launch_refresh_update(int rt, bool w16, const ProjItem* items, int64_t nite
 void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s) {
   if (nitems <= 0) return;
   hipLaunchKernelGGL(qf_image_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
-}
-
-void launch_transpose_bf16(const TrItem* items, int64_t nitems, Bases b, hipStream_t s) {
-  if (nitems <= 0) return;
-  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
 }
 
 void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s) {
