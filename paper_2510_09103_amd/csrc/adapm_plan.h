@@ -146,8 +146,8 @@ struct QsItem {            // one workgroup: one 64-column chunk of Q
 };
 
 // Stripe product of Alg. 2 (MFMA path): Out = A Q^T with A a bf16 matrix streamed once, Q (r x K, fp32)
-// given as a bf16 (hi, lo) fragment image.  Used for G R^T (A = G) and, on the transposed copy of G,
-// for (L^T G)^T = G^T L (A = G^T, Q = L^T), whose result is written back transposed.
+// given as a bf16 (hi, lo) fragment image.  Used for G R^T (A = G) and for (L^T G)^T = G^T L (A = G^T, Q = L^T;
+// what is stored is G, its column stripes are read transposed), whose result is written back transposed.
 struct StripeProb {
   Ref a;                   // A: M x K bf16, row-major, row stride K; with transpose_out: A^T (K x M, row stride M) instead
   int32_t M, K, r;         // r: rows of Q actually present
