@@ -64,7 +64,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM, OP_UPDATE_GROUPED };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM, OP_UPDATE_GROUPED, OP_COPY };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -127,6 +127,7 @@ struct adapm_ctx {
   std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
   std::vector<DevList<GramItem>> gram;  //   ... per GD iteration: the four r x r Gram-type products, from the images, in pairs that share one
   std::vector<DevList<GnormItem>> gnorm; // optional scale-normalised Alg. 2: per (path, GD iteration) the normalisers
+  DevList<CopyItem> cp;                 // T = 1, MFMA path: the factors Alg. 2 leaves in the workspace -> state
   DevList<RuBlockDev> rub;              // fused update after Alg. 2 (MFMA path): blocks, images of R^T, stripes
   DevList<ImgItem> qt;
   DevList<ProjItem> ru[6];              //   (rank class 32 / 64 / 128) x (fp32 / bf16 parameters)
@@ -436,8 +437,15 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       p = problem(r, n); p.A1 = Cinv; p.B1 = Rc; p.K1 = r; p.a1 = 1.0; p.tri = 1; p.Out = Rp; add_problem(c->gemms[l_fin], p);
       p = problem(m, r); p.A1 = Lc; p.B1 = G64; p.K1 = r; p.a1 = 1.0; p.tri = 2; p.Out = Lp; add_problem(c->gemms[l_fin], p);
     } else if (n_eff > 0) {
-      p = problem(m, r); p.X = Lc; p.g = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
-      p = problem(r, n); p.X = Rc; p.g = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
+      if (fast) {
+        for (int64_t f = 0; f < (int64_t)m * r; f += COPY_CHUNK)
+          c->cp.h.push_back(CopyItem{Lc.ref, Lp.ref, f, (int32_t)std::min<int64_t>(COPY_CHUNK, (int64_t)m * r - f), 0});
+        for (int64_t f = 0; f < (int64_t)r * n; f += COPY_CHUNK)
+          c->cp.h.push_back(CopyItem{Rc.ref, Rp.ref, f, (int32_t)std::min<int64_t>(COPY_CHUNK, (int64_t)r * n - f), 0});
+      } else {
+        p = problem(m, r); p.X = Lc; p.g = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
+        p = problem(r, n); p.X = Rc; p.g = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
+      }
     }
   }
   // stripes of one problem go to one XCD (workgroup i runs on XCD i mod 8) so that they share the image
@@ -524,10 +532,11 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
     seq.push_back(Op{OP_GEMM, l_gram, 0, 0, "regauge_gram_f64"});
     seq.push_back(Op{OP_CHOL, fast ? 1 : 0, 0, 0, "regauge_cholesky_f64"});
   }
-  if (l_fin >= 0) {
+  if (l_fin >= 0 && !c->gemms[l_fin].tiles.empty()) {
     const bool f64_fin = hp.refresh_period_T > 1;
     seq.push_back(Op{f64_fin ? OP_GEMM : gk, l_fin, 0, 0, f64_fin ? "regauge_apply_f64" : "store_factors"});
   }
+  if (fast && !c->cp.h.empty()) seq.push_back(Op{OP_COPY, 0, 0, 0, "store_factors"});
 }
 
 // step with R held, F64 path: four batched GEMM launches and the update kernel
@@ -783,7 +792,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   HIP_TRY(hipGetDevice(&dev));
   const size_t nb = c->table.size();
   size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
-                 bytes_of(c->sprob.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) + bytes_of(c->grp.h) +
+                 bytes_of(c->sprob.h) + bytes_of(c->cp.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) + bytes_of(c->grp.h) +
                  align_up(2 * nb * sizeof(void*));
   for (int i = 0; i < 6; ++i) total += bytes_of(c->ru[i].h);
   for (auto& l : c->img) total += bytes_of(l.h);
@@ -804,7 +813,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     return dst;
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
-  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->sprob); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn); PUT_LIST(c->grp);
+  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->sprob); PUT_LIST(c->cp); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn); PUT_LIST(c->grp);
   for (int i = 0; i < 6; ++i) PUT_LIST(c->ru[i]);
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
@@ -1008,6 +1017,9 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
         break;
       case OP_UPDATE_GROUPED:
         launch_update_grouped(c->blocks.d, c->grp.d, (int64_t)c->grp.h.size(), bs, sc, s);
+        break;
+      case OP_COPY:
+        launch_copy(c->cp.d, (int64_t)c->cp.h.size(), bs, s);
         break;
       case OP_GNORM:
         launch_gram_norm(c->gnorm[op.index].d, (int64_t)c->gnorm[op.index].h.size(), bs, s);

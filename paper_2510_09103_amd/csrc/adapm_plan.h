@@ -187,6 +187,12 @@ struct GramItem {          // one workgroup: Out_xs = X S^T (stored transposed i
                                     // (image row a, column k = result[k][a]; S S^T is symmetric up to rounding); < 0: none
   int32_t K, r, rc, transpose_xs;
 };
+struct CopyItem {          // one workgroup: count floats from src + first to dst + first (first is a multiple of 4)
+  Ref src, dst;
+  int64_t first;
+  int32_t count, pad;
+};
+constexpr int COPY_CHUNK = 16384;   // floats per workgroup
 struct GrpItem {           // one workgroup of the grouped update: groups g0 .. g0 + ngroups - 1 of a block's blockwise v
   int64_t g0;
   int32_t block;
@@ -246,6 +252,7 @@ void launch_gradnorm_final(const double* partials, int64_t nparts, float max_nor
 void launch_update(const BlockDev* blocks, const EwItem* items, int64_t nitems, Bases b, StepScalars sc,
                    hipStream_t s);
 void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+void launch_copy(const CopyItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_sketch(const SketchItem* items, int64_t nitems, char* state, hipStream_t s);
 void launch_chol(const CholItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gemm_mfma(const GemmProblem* probs, const GemmTile* tiles, int64_t ntiles, Bases b, hipStream_t s);

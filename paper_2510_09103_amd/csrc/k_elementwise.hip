@@ -353,6 +353,17 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint4* p, int64_t n16) {
     p[i] = make_uint4(0, 0, 0, 0);
 }
 
+// plain copy of fp32 arrays (the factors of Alg. 2 into the state where nothing else has to be done to them)
+__global__ __launch_bounds__(256) void copy_kernel(const CopyItem* __restrict__ items, Bases bs) {
+  const CopyItem it = items[blockIdx.x];
+  const float* __restrict__ src = reinterpret_cast<const float*>(resolve(it.src, bs)) + it.first;
+  float* __restrict__ dst = reinterpret_cast<float*>(resolve(it.dst, bs)) + it.first;
+  const int n4 = it.count >> 2;
+  for (int i = threadIdx.x; i < n4; i += 256)
+    reinterpret_cast<float4*>(dst)[i] = reinterpret_cast<const float4*>(src)[i];
+  for (int i = 4 * n4 + threadIdx.x; i < it.count; i += 256) dst[i] = src[i];
+}
+
 __device__ __forceinline__ uint64_t mix64(uint64_t z) {   // SplitMix64 finaliser
   z += 0x9E3779B97F4A7C15ull;
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -413,6 +424,11 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   const int64_t n16 = (int64_t)(bytes / 16);
   const unsigned grid = (unsigned)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
   hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, s, reinterpret_cast<uint4*>(p), n16);
+}
+
+void launch_copy(const CopyItem* items, int64_t nitems, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
 }
 
 void launch_sketch(const SketchItem* items, int64_t nitems, char* state, hipStream_t s) {
