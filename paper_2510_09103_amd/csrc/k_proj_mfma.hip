@@ -355,7 +355,7 @@ struct StripeTail {
   int nmat;                          // 2, or 1: only the first thin product (X' = X and B2 = B1 folded into c1)
 };
 
-// As stripe_pass1, for the 256 rows behind rG: leaves P in LDS at smem as [256][R + 4] fp32 (the caller has to
+// As stripe_pass1, for the 256 rows behind rG: leaves P in LDS at smem as [256][R + 4] ([256][R + 1] with TRA) fp32 (the caller has to
 // __syncthreads() before reading it); rsum (LDS, 256 floats, or null) receives the sums of squares of the rows.
 // With a tail, the thin products run as further rounds of the same pipeline: the streaming waves scale a 64-column
 // chunk of X by its coefficient and stage it as two bf16 tiles (hi, lo), the matrix-core waves copy the matching
@@ -376,7 +376,8 @@ constexpr int TS = 4 * BK + 32;      // LDS row stride (elements) of a transpose
 template <int RT, bool TRA>
 __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, const StripeSrc& src, const char* __restrict__ Qf,
                                                 float* rsum, const StripeTail& tl) {
-  constexpr int QF = Pass1x2<RT>::QF, G_TILE = Pass1x2<RT>::G_TILE, PS = Pass1x2<RT>::PS, D1 = Pass1x2<RT>::D1;
+  constexpr int QF = Pass1x2<RT>::QF, G_TILE = Pass1x2<RT>::G_TILE, D1 = Pass1x2<RT>::D1;
+  constexpr int PS = TRA ? 32 * RT + 1 : Pass1x2<RT>::PS;   // row stride of P (see stripe_kernel)
   static_assert(BK * TS * 2 <= G_TILE, "a transposed-read tile fits the tile buffer");
   constexpr int TPW = RT;                                 // 8 row tiles x RT rank tiles over 8 waves
   const int tid = threadIdx.x, lane = tid & 63;
@@ -1394,7 +1395,9 @@ __global__ __launch_bounds__(256) void qt_image_kernel(const ImgItem* __restrict
 template <int RT, bool TRA>
 __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restrict__ items,
                                                        const StripeProb* __restrict__ probs, Bases bs) {
-  constexpr int R = 32 * RT, PS = Pass1x2<RT>::PS, ROWS = Pass1x2<RT>::ROWS;
+  // row stride of P in LDS: with the transposed store the lanes of a wave walk down a column of P, which an odd
+  // stride spreads over all banks
+  constexpr int R = 32 * RT, PS = TRA ? R + 1 : Pass1x2<RT>::PS, ROWS = Pass1x2<RT>::ROWS;
   constexpr int SMEM = Pass1x2<RT>::BYTES > Pass1x2<RT>::P_BYTES ? Pass1x2<RT>::BYTES : Pass1x2<RT>::P_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
   const StripeItem item = items[blockIdx.x];
@@ -1483,19 +1486,32 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
       if (emit) *reinterpret_cast<float4*>(Ps + row * PS + c4) = make_float4(x[0], x[1], x[2], x[3]);
     }
   } else {
-    // Out[a][row0 + j] = P[j][a]: lanes run along j, so the global stores are contiguous
-#pragma unroll 4
-    for (int i = 0; i < (ROWS * R) / NT; ++i) {
-      const int id = tid + NT * i, j = id % ROWS, a = id / ROWS;
-      float v = gs * Ps[j * PS + a];
-      if (row0 + j < M && a < r) {
-        const int64_t at = (int64_t)a * M + row0 + j;
-        if (Xc) v += Xc[at];
-        Out[at] = v;
-      } else {
-        v = 0.f;
+    // Out[a][row0 + j] = P[j][a], four consecutive j (16 bytes) of one a per access.  A wave covers 4 values of a x 64
+    // values of j: 256 contiguous bytes per a in memory, and with the odd row stride of P its 64 lanes fall on 64
+    // different LDS banks.  The elements of the old factor are requested together, on clamped (valid) addresses,
+    // before any of them is used.  (M is a multiple of 8 here: the stripes take only such blocks.)
+    constexpr int NI = (ROWS / 4) * R / NT;
+    const int j4 = 64 * ((tid >> 6) & 3) + 4 * (tid & 15), a0 = 4 * (tid >> 8) + ((tid >> 4) & 3);
+    const bool jok = row0 + j4 < M;
+    const int64_t col = row0 + (jok ? j4 : 0);        // columns of the factor that exist
+    float4 xo[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) xo[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (Xc) {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int a = a0 + 4 * (NT / 256) * i;
+        xo[i] = *reinterpret_cast<const float4*>(Xc + (int64_t)(a < r ? a : 0) * M + col);
       }
-      if (emit) Ps[j * PS + a] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int a = a0 + 4 * (NT / 256) * i;
+      float* ps = Ps + j4 * PS + a;
+      float4 v = make_float4(gs * ps[0] + xo[i].x, gs * ps[PS] + xo[i].y, gs * ps[2 * PS] + xo[i].z, gs * ps[3 * PS] + xo[i].w);
+      if (jok && a < r) *reinterpret_cast<float4*>(Out + (int64_t)a * M + col) = v;
+      else v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (emit) { ps[0] = v.x; ps[PS] = v.y; ps[2 * PS] = v.z; ps[3 * PS] = v.w; }
     }
   }
   if (emit) __syncthreads();
@@ -1506,10 +1522,10 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
     for (int p = tid; p < ROWS * pr; p += NT) {
       const int q = p % pr, j = p / pr;
       if (row0 + (j & ~(BK - 1)) >= M) continue;   // the image ends with the chunk that holds row M - 1
-      const float4 u = *reinterpret_cast<const float4*>(Ps + j * PS + 8 * q), v = *reinterpret_cast<const float4*>(Ps + j * PS + 8 * q + 4);
+      const float* src = Ps + j * PS + 8 * q;
       uint32_t h[4], l[4];
-      split_pair(u.x, u.y, h[0], l[0]); split_pair(u.z, u.w, h[1], l[1]);
-      split_pair(v.x, v.y, h[2], l[2]); split_pair(v.z, v.w, h[3], l[3]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) split_pair(src[2 * e], src[2 * e + 1], h[e], l[e]);
       const int jc = j & (BK - 1);
       char* dst = bs.ws + P.off_timg + (int64_t)((row0 + j) / BK) * T64 + ((int64_t)jc * pr + timg_piece(R, jc, q)) * 16;
       *reinterpret_cast<uint4*>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
