@@ -356,7 +356,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         sp.a = G.ref; sp.transpose_out = 0; sp.off_img = iR;
         if (e == 0 && v_fusable(b)) { sp.v_rows = b.v_group_rows; sp.off_v = L.sv; sp.beta2 = hp.beta2; }
         sp.x_cur = Lc.ref; sp.x_prev = Lp.ref; sp.off_b1 = L.wB[0]; sp.off_b2 = L.wB[1]; sp.off_out = Ln.ref.off;
-        sp.off_next = iLn; sp.off_timg = -1;
+        sp.off_next = iLn; sp.off_timg = -1; sp.off_timg_prev = -1;
         c->sprob.h.push_back(sp);
         swork[6 * e + 2 * cls].push_back(StripeWork{(int)c->sprob.h.size() - 1, m, n});
         sp.M = n; sp.K = m; sp.transpose_out = 1; sp.off_img = iL;
@@ -364,6 +364,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         sp.x_cur = Rc.ref; sp.x_prev = Rp.ref; sp.off_b1 = L.wB[2]; sp.off_b2 = L.wB[3]; sp.off_out = Rn.ref.off;
         sp.off_next = iRn;
         sp.off_timg = e + 1 == n_eff ? L.wT2 : -1;     // the last iteration leaves the image of R_t^T for the fused update
+        sp.off_timg_prev = (e == 0 && hp.bias_correction) ? L.wT1 : -1;   // ... the first one that of R_{t-1}^T
         c->sprob.h.push_back(sp);
         swork[6 * e + 2 * cls + 1].push_back(StripeWork{(int)c->sprob.h.size() - 1, n, m});
       } else {
@@ -411,7 +412,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       d.l1 = Lp.ref; d.l2 = Lc.ref; d.q1 = Rp.ref; d.q2 = Rc.ref; d.off_img1 = L.wT1; d.off_img2 = L.wT2; d.off_v = L.sv;
       c->rub.h.push_back(d);
       for (int ch = 0; ch < (n + 63) / 64; ++ch) {
-        if (hp.bias_correction) c->qt.h.push_back(ImgItem{Rp, r, n, ch, d.rc, L.wT1});
+        if (hp.bias_correction && !(stripe_ok(b) && n_eff > 0)) c->qt.h.push_back(ImgItem{Rp, r, n, ch, d.rc, L.wT1});
         if (!(stripe_ok(b) && n_eff > 0)) c->qt.h.push_back(ImgItem{Rc, r, n, ch, d.rc, L.wT2});   // else: written by the stripes
       }
     } else {

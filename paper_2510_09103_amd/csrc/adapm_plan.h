@@ -164,6 +164,7 @@ struct StripeProb {
   int64_t off_next;        // >= 0: workspace offset where the fragment image of the new factor goes (its chunks run along M)
   int64_t off_timg;        // >= 0 (transposed output only): workspace offset where the image of the new factor's transpose
                            // goes ([hi|lo][column][R] per 64-column chunk, what the fused update reads)
+  int64_t off_timg_prev;   // >= 0 (transposed output, first GD iteration only): the same image of the factor the iteration starts from
   float c1, c2, cp;
   // v_rows > 0 (A is the gradient itself): the blockwise second moment of the block is finished here,
   // v_g <- beta2 v_g + (1 - beta2) mean of g^2 over the v_rows rows of group g (state offset off_v, one float per group)

@@ -353,6 +353,8 @@ struct StripeTail {
   const char* img2;
   float c1, c2, cp;
   int nmat;                          // 2, or 1: only the first thin product (X' = X and B2 = B1 folded into c1)
+  char* timg;                        // non-null (nmat = 1, sj = 1): also write X (unscaled) as the image of a transposed factor,
+                                     // [hi|lo][row of the stripe][R] per 64 rows, for the fused update; points at the stripe's first chunk
 };
 
 // As stripe_pass1, for the 256 rows behind rG: leaves P in LDS at smem as [256][R + 4] ([256][R + 1] with TRA) fp32 (the caller has to
@@ -602,6 +604,27 @@ __device__ __forceinline__ void stripe_pass1_x2(unsigned char* smem, const Strip
           }
           *reinterpret_cast<uint4*>(t_hi + row * GS + c8) = make_uint4(h[0], h[1], h[2], h[3]);
           *reinterpret_cast<uint4*>(t_lo + row * GS + c8) = make_uint4(l[0], l[1], l[2], l[3]);
+        }
+        if (TRA && tl.timg) {
+          // the thread holds 8 consecutive columns of X for one row of the stripe: one 16-byte piece of that row of
+          // the transposed image (rows beyond the stripe's end inside its last 64-row chunk are written as zeros)
+          constexpr int pr = 32 * RT / 8;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int row = (t512 >> 3) + 64 * i;
+            if (k0 / 8 < pr && (row & ~(BK - 1)) < tl.rows) {
+              uint32_t uh[4], ul[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                split_pair((row < tl.rows && k0 + 2 * e < tl.r) ? raw[i][2 * e] : 0.f,
+                           (row < tl.rows && k0 + 2 * e + 1 < tl.r) ? raw[i][2 * e + 1] : 0.f, uh[e], ul[e]);
+              const int jc = row & (BK - 1);
+              char* dst = tl.timg + (int64_t)(row / BK) * timg_chunk_bytes(32 * RT) +
+                          ((int64_t)jc * pr + timg_piece(32 * RT, jc, k0 / 8)) * 16;
+              *reinterpret_cast<uint4*>(dst) = make_uint4(uh[0], uh[1], uh[2], uh[3]);
+              *reinterpret_cast<uint4*>(dst + (int64_t)BK * pr * 16) = make_uint4(ul[0], ul[1], ul[2], ul[3]);
+            }
+          }
         }
         wg_barrier();
         if (q + 1 < nq) fetch_x(q + 1);
@@ -1436,6 +1459,8 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
     // first GD iteration: the factor is still the one of the previous step and the two r x r matrices are one and the
     // same product (the Gram kernel writes it to both places), so the two thin products fold into one
     if (P.x_cur.space == P.x_prev.space && P.x_cur.off == P.x_prev.off) { tl.c1 += tl.c2; tl.nmat = 1; }
+    if (TRA && tl.nmat == 1 && P.off_timg_prev >= 0)
+      tl.timg = bs.ws + P.off_timg_prev + (int64_t)(row0 / BK) * timg_chunk_bytes(R);
     gs = 1.f;
   }
   stripe_pass1_x2<RT, TRA>(smem, src, bs.ws + P.off_img, (!TRA && P.v_rows > 0) ? rsum : nullptr, tl);
