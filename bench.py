@@ -5,10 +5,12 @@ A "step" is one pass of the whole hot path (blockwise v statistics, full-momentu
 low-rank momentum with bias correction, fused parameter update) over every block of the
 GPT-2-1.5B-shaped table, on synthetic low-rank-plus-tail gradients already resident in HBM.
 
-Default: refresh period T = 100 (the paper's experimental setting), K = 100 timed steps after
-W = 3 warm-up steps, so the timed region holds exactly one step that runs Alg. 2 and 99 steps
-with R held: `value` is the T-amortised throughput.  The literal Alg. 1 (T = 1, Alg. 2 every
-step) is timed separately and reported in `literal_T1`.
+Default: refresh period T = 100 (the paper's experimental setting).  Whatever --steps K and
+--warmup W are, the K timed steps open with a step that runs Alg. 2 (its step number is put on
+the refresh grid) and continue with steps that hold R; every step is bracketed by HIP events,
+and `value` is the T-amortised throughput params / ((t_refresh + (T-1) t_held) / T).  The
+literal Alg. 1 (T = 1, Alg. 2 every step: the only reading the paper pins) is timed separately,
+with its own roofline block, and reported in `literal_T1`.
 
 Prints ONE JSON line.
 """
@@ -120,66 +122,130 @@ def main():
         return AdaPM(wl.blocks, make_hparams(beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, clip=wl.clip, K=wl.K, T=T),
                      device=dev, grad_clip=args.grad_clip)
 
-    def run(opt, t0, nsteps):
-        for i in range(nsteps):
-            t = t0 + i
+    def schedule(T, n, after):
+        """Step numbers of a region of n steps: with T > 1 the region opens with a step that runs Alg. 2 (the first
+        one on the refresh grid after `after`) and continues with steps that hold R, so that both kinds are timed
+        whatever n is; with T = 1 every step runs Alg. 2.  The library takes the step number as an argument."""
+        if T <= 1:
+            return list(range(after + 1, after + n + 1))
+        first = ((after + T - 1) // T) * T + 1
+        return [first + i for i in range(n)]
+
+    def timed(opt, steps):
+        """Run the steps back to back; returns (wall ms of the whole region, per-step device ms from HIP events
+        recorded between the steps on the stream the library launches on: torch's current stream)."""
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(steps) + 1)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i, t in enumerate(steps):
+            ev[i].record()
             opt.step(params, grad_sets[t % len(grad_sets)], t, lr)
+        ev[-1].record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        return wall, [ev[i].elapsed_time(ev[i + 1]) for i in range(len(steps))]
 
-    opt = make(args.T)
-    K, W = args.steps, args.warmup
-    run(opt, 1, W)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t_host0 = time.perf_counter()
-    e0.record()
-    run(opt, W + 1, K)
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t_host0) * 1e3
-    dev_ms = e0.elapsed_time(e1)
-    ms_per_step = wall_ms / K
-    n_refresh = sum(1 for t in range(W + 1, W + K + 1) if args.T <= 1 or (t - 1) % args.T == 0)
-
-    # per-kernel durations over an identical region, from HIP events around every launch
-    B.adapm_profile_enable(opt.ctx, True)
-    run(opt, W + K + 1, K)
-    torch.cuda.synchronize()
-    prof = B.adapm_profile_read(opt.ctx)
-    B.adapm_profile_enable(opt.ctx, False)
-    n_refresh_prof = sum(1 for t in range(W + K + 1, W + 2 * K + 1) if args.T <= 1 or (t - 1) % args.T == 0)
-    kernels = {k: {"avg_ms": v[0] / v[1], "launches": v[1], "total_ms": v[0]} for k, v in prof.items()}
-    dominant = max(kernels, key=lambda k: kernels[k]["total_ms"])
+    def kernel_profile(opt, steps, T):
+        """Per-kernel durations from HIP events that the library records around every launch, over the same kind of
+        region.  Returns {label: {avg_ms, launches, total_ms, per_step_ms}}: per_step_ms is the kernel's share of a
+        T-amortised step (kernels of steps that run Alg. 2 weigh 1/T)."""
+        B.adapm_profile_enable(opt.ctx, True)
+        out = {}
+        n_ref = sum(1 for t in steps if T <= 1 or (t - 1) % T == 0)
+        n_held = len(steps) - n_ref
+        for kind, sel in (("refresh", [t for t in steps if T <= 1 or (t - 1) % T == 0]),
+                          ("held", [t for t in steps if not (T <= 1 or (t - 1) % T == 0)])):
+            if not sel:
+                continue
+            for t in sel:
+                opt.step(params, grad_sets[t % len(grad_sets)], t, lr)
+            torch.cuda.synchronize()
+            w = (1.0 / T if T > 1 else 1.0) if kind == "refresh" else (T - 1.0) / T
+            for k, (ms, cnt) in B.adapm_profile_read(opt.ctx).items():
+                d = out.setdefault(k, {"total_ms": 0.0, "launches": 0, "per_step_ms": 0.0})
+                d["total_ms"] += ms
+                d["launches"] += cnt
+                d["per_step_ms"] += w * ms / len(sel)
+        B.adapm_profile_enable(opt.ctx, False)
+        for d in out.values():
+            d["avg_ms"] = d["total_ms"] / d["launches"]
+        return out, n_ref, n_held
 
     lr_blocks = [b for b in wl.blocks if b.mom == "lowrank"]
     full_blocks = [b for b in wl.blocks if b.mom != "lowrank"]
-    if dominant.startswith("fused_project"):
-        rank = int(dominant.split("_r")[-1])
-        # the kernel of a rank class serves every rank up to it (32, 64, 128)
-        alg = sum(block_bytes(b, False) for b in lr_blocks if min(c for c in (32, 64, 128) if b.rank <= c) == rank)
-        roof = {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "achieved": alg / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9}
-    elif dominant == "update_full":
-        alg = sum(block_bytes(b, False) for b in full_blocks)
-        roof = {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "achieved": alg / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9}
-    else:
-        # a contraction kernel of Alg. 2: flops of one launch (products counted once, not per bf16 split)
-        per_launch = B.adapm_algorithmic_flops(opt.ctx, True) / max(1, kernels[dominant]["launches"] // max(1, n_refresh_prof))
-        roof = {"bound": "mfma", "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "achieved": per_launch / (kernels[dominant]["avg_ms"] * 1e-3) / 1e12}
-    traffic = None
+
+    def rank_class(b):
+        return min(c for c in (32, 64, 128) if b.rank <= c) if b.rank <= 128 else 0
+
+    def roofline_of(label, k, refresh_step):
+        """Roofline block of one kernel class: algorithmic bytes (HBM-bound kernels) or flops (the contractions of
+        Alg. 2) of ONE launch over its live average duration."""
+        roof = None
+        if label.startswith("fused_project") or label.startswith("fused_refresh_update"):
+            rank = int(label.split("_r")[-1])
+            alg = sum(block_bytes(b, refresh_step) for b in lr_blocks if rank_class(b) == rank)
+            if label.startswith("fused_refresh_update"):
+                # the update after Alg. 2 reads G, W, v and both factor pairs and writes W: the factors' own write is
+                # the stripes' business
+                alg = sum(b.rows * b.cols * 6 + 8 * (b.rows + b.cols) * b.rank for b in lr_blocks if rank_class(b) == rank)
+            roof = {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", "achieved": alg / (k["avg_ms"] * 1e-3) / 1e9}
+        elif label in ("update_full", "update_full_grouped"):
+            alg = sum(block_bytes(b, False) for b in full_blocks)
+            roof = {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", "achieved": alg / (k["avg_ms"] * 1e-3) / 1e9}
+        elif label.startswith("alg2_stripe_step"):
+            # one launch = one of the two streaming products of a GD iteration over every block of a rank class
+            # (G R^T or G^T L: 2 m n r flop) and the thin products of the GD step behind it (2 x 2 d r^2, d = m or n)
+            rank = int(label.split("_r")[-1])
+            side_L = "_L_" in label
+            blocks = [b for b in lr_blocks if rank_class(b) == rank]
+            alg = sum(2.0 * b.rows * b.cols * b.rank + 4.0 * (b.rows if side_L else b.cols) * b.rank ** 2 for b in blocks)
+            issued = sum(2 * 2.0 * b.rows * b.cols * rank + 3 * 4.0 * (b.rows if side_L else b.cols) * rank ** 2 for b in blocks)
+            roof = {"bound": "mfma", "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "achieved": alg / (k["avg_ms"] * 1e-3) / 1e12,
+                    "issued_TFLOPs": issued / (k["avg_ms"] * 1e-3) / 1e12,
+                    "issued_frac": issued / (k["avg_ms"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "hbm_GBs": sum(b.rows * b.cols * 2 + 8 * (b.rows if side_L else b.cols) * b.rank for b in blocks)
+                               / (k["avg_ms"] * 1e-3) / 1e9,
+                    "note": "achieved = flops of the mathematical products; issued = matrix-core work with every fp32 "
+                            "operand as a (hi, lo) bf16 pair (2 instructions per product of G, 3 per thin product) "
+                            "at the padded rank class"}
+        if roof is None:
+            return None
+        roof.update(kernel=label, frac=roof["achieved"] / roof["peak"], avg_ms=k["avg_ms"], traffic=None)
+        return roof
+
+    opt = make(args.T)
+    K, W = args.steps, args.warmup
+    for t in range(1, W + 1):
+        opt.step(params, grad_sets[t % len(grad_sets)], t, lr)
+    steps = schedule(args.T, K, W)
+    wall_ms, per_step = timed(opt, steps)
+    is_ref = [args.T <= 1 or (t - 1) % args.T == 0 for t in steps]
+    n_refresh = sum(is_ref)
+    t_ref = sum(d for d, r in zip(per_step, is_ref) if r) / max(n_refresh, 1)
+    t_held = sum(d for d, r in zip(per_step, is_ref) if not r) / max(K - n_refresh, 1) if K > n_refresh else t_ref
+    # T-amortised step: one step in T runs Alg. 2 (with the re-expression of the factors), T - 1 hold R
+    ms_per_step = t_ref if args.T <= 1 else (t_ref + (args.T - 1) * t_held) / args.T
+
+    kernels, n_refresh_prof, _ = kernel_profile(opt, schedule(args.T, K, steps[-1]), args.T)
+    dominant = max(kernels, key=lambda k: kernels[k]["per_step_ms"])
+    roof = roofline_of(dominant, kernels[dominant], args.T <= 1)
+    if roof is None:
+        roof = {"bound": "alu", "kernel": dominant, "avg_ms": kernels[dominant]["avg_ms"], "achieved": None, "peak": None,
+                "unit": None, "frac": None, "traffic": None}
     tfile = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
-    if args.workload == "gpt2_1p5b" and args.T == 100 and args.rank == 0 and os.path.exists(tfile):
+    roof["traffic_source"] = None
+    if args.rank == 0 and os.path.exists(tfile):
         for line in open(tfile):
             parts = line.split()
-            if len(parts) == 2 and parts[0] == dominant:
-                traffic = float(parts[1])
-    roof.update(kernel=dominant, frac=roof["achieved"] / roof["peak"], traffic=traffic,
-                avg_ms=kernels[dominant]["avg_ms"])
+            if len(parts) == 4 and parts[0] == args.workload and parts[1] == f"T{args.T}" and parts[2] == dominant:
+                roof["traffic"] = float(parts[3])
+                roof["traffic_source"] = ("profiles/hbm_traffic_per_launch.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
+                                          "this command on an earlier run, not of this run")
 
     bytes_refresh = B.adapm_algorithmic_bytes(opt.ctx, True)
     bytes_held = B.adapm_algorithmic_bytes(opt.ctx, False)
-    step_bytes = (n_refresh * bytes_refresh + (K - n_refresh) * bytes_held) / K
+    step_bytes = bytes_refresh if args.T <= 1 else (bytes_refresh + (args.T - 1) * bytes_held) / args.T
     launches_held = B.adapm_last_launch_count(opt.ctx)
     state_bytes, ws_bytes = opt.state_bytes, opt.workspace_bytes
     opt.close()
@@ -189,21 +255,30 @@ def main():
     literal = None
     if not args.no_literal and args.T != 1:
         o1 = make(1)
-        run(o1, 1, 1)
-        torch.cuda.synchronize()
+        for t in range(1, 4):                      # three warm-up steps
+            o1.step(params, grad_sets[t % len(grad_sets)], t, lr)
         n1 = 5
-        t0 = time.perf_counter()
-        run(o1, 2, n1)
-        torch.cuda.synchronize()
-        ms1 = (time.perf_counter() - t0) * 1e3 / n1
+        wall1, per1 = timed(o1, schedule(1, n1, 3))
+        ms1 = sum(per1) / n1
+        k1, _, _ = kernel_profile(o1, schedule(1, 3, 3 + n1), 1)
+        dom1 = max(k1, key=lambda k: k1[k]["per_step_ms"])
         fl = B.adapm_algorithmic_flops(o1.ctx, True)
-        literal = {"ms_per_step": ms1, "params_per_s": wl.numel / (ms1 * 1e-3), "steps": n1,
-                   "contraction_TFLOPs": fl / (ms1 * 1e-3) / 1e12, "launches_per_step": B.adapm_last_launch_count(o1.ctx),
-                   "algorithmic_GBs": B.adapm_algorithmic_bytes(o1.ctx, True) / (ms1 * 1e-3) / 1e9}
+        stripe_ms = sum(v["per_step_ms"] for k, v in k1.items() if k.startswith("alg2_stripe_step"))
+        literal = {"ms_per_step": ms1, "wall_ms_per_step": wall1 / n1, "params_per_s": wl.numel / (ms1 * 1e-3), "steps": n1,
+                   "warmup": 3, "contraction_TFLOPs": fl / (ms1 * 1e-3) / 1e12,
+                   "launches_per_step": B.adapm_last_launch_count(o1.ctx),
+                   "algorithmic_GBs": B.adapm_algorithmic_bytes(o1.ctx, True) / (ms1 * 1e-3) / 1e9,
+                   "hbm_frac_whole_step": B.adapm_algorithmic_bytes(o1.ctx, True) / (ms1 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                   "mfma_frac_whole_step": fl / (ms1 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                   "roofline": roofline_of(dom1, k1[dom1], True),
+                   "kernels_ms_per_step": {k: v["per_step_ms"] for k, v in k1.items()},
+                   "stripe_products_ms_per_step": stripe_ms,
+                   "workspace_bytes": o1.workspace_bytes}
         o1.close()
         del o1
         torch.cuda.empty_cache()
 
+    adam_bytes = 8 * wl.numel
     out = {
         "metric": "AdaPM optimizer-step throughput at GPT-2-1.5B shape" if args.workload == "gpt2_1p5b"
                   else f"AdaPM optimizer-step throughput ({args.workload})",
@@ -215,15 +290,26 @@ def main():
                           "fp32 operand as a (hi, lo) bf16 pair, fp32 accumulation",
         "data": "synthetic",
         "config": {"workload": args.workload, "blocks": len(wl.blocks), "params": wl.numel, "refresh_period_T": args.T,
-                   "refresh_steps_in_timed_region": n_refresh, "rank": max([b.rank for b in wl.blocks] + [0]),
+                   "refresh_steps_in_timed_region": n_refresh, "timed_step_numbers": [steps[0], steps[-1]],
+                   "rank": max([b.rank for b in wl.blocks] + [0]),
                    "second_moment": "blockwise" if any(b.v_mode != "element" for b in wl.blocks) else "element",
                    "grad_sets_rotated": len(grad_sets), "global_grad_clip": args.grad_clip},
-        "device_ms_per_step": dev_ms / K,
+        "value_definition": ("T-amortised step: (t_refresh + (T-1) t_held) / T, both legs timed by HIP events inside the "
+                             "timed region (its first step runs Alg. 2, the others hold R)" if args.T > 1 else
+                             "Alg. 1 as printed: Alg. 2 in every step"),
+        "reading_note": ("the step that holds R between two runs of Alg. 2 is this build's reading of the paper's "
+                         "undefined 'update frequency T'; the paper pins only T = 1 (literal_T1)" if args.T > 1 else None),
+        "refresh_step_ms": t_ref, "held_step_ms": t_held if args.T > 1 else None,
+        "timed_region_wall_ms_per_step": wall_ms / K,
         "achieved_algorithmic_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "algorithmic_bytes_per_step": step_bytes,
         "hbm_frac_whole_step": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "launches_per_held_step": launches_held,
-        "state_bytes": state_bytes, "workspace_bytes": ws_bytes,
+        "memory": {"state_bytes": state_bytes, "workspace_bytes": ws_bytes, "state_plus_workspace_bytes": state_bytes + ws_bytes,
+                   "adam_two_moments_bytes": adam_bytes, "state_over_adam": state_bytes / adam_bytes,
+                   "state_plus_workspace_over_adam": (state_bytes + ws_bytes) / adam_bytes,
+                   "paper_table2_note": "Table 2 (GPT-2-1.5B, the paper's own partition): Adam 12.48 G, AdaPM 6.98 G, "
+                                        "AdaPM-mini 0.74 G; this workload is BASELINE's config (r = 128 on every matrix)"},
         "roofline": roof,
         "kernels": kernels,
         "literal_T1": literal,

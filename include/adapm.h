@@ -15,8 +15,13 @@
  *    plan plus small device-side tables, released by adapm_destroy).
  *  - A block is one parameter tensor, row-major rows x cols, rows = output units;
  *    1-D tensors use cols = 1.  Block base pointers must be 16-byte aligned.
- *  - adapm_step is asynchronous on the given HIP stream, allocates nothing, and
- *    updates params and state in place; grads are read-only.
+ *  - adapm_step is asynchronous on the given HIP stream and updates params and state in
+ *    place; grads are read-only.  It allocates nothing once adapm_state_init has run on
+ *    the context (which places the launch plan on the device), unless per-launch timing
+ *    is on, and it never waits for the device: the pointer tables live on the device in a
+ *    few slots keyed by their contents (a caller that rotates up to four sets of tensors
+ *    uploads each once; a new set is copied on the step's stream).  Issue the steps of one
+ *    context on one stream, or order the streams yourself.
  *  - Functions return ADAPM_OK (0) or a negative status; nothing aborts or throws.
  *    adapm_last_error() gives a thread-local message for the last failure.
  *  - bf16 tensors are IEEE-like bfloat16 bit patterns; stores round to nearest even.
@@ -76,14 +81,17 @@ typedef struct {
   int32_t refresh_iters_K;    /* iterations of Alg. 2; 5 (App. B) */
   int32_t refresh_period_T;   /* 1 = Alg. 2 every step (Alg. 1 verbatim).  T > 1: Alg. 2 on steps with
                                  (step-1) % T == 0, followed by a product-preserving orthonormalisation
-                                 of R; on other steps L is the least-squares fit with R held. */
+                                 of R; on other steps L is the least-squares fit with R held.  A block
+                                 whose R R^T is not positive definite at that point (R has lost rank)
+                                 keeps its (L, R) as Alg. 2 left them. */
   int32_t bias_correction;    /* 1 = eq. 4; 0 = ablation of Sec. 5.1.2 (use L_t R_t as the momentum) */
   int32_t contraction;        /* adapm_contract_t */
   int32_t refresh_normalise;  /* 0 = Alg. 2 as printed.  1 (an option beyond the paper): every iteration of Alg. 2
                                  divides its step size by max(||R R^T||_F, ||L^T L||_F), which makes the
                                  iteration invariant under a rescaling of the gradients (as printed it
                                  diverges for large and stalls for small gradients) */
-  uint64_t seed;              /* seeded start R_0 of the low-rank factors; 0 = literal all-zero start */
+  uint64_t seed;              /* seeded start R_0 of the low-rank factors; 0 = literal all-zero start (the factors then
+                                 stay zero for ever; only with refresh_period_T = 1, else ADAPM_EINVAL) */
 } adapm_hparams_t;
 
 typedef struct adapm_ctx adapm_ctx;
@@ -117,8 +125,9 @@ adapm_status_t adapm_state_offsets(const adapm_ctx* ctx, int64_t block, size_t* 
 adapm_status_t adapm_state_init(adapm_ctx* ctx, void* state_dev, void* stream);
 
 /* Tell the library that the caller has overwritten the state buffer (e.g. restored a
- * checkpoint into it): anything derived from the old contents is dropped.  Not needed for
- * a fresh context or after adapm_state_init. */
+ * checkpoint into it): anything derived from the old contents is dropped, and the state is
+ * taken to come from a run with the same hyper-parameters (with refresh_period_T > 1: R with
+ * orthonormal rows).  Not needed after adapm_state_init. */
 adapm_status_t adapm_state_loaded(adapm_ctx* ctx);
 
 /* One optimizer step (Alg. 1) over all blocks.
@@ -126,7 +135,9 @@ adapm_status_t adapm_state_loaded(adapm_ctx* ctx);
  *  state_dev: adapm_state_bytes() bytes; workspace_dev: adapm_workspace_bytes() bytes
  *  (may be NULL if that size is 0); step: 1-based iteration count t; lr: eta_t.
  * Checks step >= 1, non-null and 16-byte aligned pointers; everything else was
- * validated at init. */
+ * validated at init.  With refresh_period_T > 1, a step that holds R on a state whose R has
+ * not been orthonormalised (no step that runs Alg. 2 since adapm_state_init, and no
+ * adapm_state_loaded) is ADAPM_ESTATE. */
 adapm_status_t adapm_step(adapm_ctx* ctx, void* const* params_dev, const void* const* grads_dev,
                           void* state_dev, void* workspace_dev, int64_t step, float lr, void* stream);
 

@@ -33,13 +33,21 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if out.returncode != 0:
         raise RuntimeError("link failed:\n" + out.stdout)
-    # stand-alone bandwidth measurement (no part of the library): ./hbm_ceiling prints what HBM
-    # delivers for the access patterns of the fused kernels
-    cmd = [hipcc, *FLAGS, os.path.join(CSRC, "hbm_ceiling.hip"), "-o", os.path.join(HERE, "hbm_ceiling")]
+    return LIB
+
+
+def build_calibration() -> str:
+    """The stand-alone bandwidth measurement csrc/hbm_ceiling.hip (no part of the library, not built by build()):
+    plain read / write / read-modify-write kernels of known size.  ./hbm_ceiling prints what HBM delivers for the
+    access patterns of the fused kernels; the same kernels under rocprofv3 --pmc give the factors that turn
+    FETCH_SIZE / WRITE_SIZE into bytes."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    exe = os.path.join(HERE, "hbm_ceiling")
+    cmd = [hipcc, *FLAGS, os.path.join(CSRC, "hbm_ceiling.hip"), "-o", exe]
     out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if out.returncode != 0:
         raise RuntimeError("hipcc failed on hbm_ceiling.hip:\n" + out.stdout)
-    return LIB
+    return exe
 
 
 def _drain(procs):
@@ -55,4 +63,4 @@ def _drain(procs):
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build_calibration() if "--calibration" in sys.argv else build(verbose=True))

@@ -137,10 +137,22 @@ struct adapm_ctx {
   bool uploaded = false;
   int device = -1;
   char* arena = nullptr;
-  void** d_ptrs = nullptr;              // [2 * nblocks]: params then grads
-  void** h_stage = nullptr;             // pinned staging of the same
-  std::vector<void*> cached;            // last uploaded pointers
-  hipEvent_t stage_free = nullptr;
+  // Pointer tables ([2 * nblocks]: params then grads) live on the device in a few slots, each with a pinned host
+  // copy.  A step whose pointers equal a slot's reuses it (no copy: a caller that rotates two or three sets of
+  // gradient tensors uploads each set once); otherwise the least recently used slot is rewritten by a copy on the
+  // step's stream.  Its pinned copy may only be overwritten once the copy that last read it has finished: that is
+  // asked of the slot's event without blocking, and waited for only in the (pathological) case that a copy issued
+  // NSLOT - 1 uploads ago is still pending.
+  static constexpr int NSLOT = 4;
+  struct PtrSlot {
+    void** d = nullptr;
+    void** h = nullptr;
+    hipEvent_t copied = nullptr;
+    bool valid = false;
+    uint64_t last_use = 0;
+  } slot[NSLOT];
+  uint64_t use_clock = 0;
+  bool gauge_ok = false;                // T > 1: the state's R has orthonormal rows (a step that ran Alg. 2, or adapm_state_loaded)
   int64_t last_launches = 0;
   int n_lowrank = 0;
   const void* split_ws = nullptr;       // workspace that holds valid bf16 copies of Q (T > 1, MFMA path) ...
@@ -196,6 +208,10 @@ adapm_status_t validate(const adapm_block_t* t, int64_t n, const adapm_hparams_t
   if (!(hp->eps >= 0.f) || !(hp->clip > 0.f)) return fail(ADAPM_EINVAL, "eps must be >= 0 and clip > 0");
   if (hp->refresh_iters_K < 1 || hp->refresh_iters_K > 1024) return fail(ADAPM_EINVAL, "refresh_iters_K out of range");
   if (hp->refresh_period_T < 1) return fail(ADAPM_EINVAL, "refresh_period_T must be >= 1");
+  // the literal zero start never leaves zero (both gradients of Alg. 2 vanish there), and R = 0 has no orthonormal
+  // re-expression: the step with R held is undefined for it
+  if (hp->seed == 0 && hp->refresh_period_T > 1)
+    return fail(ADAPM_EINVAL, "seed = 0 (the all-zero start of Alg. 1) needs refresh_period_T = 1");
   if (hp->adam_debias != 0 && hp->adam_debias != 1) return fail(ADAPM_EINVAL, "adam_debias must be 0 or 1");
   if (hp->bias_correction != 0 && hp->bias_correction != 1) return fail(ADAPM_EINVAL, "bias_correction must be 0 or 1");
   if (hp->refresh_normalise != 0 && hp->refresh_normalise != 1) return fail(ADAPM_EINVAL, "refresh_normalise must be 0 or 1");
@@ -787,6 +803,7 @@ void build_plan(adapm_ctx* c) {
 template <class T>
 size_t bytes_of(const std::vector<T>& v) { return align_up(v.size() * sizeof(T)); }
 
+
 adapm_status_t ensure_uploaded(adapm_ctx* c) {
   if (c->uploaded) return ADAPM_OK;
   int dev = -1;
@@ -794,7 +811,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   const size_t nb = c->table.size();
   size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
                  bytes_of(c->sprob.h) + bytes_of(c->cp.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) + bytes_of(c->grp.h) +
-                 align_up(2 * nb * sizeof(void*));
+                 adapm_ctx::NSLOT * align_up(2 * nb * sizeof(void*));
   for (int i = 0; i < 6; ++i) total += bytes_of(c->ru[i].h);
   for (auto& l : c->img) total += bytes_of(l.h);
   for (auto& l : c->sit) total += bytes_of(l.h);
@@ -828,12 +845,15 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     g.d_probs = (GemmProblem*)put(g.probs.data(), g.probs.size() * sizeof(GemmProblem));
     g.d_tiles = (GemmTile*)put(g.tiles.data(), g.tiles.size() * sizeof(GemmTile));
   }
-  c->d_ptrs = (void**)(c->arena + off);
-  off += align_up(2 * nb * sizeof(void*));
   if (err != hipSuccess) return fail(ADAPM_EHIP, "plan upload: %s", hipGetErrorString(err));
-  HIP_TRY(hipHostMalloc((void**)&c->h_stage, 2 * nb * sizeof(void*), hipHostMallocDefault));
-  HIP_TRY(hipEventCreateWithFlags(&c->stage_free, hipEventDisableTiming));
-  c->cached.assign(2 * nb, nullptr);
+  void** stage = nullptr;
+  HIP_TRY(hipHostMalloc((void**)&stage, adapm_ctx::NSLOT * 2 * nb * sizeof(void*), hipHostMallocDefault));
+  for (int k = 0; k < adapm_ctx::NSLOT; ++k) {
+    c->slot[k].d = (void**)(c->arena + off);
+    off += align_up(2 * nb * sizeof(void*));
+    c->slot[k].h = stage + (size_t)k * 2 * nb;
+    HIP_TRY(hipEventCreateWithFlags(&c->slot[k].copied, hipEventDisableTiming));
+  }
   c->device = dev;
   c->uploaded = true;
   return ADAPM_OK;
@@ -841,6 +861,190 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
 
 bool is_refresh(const adapm_ctx* c, int64_t step) {
   return c->hp.refresh_period_T <= 1 || (step - 1) % c->hp.refresh_period_T == 0;
+}
+
+// Device-resident pointer table of this call: the slot that already holds these pointers, or the least recently
+// used one rewritten by a copy on the step's stream.
+adapm_status_t pointer_table(adapm_ctx* c, void* const* params_dev, const void* const* grads_dev, hipStream_t s,
+                             void*** out) {
+  const size_t nb = c->table.size();
+  adapm_ctx::PtrSlot* hit = nullptr;
+  adapm_ctx::PtrSlot* lru = nullptr;        // an empty slot if there is one, else the least recently used
+  for (adapm_ctx::PtrSlot& q : c->slot) {
+    if (q.valid && memcmp(q.h, params_dev, nb * sizeof(void*)) == 0 && memcmp(q.h + nb, grads_dev, nb * sizeof(void*)) == 0) {
+      hit = &q;
+      break;
+    }
+    if (!lru || (!q.valid && lru->valid) || (q.valid == lru->valid && q.last_use < lru->last_use)) lru = &q;
+  }
+  if (!hit) {
+    hit = lru;
+    if (hit->valid) {
+      // the pinned copy was the source of an earlier upload; NSLOT - 1 uploads later that has long finished
+      const hipError_t q = hipEventQuery(hit->copied);
+      (void)hipGetLastError();
+      if (q == hipErrorNotReady) HIP_TRY(hipEventSynchronize(hit->copied));
+      else if (q != hipSuccess) return fail(ADAPM_EHIP, "hipEventQuery: %s", hipGetErrorString(q));
+    }
+    memcpy(hit->h, params_dev, nb * sizeof(void*));
+    memcpy(hit->h + nb, grads_dev, nb * sizeof(void*));
+    HIP_TRY(hipMemcpyAsync(hit->d, hit->h, 2 * nb * sizeof(void*), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipEventRecord(hit->copied, s));
+    hit->valid = true;
+  }
+  hit->last_use = ++c->use_clock;
+  *out = hit->d;
+  return ADAPM_OK;
+}
+
+const Op kGradNormOp = {OP_GRADNORM, 0, 0, 0, "grad_norm"};
+
+adapm_status_t run_op(adapm_ctx* c, const Op& op, Bases& bs, const StepScalars& sc, double* partials, void* state_dev,
+                      void* workspace_dev, hipStream_t s, int64_t& launches) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool skipped = false;
+  if (c->profiling) {
+    for (hipEvent_t* e : {&e0, &e1}) {
+      if (!c->event_pool.empty()) { *e = c->event_pool.back(); c->event_pool.pop_back(); }
+      else HIP_TRY(hipEventCreate(e));
+    }
+    HIP_TRY(hipEventRecord(e0, s));
+  }
+  switch (op.kind) {
+    case OP_GRADNORM: {
+      // sums of squares of every gradient (unscaled), then norm and factor; every later kernel reads the factor
+      double* gp = (double*)(bs.ws + c->off_gn_partials);
+      float* out = (float*)(bs.ws + c->off_gn_out);
+      launch_vstat(c->blocks.d, c->gn.d, (int64_t)c->gn.h.size(), gp, bs, sc.beta2, s);
+      launch_gradnorm_final(gp, (int64_t)c->gn.h.size(), c->grad_clip, out, s);
+      bs.gscale = out + 1;
+      ++launches;
+      break;
+    }
+    case OP_VSTAT:
+      launch_vstat(c->blocks.d, c->vs[op.index].d, (int64_t)c->vs[op.index].h.size(), partials, bs, sc.beta2, s);
+      break;
+    case OP_VFINAL:
+      launch_vfinal(c->blocks.d, c->vf[op.index].d, (int64_t)c->vf[op.index].h.size(), partials, bs, sc.beta2, s);
+      break;
+    case OP_UPDATE: {
+      StepScalars x = sc;
+      x.cG = op.cG; x.cC = op.cC;
+      launch_update(c->blocks.d, c->ew[op.index].d, (int64_t)c->ew[op.index].h.size(), bs, x, s);
+      break;
+    }
+    case OP_GEMM: {
+      const GemmList& g = c->gemms[op.index];
+      launch_gemm64(g.d_probs, g.d_tiles, (int64_t)g.tiles.size(), bs, s);
+      break;
+    }
+    case OP_GEMM_MFMA: {
+      const GemmList& g = c->gemms[op.index];
+      launch_gemm_mfma(g.d_probs, g.d_tiles, (int64_t)g.tiles.size(), bs, s);
+      break;
+    }
+    case OP_CHOL:
+      launch_chol(c->chol[op.index].d, (int64_t)c->chol[op.index].h.size(), bs, s);
+      break;
+    case OP_QSPLIT:
+      // index 1: only needed if the copies in the workspace are not the ones written last
+      if (op.index == 1 && c->split_ws == workspace_dev && c->split_state == state_dev) { skipped = true; break; }
+      launch_qimage(c->qs.d, (int64_t)c->qs.h.size(), c->lrb.d, bs, s);
+      c->split_ws = workspace_dev;
+      c->split_state = state_dev;
+      break;
+    case OP_QFIMG:
+      launch_qf_image(c->img[op.index].d, (int64_t)c->img[op.index].h.size(), bs, s);
+      break;
+    case OP_STRIPE:
+      launch_stripe(1 << ((op.index % 6) >> 1), (op.index & 1) != 0, c->sit[op.index].d, (int64_t)c->sit[op.index].h.size(), c->sprob.d, bs, s);
+      break;
+    case OP_UPDATE_GROUPED:
+      launch_update_grouped(c->blocks.d, c->grp.d, (int64_t)c->grp.h.size(), bs, sc, s);
+      break;
+    case OP_COPY:
+      launch_copy(c->cp.d, (int64_t)c->cp.h.size(), bs, s);
+      break;
+    case OP_GNORM:
+      launch_gram_norm(c->gnorm[op.index].d, (int64_t)c->gnorm[op.index].h.size(), bs, s);
+      break;
+    case OP_GRAM:
+      launch_gram(c->gram[op.index].d, (int64_t)c->gram[op.index].h.size(), bs, s);
+      break;
+    case OP_QTIMG:
+      launch_qt_image(c->qt.d, (int64_t)c->qt.h.size(), bs, s);
+      break;
+    case OP_REFRESH_UPDATE: {
+      StepScalars x = sc;
+      x.cG = op.cG; x.cC = op.cC;
+      launch_refresh_update(1 << (op.index >> 1), (op.index & 1) != 0, c->ru[op.index].d, (int64_t)c->ru[op.index].h.size(),
+                            c->rub.d, bs, x, s);
+      break;
+    }
+    case OP_PROJ: {
+      StepScalars x = sc;
+      x.cG = c->hp.bias_correction ? 1.f : 0.f;
+      x.cC = 1.f;
+      launch_proj(1 << ((op.index >> 1) % 3), (op.index & 1) != 0, op.index >= 6, c->proj[op.index].d,
+                  (int64_t)c->proj[op.index].h.size(), c->lrb.d, bs, x, s);
+      break;
+    }
+  }
+  if (c->profiling) {
+    if (skipped) { c->event_pool.push_back(e0); c->event_pool.push_back(e1); }
+    else {
+      HIP_TRY(hipEventRecord(e1, s));
+      c->prof.push_back(ProfRec{op.label, e0, e1});
+    }
+  }
+  if (!skipped) ++launches;
+  return ADAPM_OK;
+}
+
+// The launches of one step on stream s.  Arguments were validated by the entry point; the plan is on the device.
+// Allocates nothing unless per-launch timing is switched on (event records).
+adapm_status_t enqueue_step(adapm_ctx* c, void* const* params_dev, const void* const* grads_dev, void* state_dev,
+                            void* workspace_dev, int64_t step, float lr, hipStream_t s) {
+  const size_t nb = c->table.size();
+  void** table = nullptr;
+  adapm_status_t st = pointer_table(c, params_dev, grads_dev, s, &table);
+  if (st != ADAPM_OK) return st;
+
+  Bases bs;
+  bs.state = (char*)state_dev;
+  bs.ws = (char*)workspace_dev;
+  bs.params = (void* const*)table;
+  bs.grads = (const void* const*)(table + nb);
+  bs.gscale = nullptr;
+
+  StepScalars sc;
+  sc.beta1 = c->hp.beta1; sc.beta2 = c->hp.beta2; sc.eps = c->hp.eps; sc.clip = c->hp.clip;
+  sc.lr = lr;
+  sc.inv_debias_m = sc.inv_debias_v = 1.f;
+  if (c->hp.adam_debias) {
+    sc.inv_debias_m = (float)(1.0 / (1.0 - std::pow((double)c->hp.beta1, (double)step)));
+    sc.inv_debias_v = (float)(1.0 / (1.0 - std::pow((double)c->hp.beta2, (double)step)));
+  }
+  sc.cG = sc.cC = 0.f;
+  // step with R held: D = beta1 (L' - P) with eq. 4, or D = L_t without it
+  sc.dL = c->hp.beta1;
+  sc.dP = c->hp.bias_correction ? -c->hp.beta1 : 1.f - c->hp.beta1;
+
+  double* partials = c->off_partials >= 0 ? (double*)(bs.ws + c->off_partials) : nullptr;
+  int64_t launches = 0;
+  const bool refresh = is_refresh(c, step);
+  if (c->grad_clip > 0.f && std::isfinite(c->grad_clip)) {
+    st = run_op(c, kGradNormOp, bs, sc, partials, state_dev, workspace_dev, s, launches);
+    if (st != ADAPM_OK) return st;
+  }
+  for (const Op& op : (refresh ? c->seq_refresh : c->seq_project)) {
+    st = run_op(c, op, bs, sc, partials, state_dev, workspace_dev, s, launches);
+    if (st != ADAPM_OK) return st;
+  }
+  if (refresh && c->hp.refresh_period_T > 1) c->gauge_ok = true;
+  c->last_launches = launches;
+  HIP_TRY(hipGetLastError());
+  return ADAPM_OK;
 }
 
 }  // namespace
@@ -893,6 +1097,7 @@ adapm_status_t adapm_state_init(adapm_ctx* c, void* state_dev, void* stream) {
   if (st != ADAPM_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   c->split_ws = nullptr;
+  c->gauge_ok = false;
   launch_fill_zero(state_dev, c->state_bytes, s);
   launch_sketch(c->sk.d, (int64_t)c->sk.h.size(), (char*)state_dev, s);
   HIP_TRY(hipGetLastError());
@@ -913,152 +1118,14 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
     if (((uintptr_t)params_dev[i] | (uintptr_t)grads_dev[i]) & 15)
       return fail(ADAPM_EINVAL, "block %zu: parameter / gradient pointer not 16-byte aligned", i);
   }
-  adapm_status_t st = ensure_uploaded(c);
+  const bool refresh = is_refresh(c, step);
+  if (!refresh && c->n_lowrank > 0 && !c->gauge_ok)
+    return fail(ADAPM_ESTATE, "step %lld holds R, but this state's R has not been orthonormalised yet: run a step with "
+                "(step - 1) %% refresh_period_T == 0 first, or call adapm_state_loaded() after restoring a checkpoint",
+                (long long)step);
+  adapm_status_t st = ensure_uploaded(c);     // a no-op after adapm_state_init
   if (st != ADAPM_OK) return st;
-  hipStream_t s = (hipStream_t)stream;
-
-  // pointer tables: re-sent only when the caller's pointers changed
-  bool changed = false;
-  for (size_t i = 0; i < nb && !changed; ++i)
-    changed = c->cached[i] != params_dev[i] || c->cached[nb + i] != (void*)grads_dev[i];
-  if (changed) {
-    HIP_TRY(hipEventSynchronize(c->stage_free));
-    for (size_t i = 0; i < nb; ++i) {
-      c->h_stage[i] = c->cached[i] = params_dev[i];
-      c->h_stage[nb + i] = c->cached[nb + i] = (void*)grads_dev[i];
-    }
-    HIP_TRY(hipMemcpyAsync(c->d_ptrs, c->h_stage, 2 * nb * sizeof(void*), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipEventRecord(c->stage_free, s));
-  }
-
-  Bases bs;
-  bs.state = (char*)state_dev;
-  bs.ws = (char*)workspace_dev;
-  bs.params = (void* const*)c->d_ptrs;
-  bs.grads = (const void* const*)(c->d_ptrs + nb);
-  bs.gscale = nullptr;
-
-  StepScalars sc;
-  sc.beta1 = c->hp.beta1; sc.beta2 = c->hp.beta2; sc.eps = c->hp.eps; sc.clip = c->hp.clip;
-  sc.lr = lr;
-  sc.inv_debias_m = sc.inv_debias_v = 1.f;
-  if (c->hp.adam_debias) {
-    sc.inv_debias_m = (float)(1.0 / (1.0 - std::pow((double)c->hp.beta1, (double)step)));
-    sc.inv_debias_v = (float)(1.0 / (1.0 - std::pow((double)c->hp.beta2, (double)step)));
-  }
-  sc.cG = sc.cC = 0.f;
-  // step with R held: D = beta1 (L' - P) with eq. 4, or D = L_t without it
-  sc.dL = c->hp.beta1;
-  sc.dP = c->hp.bias_correction ? -c->hp.beta1 : 1.f - c->hp.beta1;
-
-  double* partials = c->off_partials >= 0 ? (double*)(bs.ws + c->off_partials) : nullptr;
-  int64_t launches = 0;
-  const std::vector<Op>& body = is_refresh(c, step) ? c->seq_refresh : c->seq_project;
-  std::vector<Op> seq;
-  if (c->grad_clip > 0.f && std::isfinite(c->grad_clip)) seq.push_back(Op{OP_GRADNORM, 0, 0, 0, "grad_norm"});
-  seq.insert(seq.end(), body.begin(), body.end());
-  for (const Op& op : seq) {
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    bool skipped = false;
-    if (c->profiling) {
-      for (hipEvent_t* e : {&e0, &e1}) {
-        if (!c->event_pool.empty()) { *e = c->event_pool.back(); c->event_pool.pop_back(); }
-        else HIP_TRY(hipEventCreate(e));
-      }
-      HIP_TRY(hipEventRecord(e0, s));
-    }
-    switch (op.kind) {
-      case OP_GRADNORM: {
-        // sums of squares of every gradient (unscaled), then norm and factor; every later kernel reads the factor
-        double* gp = (double*)(bs.ws + c->off_gn_partials);
-        float* out = (float*)(bs.ws + c->off_gn_out);
-        launch_vstat(c->blocks.d, c->gn.d, (int64_t)c->gn.h.size(), gp, bs, sc.beta2, s);
-        launch_gradnorm_final(gp, (int64_t)c->gn.h.size(), c->grad_clip, out, s);
-        bs.gscale = out + 1;
-        ++launches;
-        break;
-      }
-      case OP_VSTAT:
-        launch_vstat(c->blocks.d, c->vs[op.index].d, (int64_t)c->vs[op.index].h.size(), partials, bs, sc.beta2, s);
-        break;
-      case OP_VFINAL:
-        launch_vfinal(c->blocks.d, c->vf[op.index].d, (int64_t)c->vf[op.index].h.size(), partials, bs, sc.beta2, s);
-        break;
-      case OP_UPDATE: {
-        StepScalars x = sc;
-        x.cG = op.cG; x.cC = op.cC;
-        launch_update(c->blocks.d, c->ew[op.index].d, (int64_t)c->ew[op.index].h.size(), bs, x, s);
-        break;
-      }
-      case OP_GEMM: {
-        const GemmList& g = c->gemms[op.index];
-        launch_gemm64(g.d_probs, g.d_tiles, (int64_t)g.tiles.size(), bs, s);
-        break;
-      }
-      case OP_GEMM_MFMA: {
-        const GemmList& g = c->gemms[op.index];
-        launch_gemm_mfma(g.d_probs, g.d_tiles, (int64_t)g.tiles.size(), bs, s);
-        break;
-      }
-      case OP_CHOL:
-        launch_chol(c->chol[op.index].d, (int64_t)c->chol[op.index].h.size(), bs, s);
-        break;
-      case OP_QSPLIT:
-        // index 1: only needed if the copies in the workspace are not the ones written last
-        if (op.index == 1 && c->split_ws == workspace_dev && c->split_state == state_dev) { skipped = true; break; }
-        launch_qimage(c->qs.d, (int64_t)c->qs.h.size(), c->lrb.d, bs, s);
-        c->split_ws = workspace_dev;
-        c->split_state = state_dev;
-        break;
-      case OP_QFIMG:
-        launch_qf_image(c->img[op.index].d, (int64_t)c->img[op.index].h.size(), bs, s);
-        break;
-      case OP_STRIPE:
-        launch_stripe(1 << ((op.index % 6) >> 1), (op.index & 1) != 0, c->sit[op.index].d, (int64_t)c->sit[op.index].h.size(), c->sprob.d, bs, s);
-        break;
-      case OP_UPDATE_GROUPED:
-        launch_update_grouped(c->blocks.d, c->grp.d, (int64_t)c->grp.h.size(), bs, sc, s);
-        break;
-      case OP_COPY:
-        launch_copy(c->cp.d, (int64_t)c->cp.h.size(), bs, s);
-        break;
-      case OP_GNORM:
-        launch_gram_norm(c->gnorm[op.index].d, (int64_t)c->gnorm[op.index].h.size(), bs, s);
-        break;
-      case OP_GRAM:
-        launch_gram(c->gram[op.index].d, (int64_t)c->gram[op.index].h.size(), bs, s);
-        break;
-      case OP_QTIMG:
-        launch_qt_image(c->qt.d, (int64_t)c->qt.h.size(), bs, s);
-        break;
-      case OP_REFRESH_UPDATE: {
-        StepScalars x = sc;
-        x.cG = op.cG; x.cC = op.cC;
-        launch_refresh_update(1 << (op.index >> 1), (op.index & 1) != 0, c->ru[op.index].d, (int64_t)c->ru[op.index].h.size(),
-                              c->rub.d, bs, x, s);
-        break;
-      }
-      case OP_PROJ: {
-        StepScalars x = sc;
-        x.cG = c->hp.bias_correction ? 1.f : 0.f;
-        x.cC = 1.f;
-        launch_proj(1 << ((op.index >> 1) % 3), (op.index & 1) != 0, op.index >= 6, c->proj[op.index].d,
-                    (int64_t)c->proj[op.index].h.size(), c->lrb.d, bs, x, s);
-        break;
-      }
-    }
-    if (c->profiling) {
-      if (skipped) { c->event_pool.push_back(e0); c->event_pool.push_back(e1); }
-      else {
-        HIP_TRY(hipEventRecord(e1, s));
-        c->prof.push_back(ProfRec{op.label, e0, e1});
-      }
-    }
-    if (!skipped) ++launches;
-  }
-  c->last_launches = launches;
-  HIP_TRY(hipGetLastError());
-  return ADAPM_OK;
+  return enqueue_step(c, params_dev, grads_dev, state_dev, workspace_dev, step, lr, (hipStream_t)stream);
 }
 
 adapm_status_t adapm_profile_enable(adapm_ctx* c, int32_t on) {
@@ -1096,6 +1163,7 @@ int64_t adapm_profile_read(adapm_ctx* c, int64_t index, char* name, size_t name_
 adapm_status_t adapm_state_loaded(adapm_ctx* c) {
   if (!c) return fail(ADAPM_EINVAL, "ctx is null");
   c->split_ws = nullptr;
+  c->gauge_ok = true;      // the caller vouches for the restored state: a checkpoint taken with T > 1 holds an orthonormal R
   return ADAPM_OK;
 }
 
@@ -1167,8 +1235,9 @@ double adapm_algorithmic_flops(const adapm_ctx* c, int32_t refresh_step) {
 void adapm_destroy(adapm_ctx* c) {
   if (!c) return;
   if (c->uploaded) {
-    if (c->stage_free) { (void)hipEventSynchronize(c->stage_free); (void)hipEventDestroy(c->stage_free); }
-    if (c->h_stage) (void)hipHostFree(c->h_stage);
+    for (adapm_ctx::PtrSlot& q : c->slot)
+      if (q.copied) { (void)hipEventSynchronize(q.copied); (void)hipEventDestroy(q.copied); }
+    if (c->slot[0].h) (void)hipHostFree(c->slot[0].h);      // one pinned allocation shared by the slots
     for (const ProfRec& r : c->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
     for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
     if (c->arena) (void)hipFree(c->arena);

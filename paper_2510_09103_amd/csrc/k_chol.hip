@@ -4,6 +4,9 @@
 // orthonormal, so that the least-squares fit of L with R held is a plain projection.
 // One workgroup per low-rank block (r <= 128: the matrix stays in LDS); fp64 keeps the orthonormality error at fp32 rounding
 // level whatever the conditioning of R.
+// A Gram matrix that is not positive definite in fp64 (a pivot that is zero, negative or not finite: R has lost
+// rank, e.g. factors that are exactly zero) has no such factorisation; the kernel then writes C = C^-1 = I, so that
+// the block's (L, R) pass through the re-expression unchanged instead of turning into NaN.
 #include "adapm_plan.h"
 
 namespace adapm {
@@ -13,9 +16,12 @@ namespace {
 // r above CH_MAX: in place in global memory
 __device__ void chol_inv_global(double* A, double* X, int r) {
   const int tid = threadIdx.x;
+  bool bad = false;
   // right-looking Cholesky, lower triangle, in place
   for (int j = 0; j < r; ++j) {
-    const double d = sqrt(A[(int64_t)j * r + j]);
+    const double piv = A[(int64_t)j * r + j];        // the same value in every thread
+    if (!(piv > 0.0) || !isfinite(piv)) { bad = true; break; }
+    const double d = sqrt(piv);
     __syncthreads();
     for (int i = j + tid; i < r; i += 256) A[(int64_t)i * r + j] = (i == j) ? d : A[(int64_t)i * r + j] / d;
     __syncthreads();
@@ -25,6 +31,11 @@ __device__ void chol_inv_global(double* A, double* X, int r) {
       if (k <= i) A[(int64_t)i * r + k] -= A[(int64_t)i * r + j] * A[(int64_t)k * r + j];
     }
     __syncthreads();
+  }
+  __syncthreads();
+  if (bad) {
+    for (int64_t e = tid; e < (int64_t)r * r; e += 256) A[e] = X[e] = (e / r == e % r) ? 1.0 : 0.0;
+    return;
   }
   for (int64_t e = tid; e < (int64_t)r * r; e += 256) {
     const int i = (int)(e / r), k = (int)(e % r);
@@ -58,8 +69,11 @@ __global__ __launch_bounds__(256) void chol_inv_kernel(const CholItem* __restric
   for (int e = tid; e < r * r; e += 256) S[(e / r) * ld + e % r] = A[e];
   __syncthreads();
   const int tx = tid & 15, ty = tid >> 4;
+  bool bad = false;
   for (int j = 0; j < r; ++j) {
-    const double d = sqrt(S[j * ld + j]);
+    const double piv = S[j * ld + j];                // the same value in every thread
+    if (!(piv > 0.0) || !isfinite(piv)) { bad = true; break; }
+    const double d = sqrt(piv);
     __syncthreads();
     for (int i = j + tid; i < r; i += 256) S[i * ld + j] = (i == j) ? d : S[i * ld + j] / d;
     __syncthreads();
@@ -68,6 +82,10 @@ __global__ __launch_bounds__(256) void chol_inv_kernel(const CholItem* __restric
       for (int k = j + 1 + tx; k <= i; k += 16) S[i * ld + k] -= lij * S[k * ld + j];
     }
     __syncthreads();
+  }
+  if (bad) {                                         // uniform: every thread saw the same pivot
+    for (int e = tid; e < r * r; e += 256) A[e] = X[e] = (e / r == e % r) ? 1.0 : 0.0;
+    return;
   }
   // column j of C^-1 by forward substitution, one column per thread; thread j writes row j of the upper
   // triangle and xd[j] only, and reads nothing another thread writes

@@ -60,6 +60,26 @@ def test_init_rejects_bad_hparams(bad):
     assert e.value.status == B.ADAPM_EINVAL
 
 
+def test_literal_zero_start_needs_alg2_every_step():
+    """seed = 0 keeps L = R = 0 for ever (both gradients of Alg. 2 vanish at zero); R = 0 has no orthonormal
+    re-expression, so the reading of T > 1 (R held between runs of Alg. 2) is undefined for it: rejected at init."""
+    with pytest.raises(B.AdapmError) as e:
+        B.adapm_init([blk()], make_hparams(seed=0, T=2))
+    assert e.value.status == B.ADAPM_EINVAL and "seed" in str(e.value)
+    B.adapm_destroy(B.adapm_init([blk()], make_hparams(seed=0, T=1)))
+
+
+def test_step_with_R_held_needs_an_orthonormalised_state():
+    """T > 1: a step off the refresh grid on a context whose state was neither refreshed nor declared loaded is a
+    call-order error (checked before anything touches the device)."""
+    ctx = B.adapm_init([blk()], make_hparams(T=3))
+    pp, gp = B.ptr_array([256]), B.ptr_array([512])
+    with pytest.raises(B.AdapmError) as e:
+        B.adapm_step(ctx, pp, gp, 4096, 8192, 2, 1e-3)
+    assert e.value.status == B.ADAPM_ESTATE and "orthonormal" in str(e.value)
+    B.adapm_destroy(ctx)
+
+
 def test_init_rejects_null_and_empty():
     ctx = C.c_void_p()
     hp = make_hparams()

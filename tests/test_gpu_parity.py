@@ -1,6 +1,11 @@
 """GPU parity: the HIP library against the CPU oracle, element by element, on the same
-seeded inputs.  Tolerances: 1e-5 relative (fp32 parameters and state, with a block-RMS
-floor) and 2e-3 relative or one bf16 ulp (bf16 parameters), 2e-3 on their state."""
+seeded inputs.  Tolerances (relative, per element, with a block-RMS floor):
+  TOL32   1e-5  fp32 parameters and their state on the exact (fp64) contraction path;
+  TOLX    2e-4  fp32 parameters and any state on the split-bf16 MFMA path: twice the worst error seen over the
+                configurations' own step counts (1.1e-4 on parameters, 9e-5 on state); the bound asked of
+                bf16-parameter runs is 2e-3;
+  bf16 parameters: 2e-3 or a bounded number of representable values, with asserted flip fractions
+                (parity_util.compare_params)."""
 import dataclasses
 
 import numpy as np
@@ -16,7 +21,8 @@ from parity_util import Pair, to_np
 pytestmark = pytest.mark.gpu
 
 TOL32 = 1e-5
-TOL16 = 2e-3
+TOLX = 2e-4
+TOL16 = TOLX      # state and fp32 parameters of runs on the MFMA path
 
 
 def run(wl, steps, hp=None, tol_state=TOL32, tol_param=TOL32, check_every=None, **kw):
@@ -248,56 +254,139 @@ def test_literal_zero_start_stays_zero_on_gpu():
     assert float(sv["L"].abs().max()) == 0.0 and float(sv["R"].abs().max()) == 0.0
 
 
+# ---------------------------------------------------------------------------------------------------------------
+# The five configurations at their own step counts.  Blocks are independent in the method, so where the oracle would
+# need too long for a whole table it follows a stratified subset at full size: one block of every distinct
+# (shape, momentum regime, kind of second moment).  Embedding-sized full-momentum blocks (tens of millions of
+# elements, seconds per oracle step) are followed for a few steps only: their update is a linear recursion per
+# element with no iteration whose error could grow.
+# ---------------------------------------------------------------------------------------------------------------
+def f32_params(wl):
+    """The same workload with fp32 parameters (bf16 gradients kept): on the MFMA path this shows the arithmetic
+    itself, without the bf16 rounding of W."""
+    return dataclasses.replace(wl, blocks=tuple(dataclasses.replace(b, param_dtype="f32") for b in wl.blocks))
+
+
+def test_config2_llama60m_whole_table():
+    """All 74 blocks (embedding with full momentum, 56 low-rank matrices at r = 32, 17 norm vectors)."""
+    run(WL.llama_60m(), 10, dict(T=1), check_every=5)
+
+
 def test_config2_llama60m_layer_100_steps():
     full = WL.llama_60m()
     names = [b.name for b in full.blocks if b.name.startswith("l0.")] + ["norm_f"]
-    run(WL.subset(full, names), 100, dict(T=1), check_every=25)
+    run(WL.subset(full, names), 100, dict(T=1), check_every=10)
 
 
-def test_config2_embedding_full_momentum():
-    run(WL.subset(WL.llama_60m(), ["embed"]), 4, dict(T=1))
+def test_config2_llama60m_layer_100_steps_R_held():
+    full = WL.llama_60m()
+    run(WL.subset(full, ["l0.attn.q", "l0.ffn.gate", "l0.ffn.down", "l0.norm1"]), 100, dict(T=10), check_every=10)
 
 
-@pytest.mark.parametrize("T", [1, 100])
-def test_config3_gpt2_350m_layer(T):
-    full = WL.gpt2_350m()
-    names = ["wpe"] + [b.name for b in full.blocks if b.name.startswith("h3.")]
-    run(WL.subset(full, names), 8, dict(T=T), tol_state=TOL16, tol_param=TOL16)
-
-
-def test_config4_llama1b_layer_odd_ffn():
-    full = WL.llama_1b()
-    names = ["l5.attn.k", "l5.ffn.gate", "l5.ffn.down", "l5.norm1"]
-    run(WL.subset(full, names), 3, dict(T=1), tol_state=TOL16, tol_param=TOL16)
+C3_STRATA = ["wpe", "h3.attn.q", "h3.mlp.fc", "h3.mlp.proj", "h3.ln1"]
 
 
 @pytest.mark.parametrize("T", [1, 100])
-def test_config5_gpt2_1p5b_layer_blockwise_v(T):
-    full = WL.gpt2_1p5b()
-    names = ["h7.attn.q", "h7.attn.v", "h7.mlp.fc", "h7.mlp.proj", "h7.ln1", "wpe"]
-    run(WL.subset(full, names), 3, dict(T=T), tol_state=TOL16, tol_param=TOL16)
+def test_config3_gpt2_350m_strata_100_steps(T):
+    run(WL.subset(WL.gpt2_350m(), C3_STRATA), 100, dict(T=T), tol_state=TOLX, tol_param=TOLX, check_every=10)
 
 
-def test_config5_full_size_sampled_blocks():
-    """All 388 blocks in the launch configuration the benchmark times (T = 100); the oracle
+def test_config3_gpt2_350m_embedding():
+    run(WL.subset(WL.gpt2_350m(), ["wte"]), 3, dict(T=1), tol_state=TOLX, tol_param=TOLX)
+
+
+def test_config3_strata_with_fp32_parameters_on_the_mfma_path():
+    """The arithmetic of the MFMA path without the bf16 rounding of W: parameters, state and product L R within
+    1e-4 of the oracle after 100 steps of the warm-started iteration."""
+    wl = f32_params(WL.subset(WL.gpt2_350m(), ["h3.attn.q", "h3.mlp.proj"]))
+    run(wl, 100, dict(T=1, contraction=B.ADAPM_CONTRACT_BF16X2), tol_state=TOLX, tol_param=TOLX, check_every=10)
+
+
+C4_STRATA = ["l5.attn.k", "l5.ffn.gate", "l5.ffn.down", "l5.norm1"]
+
+
+def test_config4_llama1b_strata_50_steps():
+    """2048 x 2048, 5461 x 2048 (odd number of rows) and 2048 x 5461 (rows of G at 2-byte alignment), per-head
+    gradient scales over two decades."""
+    run(WL.subset(WL.llama_1b(), C4_STRATA), 50, dict(T=1), tol_state=TOLX, tol_param=TOLX, check_every=10)
+
+
+def test_config4_llama1b_strata_R_held():
+    run(WL.subset(WL.llama_1b(), ["l5.attn.k", "l5.ffn.down"]), 50, dict(T=100), tol_state=TOLX, tol_param=TOLX, check_every=10)
+
+
+def test_config4_llama1b_embedding_and_head():
+    run(WL.subset(WL.llama_1b(), ["embed", "lm_head"]), 2, dict(T=1), tol_state=TOLX, tol_param=TOLX)
+
+
+def test_config4_strata_with_fp32_parameters_on_the_mfma_path():
+    wl = f32_params(WL.subset(WL.llama_1b(), ["l5.attn.k", "l5.ffn.down"]))
+    run(wl, 20, dict(T=1, contraction=B.ADAPM_CONTRACT_BF16X2), tol_state=TOLX, tol_param=TOLX, check_every=10)
+
+
+C5_STRATA = ["h7.attn.q", "h7.attn.v", "h7.mlp.fc", "h7.mlp.proj", "h7.ln1", "wpe"]
+
+
+@pytest.mark.parametrize("T", [1, 100])
+def test_config5_gpt2_1p5b_strata_20_steps(T):
+    """Per-head v (Q), per-row v (V, MLP), one v per norm vector, per-row v with full momentum (positions)."""
+    run(WL.subset(WL.gpt2_1p5b(), C5_STRATA), 20, dict(T=T), tol_state=TOLX, tol_param=TOLX, check_every=10)
+
+
+def test_config5_gpt2_1p5b_output_head():
+    run(WL.subset(WL.gpt2_1p5b(), ["lm_head"]), 2, dict(T=1), tol_state=TOLX, tol_param=TOLX)
+
+
+def test_config5_strata_with_fp32_parameters_on_the_mfma_path():
+    wl = f32_params(WL.subset(WL.gpt2_1p5b(), ["h7.attn.q", "h7.mlp.fc", "h7.mlp.proj"]))
+    run(wl, 20, dict(T=1, contraction=B.ADAPM_CONTRACT_BF16X2), tol_state=TOLX, tol_param=TOLX, check_every=10)
+
+
+@pytest.mark.parametrize("T", [1, 100])
+def test_config5_full_size_sampled_blocks(T):
+    """All 388 blocks in the launch configurations the benchmark times (T = 100: one step that runs Alg. 2, then R
+    held; T = 1: Alg. 2 every step, the whole-model work lists of its stripe, Gram and update launches); the oracle
     follows a sample of blocks (blocks are independent), the rest is checked for sanity."""
     wl = WL.gpt2_1p5b()
     names = [b.name for b in wl.blocks]
     sample = [names.index(n) for n in ("h0.attn.q", "h23.attn.o", "h47.mlp.fc", "h11.mlp.proj", "h30.ln2", "ln_f",
                                        "wpe")]
-    pair = Pair(wl, dict(T=100))
+    pair = Pair(wl, dict(T=T))
+    w0 = pair.params[names.index("h40.attn.k")].clone()
     for t in range(1, 4):
         pair.step(oracle_only=sample)
-    rep = pair.compare(TOL16, TOL16, only=sample)
-    print("gpt2_1p5b full size, sampled blocks:", rep, flush=True)
+    rep = pair.compare(TOLX, TOLX, only=sample)
+    print(f"gpt2_1p5b full size, T={T}, sampled blocks:", rep, flush=True)
     torch.cuda.synchronize()
     for i, p in enumerate(pair.params):
         assert bool(torch.isfinite(p.float()).all()), names[i]
     assert bool(torch.isfinite(pair.opt.state.view(torch.float32)).all())
-    # untouched-by-oracle blocks did move
-    j = names.index("h40.attn.k")
-    w0 = WL.initial_params(WL.subset(wl, [j]), device="cpu")
-    assert not torch.equal(pair.params[j].cpu(), w0[0]) or True
+    # blocks the oracle did not follow did move
+    assert not torch.equal(pair.params[names.index("h40.attn.k")], w0)
+
+
+def test_rank_deficient_R_passes_the_orthonormalisation_unchanged():
+    """T > 1 with factors that are exactly zero (a restored state whose R = 0): R R^T has no Cholesky factor, the
+    library leaves such a block's (L, R) as Alg. 2 left them instead of writing NaN, and the steps then equal the
+    literal zero start of Alg. 1 (factors stay 0, m^c = G), which the oracle computes with seed = 0, T = 1."""
+    for names, wl0 in ((["attn.q"], WL.tiny_block()), (["h0.attn.q"], WL.gpt2_350m())):
+        wl = WL.subset(wl0, names)
+        pair = Pair(wl, dict(T=2))
+        pair.opt.state_view(0)["R"].zero_()
+        B.adapm_state_loaded(pair.opt.ctx)
+        hp_o = O.HParams(beta1=wl.beta1, beta2=wl.beta2, eps=wl.eps, clip=wl.clip, K=wl.K, T=1, seed=0)
+        st_o = O.init_state(pair.blocks_o, hp_o)
+        W_o = pair.W_o
+        for t in range(1, 4):
+            grads = pair.stream.next()
+            pair.opt.step(pair.params, grads, t, wl.lr)
+            W_o, st_o = O.step(pair.blocks_o, hp_o, W_o, [to_np(g) for g in grads], st_o, t, wl.lr)
+        torch.cuda.synchronize()
+        sv = pair.opt.state_view(0)
+        assert float(sv["L"].abs().max()) == 0.0 and float(sv["R"].abs().max()) == 0.0
+        assert bool(torch.isfinite(pair.params[0].float()).all())
+        pair.W_o, pair.state_o, pair.t = W_o, st_o, 3
+        pair.compare(TOLX, TOL32 if wl.blocks[0].param_dtype == "f32" else TOLX)
 
 
 def test_two_runs_are_bit_identical_and_resume_from_a_state_copy():
@@ -313,6 +402,7 @@ def test_two_runs_are_bit_identical_and_resume_from_a_state_copy():
                 from paper_2510_09103_amd.optimizer import AdaPM
                 fresh = AdaPM(wl.blocks, pair.hp_c)
                 fresh.state.copy_(saved)
+                B.adapm_state_loaded(fresh.ctx)
                 pair.opt = fresh
             grads = pair.stream.next()
             pair.t = t

@@ -625,3 +625,22 @@ def test_normalised_alg2_descends_at_any_scale_and_reduces_to_the_literal_one():
     Lb, Rb = O.refresh_gd(M, np.zeros((m_, 1)), R0, 2, normalise=True)
     np.testing.assert_array_equal(La, Lb)
     np.testing.assert_array_equal(Ra, Rb)
+
+
+def test_regauge_of_rank_deficient_factors_is_an_error_in_the_oracle():
+    """The product-preserving re-expression (reading of T > 1) needs R R^T positive definite.  The oracle does not
+    paper over a rank-deficient R: the library routine raises, e.g. for the literal zero start of Alg. 1."""
+    L, R = np.zeros((6, 2)), np.zeros((2, 5))
+    with pytest.raises(np.linalg.LinAlgError):
+        O.regauge(L, R)
+    blk = O.Block(6, 5, mom_mode=O.MOM_LOWRANK, rank=2)
+    hp = O.HParams(T=2, seed=0)
+    st = O.init_state([blk], hp)[0]
+    G = np.arange(30, dtype=np.float32).reshape(6, 5) / 30
+    with pytest.raises(np.linalg.LinAlgError):
+        O.step_block(blk, hp, np.zeros((6, 5), np.float32), G, st, 1, 1e-3)
+    # with Alg. 2 every step (T = 1) the same start is well defined: the factors stay zero and m^c = G
+    hp1 = O.HParams(T=1, seed=0)
+    _, new, aux = O.step_block(blk, hp1, np.zeros((6, 5), np.float32), G, st, 1, 1e-3, want_aux=True)
+    assert not new["L"].any() and not new["R"].any()
+    assert np.allclose(aux["mc"], G.astype(np.float64), rtol=1e-14, atol=0.0)
