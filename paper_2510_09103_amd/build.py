@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadapm.so")
-SOURCES = ["adapm_api.hip", "k_elementwise.hip", "k_gemm64.hip", "k_chol.hip", "k_gemm_mfma.hip", "k_proj_mfma.hip"]
+SOURCES = ["adapm_api.hip", "k_elementwise.hip", "k_gemm64.hip", "k_chol.hip", "k_gemm_mfma.hip", "k_proj_mfma.hip", "k_proj_keep.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]

@@ -12,6 +12,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -64,7 +65,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM, OP_UPDATE_GROUPED, OP_COPY };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM, OP_UPDATE_GROUPED, OP_COPY, OP_PROJ_KEEP };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -121,6 +122,7 @@ struct adapm_ctx {
   DevList<CholItem> chol[2];    // per path
   DevList<LrBlockDev> lrb;
   DevList<ProjItem> proj[12];   // (rank 32 / 64 / 128) x (fp32 / bf16 parameters) x (blockwise / per-element v)
+  DevList<ProjItem> proj_keep;  // rank class 128, bf16 parameters, blockwise v, short rows: 64-row stripes whose G stays on chip
   DevList<QsItem> qs;
   DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
   std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T (only the first iteration has any: the stripes write the later ones)
@@ -152,6 +154,9 @@ struct adapm_ctx {
     uint64_t last_use = 0;
   } slot[NSLOT];
   uint64_t use_clock = 0;
+  bool keep_enabled = false;            // ADAPM_PROJ_KEEP=1 in the environment at adapm_init: blocks that qualify run in the kernel
+                                        // that keeps G on chip between the passes (one read of G; measured slower than the two-read
+                                        // kernel on MI355X, so it is off by default and kept for the comparison)
   bool gauge_ok = false;                // T > 1: the state's R has orthonormal rows (a step that ran Alg. 2, or adapm_state_loaded)
   int64_t last_launches = 0;
   int n_lowrank = 0;
@@ -626,33 +631,44 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
     const int rank = 32 << ((cls >> 1) % 3);
     const int pdt = (cls & 1) ? ADAPM_BF16 : ADAPM_F32;
     const bool vel = cls >= 6;
-    std::vector<int64_t> ids;
-    for (int64_t i = 0; i < nb; ++i)
-      if (lr_of[i] >= 0 && rank_class(c->table[i].rank) == rank && c->table[i].param_dtype == pdt &&
-          (c->table[i].v_mode == ADAPM_V_ELEMENT) == vel)
-        ids.push_back(i);
-    if (ids.empty()) continue;
-    // longest rows first; whole blocks dealt to the least loaded XCD
-    std::stable_sort(ids.begin(), ids.end(), [&](int64_t a, int64_t b) {
-      const double ca = (double)c->table[a].rows * c->table[a].cols, cb = (double)c->table[b].rows * c->table[b].cols;
-      if (c->table[a].cols != c->table[b].cols) return c->table[a].cols > c->table[b].cols;
-      return ca > cb;
-    });
-    std::vector<ProjItem> per[NXCD];
-    double load[NXCD] = {0};
-    for (int64_t i : ids) {
-      int x = 0;
-      for (int k = 1; k < NXCD; ++k) if (load[k] < load[x]) x = k;
-      const adapm_block_t& b = c->table[i];
-      for (int64_t r0 = 0; r0 < b.rows; r0 += 128) per[x].push_back(ProjItem{(int32_t)lr_of[i], (int32_t)r0});
-      load[x] += (double)b.rows * b.cols;
+    // blocks of rank class 128 with bf16 parameters, a blockwise v and short rows go to the kernel that reads G once
+    auto keeps = [&](const adapm_block_t& b) {
+      if (rank != 128 || pdt != ADAPM_BF16 || vel || !c->keep_enabled) return false;
+      if (b.cols % 8 != 0 || b.cols > proj_keep_max_cols()) return false;
+      return !v_fusable(b) || proj_keep_rows() % b.v_group_rows == 0;      // groups finished inside the stripe must fit it
+    };
+    for (int pass = 0; pass < 2; ++pass) {       // 0: the two-read kernel (long rows first), 1: the kernel that keeps G on chip
+      const int rows_per = pass ? proj_keep_rows() : 128;
+      std::vector<int64_t> ids;
+      for (int64_t i = 0; i < nb; ++i)
+        if (lr_of[i] >= 0 && rank_class(c->table[i].rank) == rank && c->table[i].param_dtype == pdt &&
+            (c->table[i].v_mode == ADAPM_V_ELEMENT) == vel && keeps(c->table[i]) == (pass == 1))
+          ids.push_back(i);
+      if (ids.empty()) continue;
+      // longest rows first; whole blocks dealt to the least loaded XCD
+      std::stable_sort(ids.begin(), ids.end(), [&](int64_t a, int64_t b) {
+        const double ca = (double)c->table[a].rows * c->table[a].cols, cb = (double)c->table[b].rows * c->table[b].cols;
+        if (c->table[a].cols != c->table[b].cols) return c->table[a].cols > c->table[b].cols;
+        return ca > cb;
+      });
+      std::vector<ProjItem> per[NXCD];
+      double load[NXCD] = {0};
+      for (int64_t i : ids) {
+        int x = 0;
+        for (int k = 1; k < NXCD; ++k) if (load[k] < load[x]) x = k;
+        const adapm_block_t& b = c->table[i];
+        for (int64_t r0 = 0; r0 < b.rows; r0 += rows_per) per[x].push_back(ProjItem{(int32_t)lr_of[i], (int32_t)r0});
+        load[x] += (double)b.rows * b.cols;
+      }
+      size_t longest = 0;
+      for (auto& v : per) longest = std::max(longest, v.size());
+      std::vector<ProjItem>& out = pass ? c->proj_keep.h : c->proj[cls].h;
+      for (size_t q = 0; q < longest; ++q)
+        for (int x = 0; x < NXCD; ++x) out.push_back(q < per[x].size() ? per[x][q] : ProjItem{-1, 0});
+      static const char* names[3] = {"fused_project_r32", "fused_project_r64", "fused_project_r128"};
+      if (pass) seq.push_back(Op{OP_PROJ_KEEP, 0, 0, 0, "fused_project_keep_r128"});
+      else seq.push_back(Op{OP_PROJ, cls, 0, 0, names[(cls >> 1) % 3]});
     }
-    size_t longest = 0;
-    for (auto& v : per) longest = std::max(longest, v.size());
-    for (size_t q = 0; q < longest; ++q)
-      for (int x = 0; x < NXCD; ++x) c->proj[cls].h.push_back(q < per[x].size() ? per[x][q] : ProjItem{-1, 0});
-    static const char* names[3] = {"fused_project_r32", "fused_project_r64", "fused_project_r128"};
-    seq.push_back(Op{OP_PROJ, cls, 0, 0, names[(cls >> 1) % 3]});
   }
 }
 
@@ -809,7 +825,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   int dev = -1;
   HIP_TRY(hipGetDevice(&dev));
   const size_t nb = c->table.size();
-  size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) +
+  size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) + bytes_of(c->proj_keep.h) +
                  bytes_of(c->sprob.h) + bytes_of(c->cp.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) + bytes_of(c->grp.h) +
                  adapm_ctx::NSLOT * align_up(2 * nb * sizeof(void*));
   for (int i = 0; i < 6; ++i) total += bytes_of(c->ru[i].h);
@@ -831,7 +847,7 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     return dst;
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
-  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->sprob); PUT_LIST(c->cp); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn); PUT_LIST(c->grp);
+  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->proj_keep); PUT_LIST(c->sprob); PUT_LIST(c->cp); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn); PUT_LIST(c->grp);
   for (int i = 0; i < 6; ++i) PUT_LIST(c->ru[i]);
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
@@ -981,6 +997,13 @@ adapm_status_t run_op(adapm_ctx* c, const Op& op, Bases& bs, const StepScalars& 
                             c->rub.d, bs, x, s);
       break;
     }
+    case OP_PROJ_KEEP: {
+      StepScalars x = sc;
+      x.cG = c->hp.bias_correction ? 1.f : 0.f;
+      x.cC = 1.f;
+      launch_proj_keep(c->proj_keep.d, (int64_t)c->proj_keep.h.size(), c->lrb.d, bs, x, s);
+      break;
+    }
     case OP_PROJ: {
       StepScalars x = sc;
       x.cG = c->hp.bias_correction ? 1.f : 0.f;
@@ -1066,6 +1089,8 @@ adapm_status_t adapm_init(adapm_ctx** out, const adapm_block_t* table, int64_t n
   try {
     c->table.assign(table, table + nblocks);
     c->hp = *hp;
+    const char* nk = getenv("ADAPM_PROJ_KEEP");
+    c->keep_enabled = nk && nk[0] == '1';
     build_plan(c);
   } catch (const std::bad_alloc&) {
     delete c;

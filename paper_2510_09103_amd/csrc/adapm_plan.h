@@ -259,6 +259,11 @@ void launch_chol(const CholItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gemm_mfma(const GemmProblem* probs, const GemmTile* tiles, int64_t ntiles, Bases b, hipStream_t s);
 void launch_proj(int rt, bool w16, bool vel, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
                  StepScalars sc, hipStream_t s);
+// the same step for rank class 128, bf16 parameters, blockwise v, columns % 8 == 0 and <= proj_keep_max_cols():
+// stripes of proj_keep_rows() rows whose gradient stays on chip between the two passes (k_proj_keep.hip)
+void launch_proj_keep(const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, StepScalars sc, hipStream_t s);
+int proj_keep_rows();
+int proj_keep_max_cols();
 void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b, hipStream_t s);
 void launch_stripe(int rt, bool tra, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s);
 void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
