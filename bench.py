@@ -162,10 +162,12 @@ def main():
             torch.cuda.synchronize()
             w = (1.0 / T if T > 1 else 1.0) if kind == "refresh" else (T - 1.0) / T
             for k, (ms, cnt) in B.adapm_profile_read(opt.ctx).items():
-                d = out.setdefault(k, {"total_ms": 0.0, "launches": 0, "per_step_ms": 0.0})
+                d = out.setdefault(k, {"total_ms": 0.0, "launches": 0, "per_step_ms": 0.0, "step_ms": 0.0})
                 d["total_ms"] += ms
                 d["launches"] += cnt
                 d["per_step_ms"] += w * ms / len(sel)
+                d["step_ms"] = ms / len(sel)          # per step of the kind the kernel runs in
+                d["launches_per_step"] = cnt / len(sel)
         B.adapm_profile_enable(opt.ctx, False)
         for d in out.values():
             d["avg_ms"] = d["total_ms"] / d["launches"]
@@ -177,10 +179,16 @@ def main():
     def rank_class(b):
         return min(c for c in (32, 64, 128) if b.rank <= c) if b.rank <= 128 else 0
 
+    n_gd = sum(1 for k_ in range(1, wl.K + 1) if k_ != wl.K)      # iterations of Alg. 2 with a non-zero step (eta_K = 0)
+
     def roofline_of(label, k, refresh_step):
         """Roofline block of one kernel class: algorithmic bytes (HBM-bound kernels) or flops (the contractions of
-        Alg. 2) of ONE launch over its live average duration."""
+        Alg. 2) of one pass of the class over all of its blocks, over the live duration of that pass.  A pass is one
+        launch, or one launch per group of blocks where Alg. 2 runs group by group; the stripe kernels make one pass
+        per GD iteration."""
         roof = None
+        passes = n_gd if label.startswith("alg2_") else 1
+        k = dict(k, avg_ms=k["step_ms"] / passes, launches_per_pass=k["launches_per_step"] / passes)
         if label.startswith("fused_project") or label.startswith("fused_refresh_update"):
             rank = int(label.split("_r")[-1])
             alg = sum(block_bytes(b, refresh_step) for b in lr_blocks if rank_class(b) == rank)
@@ -211,7 +219,8 @@ def main():
                             "at the padded rank class"}
         if roof is None:
             return None
-        roof.update(kernel=label, frac=roof["achieved"] / roof["peak"], avg_ms=k["avg_ms"], traffic=None)
+        roof.update(kernel=label, frac=roof["achieved"] / roof["peak"], avg_ms=k["avg_ms"],
+                    launches_per_pass=k["launches_per_pass"], traffic=None)
         return roof
 
     opt = make(args.T)

@@ -58,6 +58,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int64_t wIr = -1, wIl = -1;                               // ws: the fragment images of R, L^T during Alg. 2 ...
   int64_t wIr2 = -1, wIl2 = -1;                             // ws: ... written by the stripes of one GD iteration for the next, hence two sets
   int64_t wIr0 = -1, wIl0 = -1;                             // ws: the same images of R_{t-1}, L_{t-1}^T (first iteration; Gram matrices)
+  int64_t wGpn = -1, wGpm = -1;                             // ws: partial sums of the Gram-type products over n and over m, where those are cut into segments
   int64_t wNu = -1;                                         // ws: normaliser of the optional scale-normalised Alg. 2 (one double)
   int64_t wB[4] = {-1, -1, -1, -1};                         // ws: fragment images of R R^T, R' R^T, L^T L, L^T L' (transposed as the fused GD step needs them)
   int64_t wT1 = -1, wT2 = -1;                               // ws: images of R_{t-1}^T and R_t^T for the fused update after Alg. 2
@@ -65,7 +66,7 @@ struct Layout {                      // byte offsets, -1 = absent
   int path = PATH_NONE;
 };
 
-enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM, OP_UPDATE_GROUPED, OP_COPY, OP_PROJ_KEEP };
+enum OpKind { OP_GEMM, OP_GEMM_MFMA, OP_CHOL, OP_VSTAT, OP_VFINAL, OP_UPDATE, OP_QSPLIT, OP_PROJ, OP_QFIMG, OP_STRIPE, OP_QTIMG, OP_REFRESH_UPDATE, OP_GRADNORM, OP_GRAM, OP_GNORM, OP_UPDATE_GROUPED, OP_COPY, OP_PROJ_KEEP, OP_GRAM_FIN, OP_REGAUGE_APPLY };
 
 struct GemmList {
   std::vector<GemmProblem> probs;
@@ -77,9 +78,10 @@ struct GemmList {
 
 struct Op {
   OpKind kind;
-  int index;          // GEMM*: gemm list; UPDATE / VSTAT / VFINAL / PROJ / QFIMG / STRIPE: which item list
+  int index;          // GEMM*: gemm list; UPDATE / VSTAT / VFINAL / PROJ / QFIMG / STRIPE / ...: which item list
   float cG, cC;       // UPDATE of low-rank blocks, PROJ
   const char* label;  // profiling name
+  int aux = 0;        // REFRESH_UPDATE: which list of block descriptors the items index
 };
 
 template <class T>
@@ -113,13 +115,13 @@ struct adapm_ctx {
   float grad_clip = 0.f;                           // threshold of the global gradient-norm clipping; <= 0: off
 
   DevList<BlockDev> blocks;
-  DevList<EwItem> ew[2];        // 0: full / no momentum; 1: low-rank, F64 path (the MFMA path updates in its fused kernels)
+  std::vector<DevList<EwItem>> ew;   // 0: full / no momentum; then one per group of low-rank blocks on the F64 path (the MFMA path updates in its fused kernels)
   DevList<VsItem> vs[2];        // 0: every step; 1: only on steps that run Alg. 2 (fused elsewhere)
   DevList<VfItem> vf[2];
   DevList<GrpItem> grp;         // full / no momentum blocks whose v groups fit a wavefront: statistic + update fused
   DevList<VsItem> gn;           // every gradient in pieces: sums of squares for the global norm
   DevList<SketchItem> sk;
-  DevList<CholItem> chol[2];    // per path
+  std::vector<DevList<CholItem>> chol;   // per group of low-rank blocks (T > 1)
   DevList<LrBlockDev> lrb;
   DevList<ProjItem> proj[12];   // (rank 32 / 64 / 128) x (fp32 / bf16 parameters) x (blockwise / per-element v)
   DevList<ProjItem> proj_keep;  // rank class 128, bf16 parameters, blockwise v, short rows: 64-row stripes whose G stays on chip
@@ -127,12 +129,17 @@ struct adapm_ctx {
   DevList<StripeProb> sprob;            //   stripe products G R^T and G^T L ...
   std::vector<DevList<ImgItem>> img;    //   ... per GD iteration: fragment images of R and L^T (only the first iteration has any: the stripes write the later ones)
   std::vector<DevList<StripeItem>> sit; //   ... per GD iteration x rank class: the stripes
+  std::vector<DevList<GramFinItem>> gfin; //   ... same index as gram: the sums over the segments of the long ones
   std::vector<DevList<GramItem>> gram;  //   ... per GD iteration: the four r x r Gram-type products, from the images, in pairs that share one
   std::vector<DevList<GnormItem>> gnorm; // optional scale-normalised Alg. 2: per (path, GD iteration) the normalisers
-  DevList<CopyItem> cp;                 // T = 1, MFMA path: the factors Alg. 2 leaves in the workspace -> state
-  DevList<RuBlockDev> rub;              // fused update after Alg. 2 (MFMA path): blocks, images of R^T, stripes
-  DevList<ImgItem> qt;
-  DevList<ProjItem> ru[6];              //   (rank class 32 / 64 / 128) x (fp32 / bf16 parameters)
+  // per group of low-rank blocks (a group runs Alg. 2 from start to end in one region of scratch, see build_plan):
+  std::vector<DevList<CopyItem>> cp;    // T = 1, MFMA path: the factors Alg. 2 leaves in the workspace -> state
+  std::vector<DevList<RuBlockDev>> rub; // fused update after Alg. 2 (MFMA path): blocks, images of R^T, stripes
+  std::vector<DevList<ImgItem>> qt;
+  std::vector<DevList<ProjItem>> ru;    //   6 per group: (rank class 32 / 64 / 128) x (fp32 / bf16 parameters)
+  int n_groups = 0;
+  int rg_gram = -1, rg_chol = -1;       // T > 1, MFMA path: the re-expression of all blocks' factors after the last group
+  DevList<RegaugeItem> rg_apply;
   std::vector<GemmList> gemms;
   std::vector<Op> seq_refresh, seq_project;
 
@@ -279,6 +286,12 @@ GemmProblem problem(int M, int N) {
   return p;
 }
 
+// segments a Gram-type product over K columns is cut into (one workgroup each)
+int gram_segments(int64_t K) {
+  const int64_t nch = (K + 63) / 64;
+  return (int)((nch + GRAM_SEG_CHUNKS - 1) / GRAM_SEG_CHUNKS);
+}
+
 std::vector<double> effective_step_sizes(int K) {
   // App. B: eta_k = 0.5 (1 + cos(pi k / K)), k = 1..K.  A zero step changes nothing and is skipped.
   std::vector<double> out;
@@ -292,18 +305,24 @@ std::vector<double> effective_step_sizes(int K) {
 // Alg. 2 + eq. 3-4 for the low-rank blocks of one contraction path, as batched GEMM launches.
 //   fast = false: fp64 vector-ALU GEMM, every intermediate kept in fp64;
 //   fast = true : split-bf16 MFMA GEMM, fp32 intermediates.
-void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
-  const int want = fast ? PATH_FAST : PATH_F64;
+// `ids`: the blocks of ONE group, all on the same contraction path; the group's scratch offsets are in c->lay.
+void plan_lowrank_refresh(adapm_ctx* c, bool fast, const std::vector<int64_t>& ids) {
   const adapm_hparams_t& hp = c->hp;
-  const int64_t nb = (int64_t)c->table.size();
   const double b1 = hp.beta1;
   const int idt = fast ? DT_F32 : DT_F64;
   const OpKind gk = fast ? OP_GEMM_MFMA : OP_GEMM;
-  bool any = false;
-  for (int64_t i = 0; i < nb; ++i) any = any || c->lay[i].path == want;
-  if (!any) return;
+  if (ids.empty()) return;
   const std::vector<double> etas = effective_step_sizes(hp.refresh_iters_K);
   const int n_eff = (int)etas.size();
+  // this group's lists
+  const int grp = c->n_groups++;
+  c->cp.emplace_back(); c->rub.emplace_back(); c->qt.emplace_back(); c->chol.emplace_back();
+  const int chol_id = (int)c->chol.size() - 1;
+  c->ru.resize(c->ru.size() + 6);
+  const int ru0 = 6 * grp;
+  const int img0 = (int)c->img.size(), sit0 = (int)c->sit.size(), gram0 = (int)c->gram.size();
+  const int ew_id = fast ? -1 : (int)c->ew.size();
+  if (!fast) c->ew.emplace_back();
   auto new_list = [&](bool mfma) {
     c->gemms.emplace_back();
     c->gemms.back().tile = mfma ? 128 : 64;
@@ -317,22 +336,32 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   constexpr int NXCD = 8;
   struct StripeWork { int prob; int64_t M, K; };
   std::vector<std::vector<StripeWork>> swork(fast ? 6 * n_eff : 0);   // per GD iteration: (rank class, G / G^T)
-  if (fast) { c->img.resize(n_eff); c->sit.resize(6 * n_eff); c->gram.resize(n_eff); }
-  const int l_pre = (n_eff == 0 && hp.refresh_period_T > 1) ? new_list(fast) : -1;
+  if (fast) { c->img.resize(img0 + n_eff); c->sit.resize(sit0 + 6 * n_eff); c->gram.resize(gram0 + n_eff); c->gfin.resize(gram0 + n_eff); }
+  auto IMG = [&](int e) -> DevList<ImgItem>& { return c->img[img0 + e]; };
+  auto GRAM = [&](int e) -> DevList<GramItem>& { return c->gram[gram0 + e]; };
+  // T > 1: the product-preserving orthonormalisation of R follows Alg. 2.  F64 path: inside the group, from the fp64
+  // factors in its scratch.  MFMA path: the group stores its factors to the state like a T = 1 step does, and one pass
+  // over all blocks re-expresses them in place afterwards (build_plan), whose serial Cholesky kernel would otherwise
+  // run once per group on a fraction of the machine.
+  const bool group_regauge = hp.refresh_period_T > 1 && !fast;
+  const int l_pre = (n_eff == 0 && group_regauge) ? new_list(fast) : -1;
   const int l_epi = fast ? -1 : new_list(false);      // m x n term of eq. 3-4 (the MFMA path never forms it)
-  const int l_gram = hp.refresh_period_T > 1 ? new_list(false) : -1;
-  const int l_fin = (hp.refresh_period_T > 1 || n_eff > 0) ? new_list(fast && hp.refresh_period_T <= 1) : -1;
-  for (int64_t i = 0; i < nb; ++i) {
+  const int l_gram = group_regauge ? new_list(false) : -1;
+  const int l_fin = (!fast && (group_regauge || n_eff > 0)) ? new_list(false) : -1;
+  for (int64_t i : ids) {
     const adapm_block_t& b = c->table[i];
     const Layout& L = c->lay[i];
-    if (L.path != want) continue;
     const int m = (int)b.rows, n = (int)b.cols, r = b.rank;
     const int gdt = b.grad_dtype == ADAPM_BF16 ? DT_BF16 : DT_F32;
     const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
     const Mat Lp = mat(SP_STATE, 0, L.sL, r, 1, DT_F32), Rp = mat(SP_STATE, 0, L.sR, n, 1, DT_F32);
     auto T = [](const Mat& a) { Mat t = a; t.s0 = a.s1; t.s1 = a.s0; return t; };
-    auto fL = [&](int which) { return mat(SP_WS, 0, which ? L.wLb : L.wLa, r, 1, idt); };
-    auto fR = [&](int which) { return mat(SP_WS, 0, which ? L.wRb : L.wRa, n, 1, idt); };
+    // Where the GD step rides on the stripe products, a workgroup reads and writes only the factor rows behind its own
+    // stripe (everything else comes from the images), so the iterations after the first update one working copy in
+    // place; the batched GEMM form reads whole rows of the old factor per output tile and alternates two copies.
+    const bool inplace = fast && stripe_ok(b);
+    auto fL = [&](int which) { return mat(SP_WS, 0, (which && !inplace) ? L.wLb : L.wLa, r, 1, idt); };
+    auto fR = [&](int which) { return mat(SP_WS, 0, (which && !inplace) ? L.wRb : L.wRa, n, 1, idt); };
     const Mat P = mat(SP_WS, 0, L.wP, r, 1, idt), S = mat(SP_WS, 0, L.wS, n, 1, idt);
     const Mat Grr = mat(SP_WS, 0, L.wGrr, r, 1, idt), Gpr = mat(SP_WS, 0, L.wGpr, r, 1, idt);
     const Mat Gll = mat(SP_WS, 0, L.wGll, r, 1, idt), Glp = mat(SP_WS, 0, L.wGlp, r, 1, idt);
@@ -357,14 +386,25 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
         const int64_t iR = img_r(e), iL = img_l(e);
         const int64_t iRn = e + 1 < n_eff ? img_r(e + 1) : -1, iLn = e + 1 < n_eff ? img_l(e + 1) : -1;
         if (e == 0) {
-          for (int ch = 0; ch < (n + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{Rc, r, n, ch, rc, iR});
-          for (int ch = 0; ch < (m + 63) / 64; ++ch) c->img[e].h.push_back(ImgItem{LcT, r, m, ch, rc, iL});
+          for (int ch = 0; ch < (n + 63) / 64; ++ch) IMG(e).h.push_back(ImgItem{Rc, r, n, ch, rc, iR});
+          for (int ch = 0; ch < (m + 63) / 64; ++ch) IMG(e).h.push_back(ImgItem{LcT, r, m, ch, rc, iL});
         }
         // R' R^T with R R^T (contraction over n) and L^T L' with L^T L (over m); longest contraction first
         // ... each with the fragment images of its two results, which the GD step on the stripes multiplies by: image
         // row a, column k = B[k][a] with B = R' R^T, R R^T for L and B = (L^T L')^T, L^T L for R^T
-        c->gram[e].h.push_back(GramItem{L.wIr0, iR, L.wGpr, L.wGrr, L.wB[1], L.wB[0], n, r, rc, 0});   // R' R^T and R R^T
-        c->gram[e].h.push_back(GramItem{L.wIl0, iL, L.wGlp, L.wGll, L.wB[3], L.wB[2], m, r, rc, 1});   // (L'^T L)^T = L^T L' and L^T L
+        // a contraction longer than GRAM_SEG_CHUNKS chunks is cut into segments (one workgroup each, partial sums added
+        // in segment order by a second small launch): the longest workgroup of a launch then stays short
+        auto add_gram = [&](int64_t off_x, int64_t off_s, int64_t o_xs, int64_t o_ss, int64_t i_xs, int64_t i_ss, int K, int tx,
+                            int64_t off_part) {
+          const int nch = (K + 63) / 64, nseg = gram_segments(K), per = (nch + nseg - 1) / nseg;
+          for (int sg = 0; sg < nseg; ++sg)
+            GRAM(e).h.push_back(GramItem{off_x, off_s, o_xs, o_ss, i_xs, i_ss, K, r, rc, tx, sg * per, std::min(nch, (sg + 1) * per),
+                                         sg, nseg, off_part});
+          if (nseg > 1)
+            c->gfin[gram0 + e].h.push_back(GramFinItem{off_part, o_xs, o_ss, i_xs, i_ss, r, rc, tx, nseg, off_x == off_s ? 1 : 0, 0});
+        };
+        add_gram(L.wIr0, iR, L.wGpr, L.wGrr, L.wB[1], L.wB[0], n, 0, L.wGpn);   // R' R^T and R R^T
+        add_gram(L.wIl0, iL, L.wGlp, L.wGll, L.wB[3], L.wB[2], m, 1, L.wGpm);   // (L'^T L)^T = L^T L' and L^T L
         // the GD step rides on the stripes: L_new = L + s (-eta L (R R^T) + eta b1 L' (R' R^T) + eta (1-b1) G R^T) on the
         // rows of a stripe of G, R_new likewise on the columns of R behind a stripe of G^T.  The r x r matrices enter
         // as images with row a, column k = B[k][a]: (R R^T)^T and (R' R^T)^T for L; L^T L and L^T L' for R^T.
@@ -431,10 +471,10 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       d.param_dtype = b.param_dtype; d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
       d.a1 = hp.bias_correction ? 1.f : 0.f; d.a2 = hp.bias_correction ? -1.f : 1.f;
       d.l1 = Lp.ref; d.l2 = Lc.ref; d.q1 = Rp.ref; d.q2 = Rc.ref; d.off_img1 = L.wT1; d.off_img2 = L.wT2; d.off_v = L.sv;
-      c->rub.h.push_back(d);
+      c->rub[grp].h.push_back(d);
       for (int ch = 0; ch < (n + 63) / 64; ++ch) {
-        if (hp.bias_correction && !(stripe_ok(b) && n_eff > 0)) c->qt.h.push_back(ImgItem{Rp, r, n, ch, d.rc, L.wT1});
-        if (!(stripe_ok(b) && n_eff > 0)) c->qt.h.push_back(ImgItem{Rc, r, n, ch, d.rc, L.wT2});   // else: written by the stripes
+        if (hp.bias_correction && !(stripe_ok(b) && n_eff > 0)) c->qt[grp].h.push_back(ImgItem{Rp, r, n, ch, d.rc, L.wT1});
+        if (!(stripe_ok(b) && n_eff > 0)) c->qt[grp].h.push_back(ImgItem{Rc, r, n, ch, d.rc, L.wT2});   // else: written by the stripes
       }
     } else {
       // m x n low-rank term of m^c (eq. 4): C = L'R' - L R, or L R without the correction
@@ -448,22 +488,33 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       }
       p.Out = C;
       add_problem(c->gemms[l_epi], p);
+      for (int64_t s0 = 0; s0 < (int64_t)m * n; s0 += EW_CHUNK)
+        c->ew[ew_id].h.push_back(EwItem{s0, (int32_t)i, (int32_t)std::min<int64_t>(EW_CHUNK, (int64_t)m * n - s0)});
     }
-    if (hp.refresh_period_T > 1) {
+    if (fast && hp.refresh_period_T > 1) {
+      // the pass over all blocks that follows the last group: Gram matrix of the stored R in fp64, Cholesky, in place
+      const Mat G64 = mat(SP_WS, 0, L.wG64, r, 1, DT_F64);
+      p = problem(r, r); p.A1 = Rp; p.B1 = T(Rp); p.K1 = n; p.a1 = 1.0; p.Out = G64;
+      add_problem(c->gemms[c->rg_gram], p, 0, true);
+      c->chol[c->rg_chol].h.push_back(CholItem{L.wG64, L.wCinv, r, 0});
+      for (int f = 0; f < n; f += 64) c->rg_apply.h.push_back(RegaugeItem{L.sR, L.wCinv, r, n, f, 0});
+      for (int f = 0; f < m; f += 64) c->rg_apply.h.push_back(RegaugeItem{L.sL, L.wG64, r, m, f, 1});
+    }
+    if (group_regauge) {
       // product-preserving orthonormalisation of R, always in fp64
       const Mat G64 = mat(SP_WS, 0, L.wG64, r, 1, DT_F64), Cinv = mat(SP_WS, 0, L.wCinv, r, 1, DT_F64);
       p = problem(r, r); p.A1 = Rc; p.B1 = T(Rc); p.K1 = n; p.a1 = 1.0; p.Out = G64;
       add_problem(c->gemms[l_gram], p, 0, true);      // the Cholesky factorisation reads the lower triangle only
-      c->chol[fast ? 1 : 0].h.push_back(CholItem{L.wG64, L.wCinv, r, 0});
+      c->chol[chol_id].h.push_back(CholItem{L.wG64, L.wCinv, r, 0});
       // C^-1 and C are lower triangular
       p = problem(r, n); p.A1 = Cinv; p.B1 = Rc; p.K1 = r; p.a1 = 1.0; p.tri = 1; p.Out = Rp; add_problem(c->gemms[l_fin], p);
       p = problem(m, r); p.A1 = Lc; p.B1 = G64; p.K1 = r; p.a1 = 1.0; p.tri = 2; p.Out = Lp; add_problem(c->gemms[l_fin], p);
     } else if (n_eff > 0) {
       if (fast) {
         for (int64_t f = 0; f < (int64_t)m * r; f += COPY_CHUNK)
-          c->cp.h.push_back(CopyItem{Lc.ref, Lp.ref, f, (int32_t)std::min<int64_t>(COPY_CHUNK, (int64_t)m * r - f), 0});
+          c->cp[grp].h.push_back(CopyItem{Lc.ref, Lp.ref, f, (int32_t)std::min<int64_t>(COPY_CHUNK, (int64_t)m * r - f), 0});
         for (int64_t f = 0; f < (int64_t)r * n; f += COPY_CHUNK)
-          c->cp.h.push_back(CopyItem{Rc.ref, Rp.ref, f, (int32_t)std::min<int64_t>(COPY_CHUNK, (int64_t)r * n - f), 0});
+          c->cp[grp].h.push_back(CopyItem{Rc.ref, Rp.ref, f, (int32_t)std::min<int64_t>(COPY_CHUNK, (int64_t)r * n - f), 0});
       } else {
         p = problem(m, r); p.X = Lc; p.g = 1.0; p.Out = Lp; add_problem(c->gemms[l_fin], p);
         p = problem(r, n); p.X = Rc; p.g = 1.0; p.Out = Rp; add_problem(c->gemms[l_fin], p);
@@ -489,15 +540,17 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
     size_t longest = 0;
     for (auto& q : per) longest = std::max(longest, q.size());
     for (size_t q = 0; q < longest; ++q)
-      for (int x = 0; x < NXCD; ++x) c->sit[w].h.push_back(q < per[x].size() ? per[x][q] : StripeItem{-1, 0});
+      for (int x = 0; x < NXCD; ++x) c->sit[sit0 + w].h.push_back(q < per[x].size() ? per[x][q] : StripeItem{-1, 0});
   }
   std::vector<Op>& seq = c->seq_refresh;
   for (int e = 0; e < n_eff; ++e) {
-    const bool stripes = fast && !c->gram[e].h.empty();
+    const bool stripes = fast && !GRAM(e).h.empty();
     if (stripes) {
-      if (!c->img[e].h.empty()) seq.push_back(Op{OP_QFIMG, e, 0, 0, "alg2_factor_images"});
-      std::stable_sort(c->gram[e].h.begin(), c->gram[e].h.end(), [](const GramItem& a, const GramItem& b) { return a.K > b.K; });
-      seq.push_back(Op{OP_GRAM, e, 0, 0, "alg2_gram_products"});
+      if (!IMG(e).h.empty()) seq.push_back(Op{OP_QFIMG, img0 + e, 0, 0, "alg2_factor_images"});
+      std::stable_sort(GRAM(e).h.begin(), GRAM(e).h.end(),
+                       [](const GramItem& a, const GramItem& b) { return a.c1 - a.c0 > b.c1 - b.c0; });
+      seq.push_back(Op{OP_GRAM, gram0 + e, 0, 0, "alg2_gram_products"});
+      if (!c->gfin[gram0 + e].h.empty()) seq.push_back(Op{OP_GRAM_FIN, gram0 + e, 0, 0, "alg2_gram_segments_sum"});
     }
     if (!c->gemms[listA[e]].tiles.empty())
       seq.push_back(Op{gk, listA[e], 0, 0, fast ? "alg2_products_mfma" : "alg2_products_f64"});
@@ -507,7 +560,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       static const char* names[6] = {"alg2_stripe_step_L_r32", "alg2_stripe_step_R_r32", "alg2_stripe_step_L_r64",
                                      "alg2_stripe_step_R_r64", "alg2_stripe_step_L_r128", "alg2_stripe_step_R_r128"};
       for (int k = 0; k < 6; ++k)
-        if (!c->sit[6 * e + k].h.empty()) seq.push_back(Op{OP_STRIPE, 6 * e + k, 0, 0, names[k]});
+        if (!c->sit[sit0 + 6 * e + k].h.empty()) seq.push_back(Op{OP_STRIPE, sit0 + 6 * e + k, 0, 0, names[k]});
     }
     if (!c->gemms[listB[e]].tiles.empty())
       seq.push_back(Op{gk, listB[e], 0, 0, fast ? "alg2_update_mfma" : "alg2_update_f64"});
@@ -517,16 +570,17 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
   const float cC = hp.bias_correction ? (float)(b1 / (1.0 - b1)) : 1.f;
   if (fast) {
     // stripes of the fused update, per (rank class, parameter type), whole blocks dealt to XCDs
-    if (!c->qt.h.empty()) seq.push_back(Op{OP_QTIMG, 0, 0, 0, "update_factor_images"});
+    if (!c->qt[grp].h.empty()) seq.push_back(Op{OP_QTIMG, grp, 0, 0, "update_factor_images"});
     for (int cls = 0; cls < 6; ++cls) {
       const int rank = 32 << (cls >> 1);
       const int pdt = (cls & 1) ? ADAPM_BF16 : ADAPM_F32;
       std::vector<size_t> ids;
-      for (size_t k = 0; k < c->rub.h.size(); ++k)
-        if (c->rub.h[k].rc == rank && c->rub.h[k].param_dtype == pdt) ids.push_back(k);
+      const std::vector<RuBlockDev>& rubs = c->rub[grp].h;
+      for (size_t k = 0; k < rubs.size(); ++k)
+        if (rubs[k].rc == rank && rubs[k].param_dtype == pdt) ids.push_back(k);
       if (ids.empty()) continue;
       std::stable_sort(ids.begin(), ids.end(), [&](size_t a, size_t b2) {
-        const RuBlockDev &x = c->rub.h[a], &y = c->rub.h[b2];
+        const RuBlockDev &x = rubs[a], &y = rubs[b2];
         if (x.n != y.n) return x.n > y.n;
         return (double)x.m * x.n > (double)y.m * y.n;
       });
@@ -535,46 +589,43 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast) {
       for (size_t k : ids) {
         int x = 0;
         for (int q = 1; q < NXCD; ++q) if (load[q] < load[x]) x = q;
-        const RuBlockDev& d = c->rub.h[k];
+        const RuBlockDev& d = rubs[k];
         for (int r0 = 0; r0 < d.m; r0 += 128) per[x].push_back(ProjItem{(int32_t)k, r0});
         load[x] += (double)d.m * d.n;
       }
       size_t longest = 0;
       for (auto& q : per) longest = std::max(longest, q.size());
       for (size_t q = 0; q < longest; ++q)
-        for (int x = 0; x < NXCD; ++x) c->ru[cls].h.push_back(q < per[x].size() ? per[x][q] : ProjItem{-1, 0});
+        for (int x = 0; x < NXCD; ++x) c->ru[ru0 + cls].h.push_back(q < per[x].size() ? per[x][q] : ProjItem{-1, 0});
       static const char* names[3] = {"fused_refresh_update_r32", "fused_refresh_update_r64", "fused_refresh_update_r128"};
-      seq.push_back(Op{OP_REFRESH_UPDATE, cls, cG, cC, names[cls >> 1]});
+      seq.push_back(Op{OP_REFRESH_UPDATE, ru0 + cls, cG, cC, names[cls >> 1], grp});
     }
   } else {
     seq.push_back(Op{gk, l_epi, 0, 0, "reconstruct_f64"});
-    seq.push_back(Op{OP_UPDATE, 1, cG, cC, "update_lowrank"});
+    seq.push_back(Op{OP_UPDATE, ew_id, cG, cC, "update_lowrank"});
   }
   if (l_gram >= 0) {
     seq.push_back(Op{OP_GEMM, l_gram, 0, 0, "regauge_gram_f64"});
-    seq.push_back(Op{OP_CHOL, fast ? 1 : 0, 0, 0, "regauge_cholesky_f64"});
+    seq.push_back(Op{OP_CHOL, chol_id, 0, 0, "regauge_cholesky_f64"});
   }
   if (l_fin >= 0 && !c->gemms[l_fin].tiles.empty()) {
-    const bool f64_fin = hp.refresh_period_T > 1;
+    const bool f64_fin = group_regauge;
     seq.push_back(Op{f64_fin ? OP_GEMM : gk, l_fin, 0, 0, f64_fin ? "regauge_apply_f64" : "store_factors"});
   }
-  if (fast && !c->cp.h.empty()) seq.push_back(Op{OP_COPY, 0, 0, 0, "store_factors"});
+  if (fast && !c->cp[grp].h.empty()) seq.push_back(Op{OP_COPY, grp, 0, 0, "store_factors"});
 }
 
 // step with R held, F64 path: four batched GEMM launches and the update kernel
-void plan_lowrank_project_f64(adapm_ctx* c) {
+// `ids`: one group of blocks (the scratch of a group is reused by the next); ew_id: the group's element-wise list
+void plan_lowrank_project_f64(adapm_ctx* c, const std::vector<int64_t>& ids, int ew_id) {
   const adapm_hparams_t& hp = c->hp;
-  const int64_t nb = (int64_t)c->table.size();
   const double b1 = hp.beta1;
-  bool any = false;
-  for (int64_t i = 0; i < nb; ++i) any = any || c->lay[i].path == PATH_F64;
-  if (!any) return;
+  if (ids.empty()) return;
   auto new_list = [&]() { c->gemms.emplace_back(); return (int)c->gemms.size() - 1; };
   const int l_p = new_list(), l_d = new_list(), l_l = new_list(), l_c = new_list();
-  for (int64_t i = 0; i < nb; ++i) {
+  for (int64_t i : ids) {
     const adapm_block_t& b = c->table[i];
     const Layout& L = c->lay[i];
-    if (L.path != PATH_F64) continue;
     const int m = (int)b.rows, n = (int)b.cols, r = b.rank;
     const int gdt = b.grad_dtype == ADAPM_BF16 ? DT_BF16 : DT_F32;
     const Mat G = mat(SP_GRAD, (int32_t)i, 0, n, 1, gdt);
@@ -596,7 +647,7 @@ void plan_lowrank_project_f64(adapm_ctx* c) {
   seq.push_back(Op{OP_GEMM, l_d, 0, 0, "project_residual_f64"});
   seq.push_back(Op{OP_GEMM, l_l, 0, 0, "project_store_L_f64"});
   seq.push_back(Op{OP_GEMM, l_c, 0, 0, "reconstruct_f64"});
-  seq.push_back(Op{OP_UPDATE, 1, hp.bias_correction ? 1.f : 0.f, 1.f, "update_lowrank"});
+  seq.push_back(Op{OP_UPDATE, ew_id, hp.bias_correction ? 1.f : 0.f, 1.f, "update_lowrank"});
 }
 
 // step with R held, MFMA path: Q^T split once, then one fused launch per rank class.  Stripes of one
@@ -673,6 +724,54 @@ void plan_lowrank_project_fast(adapm_ctx* c) {
 }
 
 // Lay out state / workspace and build every work list.
+// Scratch of one low-rank block while its group runs Alg. 2 (and, on the F64 path, a step with R held): laid out
+// from `base` on; returns the end.  dry = true only measures.
+size_t layout_block_scratch(const adapm_block_t& b, const adapm_hparams_t& hp, Layout& L, size_t base, bool dry) {
+  size_t wo = base;
+  Layout tmp;
+  Layout& T = dry ? tmp : L;
+  auto walloc = [&](size_t bytes) { int64_t o = (int64_t)wo; wo += align_up(bytes); return o; };
+  const int64_t m = b.rows, n = b.cols, r = b.rank;
+  const bool fast = L.path == PATH_FAST, stripes = fast && stripe_ok(b);
+  // F64 path: every intermediate of a step stays in fp64, only the state is rounded to fp32
+  const size_t es = fast ? 4 : 8;
+  T.wLa = walloc(es * m * r); T.wRa = walloc(es * r * n);
+  // the second working copy of the factors: only where the GD step runs as batched GEMMs (see plan_lowrank_refresh)
+  if (!stripes) { T.wLb = walloc(es * m * r); T.wRb = walloc(es * r * n); }
+  // G R^T and L^T G: blocks whose GD step rides on the stripe products never store them
+  if (!stripes) { T.wP = walloc(es * m * r); T.wS = walloc(es * r * n); }
+  T.wGrr = walloc(es * r * r); T.wGpr = walloc(es * r * r);
+  T.wGll = walloc(es * r * r); T.wGlp = walloc(es * r * r);
+  if (hp.refresh_period_T > 1 && !fast) { T.wG64 = walloc(8 * r * r); T.wCinv = walloc(8 * r * r); }
+  T.wNu = walloc(8);
+  if (fast) {
+    T.wT1 = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
+    T.wT2 = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
+  } else {
+    T.wC = walloc(4 * m * n);
+  }
+  if (stripes) {
+    T.wIr = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
+    T.wIl = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
+    T.wIr2 = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
+    T.wIl2 = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
+    T.wIr0 = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
+    T.wIl0 = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
+    for (int k = 0; k < 4; ++k) T.wB[k] = walloc(proj_qf_bytes(rank_class((int)r), (int)r));
+    const size_t rc = (size_t)rank_class((int)r);
+    if (gram_segments(n) > 1) T.wGpn = walloc((size_t)gram_segments(n) * 2 * rc * rc * 4);
+    if (gram_segments(m) > 1) T.wGpm = walloc((size_t)gram_segments(m) * 2 * rc * rc * 4);
+  }
+  return wo;
+}
+
+// Lay out state / workspace and build every work list.
+//
+// Workspace = [what has to survive from step to step or is global | scratch of ONE group of low-rank blocks].
+// Alg. 2 (and the F64 form of the step with R held) runs group by group, every group from its first launch to its
+// last before the next one starts in the same scratch, so that the scratch scales with a group, not with the
+// model.  A group holds as many blocks (in table order, per contraction path) as fit a budget chosen so that the
+// whole workspace stays below the size of the optimizer state; the largest single block sets the minimum.
 void build_plan(adapm_ctx* c) {
   const int64_t nb = (int64_t)c->table.size();
   const adapm_hparams_t& hp = c->hp;
@@ -689,34 +788,12 @@ void build_plan(adapm_ctx* c) {
     if (b.mom_mode == ADAPM_MOM_LOWRANK) {
       L.sL = salloc(4 * m * r);
       L.sR = salloc(4 * r * n);
-      // F64 path: every intermediate of a step stays in fp64, only the state is rounded to fp32
-      const size_t es = L.path == PATH_FAST ? 4 : 8;
-      L.wLa = walloc(es * m * r); L.wRa = walloc(es * r * n);
-      L.wLb = walloc(es * m * r); L.wRb = walloc(es * r * n);
-      // G R^T and L^T G: blocks whose GD step rides on the stripe products never store them
-      if (!(L.path == PATH_FAST && stripe_ok(b))) { L.wP = walloc(es * m * r); L.wS = walloc(es * r * n); }
-      L.wGrr = walloc(es * r * r); L.wGpr = walloc(es * r * r);
-      L.wGll = walloc(es * r * r); L.wGlp = walloc(es * r * r);
-      L.wG64 = walloc(8 * r * r); L.wCinv = walloc(8 * r * r);
-      L.wNu = walloc(8);
-      if (L.path == PATH_FAST) {
-        L.wT1 = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
-        L.wT2 = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
-      } else {
-        L.wC = walloc(4 * m * n);
-      }
-      if (L.path == PATH_FAST && stripe_ok(b)) {
-        L.wIr = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
-        L.wIl = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
-        L.wIr2 = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
-        L.wIl2 = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
-        L.wIr0 = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
-        L.wIl0 = walloc(proj_qf_bytes(rank_class((int)r), (int)m));
-        for (int k = 0; k < 4; ++k) L.wB[k] = walloc(proj_qf_bytes(rank_class((int)r), (int)r));
-      }
+      // kept between two runs of Alg. 2: the bf16 (hi, lo) images of the held R
       if (L.path == PATH_FAST && hp.refresh_period_T > 1) {
         L.wQf = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
         L.wTimg = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
+        L.wG64 = walloc(8 * r * r);        // Gram matrix of R, then its Cholesky factor C, and C^-1: the pass over all
+        L.wCinv = walloc(8 * r * r);       // blocks that follows the last group's Alg. 2
       }
       c->n_lowrank++;
     } else if (b.mom_mode == ADAPM_MOM_FULL) {
@@ -726,6 +803,8 @@ void build_plan(adapm_ctx* c) {
     L.sv = salloc(4 * L.nv);
   }
   c->state_bytes = so;
+  c->ew.clear();
+  c->ew.emplace_back();          // list 0: full / no momentum blocks
 
   // device block table, element-wise chunks, v statistics
   int64_t npart = 0;
@@ -735,7 +814,7 @@ void build_plan(adapm_ctx* c) {
     BlockDev d;
     d.numel = b.rows * b.cols;
     d.group_elems = group_elems(b);
-    d.off_m = L.sm; d.off_v = L.sv; d.off_C = L.wC;
+    d.off_m = L.sm; d.off_v = L.sv; d.off_C = -1;      // off_C: set when the block's group is laid out
     d.param_dtype = b.param_dtype; d.grad_dtype = b.grad_dtype;
     d.mom_mode = b.mom_mode; d.v_mode = b.v_mode;
     d.lr_scale = b.lr_scale; d.wd = b.weight_decay;
@@ -749,11 +828,11 @@ void build_plan(adapm_ctx* c) {
         c->grp.h.push_back(GrpItem{g0, (int32_t)i, (int32_t)std::min<int64_t>(per, L.nv - g0)});
       continue;
     }
-    // low-rank blocks on the MFMA path are updated by the fused stripe kernels, not by the element-wise kernel
-    if (L.path != PATH_FAST) {
-      auto& ew = c->ew[L.path == PATH_NONE ? 0 : 1].h;
+    // low-rank blocks are updated by their group's launches (element-wise on the F64 path, fused stripe kernels on
+    // the MFMA path)
+    if (L.path == PATH_NONE) {
       for (int64_t s = 0; s < d.numel; s += EW_CHUNK)
-        ew.push_back(EwItem{s, (int32_t)i, (int32_t)std::min<int64_t>(EW_CHUNK, d.numel - s)});
+        c->ew[0].h.push_back(EwItem{s, (int32_t)i, (int32_t)std::min<int64_t>(EW_CHUNK, d.numel - s)});
     }
     if (b.v_mode != ADAPM_V_ELEMENT) {
       // on the MFMA path with T > 1 the fused kernel finishes fusable groups itself on steps with R held (list 1: only
@@ -793,7 +872,7 @@ void build_plan(adapm_ctx* c) {
   }
   c->off_gn_partials = (int64_t)wo; wo += align_up(8 * c->gn.h.size());
   c->off_gn_out = (int64_t)wo; wo += align_up(8);
-  c->ws_bytes = wo;
+  const size_t persistent = wo;
 
   // ---- every step starts with the v statistics and the full / no-momentum blocks
   for (int kind = 0; kind < 2; ++kind) {
@@ -807,13 +886,56 @@ void build_plan(adapm_ctx* c) {
     if (!c->ew[0].h.empty()) seq.push_back(Op{OP_UPDATE, 0, 0, 0, "update_full"});
     if (!c->grp.h.empty()) seq.push_back(Op{OP_UPDATE_GROUPED, 0, 0, 0, "update_full_grouped"});
   }
+  c->ws_bytes = persistent;
   if (c->n_lowrank == 0) return;
-  plan_lowrank_refresh(c, false);
-  plan_lowrank_refresh(c, true);
+
+  // ---- groups of low-rank blocks: scratch budget, then per group the layout and the launches
+  size_t largest = 0;
+  for (int64_t i = 0; i < nb; ++i)
+    if (c->lay[i].path != PATH_NONE) largest = std::max(largest, layout_block_scratch(c->table[i], hp, c->lay[i], 0, true));
+  const size_t floor_bytes = (size_t)32 << 20;
+  size_t budget = c->state_bytes > persistent + floor_bytes ? c->state_bytes - persistent : floor_bytes;
+  budget = std::max(budget - budget / 16, largest);          // a margin below the state size; at least one block
+  size_t scratch_max = 0;
   if (hp.refresh_period_T > 1) {
-    plan_lowrank_project_f64(c);
-    plan_lowrank_project_fast(c);
+    c->gemms.emplace_back();
+    c->rg_gram = (int)c->gemms.size() - 1;
+    c->chol.emplace_back();              // groups append theirs behind it (plan_lowrank_refresh indexes by its own position)
+    c->rg_chol = (int)c->chol.size() - 1;
   }
+  for (int path : {PATH_F64, PATH_FAST}) {
+    std::vector<int64_t> ids;
+    size_t used = 0;
+    auto flush = [&]() {
+      if (ids.empty()) return;
+      size_t at = persistent;
+      for (int64_t i : ids) {
+        at = layout_block_scratch(c->table[i], hp, c->lay[i], at, false);
+        c->blocks.h[i].off_C = c->lay[i].wC;
+      }
+      scratch_max = std::max(scratch_max, at - persistent);
+      const int ew_before = (int)c->ew.size();
+      plan_lowrank_refresh(c, path == PATH_FAST, ids);
+      if (hp.refresh_period_T > 1 && path == PATH_F64) plan_lowrank_project_f64(c, ids, ew_before);
+      ids.clear();
+      used = 0;
+    };
+    for (int64_t i = 0; i < nb; ++i) {
+      if (c->lay[i].path != path) continue;
+      const size_t need = layout_block_scratch(c->table[i], hp, c->lay[i], 0, true);
+      if (!ids.empty() && used + need > budget) flush();
+      ids.push_back(i);
+      used += need;
+    }
+    flush();
+  }
+  c->ws_bytes = persistent + scratch_max;
+  if (hp.refresh_period_T > 1 && !c->rg_apply.h.empty()) {
+    c->seq_refresh.push_back(Op{OP_GEMM, c->rg_gram, 0, 0, "regauge_gram_f64"});
+    c->seq_refresh.push_back(Op{OP_CHOL, c->rg_chol, 0, 0, "regauge_cholesky_f64"});
+    c->seq_refresh.push_back(Op{OP_REGAUGE_APPLY, 0, 0, 0, "regauge_apply_in_place"});
+  }
+  if (hp.refresh_period_T > 1) plan_lowrank_project_fast(c);
 }
 
 template <class T>
@@ -826,16 +948,21 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
   HIP_TRY(hipGetDevice(&dev));
   const size_t nb = c->table.size();
   size_t total = bytes_of(c->blocks.h) + bytes_of(c->sk.h) + bytes_of(c->lrb.h) + bytes_of(c->qs.h) + bytes_of(c->proj_keep.h) +
-                 bytes_of(c->sprob.h) + bytes_of(c->cp.h) + bytes_of(c->rub.h) + bytes_of(c->qt.h) + bytes_of(c->gn.h) + bytes_of(c->grp.h) +
+                 bytes_of(c->sprob.h) + bytes_of(c->gn.h) + bytes_of(c->grp.h) + bytes_of(c->rg_apply.h) +
                  adapm_ctx::NSLOT * align_up(2 * nb * sizeof(void*));
-  for (int i = 0; i < 6; ++i) total += bytes_of(c->ru[i].h);
+  for (auto& l : c->cp) total += bytes_of(l.h);
+  for (auto& l : c->rub) total += bytes_of(l.h);
+  for (auto& l : c->qt) total += bytes_of(l.h);
+  for (auto& l : c->ru) total += bytes_of(l.h);
+  for (auto& l : c->chol) total += bytes_of(l.h);
+  for (auto& l : c->ew) total += bytes_of(l.h);
   for (auto& l : c->img) total += bytes_of(l.h);
   for (auto& l : c->sit) total += bytes_of(l.h);
   for (auto& l : c->gram) total += bytes_of(l.h);
+  for (auto& l : c->gfin) total += bytes_of(l.h);
   for (auto& l : c->gnorm) total += bytes_of(l.h);
-  for (int i = 0; i < 2; ++i) total += bytes_of(c->ew[i].h);
   for (int i = 0; i < 12; ++i) total += bytes_of(c->proj[i].h);
-  for (int i = 0; i < 2; ++i) total += bytes_of(c->vs[i].h) + bytes_of(c->vf[i].h) + bytes_of(c->chol[i].h);
+  for (int i = 0; i < 2; ++i) total += bytes_of(c->vs[i].h) + bytes_of(c->vf[i].h);
   for (auto& g : c->gemms) total += bytes_of(g.probs) + bytes_of(g.tiles);
   HIP_TRY(hipMalloc((void**)&c->arena, total));
   size_t off = 0;
@@ -847,15 +974,20 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     return dst;
   };
 #define PUT_LIST(L) (L).d = (decltype((L).d))put((L).h.data(), (L).h.size() * sizeof((L).h[0]))
-  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->proj_keep); PUT_LIST(c->sprob); PUT_LIST(c->cp); PUT_LIST(c->rub); PUT_LIST(c->qt); PUT_LIST(c->gn); PUT_LIST(c->grp);
-  for (int i = 0; i < 6; ++i) PUT_LIST(c->ru[i]);
+  PUT_LIST(c->blocks); PUT_LIST(c->sk); PUT_LIST(c->lrb); PUT_LIST(c->qs); PUT_LIST(c->proj_keep); PUT_LIST(c->sprob); PUT_LIST(c->gn); PUT_LIST(c->grp); PUT_LIST(c->rg_apply);
+  for (auto& l : c->cp) PUT_LIST(l);
+  for (auto& l : c->rub) PUT_LIST(l);
+  for (auto& l : c->qt) PUT_LIST(l);
+  for (auto& l : c->ru) PUT_LIST(l);
+  for (auto& l : c->chol) PUT_LIST(l);
+  for (auto& l : c->ew) PUT_LIST(l);
   for (auto& l : c->img) PUT_LIST(l);
   for (auto& l : c->sit) PUT_LIST(l);
   for (auto& l : c->gram) PUT_LIST(l);
+  for (auto& l : c->gfin) PUT_LIST(l);
   for (auto& l : c->gnorm) PUT_LIST(l);
-  for (int i = 0; i < 2; ++i) PUT_LIST(c->ew[i]);
   for (int i = 0; i < 12; ++i) PUT_LIST(c->proj[i]);
-  for (int i = 0; i < 2; ++i) { PUT_LIST(c->vs[i]); PUT_LIST(c->vf[i]); PUT_LIST(c->chol[i]); }
+  for (int i = 0; i < 2; ++i) { PUT_LIST(c->vs[i]); PUT_LIST(c->vf[i]); }
 #undef PUT_LIST
   for (auto& g : c->gemms) {
     g.d_probs = (GemmProblem*)put(g.probs.data(), g.probs.size() * sizeof(GemmProblem));
@@ -979,22 +1111,28 @@ adapm_status_t run_op(adapm_ctx* c, const Op& op, Bases& bs, const StepScalars& 
       launch_update_grouped(c->blocks.d, c->grp.d, (int64_t)c->grp.h.size(), bs, sc, s);
       break;
     case OP_COPY:
-      launch_copy(c->cp.d, (int64_t)c->cp.h.size(), bs, s);
+      launch_copy(c->cp[op.index].d, (int64_t)c->cp[op.index].h.size(), bs, s);
       break;
     case OP_GNORM:
       launch_gram_norm(c->gnorm[op.index].d, (int64_t)c->gnorm[op.index].h.size(), bs, s);
+      break;
+    case OP_REGAUGE_APPLY:
+      launch_regauge_apply(c->rg_apply.d, (int64_t)c->rg_apply.h.size(), bs, s);
+      break;
+    case OP_GRAM_FIN:
+      launch_gram_finish(c->gfin[op.index].d, (int64_t)c->gfin[op.index].h.size(), bs, s);
       break;
     case OP_GRAM:
       launch_gram(c->gram[op.index].d, (int64_t)c->gram[op.index].h.size(), bs, s);
       break;
     case OP_QTIMG:
-      launch_qt_image(c->qt.d, (int64_t)c->qt.h.size(), bs, s);
+      launch_qt_image(c->qt[op.index].d, (int64_t)c->qt[op.index].h.size(), bs, s);
       break;
     case OP_REFRESH_UPDATE: {
       StepScalars x = sc;
       x.cG = op.cG; x.cC = op.cC;
-      launch_refresh_update(1 << (op.index >> 1), (op.index & 1) != 0, c->ru[op.index].d, (int64_t)c->ru[op.index].h.size(),
-                            c->rub.d, bs, x, s);
+      launch_refresh_update(1 << ((op.index % 6) >> 1), (op.index & 1) != 0, c->ru[op.index].d, (int64_t)c->ru[op.index].h.size(),
+                            c->rub[op.aux].d, bs, x, s);
       break;
     }
     case OP_PROJ_KEEP: {

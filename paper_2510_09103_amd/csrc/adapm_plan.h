@@ -187,6 +187,17 @@ struct GramItem {          // one workgroup: Out_xs = X S^T (stored transposed i
   int64_t off_img_xs, off_img_ss;   // workspace: fragment images of the two results as the GD step on the stripes reads them
                                     // (image row a, column k = result[k][a]; S S^T is symmetric up to rounding); < 0: none
   int32_t K, r, rc, transpose_xs;
+  // A long contraction is cut into segments of 64-column chunks, one workgroup each: segment [c0, c1) of nseg; with
+  // nseg > 1 the workgroup only leaves its partial sums (two R x R fp32 matrices, S S^T then X S^T) at workspace
+  // offset off_part + seg * 2 R^2 floats, and gram_finish_kernel adds them in segment order and writes the results.
+  int32_t c0, c1, seg, nseg;
+  int64_t off_part;
+};
+struct GramFinItem {       // one workgroup: the sum of the nseg partial results of one pair of products -> results and images
+  int64_t off_part;
+  int64_t off_out_xs, off_out_ss;
+  int64_t off_img_xs, off_img_ss;
+  int32_t r, rc, transpose_xs, nseg, same, pad;   // same: X = S (first GD iteration), one product serves both outputs
 };
 struct CopyItem {          // one workgroup: count floats from src + first to dst + first (first is a multiple of 4)
   Ref src, dst;
@@ -240,6 +251,16 @@ struct CholItem {
   int32_t pad;
 };
 
+// In-place re-expression of the factors after the Cholesky factorisation (T > 1, MFMA path): one workgroup owns 64
+// whole columns of R (R <- C^-1 R) or 64 whole rows of L (L <- L C), so nothing it overwrites is read by another.
+struct RegaugeItem {
+  int64_t off_x;         // state: the factor (fp32), R (r x len, row stride len) or L (len x r, row stride r)
+  int64_t off_c;         // ws: C^-1 (for R) or C (for L), r x r fp64, lower triangular
+  int32_t r, len;        // rank; columns of R / rows of L
+  int32_t first;         // first column / row of this workgroup's 64
+  int32_t is_L;
+};
+
 // launchers (defined next to their kernels)
 void launch_gemm64(const GemmProblem* probs, const GemmTile* tiles, int64_t ntiles, Bases b, hipStream_t s);
 void launch_vstat(const BlockDev* blocks, const VsItem* items, int64_t nitems, double* partials, Bases b,
@@ -256,6 +277,7 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 void launch_copy(const CopyItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_sketch(const SketchItem* items, int64_t nitems, char* state, hipStream_t s);
 void launch_chol(const CholItem* items, int64_t nitems, Bases b, hipStream_t s);
+void launch_regauge_apply(const RegaugeItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gemm_mfma(const GemmProblem* probs, const GemmTile* tiles, int64_t ntiles, Bases b, hipStream_t s);
 void launch_proj(int rt, bool w16, bool vel, const ProjItem* items, int64_t nitems, const LrBlockDev* lrb, Bases b,
                  StepScalars sc, hipStream_t s);
@@ -268,6 +290,8 @@ void launch_qimage(const QsItem* items, int64_t nitems, const LrBlockDev* lrb, B
 void launch_stripe(int rt, bool tra, const StripeItem* items, int64_t nitems, const StripeProb* probs, Bases b, hipStream_t s);
 void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gram(const GramItem* items, int64_t nitems, Bases b, hipStream_t s);
+void launch_gram_finish(const GramFinItem* items, int64_t nitems, Bases b, hipStream_t s);
+constexpr int GRAM_SEG_CHUNKS = 25;    // 64-column chunks per segment of a Gram-type product (1600 columns)
 void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_refresh_update(int rt, bool w16, const ProjItem* items, int64_t nitems, const RuBlockDev* blocks, Bases b,
                            StepScalars sc, hipStream_t s);

@@ -106,7 +106,105 @@ __global__ __launch_bounds__(256) void chol_inv_kernel(const CholItem* __restric
   }
 }
 
+// R <- C^-1 R on 64 whole columns, or L <- L C on 64 whole rows, in place (fp64 products, fp32 stores): the r x 64
+// result Out[a][j] = sum_k M[k][a] T[k][j] with T the tile of the factor (contraction index k = row of R / column of
+// L) and M[k][a] = C^-1[a][k] (for R) or C[k][a] (for L).  The whole tile goes to LDS first (fp32, as stored), so the
+// workgroup may overwrite its columns / rows afterwards; M is staged 32 values of k at a time (fp64).  A thread owns
+// two 4 x 4 pieces of the result: per k one 16-byte read of T and two of M feed 16 multiply-adds.  Entries of the
+// triangular matrices outside the triangle are exact zeros; a thread skips the slabs of k that lie wholly outside
+// its piece's part of the triangle.
+constexpr int RG_W = 64;                 // columns of R / rows of L per workgroup
+constexpr int RG_K = 32;                 // values of the contraction index per staged slab of M
+constexpr int RG_MS = 128 + 2;           // LDS row stride of M (doubles): rows stay 16-byte aligned
+__global__ __launch_bounds__(256) void regauge_apply_kernel(const RegaugeItem* __restrict__ items, Bases b) {
+  __shared__ __attribute__((aligned(16))) float T[128 * RG_W];        // T[k][j]
+  __shared__ __attribute__((aligned(16))) double Ms[RG_K * RG_MS];    // Ms[kk][a] = M[k0 + kk][a], zero for a >= r
+  const RegaugeItem it = items[blockIdx.x];
+  const int r = it.r, tid = threadIdx.x;
+  float* X = reinterpret_cast<float*>(b.state + it.off_x);
+  const double* __restrict__ Cm = reinterpret_cast<const double*>(b.ws + it.off_c);
+  const int width = it.len - it.first < RG_W ? it.len - it.first : RG_W;
+  const bool isL = it.is_L != 0;
+  if (!isL) {
+    for (int e = tid; e < r * RG_W; e += 256) {
+      const int k = e / RG_W, j = e % RG_W;
+      T[e] = j < width ? X[(int64_t)k * it.len + it.first + j] : 0.f;
+    }
+  } else {
+    for (int e = tid; e < r * RG_W; e += 256) {
+      const int j = e / r, k = e % r;                 // row j of the 64, column k of L: contiguous in memory along k
+      T[k * RG_W + j] = j < width ? X[(int64_t)(it.first + j) * r + k] : 0.f;
+    }
+  }
+  // this thread's two pieces: values a0 .. a0+3 of the free index, positions j0 .. j0+3.  R: consecutive lanes walk
+  // along j (their stores are contiguous along a row of R); L: along a (contiguous along a row of L).
+  int a0[2], j0[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int q = tid + 256 * u;
+    a0[u] = 4 * (isL ? q % 32 : q / 16);
+    j0[u] = 4 * (isL ? q / 32 : q % 16);
+  }
+  double acc[2][4][4];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+      for (int y = 0; y < 4; ++y) acc[u][x][y] = 0.0;
+  for (int k0 = 0; k0 < r; k0 += RG_K) {
+    __syncthreads();                                  // the tile is in LDS / the previous slab has been used
+    for (int e = tid; e < RG_K * 128; e += 256) {
+      int kk, a;
+      if (isL) { kk = e / 128; a = e % 128; } else { a = e / RG_K; kk = e % RG_K; }   // contiguous in memory either way
+      const int k = k0 + kk;
+      double v = 0.0;
+      if (k < r && a < r) v = isL ? Cm[(int64_t)k * r + a] : Cm[(int64_t)a * r + k];
+      Ms[kk * RG_MS + a] = v;
+    }
+    __syncthreads();
+    const int kn = r - k0 < RG_K ? r - k0 : RG_K;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      // R: M[k][a] != 0 only for k <= a; L: only for k >= a
+      const bool live = a0[u] < r && (isL ? k0 + RG_K > a0[u] : k0 <= a0[u] + 3);
+      if (!live) continue;
+      for (int kk = 0; kk < kn; ++kk) {
+        const float4 t4 = *reinterpret_cast<const float4*>(&T[(k0 + kk) * RG_W + j0[u]]);
+        const double2 m01 = *reinterpret_cast<const double2*>(&Ms[kk * RG_MS + a0[u]]);
+        const double2 m23 = *reinterpret_cast<const double2*>(&Ms[kk * RG_MS + a0[u] + 2]);
+        const double tv[4] = {(double)t4.x, (double)t4.y, (double)t4.z, (double)t4.w};
+        const double mv[4] = {m01.x, m01.y, m23.x, m23.y};
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+          for (int y = 0; y < 4; ++y) acc[u][x][y] = fma(mv[x], tv[y], acc[u][x][y]);
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int a = a0[u] + x;
+      if (a >= r) continue;
+#pragma unroll
+      for (int y = 0; y < 4; ++y) {
+        const int j = j0[u] + y;
+        if (j >= width) continue;
+        if (isL) X[(int64_t)(it.first + j) * r + a] = (float)acc[u][x][y];
+        else X[(int64_t)a * it.len + it.first + j] = (float)acc[u][x][y];
+      }
+    }
+  }
+}
+
 }  // namespace
+
+void launch_regauge_apply(const RegaugeItem* items, int64_t nitems, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(regauge_apply_kernel, dim3((unsigned)nitems), dim3(256), 0, s, items, b);
+}
 
 void launch_chol(const CholItem* items, int64_t nitems, Bases b, hipStream_t s) {
   if (nitems <= 0) return;

@@ -1347,7 +1347,7 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
   // fused GD step of Alg. 2: the factor X in the layout of Out; its coefficients take the step normaliser, the one of
   // the stripe product also the gradient scale (the store below then adds X instead of scaling)
   StripeTail tl = {};
-  const float* __restrict__ Xc = nullptr;
+  const float* Xc = nullptr;        // may be the very buffer Out points at (iterations after the first update in place)
   if (P.upd) {
     const float s = P.off_s >= 0 ? (float)*reinterpret_cast<const double*>(bs.ws + P.off_s) : 1.f;
     Xc = reinterpret_cast<const float*>(resolve(P.x_cur, bs));
@@ -1379,7 +1379,7 @@ __global__ __launch_bounds__(NT, 1) void stripe_kernel(const StripeItem* __restr
     }
   }
   float* Ps = reinterpret_cast<float*>(smem);
-  float* __restrict__ Out = reinterpret_cast<float*>(bs.ws + P.off_out);
+  float* Out = reinterpret_cast<float*>(bs.ws + P.off_out);
   // with the GD step, the new factor values (zeros outside the factor) go back into P for the image below
   const bool emit_f = P.upd && P.off_next >= 0, emit_t = P.upd && P.off_timg >= 0, emit = emit_f || emit_t;
   if (!P.transpose_out) {
@@ -1529,6 +1529,11 @@ __global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict
 // results (all row tiles) and half w / 4 of the k-steps of every chunk.  In the first GD iteration X = S and one
 // product serves both outputs.
 template <int RT>
+__device__ __forceinline__ void gram_emit(const float* Mss, const float* Mxs, const Bases& bs, int64_t off_out_ss,
+                                          int64_t off_out_xs, int64_t off_img_ss, int64_t off_img_xs, int r,
+                                          int transpose_xs, int nthreads);
+
+template <int RT>
 __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, unsigned char* smem) {
   constexpr int R = 32 * RT;
   constexpr int QF = qf_chunk_bytes(R);
@@ -1538,7 +1543,7 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
   const char* __restrict__ X = bs.ws + it.off_x;
   const char* __restrict__ S = bs.ws + it.off_s;
   const bool same = it.off_x == it.off_s;
-  const int nch = (it.K + BK - 1) / BK;                               // the images are zero-padded to whole chunks
+  const int c_first = it.c0, nch = it.c1;                             // this workgroup's chunks (the images are zero-padded to whole chunks)
   lds_u8* const lds = (lds_u8*)smem;                                  // [2 buffers][S | X][QF]
   auto copy = [&](int c, int buf) {
     for (int k = wave; k < QF / 1024; k += 8) {
@@ -1554,8 +1559,8 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
   for (int t = 0; t < RT; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) ass[t][i] = axs[t][i] = 0.f;
-  copy(0, 0);
-  for (int c = 0; c < nch; ++c) {
+  copy(c_first, c_first & 1);
+  for (int c = c_first; c < nch; ++c) {
     // chunk c has landed (every wave waits for its own copies, the barrier collects them) and everybody is done
     // with the buffer chunk c+1 goes to; its copy runs while chunk c is multiplied
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1627,10 +1632,27 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
   __syncthreads();                                                     // the partial sums are read: LDS takes the results
   float* const Mss = reinterpret_cast<float*>(smem);                   // [R][R] each; rows and columns beyond r are zero
   float* const Mxs = Mss + R * R;                                      // (the images of the factors are zero-padded)
+  if (it.nseg > 1) {
+    // one segment of a long contraction: leave the two partial matrices for gram_finish_kernel
+    if (owner) {
+      float* __restrict__ part_ss = reinterpret_cast<float*>(bs.ws + it.off_part) + (int64_t)it.seg * 2 * R * R;
+      float* __restrict__ part_xs = part_ss + R * R;
+      const int col = 32 * cw + l32;
+#pragma unroll
+      for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const int row = 32 * t + 8 * q + 4 * lh + p;
+            part_ss[row * R + col] = ass[t][4 * q + p];
+            if (!same) part_xs[row * R + col] = axs[t][4 * q + p];
+          }
+    }
+    return;
+  }
   if (owner) {
-    float* __restrict__ Oss = reinterpret_cast<float*>(bs.ws + it.off_out_ss);
-    float* __restrict__ Oxs = reinterpret_cast<float*>(bs.ws + it.off_out_xs);
-    const int r = it.r, col = 32 * cw + l32;
+    const int col = 32 * cw + l32;
 #pragma unroll
     for (int t = 0; t < RT; ++t)
 #pragma unroll
@@ -1638,21 +1660,33 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const int row = 32 * t + 8 * q + 4 * lh + p;
-          const float vss = ass[t][4 * q + p], vxs = axs[t][4 * q + p];
-          Mss[row * R + col] = vss;
-          Mxs[row * R + col] = vxs;
-          if (row < r && col < r) {
-            Oss[(int64_t)row * r + col] = vss;
-            Oxs[it.transpose_xs ? (int64_t)col * r + row : (int64_t)row * r + col] = vxs;
-          }
+          Mss[row * R + col] = ass[t][4 * q + p];
+          Mxs[row * R + col] = axs[t][4 * q + p];
         }
   }
-  if (it.off_img_ss < 0) return;
   __syncthreads();
-  // fragment images of the two results for the GD step on the stripes (the layout qf_image_kernel writes), 64-wide
-  // chunks of the contraction index k: lane l of a piece holds result[64 c + 16 kk + 8 (l / 32) .. + 7][32 tile + l % 32]
-  const int nk2 = (it.r + BK - 1) / BK;
-  for (int p = threadIdx.x; p < 2 * nk2 * (BK / 16) * RT * 64; p += 512) {
+  gram_emit<RT>(Mss, Mxs, bs, it.off_out_ss, it.off_out_xs, it.off_img_ss, it.off_img_xs, it.r, it.transpose_xs, 512);
+}
+
+// Results of a pair of Gram-type products, complete in LDS as [R][R] fp32 each: the r x r matrices themselves and
+// their fragment images for the GD step on the stripes (the layout qf_image_kernel writes), 64-wide chunks of the
+// contraction index k: lane l of a piece holds result[64 c + 16 kk + 8 (l / 32) .. + 7][32 tile + l % 32].
+template <int RT>
+__device__ __forceinline__ void gram_emit(const float* Mss, const float* Mxs, const Bases& bs, int64_t off_out_ss,
+                                          int64_t off_out_xs, int64_t off_img_ss, int64_t off_img_xs, int r,
+                                          int transpose_xs, int nthreads) {
+  constexpr int R = 32 * RT;
+  constexpr int QF = qf_chunk_bytes(R);
+  float* __restrict__ Oss = reinterpret_cast<float*>(bs.ws + off_out_ss);
+  float* __restrict__ Oxs = reinterpret_cast<float*>(bs.ws + off_out_xs);
+  for (int id = threadIdx.x; id < r * r; id += nthreads) {
+    const int row = id / r, col = id % r;
+    Oss[id] = Mss[row * R + col];
+    Oxs[transpose_xs ? (int64_t)col * r + row : (int64_t)id] = Mxs[row * R + col];
+  }
+  if (off_img_ss < 0) return;
+  const int nk2 = (r + BK - 1) / BK;
+  for (int p = threadIdx.x; p < 2 * nk2 * (BK / 16) * RT * 64; p += nthreads) {
     const int ln = p & 63, rest = p >> 6, tile = rest % RT, kk = (rest / RT) % (BK / 16), kc = (rest / (RT * (BK / 16))) % nk2;
     const int which = rest / (RT * (BK / 16) * nk2);
     const float* M = (which ? Mxs : Mss) + 32 * tile + (ln & 31);
@@ -1663,7 +1697,7 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
     uint32_t h[4], l[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) split_pair(x[2 * e], x[2 * e + 1], h[e], l[e]);
-    char* dst = bs.ws + (which ? it.off_img_xs : it.off_img_ss) + (int64_t)kc * QF + ((int64_t)((kk * RT + tile) * 2) * 64 + ln) * 16;
+    char* dst = bs.ws + (which ? off_img_xs : off_img_ss) + (int64_t)kc * QF + ((int64_t)((kk * RT + tile) * 2) * 64 + ln) * 16;
     *reinterpret_cast<uint4*>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
     *reinterpret_cast<uint4*>(dst + 1024) = make_uint4(l[0], l[1], l[2], l[3]);
   }
@@ -1675,6 +1709,35 @@ __global__ __launch_bounds__(512) void gram_kernel(const GramItem* __restrict__ 
   if (it.rc == 32) gram_body<1>(it, bs, smem);
   else if (it.rc == 64) gram_body<2>(it, bs, smem);
   else gram_body<4>(it, bs, smem);
+}
+
+// Sum of the partial results that the segments of a long contraction left (fixed order: segment 0, 1, ...), then the
+// same results and images a single-segment workgroup writes itself.
+template <int RT>
+__device__ __forceinline__ void gram_finish_body(const GramFinItem& it, const Bases& bs, unsigned char* smem) {
+  constexpr int R = 32 * RT;
+  float* const Mss = reinterpret_cast<float*>(smem);
+  float* const Mxs = Mss + R * R;
+  const float* __restrict__ part = reinterpret_cast<const float*>(bs.ws + it.off_part);
+  for (int id = threadIdx.x; id < R * R; id += 512) {
+    float a = 0.f, x = 0.f;
+    for (int sg = 0; sg < it.nseg; ++sg) {
+      a += part[(int64_t)sg * 2 * R * R + id];
+      if (!it.same) x += part[(int64_t)sg * 2 * R * R + R * R + id];
+    }
+    Mss[id] = a;
+    Mxs[id] = it.same ? a : x;
+  }
+  __syncthreads();
+  gram_emit<RT>(Mss, Mxs, bs, it.off_out_ss, it.off_out_xs, it.off_img_ss, it.off_img_xs, it.r, it.transpose_xs, 512);
+}
+
+__global__ __launch_bounds__(512) void gram_finish_kernel(const GramFinItem* __restrict__ items, Bases bs) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * 128 * 128 * 4];
+  const GramFinItem it = items[blockIdx.x];
+  if (it.rc == 32) gram_finish_body<1>(it, bs, smem);
+  else if (it.rc == 64) gram_finish_body<2>(it, bs, smem);
+  else gram_finish_body<4>(it, bs, smem);
 }
 
 template <int RT>
@@ -1718,6 +1781,11 @@ void launch_stripe(int rt, bool tra, const StripeItem* items, int64_t nitems, co
 void launch_gram(const GramItem* items, int64_t nitems, Bases b, hipStream_t s) {
   if (nitems <= 0) return;
   hipLaunchKernelGGL(gram_kernel, dim3((unsigned)nitems), dim3(512), 0, s, items, b);
+}
+
+void launch_gram_finish(const GramFinItem* items, int64_t nitems, Bases b, hipStream_t s) {
+  if (nitems <= 0) return;
+  hipLaunchKernelGGL(gram_finish_kernel, dim3((unsigned)nitems), dim3(512), 0, s, items, b);
 }
 
 void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s) {
