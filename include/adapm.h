@@ -141,6 +141,22 @@ adapm_status_t adapm_state_loaded(adapm_ctx* ctx);
 adapm_status_t adapm_step(adapm_ctx* ctx, void* const* params_dev, const void* const* grads_dev,
                           void* state_dev, void* workspace_dev, int64_t step, float lr, void* stream);
 
+/* adapm_step for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same step with the library's OWN scratch buffer in place of
+ * workspace_dev, a fixed array in device memory of adapm_static_scratch_bytes() bytes (64 MiB) that every GPU
+ * the library runs on holds until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no
+ * event creation): the context must have been set up by adapm_state_init beforehand (else ADAPM_ESTATE) and
+ * per-launch timing must be off.  A table whose adapm_workspace_bytes() exceeds the array is ADAPM_EINVAL.
+ * All contexts on a GPU share that GPU's array, which keeps whatever the last call left there: the library
+ * rebuilds what a context keeps in scratch between steps when another context has used the array in the
+ * meantime, and nothing in it is expected to start at zero; calls that overlap in time on one GPU (different
+ * streams, different host threads) race on it and are not allowed.  Everything else as adapm_step. */
+adapm_status_t adapm_step_static(adapm_ctx* ctx, void* const* params_dev, const void* const* grads_dev,
+                                 void* state_dev, int64_t step, float lr, void* stream);
+
+/* Size of the library's own scratch array (see adapm_step_static). */
+size_t adapm_static_scratch_bytes(void);
+
 /* Global gradient-norm clipping of the paper's pre-training runs (Sec. 5.1, set-ups: threshold 1.0),
  * folded into the step.  After adapm_set_grad_clip(ctx, c) with c > 0, every adapm_step first sums the
  * squares of all gradients of the table on the device (fixed order, fp64 partial sums), derives
@@ -150,8 +166,9 @@ adapm_status_t adapm_step(adapm_ctx* ctx, void* const* params_dev, const void* c
  * default); NaN is ADAPM_EINVAL.  Costs one extra pass over the gradients. */
 adapm_status_t adapm_set_grad_clip(adapm_ctx* ctx, float max_norm);
 
-/* Norm and factor of the last clipped adapm_step that used workspace_dev (device pointer): copies two
- * floats to the host and synchronises `stream`.  Either output may be NULL. */
+/* Norm and factor of the last clipped adapm_step that used workspace_dev (device pointer; NULL: the
+ * library's own scratch array, after adapm_step_static): copies two floats to the host and synchronises
+ * `stream`.  Either output may be NULL. */
 adapm_status_t adapm_last_grad_norm(adapm_ctx* ctx, const void* workspace_dev, void* stream, float* norm, float* scale);
 
 /* Learning-rate schedule of the same runs (Sec. 5.1, set-ups: cosine decay with warm-up), a host helper

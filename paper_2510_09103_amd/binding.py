@@ -44,7 +44,8 @@ EXPORTS = ["adapm_init", "adapm_state_bytes", "adapm_workspace_bytes", "adapm_st
            "adapm_state_init", "adapm_state_loaded", "adapm_step", "adapm_block_contraction", "adapm_last_launch_count",
            "adapm_algorithmic_bytes",
            "adapm_algorithmic_flops", "adapm_profile_enable", "adapm_profile_read", "adapm_last_error",
-           "adapm_set_grad_clip", "adapm_last_grad_norm", "adapm_lr_cosine_warmup", "adapm_destroy"]
+           "adapm_set_grad_clip", "adapm_last_grad_norm", "adapm_lr_cosine_warmup", "adapm_destroy",
+           "adapm_step_static", "adapm_static_scratch_bytes"]
 
 
 def _load() -> C.CDLL:
@@ -74,6 +75,10 @@ def _load() -> C.CDLL:
     lib.adapm_state_loaded.argtypes = [P]
     lib.adapm_step.restype = C.c_int
     lib.adapm_step.argtypes = [P, C.POINTER(P), C.POINTER(P), P, P, C.c_int64, C.c_float, P]
+    lib.adapm_step_static.restype = C.c_int
+    lib.adapm_step_static.argtypes = [P, C.POINTER(P), C.POINTER(P), P, C.c_int64, C.c_float, P]
+    lib.adapm_static_scratch_bytes.restype = C.c_size_t
+    lib.adapm_static_scratch_bytes.argtypes = []
     lib.adapm_block_contraction.restype = C.c_int32
     lib.adapm_block_contraction.argtypes = [P, C.c_int64]
     lib.adapm_last_launch_count.restype = C.c_int64
@@ -148,6 +153,15 @@ def adapm_step(ctx, params_ptrs, grads_ptrs, state_ptr: int, workspace_ptr: int,
     """params_ptrs / grads_ptrs: ctypes arrays of c_void_p (see ptr_array)."""
     _check(lib.adapm_step(ctx, params_ptrs, grads_ptrs, C.c_void_p(state_ptr), C.c_void_p(workspace_ptr),
                           step, lr, C.c_void_p(stream)))
+
+
+def adapm_step_static(ctx, params_ptrs, grads_ptrs, state_ptr: int, step: int, lr: float, stream: int = 0):
+    """adapm_step on the library's own scratch array (allocates nothing)."""
+    _check(lib.adapm_step_static(ctx, params_ptrs, grads_ptrs, C.c_void_p(state_ptr), step, lr, C.c_void_p(stream)))
+
+
+def adapm_static_scratch_bytes() -> int:
+    return lib.adapm_static_scratch_bytes()
 
 
 def adapm_block_contraction(ctx, block: int) -> int:

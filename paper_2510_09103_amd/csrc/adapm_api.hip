@@ -941,6 +941,33 @@ void build_plan(adapm_ctx* c) {
 template <class T>
 size_t bytes_of(const std::vector<T>& v) { return align_up(v.size() * sizeof(T)); }
 
+// ---------------------------------------------------------------------------
+// The library's own scratch buffer, for callers that cannot allocate device memory (adapm_step_static).  Every GPU
+// the library runs on holds one copy of the array at its own address until the process ends.  In host code the
+// array's NAME is only a stand-in for the symbol, not a device address: host code uses the pointer that
+// hipGetSymbolAddress returned for the device in question, looked up once per device at set-up.
+// ---------------------------------------------------------------------------
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)64 << 20;
+constexpr int MAX_DEVICES = 64;
+char* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+const adapm_ctx* g_scratch_user[MAX_DEVICES] = {nullptr};     // context whose step used a device's scratch array last
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+namespace {
+
+// Address of the scratch array on device `dev` (which must be the current device); looked up on first use.
+adapm_status_t scratch_address(int dev, char** out) {
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(ADAPM_EINVAL, "device index %d out of range", dev);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(ADAPM_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = (char*)p;
+  }
+  if (out) *out = g_scratch_ptr[dev];
+  return ADAPM_OK;
+}
+
 
 adapm_status_t ensure_uploaded(adapm_ctx* c) {
   if (c->uploaded) return ADAPM_OK;
@@ -1002,6 +1029,9 @@ adapm_status_t ensure_uploaded(adapm_ctx* c) {
     c->slot[k].h = stage + (size_t)k * 2 * nb;
     HIP_TRY(hipEventCreateWithFlags(&c->slot[k].copied, hipEventDisableTiming));
   }
+  // set-up also looks up this device's copy of the library's scratch array (adapm_step_static)
+  adapm_status_t st = scratch_address(dev, nullptr);
+  if (st != ADAPM_OK) return st;
   c->device = dev;
   c->uploaded = true;
   return ADAPM_OK;
@@ -1291,6 +1321,43 @@ adapm_status_t adapm_step(adapm_ctx* c, void* const* params_dev, const void* con
   return enqueue_step(c, params_dev, grads_dev, state_dev, workspace_dev, step, lr, (hipStream_t)stream);
 }
 
+adapm_status_t adapm_step_static(adapm_ctx* c, void* const* params_dev, const void* const* grads_dev, void* state_dev,
+                                 int64_t step, float lr, void* stream) {
+  if (!c) return fail(ADAPM_EINVAL, "ctx is null");
+  if (step < 1) return fail(ADAPM_ESTATE, "step must be >= 1 (got %lld)", (long long)step);
+  if (!params_dev || !grads_dev) return fail(ADAPM_EINVAL, "params_dev / grads_dev is null");
+  if (!state_dev || ((uintptr_t)state_dev & 15)) return fail(ADAPM_EINVAL, "state_dev is null or misaligned");
+  if (c->ws_bytes > STATIC_SCRATCH_BYTES)
+    return fail(ADAPM_EINVAL, "this table needs %zu bytes of scratch, the library's own buffer holds %zu: use adapm_step "
+                "with a caller-allocated workspace", c->ws_bytes, STATIC_SCRATCH_BYTES);
+  const size_t nb = c->table.size();
+  for (size_t i = 0; i < nb; ++i) {
+    if (!params_dev[i] || !grads_dev[i]) return fail(ADAPM_EINVAL, "block %zu: null parameter or gradient pointer", i);
+    if (((uintptr_t)params_dev[i] | (uintptr_t)grads_dev[i]) & 15)
+      return fail(ADAPM_EINVAL, "block %zu: parameter / gradient pointer not 16-byte aligned", i);
+  }
+  if (!c->uploaded)
+    return fail(ADAPM_ESTATE, "adapm_step_static allocates nothing: run adapm_state_init on this context first (it places "
+                "the launch plan on the device)");
+  if (c->profiling) return fail(ADAPM_ESTATE, "per-launch timing creates events: switch it off for adapm_step_static");
+  const bool refresh = is_refresh(c, step);
+  if (!refresh && c->n_lowrank > 0 && !c->gauge_ok)
+    return fail(ADAPM_ESTATE, "step %lld holds R, but this state's R has not been orthonormalised yet", (long long)step);
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev != c->device) return fail(ADAPM_ESTATE, "the context was set up on device %d, the current device is %d", c->device, dev);
+  char* ws = nullptr;
+  adapm_status_t st = scratch_address(dev, &ws);      // a table look-up: the address was resolved at set-up
+  if (st != ADAPM_OK) return st;
+  // the array is shared by every context on this device: whatever another context (or another state buffer of this
+  // one, see the workspace rule of adapm_step) left there is not ours
+  if (g_scratch_user[dev] != c) c->split_ws = nullptr;
+  g_scratch_user[dev] = c;
+  return enqueue_step(c, params_dev, grads_dev, state_dev, ws, step, lr, (hipStream_t)stream);
+}
+
+size_t adapm_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
 adapm_status_t adapm_profile_enable(adapm_ctx* c, int32_t on) {
   if (!c) return fail(ADAPM_EINVAL, "ctx is null");
   c->profiling = on != 0;
@@ -1338,8 +1405,13 @@ adapm_status_t adapm_set_grad_clip(adapm_ctx* c, float max_norm) {
 }
 
 adapm_status_t adapm_last_grad_norm(adapm_ctx* c, const void* workspace_dev, void* stream, float* norm, float* scale) {
-  if (!c || !workspace_dev) return fail(ADAPM_EINVAL, "ctx or workspace_dev is null");
+  if (!c) return fail(ADAPM_EINVAL, "ctx is null");
   if (c->off_gn_out < 0) return fail(ADAPM_ESTATE, "no plan");
+  if (!workspace_dev) {      // the step ran on the library's own scratch array
+    char* ws = nullptr;
+    if (!c->uploaded || scratch_address(c->device, &ws) != ADAPM_OK) return fail(ADAPM_ESTATE, "no step has run on this context");
+    workspace_dev = ws;
+  }
   float h[2] = {0.f, 1.f};
   hipStream_t s = (hipStream_t)stream;
   HIP_TRY(hipMemcpyAsync(h, (const char*)workspace_dev + c->off_gn_out, sizeof h, hipMemcpyDeviceToHost, s));
@@ -1397,6 +1469,8 @@ double adapm_algorithmic_flops(const adapm_ctx* c, int32_t refresh_step) {
 
 void adapm_destroy(adapm_ctx* c) {
   if (!c) return;
+  for (const adapm_ctx*& u : g_scratch_user)
+    if (u == c) u = nullptr;
   if (c->uploaded) {
     for (adapm_ctx::PtrSlot& q : c->slot)
       if (q.copied) { (void)hipEventSynchronize(q.copied); (void)hipEventDestroy(q.copied); }
