@@ -25,6 +25,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+FP64_VECTOR_PEAK_TFLOPS = 78.6  # fp64 vector arithmetic (the exact path's products run as fp64 fused multiply-adds)
 
 
 def block_bytes(b, refresh):
@@ -208,15 +209,31 @@ def main():
             blocks = [b for b in lr_blocks if rank_class(b) == rank]
             alg = sum(2.0 * b.rows * b.cols * b.rank + 4.0 * (b.rows if side_L else b.cols) * b.rank ** 2 for b in blocks)
             issued = sum(2 * 2.0 * b.rows * b.cols * rank + 3 * 4.0 * (b.rows if side_L else b.cols) * rank ** 2 for b in blocks)
-            roof = {"bound": "mfma", "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "achieved": alg / (k["avg_ms"] * 1e-3) / 1e12,
-                    "issued_TFLOPs": issued / (k["avg_ms"] * 1e-3) / 1e12,
-                    "issued_frac": issued / (k["avg_ms"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                    "hbm_GBs": sum(b.rows * b.cols * 2 + 8 * (b.rows if side_L else b.cols) * b.rank for b in blocks)
-                               / (k["avg_ms"] * 1e-3) / 1e9,
-                    "note": "achieved = flops of the mathematical products; issued = matrix-core work with every fp32 "
+            alg_bytes = sum(b.rows * b.cols * 2 + 12 * (b.rows if side_L else b.cols) * b.rank for b in blocks)
+            sec = k["avg_ms"] * 1e-3
+            # arithmetic intensity (about 110 flop per byte at r = 128, 220 as issued) is below the machine balance
+            # (2.5 PFLOP/s / 8 TB/s = 312 flop per byte): HBM is the nearer roof; the matrix-core figures ride along
+            roof = {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", "achieved": alg_bytes / sec / 1e9,
+                    "flop_per_byte": alg / alg_bytes,
+                    "mfma": {"peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "achieved_TFLOPs": alg / sec / 1e12,
+                             "frac": alg / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                             "issued_TFLOPs": issued / sec / 1e12,
+                             "issued_frac": issued / sec / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+                    "note": "bytes: G once plus the factor it updates (current and previous read, new written: fp32); mfma.achieved = "
+                            "flops of the mathematical products; mfma.issued = matrix-core work with every fp32 "
                             "operand as a (hi, lo) bf16 pair (2 instructions per product of G, 3 per thin product) "
                             "at the padded rank class"}
+        elif label in ("project_f64", "reconstruct_f64", "alg2_products_f64"):
+            # exact path: batched fp64 products on the vector units.  project: G Q^T; reconstruct: the m x n term of
+            # the update from the thin factors; Alg. 2: G R^T and L^T G per GD iteration (plus the r x r ones)
+            per_block = {"project_f64": lambda b: 2.0 * b.rows * b.cols * b.rank,
+                         "reconstruct_f64": lambda b: 2.0 * b.rows * b.cols * b.rank,
+                         "alg2_products_f64": lambda b: 4.0 * b.rows * b.cols * b.rank + 8.0 * (b.rows + b.cols) * b.rank ** 2}[label]
+            alg = sum(per_block(b) for b in lr_blocks)
+            roof = {"bound": "alu", "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "achieved": alg / (k["avg_ms"] * 1e-3) / 1e12,
+                    "note": "fp64 multiply-adds of the products, against the chip's fp64 vector rate (256 compute units x "
+                            "4 SIMDs x 16 lanes x 2 flop x 2.4 GHz = 78.6 TFLOP/s)"}
         if roof is None:
             return None
         roof.update(kernel=label, frac=roof["achieved"] / roof["peak"], avg_ms=k["avg_ms"],
@@ -242,15 +259,20 @@ def main():
     if roof is None:
         roof = {"bound": "alu", "kernel": dominant, "avg_ms": kernels[dominant]["avg_ms"], "achieved": None, "peak": None,
                 "unit": None, "frac": None, "traffic": None}
-    tfile = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
-    roof["traffic_source"] = None
-    if args.rank == 0 and os.path.exists(tfile):
+    def counter_traffic(roof_block, T):
+        """HBM bytes per pass of the block's kernel from the committed counter summary (not a measurement of this run)."""
+        tfile = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+        roof_block["traffic_source"] = None
+        if args.rank != 0 or not os.path.exists(tfile):
+            return
         for line in open(tfile):
             parts = line.split()
-            if len(parts) == 4 and parts[0] == args.workload and parts[1] == f"T{args.T}" and parts[2] == dominant:
-                roof["traffic"] = float(parts[3])
-                roof["traffic_source"] = ("profiles/hbm_traffic_per_launch.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
-                                          "this command on an earlier run, not of this run")
+            if len(parts) == 4 and parts[0] == args.workload and parts[1] == f"T{T}" and parts[2] == roof_block["kernel"]:
+                roof_block["traffic"] = float(parts[3])
+                roof_block["traffic_source"] = ("profiles/hbm_traffic_per_launch.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                                "of this command on an earlier run, not of this run")
+
+    counter_traffic(roof, args.T)
 
     bytes_refresh = B.adapm_algorithmic_bytes(opt.ctx, True)
     bytes_held = B.adapm_algorithmic_bytes(opt.ctx, False)
@@ -279,10 +301,12 @@ def main():
                    "algorithmic_GBs": B.adapm_algorithmic_bytes(o1.ctx, True) / (ms1 * 1e-3) / 1e9,
                    "hbm_frac_whole_step": B.adapm_algorithmic_bytes(o1.ctx, True) / (ms1 * 1e-3) / 1e9 / HBM_PEAK_GBS,
                    "mfma_frac_whole_step": fl / (ms1 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                   "roofline": roofline_of(dom1, k1[dom1], True),
+                   "roofline": roofline_of(dom1, k1[dom1], True),   # counter traffic added below
                    "kernels_ms_per_step": {k: v["per_step_ms"] for k, v in k1.items()},
                    "stripe_products_ms_per_step": stripe_ms,
                    "workspace_bytes": o1.workspace_bytes}
+        if literal["roofline"] is not None:
+            counter_traffic(literal["roofline"], 1)
         o1.close()
         del o1
         torch.cuda.empty_cache()

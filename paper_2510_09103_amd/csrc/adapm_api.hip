@@ -314,6 +314,33 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast, const std::vector<int64_t>& i
   if (ids.empty()) return;
   const std::vector<double> etas = effective_step_sizes(hp.refresh_iters_K);
   const int n_eff = (int)etas.size();
+  // Segment length of the Gram-type products of this group.  A workgroup of that launch owns a whole CU (its LDS), so
+  // the launch takes (rounds of workgroups over the CUs) x (chunks of the longest workgroup); the scratch of a block
+  // holds partial sums for segments of GRAM_SEG_CHUNKS chunks, so only longer segments (fewer of them) are eligible.
+  // E.g. 16 layers of the GPT-2-1.5B shape: 25 chunks give 288 workgroups (two rounds on 256 CUs), 34 give 256.
+  int gram_seg = GRAM_SEG_CHUNKS;
+  if (fast) {
+    constexpr int CUS = 256;
+    int longest = 1;
+    for (int64_t i : ids)
+      if (stripe_ok(c->table[i]))
+        longest = std::max<int>(longest, (int)((std::max(c->table[i].rows, c->table[i].cols) + 63) / 64));
+    int64_t best = -1;
+    for (int seg = GRAM_SEG_CHUNKS; seg <= std::max(longest, GRAM_SEG_CHUNKS); ++seg) {
+      int64_t wgs = 0;
+      int maxlen = 0;
+      for (int64_t i : ids) {
+        if (!stripe_ok(c->table[i])) continue;
+        for (int64_t K : {c->table[i].rows, c->table[i].cols}) {
+          const int nch = (int)((K + 63) / 64), nseg = (nch + seg - 1) / seg;
+          wgs += nseg;
+          maxlen = std::max(maxlen, (nch + nseg - 1) / nseg);
+        }
+      }
+      const int64_t cost = ((wgs + CUS - 1) / CUS) * maxlen;
+      if (best < 0 || cost < best) { best = cost; gram_seg = seg; }
+    }
+  }
   // this group's lists
   const int grp = c->n_groups++;
   c->cp.emplace_back(); c->rub.emplace_back(); c->qt.emplace_back(); c->chol.emplace_back();
@@ -396,7 +423,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast, const std::vector<int64_t>& i
         // in segment order by a second small launch): the longest workgroup of a launch then stays short
         auto add_gram = [&](int64_t off_x, int64_t off_s, int64_t o_xs, int64_t o_ss, int64_t i_xs, int64_t i_ss, int K, int tx,
                             int64_t off_part) {
-          const int nch = (K + 63) / 64, nseg = gram_segments(K), per = (nch + nseg - 1) / nseg;
+          const int nch = (K + 63) / 64, nseg = (nch + gram_seg - 1) / gram_seg, per = (nch + nseg - 1) / nseg;
           for (int sg = 0; sg < nseg; ++sg)
             GRAM(e).h.push_back(GramItem{off_x, off_s, o_xs, o_ss, i_xs, i_ss, K, r, rc, tx, sg * per, std::min(nch, (sg + 1) * per),
                                          sg, nseg, off_part});

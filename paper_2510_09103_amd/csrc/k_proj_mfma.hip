@@ -1543,15 +1543,23 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
   const char* __restrict__ X = bs.ws + it.off_x;
   const char* __restrict__ S = bs.ws + it.off_s;
   const bool same = it.off_x == it.off_s;
-  const int c_first = it.c0, nch = it.c1;                             // this workgroup's chunks (the images are zero-padded to whole chunks)
-  lds_u8* const lds = (lds_u8*)smem;                                  // [2 buffers][S | X][QF]
-  auto copy = [&](int c, int buf) {
-    for (int k = wave; k < QF / 1024; k += 8) {
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(S + (int64_t)c * QF + k * 1024 + lane * 16),
-                                       (__attribute__((address_space(3))) void*)(lds + (buf * 2) * QF + k * 1024), 16, 0, 0);
+  // this workgroup's chunks (the images are zero-padded to whole chunks), walked in halves of 32 columns: a ring of
+  // four half-chunk buffers per image keeps two to three copies in flight while one half is multiplied
+  constexpr int HB = QF / 2;                                          // bytes of half a chunk of one image
+  constexpr int NP = HB / 1024;                                       // 1 KB pieces of half a chunk: one copy instruction each
+  constexpr int LPC = NP >= 8 ? NP / 8 : 1;                           // copy instructions per wave, image and half (waves beyond NP issue none)
+  const int h_first = 2 * it.c0, h_end = 2 * it.c1;
+  lds_u8* const lds = (lds_u8*)smem;                                  // [4 buffers][S | X][HB]
+  auto copy = [&](int h, int buf) {
+#pragma unroll
+    for (int u = 0; u < LPC; ++u) {
+      const int k = wave + 8 * u;
+      if (k >= NP) continue;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(S + (int64_t)h * HB + k * 1024 + lane * 16),
+                                       (__attribute__((address_space(3))) void*)(lds + (buf * 2) * HB + k * 1024), 16, 0, 0);
       if (!same)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(X + (int64_t)c * QF + k * 1024 + lane * 16),
-                                         (__attribute__((address_space(3))) void*)(lds + (buf * 2 + 1) * QF + k * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(X + (int64_t)h * HB + k * 1024 + lane * 16),
+                                         (__attribute__((address_space(3))) void*)(lds + (buf * 2 + 1) * HB + k * 1024), 16, 0, 0);
     }
   };
   f32x16 ass[RT], axs[RT];
@@ -1559,48 +1567,55 @@ __device__ __forceinline__ void gram_body(const GramItem& it, const Bases& bs, u
   for (int t = 0; t < RT; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) ass[t][i] = axs[t][i] = 0.f;
-  copy(c_first, c_first & 1);
-  for (int c = c_first; c < nch; ++c) {
-    // chunk c has landed (every wave waits for its own copies, the barrier collects them) and everybody is done
-    // with the buffer chunk c+1 goes to; its copy runs while chunk c is multiplied
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  for (int h = h_first; h < h_end && h < h_first + 3; ++h) copy(h, h & 3);
+  for (int h = h_first; h < h_end; ++h) {
+    // half h has landed: every wave waits until at most the copies it issued after h are in flight (LPC instructions
+    // per copy, twice that with two images), the barrier collects the waves and says that everybody is done with
+    // half h - 1, whose buffer half h + 3 goes to
+    const int newer = h_end - 1 - h < 2 ? h_end - 1 - h : 2;
+    if (newer == 2) {
+      if (same) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPC) : "memory");
+      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * LPC) : "memory");
+    } else if (newer == 1) {
+      if (same) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPC) : "memory");
+      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPC) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     wg_barrier();
-    if (c + 1 < nch) copy(c + 1, (c + 1) & 1);
+    if (h + 3 < h_end) copy(h + 3, (h + 3) & 3);
     if (cw < RT) {
-      const unsigned ss = lds_addr(lds) + ((c & 1) * 2) * QF, xs = ss + QF;
+      const unsigned ss = lds_addr(lds) + ((h & 3) * 2) * HB, xs = ss + HB;
+      const int kk = kh;                                              // a half holds two 16-wide k-steps: one per wave half
+      bf16x8 ah[RT], al[RT];
 #pragma unroll
-      for (int q = 0; q < BK / 32; ++q) {
-        const int kk = (BK / 32) * kh + q;
-        bf16x8 ah[RT], al[RT];
+      for (int t = 0; t < RT; ++t) {
+        ah[t] = lds_frag_raw(ss + (((kk * RT + t) * 2) * 64 + lane) * 16);
+        al[t] = lds_frag_raw(ss + (((kk * RT + t) * 2 + 1) * 64 + lane) * 16);
+      }
+      bf16x8 bh = lds_frag_raw(ss + (((kk * RT + cw) * 2) * 64 + lane) * 16);
+      bf16x8 bl = lds_frag_raw(ss + (((kk * RT + cw) * 2 + 1) * 64 + lane) * 16);
+#pragma unroll
+      for (int t = 0; t < RT; ++t) lds_wait(ah[t], al[t], bh, bl);
+#pragma unroll
+      for (int t = 0; t < RT; ++t) {
+        ass[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bh, ass[t], 0, 0, 0);
+        ass[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[t], bh, ass[t], 0, 0, 0);
+        ass[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bl, ass[t], 0, 0, 0);
+      }
+      if (!same) {
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-          ah[t] = lds_frag_raw(ss + (((kk * RT + t) * 2) * 64 + lane) * 16);
-          al[t] = lds_frag_raw(ss + (((kk * RT + t) * 2 + 1) * 64 + lane) * 16);
+          ah[t] = lds_frag_raw(xs + (((kk * RT + t) * 2) * 64 + lane) * 16);
+          al[t] = lds_frag_raw(xs + (((kk * RT + t) * 2 + 1) * 64 + lane) * 16);
         }
-        bf16x8 bh = lds_frag_raw(ss + (((kk * RT + cw) * 2) * 64 + lane) * 16);
-        bf16x8 bl = lds_frag_raw(ss + (((kk * RT + cw) * 2 + 1) * 64 + lane) * 16);
 #pragma unroll
         for (int t = 0; t < RT; ++t) lds_wait(ah[t], al[t], bh, bl);
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-          ass[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bh, ass[t], 0, 0, 0);
-          ass[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[t], bh, ass[t], 0, 0, 0);
-          ass[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bl, ass[t], 0, 0, 0);
-        }
-        if (!same) {
-#pragma unroll
-          for (int t = 0; t < RT; ++t) {
-            ah[t] = lds_frag_raw(xs + (((kk * RT + t) * 2) * 64 + lane) * 16);
-            al[t] = lds_frag_raw(xs + (((kk * RT + t) * 2 + 1) * 64 + lane) * 16);
-          }
-#pragma unroll
-          for (int t = 0; t < RT; ++t) lds_wait(ah[t], al[t], bh, bl);
-#pragma unroll
-          for (int t = 0; t < RT; ++t) {
-            axs[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bh, axs[t], 0, 0, 0);
-            axs[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[t], bh, axs[t], 0, 0, 0);
-            axs[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bl, axs[t], 0, 0, 0);
-          }
+          axs[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bh, axs[t], 0, 0, 0);
+          axs[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[t], bh, axs[t], 0, 0, 0);
+          axs[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[t], bl, axs[t], 0, 0, 0);
         }
       }
     }
@@ -1718,15 +1733,39 @@ __device__ __forceinline__ void gram_finish_body(const GramFinItem& it, const Ba
   constexpr int R = 32 * RT;
   float* const Mss = reinterpret_cast<float*>(smem);
   float* const Mxs = Mss + R * R;
-  const float* __restrict__ part = reinterpret_cast<const float*>(bs.ws + it.off_part);
-  for (int id = threadIdx.x; id < R * R; id += 512) {
-    float a = 0.f, x = 0.f;
-    for (int sg = 0; sg < it.nseg; ++sg) {
-      a += part[(int64_t)sg * 2 * R * R + id];
-      if (!it.same) x += part[(int64_t)sg * 2 * R * R + R * R + id];
+  // 16 bytes per load, every load of a thread independent of the others: the launch is a few latencies long
+  const float4* __restrict__ part = reinterpret_cast<const float4*>(bs.ws + it.off_part);
+  constexpr int Q = R * R / 4;                       // float4 per matrix
+  constexpr int PER = (Q + 511) / 512;               // per thread: 8 at R = 128
+  float4 a[PER], x[PER];
+#pragma unroll
+  for (int u = 0; u < PER; ++u) a[u] = x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int sg = 0; sg < it.nseg; ++sg) {
+    float4 pa[PER], px[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int id = threadIdx.x + 512 * u;
+      if (id < Q) {
+        pa[u] = part[(int64_t)sg * 2 * Q + id];
+        if (!it.same) px[u] = part[(int64_t)sg * 2 * Q + Q + id];
+      }
     }
-    Mss[id] = a;
-    Mxs[id] = it.same ? a : x;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int id = threadIdx.x + 512 * u;
+      if (id < Q) {
+        a[u].x += pa[u].x; a[u].y += pa[u].y; a[u].z += pa[u].z; a[u].w += pa[u].w;
+        if (!it.same) { x[u].x += px[u].x; x[u].y += px[u].y; x[u].z += px[u].z; x[u].w += px[u].w; }
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int id = threadIdx.x + 512 * u;
+    if (id < Q) {
+      reinterpret_cast<float4*>(Mss)[id] = a[u];
+      reinterpret_cast<float4*>(Mxs)[id] = it.same ? a[u] : x[u];
+    }
   }
   __syncthreads();
   gram_emit<RT>(Mss, Mxs, bs, it.off_out_ss, it.off_out_xs, it.off_img_ss, it.off_img_xs, it.r, it.transpose_xs, 512);
