@@ -815,10 +815,7 @@ void build_plan(adapm_ctx* c) {
     if (b.mom_mode == ADAPM_MOM_LOWRANK) {
       L.sL = salloc(4 * m * r);
       L.sR = salloc(4 * r * n);
-      // kept between two runs of Alg. 2: the bf16 (hi, lo) images of the held R
       if (L.path == PATH_FAST && hp.refresh_period_T > 1) {
-        L.wQf = walloc(proj_qf_bytes(rank_class((int)r), (int)n));
-        L.wTimg = walloc(proj_timg_bytes(rank_class((int)r), (int)n));
         L.wG64 = walloc(8 * r * r);        // Gram matrix of R, then its Cholesky factor C, and C^-1: the pass over all
         L.wCinv = walloc(8 * r * r);       // blocks that follows the last group's Alg. 2
       }
@@ -899,7 +896,22 @@ void build_plan(adapm_ctx* c) {
   }
   c->off_gn_partials = (int64_t)wo; wo += align_up(8 * c->gn.h.size());
   c->off_gn_out = (int64_t)wo; wo += align_up(8);
-  const size_t persistent = wo;
+  // kept between two runs of Alg. 2: the bf16 (hi, lo) images of the held R, last in this part of the workspace.
+  // A step that runs Alg. 2 rebuilds them at its end and reads them nowhere, so where no other step needs scratch
+  // (the F64 form of the step with R held does) the groups' scratch starts where the images start.
+  const size_t images_at = wo;
+  bool scratch_in_held_steps = false;
+  for (int64_t i = 0; i < nb; ++i) {
+    const adapm_block_t& b = c->table[i];
+    Layout& L = c->lay[i];
+    if (L.path == PATH_F64) scratch_in_held_steps = true;
+    if (L.path != PATH_FAST || hp.refresh_period_T <= 1) continue;
+    auto walloc = [&](size_t bytes) { int64_t o = (int64_t)wo; wo += align_up(bytes); return o; };
+    L.wQf = walloc(proj_qf_bytes(rank_class(b.rank), (int)b.cols));
+    L.wTimg = walloc(proj_timg_bytes(rank_class(b.rank), (int)b.cols));
+  }
+  const size_t images_end = wo;
+  const size_t persistent = scratch_in_held_steps ? images_end : images_at;     // where the groups' scratch starts
 
   // ---- every step starts with the v statistics and the full / no-momentum blocks
   for (int kind = 0; kind < 2; ++kind) {
@@ -913,7 +925,7 @@ void build_plan(adapm_ctx* c) {
     if (!c->ew[0].h.empty()) seq.push_back(Op{OP_UPDATE, 0, 0, 0, "update_full"});
     if (!c->grp.h.empty()) seq.push_back(Op{OP_UPDATE_GROUPED, 0, 0, 0, "update_full_grouped"});
   }
-  c->ws_bytes = persistent;
+  c->ws_bytes = images_end;
   if (c->n_lowrank == 0) return;
 
   // ---- groups of low-rank blocks: scratch budget, then per group the layout and the launches
@@ -931,6 +943,12 @@ void build_plan(adapm_ctx* c) {
     c->rg_chol = (int)c->chol.size() - 1;
   }
   for (int path : {PATH_F64, PATH_FAST}) {
+    // groups of about equal size: as few as the budget allows, none above it
+    size_t total = 0;
+    for (int64_t i = 0; i < nb; ++i)
+      if (c->lay[i].path == path) total += layout_block_scratch(c->table[i], hp, c->lay[i], 0, true);
+    const size_t n_groups = (total + budget - 1) / budget;
+    const size_t target = n_groups ? (total + n_groups - 1) / n_groups : 0;
     std::vector<int64_t> ids;
     size_t used = 0;
     auto flush = [&]() {
@@ -950,13 +968,13 @@ void build_plan(adapm_ctx* c) {
     for (int64_t i = 0; i < nb; ++i) {
       if (c->lay[i].path != path) continue;
       const size_t need = layout_block_scratch(c->table[i], hp, c->lay[i], 0, true);
-      if (!ids.empty() && used + need > budget) flush();
+      if (!ids.empty() && (used + need > budget || used >= target)) flush();
       ids.push_back(i);
       used += need;
     }
     flush();
   }
-  c->ws_bytes = persistent + scratch_max;
+  c->ws_bytes = std::max(images_end, persistent + scratch_max);
   if (hp.refresh_period_T > 1 && !c->rg_apply.h.empty()) {
     c->seq_refresh.push_back(Op{OP_GEMM, c->rg_gram, 0, 0, "regauge_gram_f64"});
     c->seq_refresh.push_back(Op{OP_CHOL, c->rg_chol, 0, 0, "regauge_cholesky_f64"});
