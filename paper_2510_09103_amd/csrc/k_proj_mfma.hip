@@ -1697,7 +1697,7 @@ __device__ __forceinline__ void gram_emit(const float* Mss, const float* Mxs, co
   for (int id = threadIdx.x; id < r * r; id += nthreads) {
     const int row = id / r, col = id % r;
     Oss[id] = Mss[row * R + col];
-    Oxs[transpose_xs ? (int64_t)col * r + row : (int64_t)id] = Mxs[row * R + col];
+    Oxs[id] = transpose_xs ? Mxs[col * R + row] : Mxs[row * R + col];      // the transposition is an LDS read: stores stay contiguous
   }
   if (off_img_ss < 0) return;
   const int nk2 = (r + BK - 1) / BK;
