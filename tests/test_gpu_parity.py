@@ -116,6 +116,14 @@ def test_ragged_shapes_on_the_mfma_path(hp):
     run(ragged_bf16_table(), 6, hp, tol_state=TOL16, tol_param=TOL16, check_every=2)
 
 
+@pytest.mark.parametrize("hp", [dict(T=1), dict(T=3)])
+def test_both_contraction_paths_in_one_table(hp):
+    """Automatic choice of the contraction: the fp32-parameter blocks of the table take the exact path, the bf16 ones
+    the MFMA path.  With T > 1 the exact path's step with R held needs scratch in every step while the MFMA path's
+    bf16 copies of R have to survive beside it (the layout that may not put the one over the other)."""
+    run(ragged_bf16_table(), 6, dict(hp), tol_state=TOL16, tol_param=TOL16, check_every=2)
+
+
 def odd_rank_table():
     """bf16 blocks whose rank is not 32, 64 or 128 (the paper takes r = 5 % of the smaller dimension): the
     MFMA kernels run them in the next rank class with zero-padded images of the factors.  Ranks that are
