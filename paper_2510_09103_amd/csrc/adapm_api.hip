@@ -286,7 +286,7 @@ GemmProblem problem(int M, int N) {
   return p;
 }
 
-// segments a Gram-type product over K columns is cut into (one workgroup each)
+// most segments a Gram-type product over K columns is cut into (sizes the partial sums; a group may use fewer, longer ones)
 int gram_segments(int64_t K) {
   const int64_t nch = (K + 63) / 64;
   return (int)((nch + GRAM_SEG_CHUNKS - 1) / GRAM_SEG_CHUNKS);
@@ -419,7 +419,7 @@ void plan_lowrank_refresh(adapm_ctx* c, bool fast, const std::vector<int64_t>& i
         // R' R^T with R R^T (contraction over n) and L^T L' with L^T L (over m); longest contraction first
         // ... each with the fragment images of its two results, which the GD step on the stripes multiplies by: image
         // row a, column k = B[k][a] with B = R' R^T, R R^T for L and B = (L^T L')^T, L^T L for R^T
-        // a contraction longer than GRAM_SEG_CHUNKS chunks is cut into segments (one workgroup each, partial sums added
+        // a contraction longer than the group's segment length is cut into segments (one workgroup each, partial sums added
         // in segment order by a second small launch): the longest workgroup of a launch then stays short
         auto add_gram = [&](int64_t off_x, int64_t off_s, int64_t o_xs, int64_t o_ss, int64_t i_xs, int64_t i_ss, int K, int tx,
                             int64_t off_part) {

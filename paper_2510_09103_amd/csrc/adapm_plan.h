@@ -291,7 +291,7 @@ void launch_stripe(int rt, bool tra, const StripeItem* items, int64_t nitems, co
 void launch_qf_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gram(const GramItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_gram_finish(const GramFinItem* items, int64_t nitems, Bases b, hipStream_t s);
-constexpr int GRAM_SEG_CHUNKS = 25;    // 64-column chunks per segment of a Gram-type product (1600 columns)
+constexpr int GRAM_SEG_CHUNKS = 25;    // shortest segment of a Gram-type product in 64-column chunks (1600 columns): sizes the partial sums
 void launch_qt_image(const ImgItem* items, int64_t nitems, Bases b, hipStream_t s);
 void launch_refresh_update(int rt, bool w16, const ProjItem* items, int64_t nitems, const RuBlockDev* blocks, Bases b,
                            StepScalars sc, hipStream_t s);

@@ -1523,11 +1523,12 @@ __global__ __launch_bounds__(256) void qf_image_kernel(const ImgItem* __restrict
 // r x r Gram-type products of Alg. 2 straight from the fragment images: a lane's 16 bytes of an image hold 8
 // consecutive k of one row, which is the A-operand layout for rows of X and equally the B-operand layout for columns
 // of S^T.  One workgroup (8 waves) per pair of products that share an image: X S^T and S S^T, i.e. (R' R^T, R R^T)
-// with X = R', S = R and ((L^T L')^T, L^T L) with X = L'^T, S = L^T.  The 64-column chunks of the two images are
-// copied global -> LDS without registers, two buffers deep, so that every image byte is read from L2 once per pair
-// (read per wave, or once per product, the launch was bound by L2 bandwidth); wave w owns column tile w % 4 of both
-// results (all row tiles) and half w / 4 of the k-steps of every chunk.  In the first GD iteration X = S and one
-// product serves both outputs.
+// with X = R', S = R and ((L^T L')^T, L^T L) with X = L'^T, S = L^T.  The two images are copied global -> LDS
+// without registers, in halves of a 64-column chunk through a ring of four buffers per image, so that every image
+// byte is read from L2 once per pair (read per wave, or once per product, the launch was bound by L2 bandwidth);
+// wave w owns column tile w % 4 of both results (all row tiles) and k-step w / 4 of every half.  In the first GD
+// iteration X = S and one product serves both outputs.  A long contraction is cut into segments, one workgroup each
+// (chunks c0 .. c1 - 1): a segment leaves its partial sums for gram_finish_kernel.
 template <int RT>
 __device__ __forceinline__ void gram_emit(const float* Mss, const float* Mxs, const Bases& bs, int64_t off_out_ss,
                                           int64_t off_out_xs, int64_t off_img_ss, int64_t off_img_xs, int r,
