@@ -99,6 +99,10 @@ def main():
         print("bench.py: this build is single-GPU (blocks are independent, the library has no collectives); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.T > 1 and args.steps < 2:
+        print("bench.py: with a refresh period T > 1 the timed region needs --steps >= 2: its first step runs Alg. 2, "
+              "the others hold R, and the value weighs the two kinds 1 : T - 1", file=sys.stderr)
+        sys.exit(2)
 
     import torch
     from paper_2510_09103_amd import binding as B

@@ -12,6 +12,11 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert "single-GPU" in out.stderr and out.stdout.strip() == ""
 
 
+def test_one_timed_step_cannot_weigh_both_kinds_of_step():
+    out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "1"], capture_output=True, text=True)
+    assert out.returncode != 0 and "--steps >= 2" in out.stderr and out.stdout.strip() == ""
+
+
 def test_oracle_baseline_leg_reports_the_contract_fields():
     sys.path.insert(0, ROOT)
     import bench
